@@ -1,0 +1,133 @@
+/*
+ * kfac.h -- C ABI of the MI355X (gfx950) K-FAC preconditioner library.
+ *
+ * The library computes, per layer, the steps of the K-FAC gradient
+ * preconditioner of arXiv 2007.00784 ("Convolutional Neural Network Training
+ * with Distributed K-FAC"):
+ *   unfold conv inputs -> Kronecker factors A, G with running average ->
+ *   symmetric eigendecomposition of each factor -> eigenbasis preconditioning.
+ *
+ * Conventions for every call
+ *  - C linkage, plain structs, int status (0 = KFAC_OK, negative = error).
+ *    No exception crosses the boundary.  kfac_strerror() names a status.
+ *  - Every data pointer is a DEVICE pointer owned by the caller unless it is
+ *    marked "host".  The library never allocates or frees user-visible memory
+ *    and keeps no pointer after a call returns, except the workspace given to
+ *    kfac_create(), which it uses as scratch until kfac_destroy().
+ *  - Work is enqueued on the hipStream_t given to kfac_create().  All calls
+ *    are asynchronous with respect to the host except kfac_eig(), which waits
+ *    on the stream between sweeps to decide convergence and returns with its
+ *    outputs complete.
+ *  - Matrices are row-major, fp32 unless stated.  Outputs must not alias
+ *    inputs except where a parameter is marked in/out.
+ *  - A context is not thread-safe; use one context per stream.
+ *  - Arguments are validated on the host before any kernel is launched; an
+ *    invalid argument returns KFAC_EINVAL and launches nothing.
+ */
+#ifndef KFAC_H
+#define KFAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    KFAC_OK = 0,
+    KFAC_EINVAL = -1,     /* NULL / out-of-range / unsupported argument            */
+    KFAC_ENOCONV = -2,    /* eigensolver reached max_sweeps; outputs still written */
+    KFAC_EHIP = -3,       /* a HIP runtime call failed                             */
+    KFAC_EWORKSPACE = -4  /* the context's workspace is too small for this call    */
+};
+
+typedef enum { KFAC_F32 = 0, KFAC_BF16 = 1 } kfac_dtype;
+
+/* Layout of a sample matrix X with R = N*T sample rows and d features.
+ *   KFAC_LAYOUT_RD : [R][d], d contiguous (FC activations and gradients; T = 1 is typical)
+ *   KFAC_LAYOUT_NDT: [N][d][T], T contiguous: per-example slabs.  This is the NCHW layout of
+ *                    conv output gradients ([N][C_out][Ho*Wo]) and of the input of a 1x1
+ *                    stride-1 unpadded conv, and it is what kfac_unfold() writes.          */
+typedef enum { KFAC_LAYOUT_RD = 0, KFAC_LAYOUT_NDT = 1 } kfac_layout;
+
+typedef struct {
+    int N, C, H, W;          /* input tensor, NCHW                               */
+    int kh, kw;              /* kernel                                           */
+    int stride_h, stride_w;
+    int pad_h, pad_w;        /* zero padding on each side                        */
+    int dtype;               /* kfac_dtype of x and of the patches               */
+} kfac_conv_desc;
+
+typedef struct {
+    int max_sweeps;          /* cap on Jacobi sweeps (<=0: 30)                    */
+    float tol;               /* stop when off(F)_F <= tol * ||F||_F (<=0: 1e-6)   */
+} kfac_eig_opts;
+
+typedef struct {             /* host memory, filled when kfac_eig() returns       */
+    int sweeps;              /* sweeps performed                                  */
+    float off_norm_rel;      /* off(F)_F / ||F||_F of the rotated matrix at exit  */
+    int converged;           /* 1 if the tolerance was met                        */
+} kfac_eig_info;
+
+typedef struct kfac_ctx kfac_ctx;
+
+/* Create a context bound to HIP device `device` and stream `hip_stream` (a hipStream_t; NULL is
+ * the default stream).  `workspace_dev` is caller-owned device scratch of `workspace_bytes` bytes,
+ * 256-byte aligned, which must outlive the context; see kfac_workspace_bytes().  */
+int kfac_create(kfac_ctx **ctx, int device, void *hip_stream, void *workspace_dev, size_t workspace_bytes);
+int kfac_destroy(kfac_ctx *ctx);
+
+/* Pure host functions: bytes of workspace that suffice for any call with factor dimension <= max_d,
+ * at most max_batch_factors factors per kfac_eig() call and at most max_R sample rows; and the exact
+ * requirement of one kfac_eig() call on the given host array of dimensions.  */
+size_t kfac_workspace_bytes(int max_d, int max_batch_factors, int64_t max_R);
+size_t kfac_eig_workspace_bytes(int batch, const int *d /* host */);
+
+const char *kfac_strerror(int code);
+
+/* Unfold of a conv input (the paper handles Conv2D layers, Sec. V, treating every output location
+ * of every example as one sample): patches[n][(c*kh+ky)*kw+kx][ho*Wo+wo] = x[n][c][ho*sh-ph+ky][wo*sw-pw+kx],
+ * zero outside the image; Ho = (H+2ph-kh)/sh+1, Wo likewise.
+ *   x       : [N][C][H][W], dtype desc->dtype
+ *   patches : [N][C*kh*kw][Ho*Wo] (KFAC_LAYOUT_NDT), same dtype, no bias row.  */
+int kfac_unfold(kfac_ctx *ctx, const kfac_conv_desc *desc, const void *x, void *patches);
+
+/* Kronecker factor of a mini-batch folded into its running average (Sec. II-C: A = a a^T, G = g g^T
+ * over the samples; Sec. IV-B: running average with parameter xi):
+ *   F <- decay * F + (1 - decay) * scale * Xt^T Xt,   Xt = [X | 1] if append_ones else X
+ *   X     : samples, dtype `dtype`, layout `layout`, N examples x T locations x d features
+ *   F     : [D][D] fp32, D = d + append_ones, full symmetric storage, in/out
+ *   decay : xi, weight of the history; decay = 0 overwrites F with the batch factor
+ * The result is exactly symmetric.  Split-K partial sums are reduced in a fixed order, so the
+ * result is bit-reproducible run to run.  */
+int kfac_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layout, int N, int d, int T,
+                        int append_ones, float scale, float decay, float *F);
+
+/* Symmetric eigendecompositions F_i = Q_i diag(lam_i) Q_i^T (Sec. IV-A, Algorithm 1 step 2) of a
+ * batch of factors by (block) Jacobi iteration; lam ascending, eigenvectors in the columns of Q.
+ *   F, Q, lam : HOST arrays of `batch` device pointers; F_i is [d_i][d_i] (read only),
+ *               Q_i [d_i][d_i], lam_i [d_i]
+ *   d         : host array of dimensions, 1 <= d_i <= 8192
+ *   opts      : host, may be NULL for defaults;  info: host array [batch], may be NULL
+ * Returns KFAC_ENOCONV if any factor missed the tolerance within max_sweeps (all outputs are
+ * still the current iterate).  Non-finite input gives non-finite output and KFAC_ENOCONV.  */
+int kfac_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,
+             float *const *lam, const kfac_eig_opts *opts, kfac_eig_info *info);
+
+/* Eigenbasis preconditioning, Eqs. (v1), (v2), (kfac-eigen) of Sec. IV-A, in place:
+ *   V1 = QG^T grad QA;  V2 = V1 / (max(lamG,0) max(lamA,0)^T + damping);  grad <- QG V2 QA^T
+ *   QA [dA][dA], lamA [dA], QG [dG][dG], lamG [dG] : fp32
+ *   grad : [dG][dA], dtype grad_dtype, in/out; its last column is the bias gradient when the
+ *          A factor was built with append_ones.  damping > 0.  */
+int kfac_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,
+                      const float *lamG, int dG, float damping, void *grad, int grad_dtype);
+
+/* Update-decoupled schedule (Sec. IV-C, Sec. V-C), host only: at iteration k refresh the factors
+ * when k % f_fac == 0 and the eigendecompositions when k % f_eig == 0; precondition always.  */
+int kfac_schedule_due(int64_t k, int f_fac, int f_eig, int *do_factors, int *do_eig);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KFAC_H */

@@ -1,0 +1,585 @@
+// Batched symmetric eigensolver F = Q diag(lam) Q^T (Sec. IV-A; Algorithm 1, step 2) by two-sided
+// Jacobi iteration in fp32.
+//
+//  * d <= 128: one workgroup per factor.  The rotated matrix and the accumulated eigenvectors both
+//    stay in LDS for the whole solve; every round applies d/2 disjoint plane rotations (round-robin
+//    tournament ordering), each computed by one lane and applied by the whole workgroup.
+//  * d  > 128: blocked Jacobi.  The matrix is cut into 64-wide blocks; a round pairs the blocks by
+//    the same tournament, solves each 128x128 pivot sub-problem with the LDS solver above (one
+//    workgroup per pair), and applies the resulting orthogonal 128x128 transforms to the whole
+//    matrix and to the eigenvector accumulator as fp32 MFMA products on LDS-resident tiles.  Only
+//    the lower block-triangle is computed; the mirror image is written from LDS, so the working
+//    matrix stays exactly symmetric.  Factors of equal block count are advanced together.
+//
+// Convergence is decided on the host once per sweep from off(F)_F / ||F||_F.
+#include <algorithm>
+#include <vector>
+#include "kfac_internal.h"
+#include "mfma_gemm.h"
+
+namespace {
+
+constexpr int EB = KFAC_EIG_B;  // block width of the blocked path
+constexpr int SK = 2 * EB;      // pivot sub-problem size (128)
+constexpr int SLD = SK + 1;     // LDS pitch (odd: column walks are bank-conflict free)
+constexpr int NT = 256;
+
+struct SmallItem { const float *F; float *Q; float *lam; int n; int pad_; };
+struct EigStat { float sweeps, off_rel, converged, rotations; };
+
+// Tournament schedule on `players` (even) players: round r in [0, players-1), pair j in [0, players/2).
+__host__ __device__ inline void rr_pair(int players, int r, int j, int &p, int &q) {
+    int a, b;
+    const int m1 = players - 1;
+    if (j == 0) { a = m1; b = r; }
+    else { a = (r + j) % m1; b = (r - j + m1) % m1; }
+    p = a < b ? a : b;
+    q = a < b ? b : a;
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+
+// Sum over the workgroup (NT threads); result valid in all threads.  red: >= 5 floats of LDS.
+__device__ inline float block_sum(float v, float *red) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float s = 0.f;
+    for (int w = 0; w < NT / 64; ++w) s += red[w];
+    return s;
+}
+
+struct JacobiResult { int sweeps; float off2, nrm2; int rotations; };
+
+// Two-sided Jacobi on the k x k symmetric matrix S (k even), accumulating V <- V J, both in LDS with
+// pitch ld.  Stops when off(S)^2 <= tol^2 * ||S||^2 or after max_sweeps.  Rotations use the smaller
+// angle, so the accumulated transform stays close to the identity ordering.  Entries whose magnitude
+// is below skip_rel * ||S||_F / k are left alone (and exact zeros always are, which keeps zero-padded
+// rows and columns decoupled).
+__device__ JacobiResult jacobi_lds(float *S, float *V, int k, int ld, int max_sweeps, float tol, float skip_rel,
+                                   float *red, float2 *cs, int *pp, int *qq, int *rotcount) {
+    const int tid = threadIdx.x;
+    const int half = k >> 1;
+    JacobiResult res{0, 0.f, 0.f, 0};
+    if (tid == 0) *rotcount = 0;
+    for (int sweep = 0;; ++sweep) {
+        float o2 = 0.f, d2 = 0.f;
+        for (int e = tid; e < k * k; e += NT) {
+            const int i = e / k, j = e - i * k;
+            const float v = S[i * ld + j];
+            if (i == j) d2 += v * v; else o2 += v * v;
+        }
+        o2 = block_sum(o2, red);
+        d2 = block_sum(d2, red);
+        res.off2 = o2;
+        res.nrm2 = o2 + d2;
+        res.sweeps = sweep;
+        if (!(o2 > tol * tol * res.nrm2) || sweep >= max_sweeps) break;
+        const float thr = skip_rel * sqrtf(res.nrm2) / (float)k;
+        for (int r = 0; r < k - 1; ++r) {
+            if (tid < half) {
+                int p, q;
+                rr_pair(k, r, tid, p, q);
+                const float app = S[p * ld + p], aqq = S[q * ld + q], apq = S[p * ld + q];
+                float c = 1.f, s = 0.f;
+                if (fabsf(apq) > thr) {
+                    // rotation parameters in fp64, so that c^2 + s^2 = 1 to fp32 rounding without bias
+                    const double theta = ((double)aqq - (double)app) / (2.0 * (double)apq);
+                    const double t = copysign(1.0, theta) / (fabs(theta) + sqrt(theta * theta + 1.0));
+                    const double cd = 1.0 / sqrt(t * t + 1.0);
+                    c = (float)cd;
+                    s = (float)(t * cd);
+                    atomicAdd(rotcount, 1);
+                }
+                cs[tid] = make_float2(c, s);
+                pp[tid] = p;
+                qq[tid] = q;
+            }
+            __syncthreads();
+            // S <- J^T S J on 2x2 blocks (rows of pair j1, columns of pair j2)
+            for (int e = tid; e < half * half; e += NT) {
+                const int j1 = e / half, j2 = e - j1 * half;
+                const int p1 = pp[j1], q1 = qq[j1], p2 = pp[j2], q2 = qq[j2];
+                const float2 r1 = cs[j1], r2 = cs[j2];
+                float a = S[p1 * ld + p2], b = S[p1 * ld + q2], c_ = S[q1 * ld + p2], d = S[q1 * ld + q2];
+                // columns: [a b; c d] * [[c2, s2], [-s2, c2]]
+                const float a1 = r2.x * a - r2.y * b, b1 = r2.y * a + r2.x * b;
+                const float c1 = r2.x * c_ - r2.y * d, d1 = r2.y * c_ + r2.x * d;
+                // rows: [[c1, -s1], [s1, c1]] * [...]
+                S[p1 * ld + p2] = r1.x * a1 - r1.y * c1;
+                S[p1 * ld + q2] = r1.x * b1 - r1.y * d1;
+                S[q1 * ld + p2] = r1.y * a1 + r1.x * c1;
+                S[q1 * ld + q2] = r1.y * b1 + r1.x * d1;
+            }
+            // V <- V J
+            for (int e = tid; e < k * half; e += NT) {
+                const int j = e / k, i = e - j * k;
+                const int p = pp[j], q = qq[j];
+                const float2 rc = cs[j];
+                const float vp = V[i * ld + p], vq = V[i * ld + q];
+                V[i * ld + p] = rc.x * vp - rc.y * vq;
+                V[i * ld + q] = rc.y * vp + rc.x * vq;
+            }
+            __syncthreads();
+        }
+    }
+    res.rotations = *rotcount;
+    return res;
+}
+
+// Dynamic LDS layout shared by the small solver and the pivot solver.
+struct JacobiSmem {
+    float *S, *V, *red;
+    float2 *cs;
+    int *pp, *qq, *rot;
+    __device__ JacobiSmem(char *base, int k, int ld) {
+        S = (float *)base;
+        V = S + k * ld;
+        red = V + k * ld;
+        cs = (float2 *)(red + 8);
+        pp = (int *)(cs + SK / 2);
+        qq = pp + SK / 2;
+        rot = qq + SK / 2;
+    }
+    static size_t bytes(int k, int ld) { return ((size_t)2 * k * ld + 8 + 4 * (SK / 2) + 4) * sizeof(float); }
+};
+
+// ------------------------------------------------------------------------------------------------
+// d <= 128: whole factor in LDS
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void eig_small_kernel(const SmallItem *items, EigStat *stats, int max_sweeps,
+                                                       float tol) {
+    extern __shared__ __align__(16) char smem[];
+    const SmallItem it = items[blockIdx.x];
+    const int n = it.n;
+    const int k = (n + 1) & ~1;
+    const int ld = k + 1;
+    JacobiSmem sm(smem, k, ld);
+    const int tid = threadIdx.x;
+    for (int e = tid; e < k * k; e += NT) {
+        const int i = e / k, j = e - i * k;
+        sm.S[i * ld + j] = (i < n && j < n) ? it.F[(int64_t)i * n + j] : 0.f;
+        sm.V[i * ld + j] = (i == j) ? 1.f : 0.f;
+    }
+    __syncthreads();
+    const JacobiResult res = jacobi_lds(sm.S, sm.V, k, ld, max_sweeps, tol, 1e-9f, sm.red, sm.cs, sm.pp, sm.qq, sm.rot);
+    // rank of every eigenvalue (ascending, ties by index) -> pp[]
+    for (int i = tid; i < n; i += NT) {
+        const float li = sm.S[i * ld + i];
+        int rank = 0;
+        for (int j = 0; j < n; ++j) {
+            const float lj = sm.S[j * ld + j];
+            rank += (lj < li) || (lj == li && j < i);
+        }
+        sm.pp[i] = rank;
+        it.lam[rank] = li;
+    }
+    __syncthreads();
+    for (int e = tid; e < n * n; e += NT) {
+        const int i = e / n, j = e - i * n;
+        it.Q[(int64_t)i * n + sm.pp[j]] = sm.V[i * ld + j];
+    }
+    if (tid == 0) {
+        EigStat st;
+        st.sweeps = (float)res.sweeps;
+        st.off_rel = res.nrm2 > 0.f ? sqrtf(res.off2 / res.nrm2) : 0.f;
+        st.converged = (res.off2 <= tol * tol * res.nrm2) ? 1.f : 0.f;
+        st.rotations = (float)res.rotations;
+        stats[blockIdx.x] = st;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// d > 128: blocked path.  Per group of `nmat` factors with `nblk` 64-wide blocks (npad = 64*nblk):
+//   W  [nmat][npad][npad]   rotated matrix         Qw [nmat][npad][npad]  accumulated eigenvectors
+//   J  [nmat][npairs][128][128] pivot transforms   idt[nmat][npairs]      1 = transform is identity
+// ------------------------------------------------------------------------------------------------
+struct BlkGroup {
+    float *W, *Qw, *J;
+    int *idt;
+    double *norms;   // [nmat][2] = off^2, diag^2
+    int nmat, nblk, npad, players, npairs;
+};
+struct BlkItem { const float *F; float *Q; float *lam; int n; int pad_; };
+
+__global__ void blk_init_kernel(BlkGroup g, const BlkItem *items) {
+    const int m = blockIdx.y;
+    const BlkItem it = items[m];
+    const int64_t np2 = (int64_t)g.npad * g.npad;
+    float *W = g.W + m * np2, *Qw = g.Qw + m * np2;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < np2; e += (int64_t)gridDim.x * blockDim.x) {
+        const int i = (int)(e / g.npad), j = (int)(e - (int64_t)i * g.npad);
+        W[e] = (i < it.n && j < it.n) ? it.F[(int64_t)i * it.n + j] : 0.f;
+        Qw[e] = (i == j) ? 1.f : 0.f;
+    }
+}
+
+__global__ void blk_zero_norms_kernel(double *norms, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) norms[i] = 0.0;
+}
+
+__global__ __launch_bounds__(NT) void blk_offnorm_kernel(BlkGroup g) {
+    __shared__ float red[8];
+    const int m = blockIdx.y;
+    const int64_t np2 = (int64_t)g.npad * g.npad;
+    const float *W = g.W + m * np2;
+    float o2 = 0.f, d2 = 0.f;
+    for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < np2; e += (int64_t)gridDim.x * NT) {
+        const int i = (int)(e / g.npad), j = (int)(e - (int64_t)i * g.npad);
+        const float v = W[e];
+        if (i == j) d2 += v * v; else o2 += v * v;
+    }
+    o2 = block_sum(o2, red);
+    d2 = block_sum(d2, red);
+    if (threadIdx.x == 0) {
+        atomicAdd(&g.norms[2 * m], (double)o2);
+        atomicAdd(&g.norms[2 * m + 1], (double)d2);
+    }
+}
+
+// Row/column index in the padded matrix of element a (0..127) of the pair (p, q); -1 if the block is
+// the phantom one that completes an odd block count.
+__device__ inline int pair_index(int a, int p, int q, int nblk) {
+    const int blk = a < EB ? p : q;
+    return blk < nblk ? blk * EB + (a & (EB - 1)) : -1;
+}
+
+__global__ __launch_bounds__(NT) void blk_solve_kernel(BlkGroup g, int round, int inner_sweeps, float inner_tol) {
+    extern __shared__ __align__(16) char smem[];
+    JacobiSmem sm(smem, SK, SLD);
+    const int m = blockIdx.y, pj = blockIdx.x, tid = threadIdx.x;
+    const float *W = g.W + (int64_t)m * g.npad * g.npad;
+    int p, q;
+    rr_pair(g.players, round, pj, p, q);
+    for (int e = tid; e < SK * SK; e += NT) {
+        const int a = e / SK, b = e - a * SK;
+        const int gi = pair_index(a, p, q, g.nblk), gj = pair_index(b, p, q, g.nblk);
+        // read the lower triangle only, so the sub-problem is exactly symmetric
+        float v = 0.f;
+        if (gi >= 0 && gj >= 0) v = (gi >= gj) ? W[(int64_t)gi * g.npad + gj] : W[(int64_t)gj * g.npad + gi];
+        sm.S[a * SLD + b] = v;
+        sm.V[a * SLD + b] = (a == b) ? 1.f : 0.f;
+    }
+    __syncthreads();
+    const JacobiResult res = jacobi_lds(sm.S, sm.V, SK, SLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.cs, sm.pp, sm.qq, sm.rot);
+    float *J = g.J + ((int64_t)m * g.npairs + pj) * (SK * SK);
+    for (int e = tid; e < SK * SK; e += NT) {
+        const int a = e / SK, b = e - a * SK;
+        J[e] = sm.V[a * SLD + b];
+    }
+    if (tid == 0) g.idt[m * g.npairs + pj] = res.rotations == 0;
+}
+
+__device__ inline void tri_decode(int idx, int &ti, int &tj) {
+    int t = (int)((sqrtf(8.f * (float)idx + 1.f) - 1.f) * 0.5f);
+    while ((t + 1) * (t + 2) / 2 <= idx) ++t;
+    while (t * (t + 1) / 2 > idx) --t;
+    ti = t;
+    tj = idx - t * (t + 1) / 2;
+}
+
+// 128x128x128 product on LDS-resident operands: acc = A * B with A(m,k) = Am[m*am + k*ak],
+// B(k,n) = Bm[k*SLD + n].
+__device__ inline void lds_gemm128(const float *Am, int am, int ak, const float *Bm, floatx16 (&acc)[2][2]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lk = lane >> 5, lc = lane & 31;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll 4
+    for (int kk = 0; kk < SK; kk += 2) {
+        const float a0 = Am[(wm + lc) * am + (kk + lk) * ak];
+        const float a1 = Am[(wm + 32 + lc) * am + (kk + lk) * ak];
+        const float b0 = Bm[(kk + lk) * SLD + wn + lc];
+        const float b1 = Bm[(kk + lk) * SLD + wn + 32 + lc];
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+}
+
+__device__ inline void acc_to_lds(const floatx16 (&acc)[2][2], float *X) {
+    kfac::for_each_acc(acc, [&](int r, int c, float v) { X[r * SLD + c] = v; });
+}
+
+__device__ inline void load_J(float *Js, const float *J) {
+    for (int e = threadIdx.x; e < SK * SK; e += NT) Js[(e >> 7) * SLD + (e & 127)] = J[e];
+}
+
+// One round of transforms: W_IJ <- J_I^T W_IJ J_J for pair-tiles I >= J (mirrored into J,I), and
+// Qw[:, J] <- Qw[:, J] J_J for every 128-row slab of the accumulator.
+__global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, int ntiles_w, int nrb) {
+    extern __shared__ __align__(16) char smem[];
+    float *Xs = (float *)smem;
+    float *Js = Xs + SK * SLD;
+    const int m = blockIdx.y, tid = threadIdx.x;
+    const int64_t np2 = (int64_t)g.npad * g.npad;
+    const int *idt = g.idt + m * g.npairs;
+    const float *Jall = g.J + (int64_t)m * g.npairs * (SK * SK);
+    floatx16 acc[2][2];
+    if ((int)blockIdx.x < ntiles_w) {
+        float *W = g.W + m * np2;
+        int I, Jp;
+        tri_decode(blockIdx.x, I, Jp);
+        if (idt[I] && idt[Jp]) return;
+        int pi, qi, pj, qj;
+        rr_pair(g.players, round, I, pi, qi);
+        rr_pair(g.players, round, Jp, pj, qj);
+        for (int e = tid; e < SK * SK; e += NT) {
+            const int a = e >> 7, b = e & 127;
+            const int gi = pair_index(a, pi, qi, g.nblk), gj = pair_index(b, pj, qj, g.nblk);
+            Xs[a * SLD + b] = (gi >= 0 && gj >= 0) ? W[(int64_t)gi * g.npad + gj] : 0.f;
+        }
+        load_J(Js, Jall + (int64_t)Jp * (SK * SK));
+        __syncthreads();
+        lds_gemm128(Xs, SLD, 1, Js, acc);  // T = X J_J
+        __syncthreads();
+        acc_to_lds(acc, Xs);
+        load_J(Js, Jall + (int64_t)I * (SK * SK));
+        __syncthreads();
+        lds_gemm128(Js, 1, SLD, Xs, acc);  // W' = J_I^T T
+        __syncthreads();
+        acc_to_lds(acc, Xs);
+        __syncthreads();
+        for (int e = tid; e < SK * SK; e += NT) {
+            const int a = e >> 7, b = e & 127;
+            const int gi = pair_index(a, pi, qi, g.nblk), gj = pair_index(b, pj, qj, g.nblk);
+            if (gi >= 0 && gj >= 0) W[(int64_t)gi * g.npad + gj] = Xs[a * SLD + b];
+        }
+        if (I != Jp) {
+            for (int e = tid; e < SK * SK; e += NT) {
+                const int b = e >> 7, a = e & 127;  // a fastest: contiguous along the mirrored row
+                const int gi = pair_index(a, pi, qi, g.nblk), gj = pair_index(b, pj, qj, g.nblk);
+                if (gi >= 0 && gj >= 0) W[(int64_t)gj * g.npad + gi] = Xs[a * SLD + b];
+            }
+        }
+    } else {
+        float *Qw = g.Qw + m * np2;
+        const int t = blockIdx.x - ntiles_w;
+        const int rb = t % nrb, Jp = t / nrb;
+        if (idt[Jp]) return;
+        int pj, qj;
+        rr_pair(g.players, round, Jp, pj, qj);
+        const int row0 = rb * SK;
+        for (int e = tid; e < SK * SK; e += NT) {
+            const int a = e >> 7, b = e & 127;
+            const int gi = row0 + a, gj = pair_index(b, pj, qj, g.nblk);
+            Xs[a * SLD + b] = (gi < g.npad && gj >= 0) ? Qw[(int64_t)gi * g.npad + gj] : 0.f;
+        }
+        load_J(Js, Jall + (int64_t)Jp * (SK * SK));
+        __syncthreads();
+        lds_gemm128(Xs, SLD, 1, Js, acc);
+        __syncthreads();
+        acc_to_lds(acc, Xs);
+        __syncthreads();
+        for (int e = tid; e < SK * SK; e += NT) {
+            const int a = e >> 7, b = e & 127;
+            const int gi = row0 + a, gj = pair_index(b, pj, qj, g.nblk);
+            if (gi < g.npad && gj >= 0) Qw[(int64_t)gi * g.npad + gj] = Xs[a * SLD + b];
+        }
+    }
+}
+
+// perm[rank] = index of the rank-th smallest diagonal entry (ties by index); lam[rank] = that entry.
+__global__ __launch_bounds__(NT) void blk_rank_kernel(BlkGroup g, const BlkItem *items, int *perm) {
+    const int m = blockIdx.y;
+    const BlkItem it = items[m];
+    const float *W = g.W + (int64_t)m * g.npad * g.npad;
+    const int i = blockIdx.x * NT + threadIdx.x;
+    if (i >= it.n) return;
+    const float li = W[(int64_t)i * g.npad + i];
+    int rank = 0;
+    for (int j = 0; j < it.n; ++j) {
+        const float lj = W[(int64_t)j * g.npad + j];
+        rank += (lj < li) || (lj == li && j < i);
+    }
+    perm[m * g.npad + rank] = i;
+    it.lam[rank] = li;
+}
+
+__global__ __launch_bounds__(NT) void blk_gather_kernel(BlkGroup g, const BlkItem *items, const int *perm) {
+    const int m = blockIdx.y;
+    const BlkItem it = items[m];
+    const float *Qw = g.Qw + (int64_t)m * g.npad * g.npad;
+    const int64_t n2 = (int64_t)it.n * it.n;
+    for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < n2; e += (int64_t)gridDim.x * NT) {
+        const int i = (int)(e / it.n), j = (int)(e - (int64_t)i * it.n);
+        int c = perm[m * g.npad + j];
+        c = c < 0 ? 0 : (c >= it.n ? it.n - 1 : c);  // ranks collide only when the input holds NaNs
+        it.Q[e] = Qw[(int64_t)i * g.npad + c];
+    }
+}
+
+// ---- host side ---------------------------------------------------------------------------------
+struct GroupPlan {
+    int nblk, npad, players, npairs;
+    std::vector<int> members;
+    size_t bytes() const {
+        const size_t nm = members.size();
+        size_t b = 0;
+        b += kfac_align_up(nm * 2 * (size_t)npad * npad * sizeof(float), 256);       // W, Qw
+        b += kfac_align_up(nm * (size_t)npairs * SK * SK * sizeof(float), 256);      // J
+        b += kfac_align_up(nm * (size_t)npairs * sizeof(int), 256);                  // idt
+        b += kfac_align_up(nm * 2 * sizeof(double), 256);                            // norms
+        b += kfac_align_up(nm * (size_t)npad * sizeof(int), 256);                    // perm
+        b += kfac_align_up(nm * sizeof(BlkItem), 256);                               // items
+        return b;
+    }
+};
+
+void make_plan(int batch, const int *d, std::vector<int> &small, std::vector<GroupPlan> &groups) {
+    for (int i = 0; i < batch; ++i) {
+        if (d[i] <= KFAC_EIG_SMALL) { small.push_back(i); continue; }
+        const int nblk = (d[i] + EB - 1) / EB;
+        GroupPlan *gp = nullptr;
+        for (auto &g : groups) if (g.nblk == nblk) gp = &g;
+        if (!gp) {
+            GroupPlan g;
+            g.nblk = nblk;
+            g.npad = nblk * EB;
+            g.players = (nblk + 1) & ~1;
+            g.npairs = g.players / 2;
+            groups.push_back(g);
+            gp = &groups.back();
+        }
+        gp->members.push_back(i);
+    }
+    std::sort(groups.begin(), groups.end(), [](const GroupPlan &a, const GroupPlan &b) { return a.nblk > b.nblk; });
+}
+
+size_t small_bytes(size_t nsmall) {
+    return kfac_align_up(nsmall * sizeof(SmallItem), 256) + kfac_align_up(nsmall * sizeof(EigStat), 256);
+}
+
+}  // namespace
+
+size_t kfac_eig_ws_bytes_impl(int batch, const int *d) {
+    std::vector<int> small;
+    std::vector<GroupPlan> groups;
+    make_plan(batch, d, small, groups);
+    size_t need = small_bytes(small.size());
+    for (auto &g : groups) need = std::max(need, g.bytes());  // groups run one after another
+    return need;
+}
+
+int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,
+                    float *const *lam, const kfac_eig_opts *opts, kfac_eig_info *info) {
+    const int max_sweeps = (opts && opts->max_sweeps > 0) ? opts->max_sweeps : 30;
+    const float tol = (opts && opts->tol > 0.f) ? opts->tol : 1e-6f;
+    std::vector<int> small;
+    std::vector<GroupPlan> groups;
+    make_plan(batch, d, small, groups);
+    if (kfac_eig_ws_bytes_impl(batch, d) > ctx->ws_bytes) return KFAC_EWORKSPACE;
+    bool all_conv = true;
+    hipStream_t st = ctx->stream;
+
+    if (!small.empty()) {
+        const size_t ns = small.size();
+        std::vector<SmallItem> items(ns);
+        int kmax = 2;
+        for (size_t i = 0; i < ns; ++i) {
+            items[i] = SmallItem{F[small[i]], Q[small[i]], lam[small[i]], d[small[i]], 0};
+            kmax = std::max(kmax, (d[small[i]] + 1) & ~1);
+        }
+        SmallItem *d_items = (SmallItem *)ctx->ws;
+        EigStat *d_stats = (EigStat *)(ctx->ws + kfac_align_up(ns * sizeof(SmallItem), 256));
+        KFAC_HIP_CHECK(hipMemcpyAsync(d_items, items.data(), ns * sizeof(SmallItem), hipMemcpyHostToDevice, st));
+        const size_t lds = JacobiSmem::bytes(kmax, kmax + 1);
+        if ((int)lds > ctx->max_lds) return KFAC_EHIP;
+        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)eig_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(eig_small_kernel, dim3((unsigned)ns), dim3(NT), lds, st, d_items, d_stats, max_sweeps, tol);
+        KFAC_HIP_CHECK(hipGetLastError());
+        std::vector<EigStat> stats(ns);
+        KFAC_HIP_CHECK(hipMemcpyAsync(stats.data(), d_stats, ns * sizeof(EigStat), hipMemcpyDeviceToHost, st));
+        KFAC_HIP_CHECK(hipStreamSynchronize(st));
+        for (size_t i = 0; i < ns; ++i) {
+            const bool conv = stats[i].converged > 0.5f;
+            all_conv &= conv;
+            if (info) info[small[i]] = kfac_eig_info{(int)stats[i].sweeps, stats[i].off_rel, conv ? 1 : 0};
+        }
+    }
+
+    for (auto &gp : groups) {
+        const int nm = (int)gp.members.size();
+        const size_t np2 = (size_t)gp.npad * gp.npad;
+        char *p = ctx->ws;
+        BlkGroup g;
+        g.nmat = nm; g.nblk = gp.nblk; g.npad = gp.npad; g.players = gp.players; g.npairs = gp.npairs;
+        g.W = (float *)p;
+        g.Qw = g.W + nm * np2;
+        p += kfac_align_up(nm * 2 * np2 * sizeof(float), 256);
+        g.J = (float *)p; p += kfac_align_up((size_t)nm * gp.npairs * SK * SK * sizeof(float), 256);
+        g.idt = (int *)p; p += kfac_align_up((size_t)nm * gp.npairs * sizeof(int), 256);
+        g.norms = (double *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(double), 256);
+        int *perm = (int *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(int), 256);
+        BlkItem *d_items = (BlkItem *)p;
+        std::vector<BlkItem> items(nm);
+        for (int i = 0; i < nm; ++i) {
+            const int b = gp.members[i];
+            items[i] = BlkItem{F[b], Q[b], lam[b], d[b], 0};
+        }
+        KFAC_HIP_CHECK(hipMemcpyAsync(d_items, items.data(), nm * sizeof(BlkItem), hipMemcpyHostToDevice, st));
+        const int fill_blocks = (int)std::min<size_t>((np2 + NT - 1) / NT, 4096);
+        hipLaunchKernelGGL(blk_init_kernel, dim3(fill_blocks, nm), dim3(NT), 0, st, g, d_items);
+        KFAC_HIP_CHECK(hipGetLastError());
+
+        const size_t lds_solve = JacobiSmem::bytes(SK, SLD);
+        const size_t lds_apply = (size_t)2 * SK * SLD * sizeof(float);
+        if ((int)lds_solve > ctx->max_lds || (int)lds_apply > ctx->max_lds) return KFAC_EHIP;
+        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_solve));
+        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_apply));
+        const int ntiles_w = gp.npairs * (gp.npairs + 1) / 2;
+        int nmax = 0;
+        for (int i = 0; i < nm; ++i) nmax = std::max(nmax, items[i].n);
+        const int nrb = (nmax + SK - 1) / SK;
+        const int ntiles = ntiles_w + nrb * gp.npairs;
+
+        std::vector<double> norms(2 * nm);
+        std::vector<int> sweeps_done(nm, 0);
+        std::vector<char> conv(nm, 0);
+        std::vector<float> offrel(nm, 0.f);
+        int sweep = 0;
+        for (;; ++sweep) {
+            hipLaunchKernelGGL(blk_zero_norms_kernel, dim3(1), dim3(256), 0, st, g.norms, 2 * nm);
+            hipLaunchKernelGGL(blk_offnorm_kernel, dim3(std::min(fill_blocks, 512), nm), dim3(NT), 0, st, g);
+            KFAC_HIP_CHECK(hipGetLastError());
+            KFAC_HIP_CHECK(hipMemcpyAsync(norms.data(), g.norms, 2 * nm * sizeof(double), hipMemcpyDeviceToHost, st));
+            KFAC_HIP_CHECK(hipStreamSynchronize(st));
+            bool all = true;
+            for (int i = 0; i < nm; ++i) {
+                const double o2 = norms[2 * i], n2 = o2 + norms[2 * i + 1];
+                offrel[i] = n2 > 0 ? (float)std::sqrt(o2 / n2) : 0.f;
+                const bool c = o2 <= (double)tol * tol * n2;   // false for NaN
+                if (c && !conv[i]) sweeps_done[i] = sweep;
+                conv[i] = c;
+                all &= c;
+            }
+            if (all || sweep >= max_sweeps) break;
+            for (int r = 0; r < gp.players - 1; ++r) {
+                hipLaunchKernelGGL(blk_solve_kernel, dim3(gp.npairs, nm), dim3(NT), lds_solve, st, g, r, 6, 1e-7f);
+                hipLaunchKernelGGL(blk_apply_kernel, dim3(ntiles, nm), dim3(NT), lds_apply, st, g, r, ntiles_w, nrb);
+            }
+            KFAC_HIP_CHECK(hipGetLastError());
+        }
+        hipLaunchKernelGGL(blk_rank_kernel, dim3((nmax + NT - 1) / NT, nm), dim3(NT), 0, st, g, d_items, perm);
+        hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(fill_blocks, 2048), nm), dim3(NT), 0, st, g, d_items, perm);
+        KFAC_HIP_CHECK(hipGetLastError());
+        KFAC_HIP_CHECK(hipStreamSynchronize(st));  // the workspace is reused by the next group
+        for (int i = 0; i < nm; ++i) {
+            all_conv &= (bool)conv[i];
+            if (info) info[gp.members[i]] = kfac_eig_info{conv[i] ? sweeps_done[i] : sweep, offrel[i], conv[i] ? 1 : 0};
+        }
+    }
+    return all_conv ? KFAC_OK : KFAC_ENOCONV;
+}

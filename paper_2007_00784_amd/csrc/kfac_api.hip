@@ -1,0 +1,140 @@
+// C-ABI entry points: argument validation, workspace accounting, dispatch to the kernel launchers.
+#include <algorithm>
+#include <cmath>
+#include <new>
+#include <string_view>
+#include <vector>
+#include "kfac_internal.h"
+
+namespace {
+
+bool valid_dtype(int t) { return t == KFAC_F32 || t == KFAC_BF16; }
+
+// cheap sanity check that a pointer the caller calls "device" is usable from this device
+bool is_device_ptr(const void *p) {
+    if (!p) return false;
+    hipPointerAttribute_t a;
+    if (hipPointerGetAttributes(&a, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return a.type == hipMemoryTypeDevice || a.type == hipMemoryTypeManaged;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *kfac_strerror(int code) {
+    switch (code) {
+        case KFAC_OK: return "success";
+        case KFAC_EINVAL: return "invalid or unsupported argument";
+        case KFAC_ENOCONV: return "eigensolver did not reach the tolerance within max_sweeps";
+        case KFAC_EHIP: return "HIP runtime failure";
+        case KFAC_EWORKSPACE: return "workspace too small";
+        default: return "unknown status";
+    }
+}
+
+int kfac_create(kfac_ctx **out, int device, void *hip_stream, void *workspace_dev, size_t workspace_bytes) {
+    if (!out) return KFAC_EINVAL;
+    *out = nullptr;
+    int ndev = 0;
+    KFAC_HIP_CHECK(hipGetDeviceCount(&ndev));
+    if (device < 0 || device >= ndev) return KFAC_EINVAL;
+    if (workspace_bytes > 0 && (!workspace_dev || ((uintptr_t)workspace_dev & 255))) return KFAC_EINVAL;
+    KFAC_HIP_CHECK(hipSetDevice(device));
+    hipDeviceProp_t prop;
+    KFAC_HIP_CHECK(hipGetDeviceProperties(&prop, device));
+    if (std::string_view(prop.gcnArchName).substr(0, 6) != "gfx950") return KFAC_EINVAL;  // built for gfx950 only
+    if (workspace_bytes > 0 && !is_device_ptr(workspace_dev)) return KFAC_EINVAL;
+    kfac_ctx *c = new (std::nothrow) kfac_ctx();
+    if (!c) return KFAC_EHIP;
+    c->device = device;
+    c->stream = (hipStream_t)hip_stream;
+    c->ws = (char *)workspace_dev;
+    c->ws_bytes = workspace_bytes;
+    c->host_flags = nullptr;
+    int lds = 0;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) lds = 65536;
+    c->max_lds = lds;
+    *out = c;
+    return KFAC_OK;
+}
+
+int kfac_destroy(kfac_ctx *ctx) {
+    if (!ctx) return KFAC_EINVAL;
+    delete ctx;
+    return KFAC_OK;
+}
+
+size_t kfac_eig_workspace_bytes(int batch, const int *d) {
+    if (batch <= 0 || !d) return 0;
+    for (int i = 0; i < batch; ++i)
+        if (d[i] < 1 || d[i] > KFAC_MAX_D) return 0;
+    return kfac_eig_ws_bytes_impl(batch, d);
+}
+
+size_t kfac_workspace_bytes(int max_d, int max_batch_factors, int64_t max_R) {
+    if (max_d < 1 || max_d > KFAC_MAX_D || max_batch_factors < 1 || max_R < 1) return 0;
+    // SYRK split partials: at most 512 + one tile per lower-triangular tile, 64 KB each
+    const size_t nt = (max_d + KFAC_TILE) / KFAC_TILE + 1;
+    size_t need = (512 + nt * (nt + 1) / 2) * (size_t)KFAC_TILE * KFAC_TILE * sizeof(float);
+    // precondition: two dG x dA temporaries
+    need = std::max(need, 2 * kfac_align_up((size_t)max_d * max_d, 64) * sizeof(float));
+    // eig: every factor of the batch at the largest size, advanced together
+    std::vector<int> d((size_t)max_batch_factors, max_d);
+    need = std::max(need, kfac_eig_ws_bytes_impl(max_batch_factors, d.data()));
+    return kfac_align_up(need, 256);
+}
+
+int kfac_unfold(kfac_ctx *ctx, const kfac_conv_desc *desc, const void *x, void *patches) {
+    if (!ctx || !desc || !x || !patches || x == patches) return KFAC_EINVAL;
+    const kfac_conv_desc &d = *desc;
+    if (d.N < 1 || d.C < 1 || d.H < 1 || d.W < 1 || d.kh < 1 || d.kw < 1) return KFAC_EINVAL;
+    if (d.stride_h < 1 || d.stride_w < 1 || d.pad_h < 0 || d.pad_w < 0) return KFAC_EINVAL;
+    if (d.pad_h >= d.kh || d.pad_w >= d.kw) return KFAC_EINVAL;  // every window must touch the image
+    if (d.H + 2 * d.pad_h < d.kh || d.W + 2 * d.pad_w < d.kw) return KFAC_EINVAL;
+    if (!valid_dtype(d.dtype)) return KFAC_EINVAL;
+    if ((int64_t)d.C * d.kh * d.kw > KFAC_MAX_D) return KFAC_EINVAL;
+    return kfac_launch_unfold(ctx, desc, x, patches);
+}
+
+int kfac_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layout, int N, int d, int T,
+                        int append_ones, float scale, float decay, float *F) {
+    if (!ctx || !X || !F || (const void *)F == X) return KFAC_EINVAL;
+    if (!valid_dtype(dtype) || (layout != KFAC_LAYOUT_RD && layout != KFAC_LAYOUT_NDT)) return KFAC_EINVAL;
+    if (N < 1 || d < 1 || T < 1 || (append_ones != 0 && append_ones != 1)) return KFAC_EINVAL;
+    if (d + append_ones > KFAC_MAX_D) return KFAC_EINVAL;
+    if ((int64_t)N * T >= (int64_t)1 << 30) return KFAC_EINVAL;
+    if (!(decay >= 0.f && decay <= 1.f) || !std::isfinite(scale)) return KFAC_EINVAL;
+    return kfac_launch_update_factors(ctx, X, dtype, layout, N, d, T, append_ones, scale, decay, F);
+}
+
+int kfac_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,
+             float *const *lam, const kfac_eig_opts *opts, kfac_eig_info *info) {
+    if (!ctx || batch < 0 || (batch > 0 && (!F || !d || !Q || !lam))) return KFAC_EINVAL;
+    for (int i = 0; i < batch; ++i) {
+        if (d[i] < 1 || d[i] > KFAC_MAX_D || !F[i] || !Q[i] || !lam[i] || (const float *)Q[i] == F[i]) return KFAC_EINVAL;
+    }
+    if (opts && (opts->max_sweeps > 1000 || !(opts->tol < 1.f))) return KFAC_EINVAL;
+    if (batch == 0) return KFAC_OK;
+    return kfac_launch_eig(ctx, batch, F, d, Q, lam, opts, info);
+}
+
+int kfac_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,
+                      const float *lamG, int dG, float damping, void *grad, int grad_dtype) {
+    if (!ctx || !QA || !lamA || !QG || !lamG || !grad) return KFAC_EINVAL;
+    if (dA < 1 || dG < 1 || dA > KFAC_MAX_D || dG > KFAC_MAX_D) return KFAC_EINVAL;
+    if (!(damping > 0.f) || !std::isfinite(damping) || !valid_dtype(grad_dtype)) return KFAC_EINVAL;
+    return kfac_launch_precondition(ctx, QA, lamA, dA, QG, lamG, dG, damping, grad, grad_dtype);
+}
+
+int kfac_schedule_due(int64_t k, int f_fac, int f_eig, int *do_factors, int *do_eig) {
+    if (k < 0 || f_fac < 1 || f_eig < 1 || !do_factors || !do_eig) return KFAC_EINVAL;
+    *do_factors = (k % f_fac) == 0;
+    *do_eig = (k % f_eig) == 0;
+    return KFAC_OK;
+}
+
+}  // extern "C"

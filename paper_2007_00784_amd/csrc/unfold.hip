@@ -1,0 +1,113 @@
+// Unfold (im2col) of a conv input into per-example patch slabs [N][C*kh*kw][Ho*Wo].
+// Pure data movement, HBM-bound: each workgroup stages the input rows of a group of channels it
+// needs once in LDS (zero padding materialised there), then writes the kh*kw shifted copies.  For a
+// fixed example and channel the kh*kw patch rows are adjacent in the output, so a workgroup's
+// output is one contiguous run (full-height chunks) or kh*kw runs of whole output rows, and both
+// the global reads (along W) and the global writes (along Ho*Wo) are coalesced.
+#include "kfac_internal.h"
+
+namespace {
+
+constexpr int UNFOLD_LDS_ELEMS = 8192;  // staged input elements per workgroup (32 KB as fp32)
+
+struct UnfoldArgs {
+    int N, C, H, W, kh, kw, sh, sw, ph, pw, Ho, Wo;
+    int cpb;       // channels per workgroup
+    int rows_out;  // output rows per workgroup
+    int rows_in;   // staged input rows = (rows_out-1)*sh + kh
+    int Wp;        // staged row width = W + 2*pw
+    float inv_Wp, inv_rows_in, inv_Tc, inv_Wo, inv_kw, inv_kh;
+};
+
+// q = e / d, r = e % d for 0 <= e < 2^24 using a float reciprocal and one correction step each way.
+__device__ inline void fdivmod(int e, int d, float inv_d, int &q, int &r) {
+    q = (int)((float)e * inv_d);
+    r = e - q * d;
+    if (r < 0) { --q; r += d; }
+    if (r >= d) { ++q; r -= d; }
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void unfold_kernel(const E *__restrict__ x, E *__restrict__ out, UnfoldArgs a) {
+    __shared__ E tile[UNFOLD_LDS_ELEMS];
+    const int n = blockIdx.z;
+    const int c0 = blockIdx.y * a.cpb;
+    const int ho0 = blockIdx.x * a.rows_out;
+    const int nch = min(a.cpb, a.C - c0);
+    const int rows_out = min(a.rows_out, a.Ho - ho0);
+    const int rows_in = (rows_out - 1) * a.sh + a.kh;
+    const int h_first = ho0 * a.sh - a.ph;
+    const int plane = a.rows_in * a.Wp;  // LDS pitch per channel
+    // ---- stage: tile[cc][hr][wc] = x[n][c0+cc][h_first+hr][wc-pw] or 0 ----
+    const int stage_n = nch * rows_in * a.Wp;
+    for (int e = threadIdx.x; e < stage_n; e += 256) {
+        int row, wc, cc, hr;
+        fdivmod(e, a.Wp, a.inv_Wp, row, wc);
+        fdivmod(row, rows_in, 1.0f / (float)rows_in, cc, hr);
+        const int h = h_first + hr, w = wc - a.pw;
+        E v = 0;
+        if (h >= 0 && h < a.H && w >= 0 && w < a.W) v = x[(((int64_t)n * a.C + c0 + cc) * a.H + h) * a.W + w];
+        tile[cc * plane + hr * a.Wp + wc] = v;
+    }
+    __syncthreads();
+    // ---- write: for each (cc, ky, kx) the run of rows_out*Wo outputs starting at (ho0, 0) ----
+    const int Tc = rows_out * a.Wo;
+    const int T = a.Ho * a.Wo;
+    const int khw = a.kh * a.kw;
+    const int total = nch * khw * Tc;
+    const float inv_Tc = 1.0f / (float)Tc;
+    for (int e = threadIdx.x; e < total; e += 256) {
+        int prow, t, cc, kk, ky, kx, hoo, wo;
+        fdivmod(e, Tc, inv_Tc, prow, t);
+        fdivmod(prow, khw, 1.0f / (float)khw, cc, kk);
+        fdivmod(kk, a.kw, a.inv_kw, ky, kx);
+        fdivmod(t, a.Wo, a.inv_Wo, hoo, wo);
+        const E v = tile[cc * plane + (hoo * a.sh + ky) * a.Wp + wo * a.sw + kx];
+        out[((int64_t)n * a.C * khw + (int64_t)(c0 + cc) * khw + kk) * T + (int64_t)ho0 * a.Wo + t] = v;
+    }
+}
+
+}  // namespace
+
+int kfac_launch_unfold(kfac_ctx *ctx, const kfac_conv_desc *d, const void *x, void *patches) {
+    UnfoldArgs a;
+    a.N = d->N; a.C = d->C; a.H = d->H; a.W = d->W; a.kh = d->kh; a.kw = d->kw;
+    a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w;
+    a.Ho = (d->H + 2 * d->pad_h - d->kh) / d->stride_h + 1;
+    a.Wo = (d->W + 2 * d->pad_w - d->kw) / d->stride_w + 1;
+    a.Wp = d->W + 2 * d->pad_w;
+    const int rows_in_full = (a.Ho - 1) * a.sh + a.kh;
+    if ((int64_t)d->kh * a.Wp > UNFOLD_LDS_ELEMS) return KFAC_EINVAL;  // one output row must fit
+    if ((int64_t)rows_in_full * a.Wp <= UNFOLD_LDS_ELEMS) {
+        a.rows_out = a.Ho;
+        int cpb = UNFOLD_LDS_ELEMS / (rows_in_full * a.Wp);
+        int64_t want_blocks = 2048;  // keep the grid large enough to fill 256 CUs several times over
+        int64_t cap = ((int64_t)d->N * d->C + want_blocks - 1) / want_blocks;
+        if (cap < 1) cap = 1;
+        if (cpb > cap) cpb = (int)cap;
+        if (cpb > d->C) cpb = d->C;
+        a.cpb = cpb < 1 ? 1 : cpb;
+    } else {
+        a.cpb = 1;
+        a.rows_out = (UNFOLD_LDS_ELEMS / a.Wp - a.kh) / a.sh + 1;
+        if (a.rows_out < 1) a.rows_out = 1;
+    }
+    a.rows_in = (a.rows_out - 1) * a.sh + a.kh;
+    // the flattened per-workgroup counters must stay exactly representable in fp32
+    if ((int64_t)a.cpb * a.kh * a.kw * a.rows_out * a.Wo >= (1 << 24)) return KFAC_EINVAL;
+    a.inv_Wp = 1.0f / (float)a.Wp;
+    a.inv_Wo = 1.0f / (float)a.Wo;
+    a.inv_kw = 1.0f / (float)a.kw;
+    a.inv_kh = 1.0f / (float)a.kh;
+    a.inv_rows_in = 0.f;
+    a.inv_Tc = 0.f;
+    const dim3 grid((a.Ho + a.rows_out - 1) / a.rows_out, (d->C + a.cpb - 1) / a.cpb, d->N);
+    if (grid.y > 65535 || grid.z > 65535) return KFAC_EINVAL;
+    if (d->dtype == KFAC_F32)
+        hipLaunchKernelGGL(unfold_kernel<float>, grid, dim3(256), 0, ctx->stream, (const float *)x, (float *)patches, a);
+    else
+        hipLaunchKernelGGL(unfold_kernel<unsigned short>, grid, dim3(256), 0, ctx->stream,
+                           (const unsigned short *)x, (unsigned short *)patches, a);
+    KFAC_HIP_CHECK(hipGetLastError());
+    return KFAC_OK;
+}

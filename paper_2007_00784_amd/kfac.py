@@ -1,0 +1,171 @@
+"""ctypes binding of libkfac_hip.so: the same entry points as ``include/kfac.h``.
+
+Argument marshalling only.  Device buffers are torch tensors (PyTorch is used for device memory and
+streams, nothing else) or raw integer device addresses; every step of the path runs in the HIP
+library.  Loading fails loudly if the library has not been built (``python -m
+paper_2007_00784_amd.build`` or ``__graft_entry__.build()``); there is no fallback.
+"""
+import ctypes
+import os
+
+KFAC_OK, KFAC_EINVAL, KFAC_ENOCONV, KFAC_EHIP, KFAC_EWORKSPACE = 0, -1, -2, -3, -4
+KFAC_F32, KFAC_BF16 = 0, 1
+KFAC_LAYOUT_RD, KFAC_LAYOUT_NDT = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkfac_hip.so")
+
+EXPORTS = (
+    "kfac_create", "kfac_destroy", "kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
+    "kfac_unfold", "kfac_update_factors", "kfac_eig", "kfac_precondition", "kfac_schedule_due",
+)
+
+
+class kfac_conv_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("N", "C", "H", "W", "kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w", "dtype")]
+
+
+class kfac_eig_opts(ctypes.Structure):
+    _fields_ = [("max_sweeps", ctypes.c_int), ("tol", ctypes.c_float)]
+
+
+class kfac_eig_info(ctypes.Structure):
+    _fields_ = [("sweeps", ctypes.c_int), ("off_norm_rel", ctypes.c_float), ("converged", ctypes.c_int)]
+
+
+class KfacError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, kfac_strerror(code), code))
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libkfac_hip.so is not built: run `python -m paper_2007_00784_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i, f, sz, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_int64
+    ip = ctypes.POINTER(ctypes.c_int)
+    L.kfac_create.argtypes = [ctypes.POINTER(vp), i, vp, vp, sz]
+    L.kfac_destroy.argtypes = [vp]
+    L.kfac_workspace_bytes.argtypes = [i, i, i64]
+    L.kfac_workspace_bytes.restype = sz
+    L.kfac_eig_workspace_bytes.argtypes = [i, ip]
+    L.kfac_eig_workspace_bytes.restype = sz
+    L.kfac_strerror.argtypes = [i]
+    L.kfac_strerror.restype = ctypes.c_char_p
+    L.kfac_unfold.argtypes = [vp, ctypes.POINTER(kfac_conv_desc), vp, vp]
+    L.kfac_update_factors.argtypes = [vp, vp, i, i, i, i, i, i, f, f, vp]
+    L.kfac_eig.argtypes = [vp, i, ctypes.POINTER(vp), ip, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                           ctypes.POINTER(kfac_eig_opts), ctypes.POINTER(kfac_eig_info)]
+    L.kfac_precondition.argtypes = [vp, vp, vp, i, vp, vp, i, f, vp, i]
+    L.kfac_schedule_due.argtypes = [i64, i, i, ip, ip]
+    for name in EXPORTS:
+        if name not in ("kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror"):
+            getattr(L, name).restype = i
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    """Device address of a torch tensor (must be contiguous) or a raw integer address."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return KFAC_F32
+    if t.dtype == torch.bfloat16:
+        return KFAC_BF16
+    raise ValueError("unsupported dtype %s" % t.dtype)
+
+
+def _check(rc, where, allow=()):
+    if rc != KFAC_OK and rc not in allow:
+        raise KfacError(rc, where)
+    return rc
+
+
+def kfac_strerror(code):
+    return lib().kfac_strerror(int(code)).decode()
+
+
+def kfac_workspace_bytes(max_d, max_batch_factors, max_R):
+    return int(lib().kfac_workspace_bytes(int(max_d), int(max_batch_factors), int(max_R)))
+
+
+def kfac_eig_workspace_bytes(dims):
+    arr = (ctypes.c_int * len(dims))(*[int(x) for x in dims])
+    return int(lib().kfac_eig_workspace_bytes(len(dims), arr))
+
+
+def kfac_create(device, stream, workspace, workspace_bytes=None):
+    """Returns an opaque context handle.  `stream` is a hipStream_t value (torch: stream.cuda_stream),
+    `workspace` a uint8 torch tensor (or address) that must stay alive as long as the context."""
+    h = ctypes.c_void_p()
+    nbytes = workspace_bytes if workspace_bytes is not None else (workspace.numel() * workspace.element_size()
+                                                                  if workspace is not None else 0)
+    _check(lib().kfac_create(ctypes.byref(h), int(device), stream or None, _ptr(workspace), nbytes), "kfac_create")
+    return h
+
+
+def kfac_destroy(ctx):
+    _check(lib().kfac_destroy(ctx), "kfac_destroy")
+
+
+def kfac_unfold(ctx, x, kh, kw, stride, pad, patches):
+    """x [N,C,H,W] -> patches [N, C*kh*kw, Ho*Wo] (same dtype)."""
+    N, C, H, W = x.shape
+    sh, sw = (stride, stride) if isinstance(stride, int) else stride
+    ph, pw = (pad, pad) if isinstance(pad, int) else pad
+    d = kfac_conv_desc(N, C, H, W, kh, kw, sh, sw, ph, pw, _dtype_code(x))
+    _check(lib().kfac_unfold(ctx, ctypes.byref(d), _ptr(x), _ptr(patches)), "kfac_unfold")
+
+
+def kfac_update_factors(ctx, X, layout, N, d, T, append_ones, scale, decay, F, dtype=None):
+    code = _dtype_code(X) if dtype is None else dtype
+    _check(lib().kfac_update_factors(ctx, _ptr(X), code, int(layout), int(N), int(d), int(T), int(append_ones),
+                                     float(scale), float(decay), _ptr(F)), "kfac_update_factors")
+
+
+def kfac_eig(ctx, F, Q, lam, max_sweeps=0, tol=0.0, raise_on_noconv=True):
+    """F, Q, lam: lists of device tensors.  Returns a list of (sweeps, off_norm_rel, converged)."""
+    n = len(F)
+    vp = ctypes.c_void_p
+    Fa = (vp * n)(*[_ptr(t) for t in F])
+    Qa = (vp * n)(*[_ptr(t) for t in Q])
+    La = (vp * n)(*[_ptr(t) for t in lam])
+    dims = (ctypes.c_int * n)(*[int(t.shape[0]) for t in F])
+    opts = kfac_eig_opts(int(max_sweeps), float(tol))
+    info = (kfac_eig_info * n)()
+    rc = lib().kfac_eig(ctx, n, Fa, dims, Qa, La, ctypes.byref(opts), info)
+    _check(rc, "kfac_eig", allow=() if raise_on_noconv else (KFAC_ENOCONV,))
+    return [(info[i].sweeps, info[i].off_norm_rel, bool(info[i].converged)) for i in range(n)]
+
+
+def kfac_precondition(ctx, QA, lamA, QG, lamG, damping, grad):
+    dA, dG = int(QA.shape[0]), int(QG.shape[0])
+    if tuple(grad.shape) != (dG, dA):
+        raise ValueError("grad must be [dG, dA]")
+    _check(lib().kfac_precondition(ctx, _ptr(QA), _ptr(lamA), dA, _ptr(QG), _ptr(lamG), dG, float(damping),
+                                   _ptr(grad), _dtype_code(grad)), "kfac_precondition")
+
+
+def kfac_schedule_due(k, f_fac, f_eig):
+    a, b = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().kfac_schedule_due(int(k), int(f_fac), int(f_eig), ctypes.byref(a), ctypes.byref(b)),
+           "kfac_schedule_due")
+    return bool(a.value), bool(b.value)

@@ -1,0 +1,271 @@
+"""GPU parity: every C-ABI call against the fp64 CPU oracle on the same seeded inputs.
+
+Tolerances (the benchmark spec): factors and preconditioned gradients relative Frobenius error
+<= 1e-4 in fp32 (<= 2e-2 with bf16 inputs); eigenpairs: ||F - Q diag(lam) Q^T||_F <= 1e-5 ||F||_F and
+eigenvalues within 1e-5 * lam_max of the oracle's; unfold is bit-exact (data movement only).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2007_00784_amd import kfac as K
+from paper_2007_00784_amd import synthetic as S
+from gpu_util import Ctx, relfro, ndt_to_rows
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+TOL_RES = 1e-5
+TOL_LAM = 1e-5
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = Ctx(1 << 30)
+    yield c
+    c.close()
+
+
+# ------------------------------------------------------------------ unfold
+UNFOLD_CASES = [
+    # N, C, H, k, stride, pad
+    (2, 3, 5, 3, 1, 1),
+    (1, 1, 5, 7, 1, 3),
+    (2, 2, 7, 3, 2, 1),
+    (3, 4, 8, 1, 2, 0),
+    (2, 3, 37, 7, 2, 3),       # several row chunks per plane after staging limits
+    (4, 16, 8, 3, 1, 1),       # config-1 layer
+    (2, 64, 14, 3, 1, 1),
+    (2, 130, 7, 3, 2, 1),      # many channels per workgroup, ragged channel tail
+    (1, 3, 224, 7, 2, 3),      # stem geometry: chunked rows
+    (2, 8, 56, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", UNFOLD_CASES)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_unfold_bit_exact(ctx, case, bf16):
+    N, C, H, k, s, p = case
+    x = np.random.default_rng(1).standard_normal((N, C, H, H)).astype(np.float32)
+    if bf16:
+        x = S.bf16_bits_to_f32(S.to_bf16_bits(x)).reshape(x.shape)
+    out = ctx.unfold(x, k, k, s, p, bf16=bf16).float().cpu().numpy()
+    ref = oracle.unfold(x, k, k, s, s, p, p)
+    assert np.array_equal(ndt_to_rows(out), ref)
+
+
+# ------------------------------------------------------------------ factors
+FACTOR_CASES = [
+    # layout, N, d, T, ones
+    ("RD", 64, 10, 1, 0),
+    ("RD", 300, 65, 1, 1),
+    ("RD", 2048, 144, 1, 1),
+    ("NDT", 32, 144, 64, 1),       # config-1 A factor
+    ("NDT", 32, 16, 64, 0),        # config-1 G factor
+    ("NDT", 7, 130, 49, 1),        # T = 49, ragged tiles
+    ("NDT", 3, 257, 196, 0),
+    ("NDT", 5, 300, 5, 1),         # T < K slab
+    ("RD", 5000, 33, 1, 1),        # split-K on a single tile
+    ("NDT", 64, 64, 784, 1),       # deep split-K
+]
+
+
+@pytest.mark.parametrize("case", FACTOR_CASES)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_update_factors_matches_oracle(ctx, case, bf16):
+    layout, N, d, T, ones = case
+    rng = np.random.default_rng(2)
+    D = d + ones
+    F = None
+    Fd = torch.full((D, D), float("nan"), dtype=torch.float32, device=ctx.dev)
+    for upd, decay in enumerate([0.0, 0.95, 0.95]):
+        X = np.maximum(rng.standard_normal((N, d, T)), 0).astype(np.float32) if layout == "NDT" else \
+            np.maximum(rng.standard_normal((N * T, d)), 0).astype(np.float32)
+        if bf16:
+            X = S.bf16_bits_to_f32(S.to_bf16_bits(X)).reshape(X.shape)
+        rows = ndt_to_rows(X) if layout == "NDT" else X.astype(np.float64)
+        R = rows.shape[0]
+        Fb = oracle.gram(rows, ones, 1.0 / R)
+        F = Fb if upd == 0 else oracle.ema(F, Fb, decay)
+        Xd = ctx.to_dev(X, bf16)
+        ctx.update_factors(Xd, K.KFAC_LAYOUT_NDT if layout == "NDT" else K.KFAC_LAYOUT_RD, N, d, T, ones,
+                           1.0 / R, decay, Fd)
+        torch.cuda.synchronize()
+        got = Fd.cpu().numpy()
+        assert np.isfinite(got).all()
+        assert np.array_equal(got, got.T)
+        assert relfro(got, F) <= TOL_F32
+    if ones:
+        assert abs(got[D - 1, D - 1] - 1.0) < 1e-6
+
+
+def test_update_factors_deterministic(ctx):
+    rng = np.random.default_rng(3)
+    X = ctx.to_dev(rng.standard_normal((20000, 70)).astype(np.float32))
+    outs = []
+    for _ in range(2):
+        Fd = torch.zeros((71, 71), dtype=torch.float32, device=ctx.dev)
+        ctx.update_factors(X, K.KFAC_LAYOUT_RD, 20000, 70, 1, 1, 1.0 / 20000, 0.0, Fd)
+        torch.cuda.synchronize()
+        outs.append(Fd.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])
+
+
+# ------------------------------------------------------------------ eig
+def gram_factor(n, rows, seed, ones=True):
+    rng = np.random.default_rng(seed)
+    X = np.maximum(rng.standard_normal((rows, n - (1 if ones else 0))), 0)
+    return oracle.gram(X, 1 if ones else 0, 1.0 / rows).astype(np.float32)
+
+
+def check_eigpairs(F32, lam, Q, label=""):
+    F = F32.astype(np.float64)
+    lam = lam.astype(np.float64)
+    Q = Q.astype(np.float64)
+    n = F.shape[0]
+    nf = np.linalg.norm(F)
+    assert np.isfinite(lam).all() and np.isfinite(Q).all(), label
+    assert np.all(np.diff(lam) >= 0), label
+    res = np.linalg.norm(F - (Q * lam) @ Q.T) / nf
+    orth = np.linalg.norm(Q.T @ Q - np.eye(n), 2)
+    ref, _ = oracle.eigh(F)
+    lerr = np.abs(lam - ref).max() / max(abs(ref).max(), 1e-300)
+    print("%s n=%d residual=%.2e orth2=%.2e lam_err=%.2e" % (label, n, res, orth, lerr))
+    assert res <= TOL_RES, label
+    assert lerr <= TOL_LAM, label
+    assert orth <= 1e-4, label
+
+
+EIG_SIZES = [(1, 1), (2, 5), (16, 40), (17, 9), (65, 200), (128, 64), (129, 300), (145, 2048), (257, 100),
+             (289, 600), (577, 300), (640, 2000)]
+
+
+@pytest.mark.parametrize("n,rows", EIG_SIZES)
+def test_eig_single(ctx, n, rows):
+    F = gram_factor(n, rows, seed=n)
+    Ld, Qd, info = ctx.eig([F])
+    assert info[0][2], info
+    check_eigpairs(F, Ld[0].cpu().numpy(), Qd[0].cpu().numpy(), "single")
+
+
+def test_eig_batch_mixed_sizes(ctx):
+    sizes = [(16, 50), (145, 500), (10, 3), (145, 700), (289, 100), (64, 64), (300, 1000), (33, 100), (289, 900)]
+    mats = [gram_factor(n, r, seed=100 + i, ones=(i % 2 == 0)) for i, (n, r) in enumerate(sizes)]
+    Ld, Qd, info = ctx.eig(mats)
+    for i, F in enumerate(mats):
+        assert info[i][2]
+        check_eigpairs(F, Ld[i].cpu().numpy(), Qd[i].cpu().numpy(), "batch[%d]" % i)
+
+
+def test_eig_known_spectrum_and_diagonal(ctx):
+    n = 200
+    u = np.random.default_rng(5).standard_normal(n); u /= np.linalg.norm(u)
+    H = np.eye(n) - 2 * np.outer(u, u)
+    D = np.concatenate([np.zeros(50), np.full(60, 0.5), np.linspace(1, 9, 89), [100.0]])
+    F = (H @ np.diag(D) @ H).astype(np.float32)
+    Dg = np.diag(np.random.default_rng(6).random(150)).astype(np.float32)
+    Ld, Qd, info = ctx.eig([F, Dg])
+    lam = Ld[0].cpu().numpy()
+    assert np.abs(lam - np.sort(D)).max() <= TOL_LAM * 100
+    check_eigpairs(F, lam, Qd[0].cpu().numpy(), "householder")
+    assert np.array_equal(Ld[1].cpu().numpy(), np.sort(np.diag(Dg)))
+    assert info[1][0] == 0
+
+
+def test_eig_max_sweeps_reports_noconv(ctx):
+    F = gram_factor(300, 500, seed=7)
+    with pytest.raises(K.KfacError) as e:
+        ctx.eig([F], max_sweeps=1, tol=1e-7)
+    assert e.value.code == K.KFAC_ENOCONV
+    Ld, Qd, info = ctx.eig([F], max_sweeps=1, tol=1e-7, raise_on_noconv=False)
+    assert not info[0][2] and info[0][0] == 1
+    assert np.isfinite(Qd[0].cpu().numpy()).all()
+
+
+# ------------------------------------------------------------------ precondition
+PRECOND_CASES = [(10, 4), (145, 16), (65, 10), (289, 32), (577, 64), (130, 257)]
+
+
+@pytest.mark.parametrize("dA,dG", PRECOND_CASES)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_precondition_matches_oracle(ctx, dA, dG, bf16):
+    rng = np.random.default_rng(8)
+    A = gram_factor(dA, 3 * dA, seed=dA).astype(np.float64)
+    G = oracle.gram(rng.standard_normal((3 * dG, dG)) * 1e-2, 0, 1.0 / (3 * dG))
+    lamA, QA = oracle.eigh(A)
+    lamG, QG = oracle.eigh(G)
+    gamma = 1e-3 * lamA.mean() * lamG.mean()
+    grad = (rng.standard_normal((dG, dA)) * 1e-2).astype(np.float32)
+    if bf16:
+        grad = S.bf16_bits_to_f32(S.to_bf16_bits(grad)).reshape(grad.shape)
+    ref = oracle.precondition(QA, lamA, QG, lamG, gamma, grad)
+    gd = ctx.to_dev(grad, bf16)
+    K.kfac_precondition(ctx.h, ctx.to_dev(QA.astype(np.float32)), ctx.to_dev(lamA.astype(np.float32)),
+                        ctx.to_dev(QG.astype(np.float32)), ctx.to_dev(lamG.astype(np.float32)), gamma, gd)
+    torch.cuda.synchronize()
+    got = gd.float().cpu().numpy()
+    assert relfro(got, ref) <= (TOL_BF16 if bf16 else TOL_F32)
+
+
+# ------------------------------------------------------------------ whole path, config 1
+def test_single_conv_layer_end_to_end(ctx):
+    """3x3 conv 16->16 on 8x8, batch 32: three factor updates, eig, precondition, against the oracle and
+    against brute-force inversion of the damped Kronecker product."""
+    wl = S.workload("single_conv")
+    lay = wl.layers[0]
+    A = G = None
+    Ad = torch.full((145, 145), float("nan"), dtype=torch.float32, device=ctx.dev)
+    Gd = torch.full((16, 16), float("nan"), dtype=torch.float32, device=ctx.dev)
+    for upd in range(3):
+        t = S.layer_inputs(wl, 0, update=upd)
+        P = oracle.unfold(t["x"], 3, 3, 1, 1, 1, 1)
+        gr = t["g"].transpose(0, 2, 3, 1).reshape(-1, lay.c_out)
+        R = P.shape[0]
+        Ab, Gb = oracle.gram(P, 1, 1.0 / R), oracle.gram(gr, 0, 1.0 / R)
+        A = Ab if A is None else oracle.ema(A, Ab, wl.decay)
+        G = Gb if G is None else oracle.ema(G, Gb, wl.decay)
+        decay = 0.0 if upd == 0 else wl.decay
+        Pd = ctx.unfold(t["x"], 3, 3, 1, 1)
+        ctx.update_factors(Pd, K.KFAC_LAYOUT_NDT, wl.batch, 144, lay.T, 1, 1.0 / R, decay, Ad)
+        gd = ctx.to_dev(t["g"].reshape(wl.batch, lay.c_out, lay.T))
+        ctx.update_factors(gd, K.KFAC_LAYOUT_NDT, wl.batch, 16, lay.T, 0, 1.0 / R, decay, Gd)
+    torch.cuda.synchronize()
+    assert relfro(Ad.cpu().numpy(), A) <= TOL_F32
+    assert relfro(Gd.cpu().numpy(), G) <= TOL_F32
+    Ld, Qd, info = ctx.eig([Ad, Gd])
+    check_eigpairs(Ad.cpu().numpy(), Ld[0].cpu().numpy(), Qd[0].cpu().numpy(), "A")
+    check_eigpairs(Gd.cpu().numpy(), Ld[1].cpu().numpy(), Qd[1].cpu().numpy(), "G")
+    lamA, QA = oracle.eigh(A)
+    lamG, QG = oracle.eigh(G)
+    for gamma in (wl.damping, 1e-3 * lamA.mean() * lamG.mean()):
+        ref = oracle.precondition(QA, lamA, QG, lamG, gamma, t["gradw"])
+        gd = ctx.to_dev(t["gradw"])
+        K.kfac_precondition(ctx.h, Qd[0], Ld[0], Qd[1], Ld[1], gamma, gd)
+        torch.cuda.synchronize()
+        got = gd.cpu().numpy()
+        assert relfro(got, ref) <= TOL_F32
+        assert relfro(got, oracle.bruteforce(G, A, gamma, t["gradw"])) <= TOL_F32
+
+
+# ------------------------------------------------------------------ error paths (host-side validation)
+def test_invalid_arguments_are_rejected(ctx):
+    F = torch.zeros((4, 4), device=ctx.dev)
+    X = torch.zeros((8, 4), device=ctx.dev)
+    L = K.lib()
+    assert L.kfac_update_factors(ctx.h, None, 0, 0, 8, 4, 1, 0, 1.0, 0.0, F.data_ptr()) == K.KFAC_EINVAL
+    assert L.kfac_update_factors(ctx.h, X.data_ptr(), 7, 0, 8, 4, 1, 0, 1.0, 0.0, F.data_ptr()) == K.KFAC_EINVAL
+    assert L.kfac_update_factors(ctx.h, X.data_ptr(), 0, 0, 8, 4, 1, 0, 1.0, 1.5, F.data_ptr()) == K.KFAC_EINVAL
+    assert L.kfac_update_factors(ctx.h, X.data_ptr(), 0, 0, 0, 4, 1, 0, 1.0, 0.5, F.data_ptr()) == K.KFAC_EINVAL
+    assert L.kfac_precondition(ctx.h, F.data_ptr(), F.data_ptr(), 4, F.data_ptr(), F.data_ptr(), 4, 0.0,
+                               F.data_ptr(), 0) == K.KFAC_EINVAL
+    d = K.kfac_conv_desc(1, 1, 4, 4, 3, 3, 0, 1, 1, 1, 0)
+    import ctypes
+    assert L.kfac_unfold(ctx.h, ctypes.byref(d), X.data_ptr(), F.data_ptr()) == K.KFAC_EINVAL
+    small = Ctx(1 << 16)
+    big = torch.zeros((300, 300), device=ctx.dev)
+    with pytest.raises(K.KfacError) as e:
+        K.kfac_eig(small.h, [big], [torch.empty_like(big)], [torch.empty(300, device=ctx.dev)])
+    assert e.value.code == K.KFAC_EWORKSPACE
+    small.close()
