@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark: one K-FAC preconditioner step (factor update + eigendecomposition + preconditioning) over
+the ResNet-50-shaped layer set (53 convs + FC, 224x224 inputs, per-GPU batch 32, fp32) on one MI355X.
+
+A step = every layer: unfold -> A and G factor update folded into the running average; then the
+eigendecomposition of all 108 factors; then the eigenbasis-preconditioned gradient of all 54 layers.
+Inputs are seeded synthetic tensors resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32 = 157.3e12   # MI355X dense fp32 matrix FLOP/s
+PEAK_VALU_F32 = 157.3e12   # fp32 vector FLOP/s (256 CUs x 128 lanes x 2 flops x 2.4 GHz)
+PEAK_HBM = 8.0e12          # bytes/s
+
+BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
+    "unfold": ("hbm", PEAK_HBM, "GB/s", "bytes"),
+    "syrk": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
+    "syrk_reduce": ("hbm", PEAK_HBM, "GB/s", "bytes"),
+    "precond_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
+    "eig_small": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
+    "eig_pivot_solve": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
+    "eig_apply": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
+    "eig_misc": ("hbm", PEAK_HBM, "GB/s", "bytes"),
+    "eig_post_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
+}
+
+
+def cpu_baseline(wl_name, seconds_hint=20.0):
+    """The fp64 oracle, as it stands, timed on this host on one mid-size layer of the workload
+    (unfold + both factors + both eigendecompositions + preconditioning)."""
+    import numpy as np
+    import oracle
+    from paper_2007_00784_amd import synthetic as S
+    wl = S.workload(wl_name)
+    name = "s3b1.conv3" if len(wl.layers) > 1 else wl.layers[0].name
+    li = [i for i, l in enumerate(wl.layers) if l.name == name][0]
+    lay = wl.layers[li]
+    t = S.layer_inputs(wl, li, update=0)
+    R = wl.batch * lay.T
+    t0 = time.perf_counter()
+    P = oracle.unfold(t["x"], lay.k, lay.k, lay.stride, lay.stride, lay.pad, lay.pad)
+    A = oracle.gram(P, 1, 1.0 / R)
+    G = oracle.gram(t["g"].transpose(0, 2, 3, 1).reshape(R, lay.c_out), 0, 1.0 / R)
+    t1 = time.perf_counter()
+    la, qa = oracle.eigh(A)
+    lg, qg = oracle.eigh(G)
+    t2 = time.perf_counter()
+    oracle.precondition(qa, la, qg, lg, wl.damping, t["gradw"])
+    t3 = time.perf_counter()
+    return {
+        "value": round((t3 - t0) * 1e3, 1), "unit": "ms", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "one layer of the set (%s: %dx%d conv %d->%d on %dx%d, batch %d; d_A=%d, d_G=%d), "
+                  "one K-FAC step of that layer" % (name, lay.k, lay.k, lay.c_in, lay.c_out, lay.h_in, lay.h_in,
+                                                    wl.batch, lay.d_a, lay.d_g),
+        "phases_ms": {"factors": round((t1 - t0) * 1e3, 1), "eig": round((t2 - t1) * 1e3, 1),
+                      "precondition": round((t3 - t2) * 1e3, 1)},
+        "layer_index": li,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every GPU box here has one GPU); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2007_00784_amd import kfac as K
+    from paper_2007_00784_amd import synthetic as S
+    from paper_2007_00784_amd.runner import KfacRunner
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = S.workload(args.workload)
+    t_setup = time.time()
+    run = KfacRunner(wl, "cuda:0", n_updates=2)
+    print("[bench] inputs generated and resident in %.1f s" % (time.time() - t_setup), file=sys.stderr, flush=True)
+    # warm state: the first factor update has no history (decay 0)
+    run.update_factors(0, 0.0)
+    torch.cuda.synchronize()
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(marks=None):
+        if marks is not None:
+            marks[0].record()
+        run.update_factors(1, wl.decay)
+        if marks is not None:
+            marks[1].record()
+        run.eig(raise_on_noconv=False)
+        if marks is not None:
+            marks[2].record()
+        run.precondition()
+        if marks is not None:
+            marks[3].record()
+
+    for i in range(args.warmup):
+        step()
+        torch.cuda.synchronize()
+        print("[bench] warmup step %d done" % i, file=sys.stderr, flush=True)
+    all_marks = [[ev() for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(all_marks[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    phases = {"factors": 0.0, "eig": 0.0, "precondition": 0.0}
+    for m in all_marks:
+        phases["factors"] += m[0].elapsed_time(m[1]) / args.steps
+        phases["eig"] += m[1].elapsed_time(m[2]) / args.steps
+        phases["precondition"] += m[2].elapsed_time(m[3]) / args.steps
+    info = run.eig_info
+    sweeps = [s for (s, _, _) in info]
+    nconv = sum(1 for (_, _, c) in info if c)
+
+    # one more, instrumented step: every kernel launch bracketed by hipEvents on the library's stream
+    K.kfac_profile_begin(run.ctx)
+    step()
+    stats = K.kfac_profile_end(run.ctx)
+    kernels = {}
+    for name, st in stats.items():
+        bound, peak, unit, which = BOUNDS[name]
+        work = st[which]
+        avg_ms = st["ms"] / max(st["launches"], 1)
+        ach = work / (st["ms"] * 1e-3) if st["ms"] > 0 else 0.0
+        kernels[name] = {"launches": st["launches"], "total_ms": round(st["ms"], 3), "avg_ms": round(avg_ms, 5),
+                         "bound": bound, "achieved": round(ach / (1e9 if unit == "GB/s" else 1e12), 3),
+                         "peak": peak / (1e9 if unit == "GB/s" else 1e12), "unit": unit,
+                         "frac": round(ach / peak, 4)}
+    dom = max(stats, key=lambda k: stats[k]["ms"])
+    roofline = dict(kernels[dom])
+    roofline["kernel"] = dom
+    roofline["traffic"] = None
+    roofline = {k: roofline[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic",
+                                         "launches", "avg_ms", "total_ms")}
+    w = run.work()
+    derived = {
+        "syrk_tflops": round(w["syrk_flops"] / (phases["factors"] * 1e-3) / 1e12, 2),
+        "syrk_frac_of_mfma_peak": round(w["syrk_flops"] / (phases["factors"] * 1e-3) / PEAK_MFMA_F32, 4),
+        "precondition_tflops": round(w["precond_flops"] / (phases["precondition"] * 1e-3) / 1e12, 2),
+        "precondition_frac_of_mfma_peak": round(w["precond_flops"] / (phases["precondition"] * 1e-3) / PEAK_MFMA_F32, 4),
+        "eig_sum_d3_per_s": round(w["sum_d3"] / (phases["eig"] * 1e-3), 1),
+        "eig_sweeps_max": max(sweeps), "eig_converged": "%d/%d" % (nconv, len(info)),
+    }
+    out = {
+        "metric": "kfac_step_ms", "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if not wl.bf16 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d layers, batch %d, %s; factor update + eig of %d factors + precondition"
+                               % (wl.name, len(wl.layers), wl.batch, "bf16 in / fp32 factors" if wl.bf16 else "fp32",
+                                  2 * len(wl.layers))},
+        "phases_ms": {k: round(v, 3) for k, v in phases.items()},
+        "derived": derived,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    run.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -127,6 +127,22 @@ int kfac_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA,
  * when k % f_fac == 0 and the eigendecompositions when k % f_eig == 0; precondition always.  */
 int kfac_schedule_due(int64_t k, int f_fac, int f_eig, int *do_factors, int *do_eig);
 
+/* Optional per-kernel timing, for benchmarks.  Between kfac_profile_begin() and kfac_profile_end()
+ * every kernel launch of this context is bracketed by a pair of hipEvents on the context's stream.
+ * kfac_profile_end() waits for the stream and fills up to `max` records (host memory), one per
+ * kernel class that was launched, with the launch count, the summed duration and the summed
+ * algorithmic work of those launches (flops for contractions and rotations, bytes for data
+ * movement), and stores the number of records in *n.  */
+typedef struct {
+    char name[32];
+    int launches;
+    double ms;       /* total over the launches */
+    double flops;    /* algorithmic floating-point operations, total */
+    double bytes;    /* algorithmic HBM bytes, total */
+} kfac_kernel_stat;
+int kfac_profile_begin(kfac_ctx *ctx);
+int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out /* host */, int max, int *n /* host */);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,6 +13,7 @@
 //
 // Convergence is decided on the host once per sweep from off(F)_F / ||F||_F.
 #include <algorithm>
+#include <cstdlib>
 #include <vector>
 #include "kfac_internal.h"
 #include "mfma_gemm.h"
@@ -23,6 +24,7 @@ constexpr int EB = KFAC_EIG_B;  // block width of the blocked path
 constexpr int SK = 2 * EB;      // pivot sub-problem size (128)
 constexpr int SLD = SK + 1;     // LDS pitch (odd: column walks are bank-conflict free)
 constexpr int NT = 256;
+static_assert(NT == 256 && SK == 128, "the fixed-size Jacobi thread mapping assumes 256 threads and 128 x 128 pivots");
 
 struct SmallItem { const float *F; float *Q; float *lam; int n; int pad_; };
 struct EigStat { float sweeps, off_rel, converged, rotations; };
@@ -60,13 +62,18 @@ struct JacobiResult { int sweeps; float off2, nrm2; int rotations; };
 // pitch ld.  Stops when off(S)^2 <= tol^2 * ||S||^2 or after max_sweeps.  Rotations use the smaller
 // angle, so the accumulated transform stays close to the identity ordering.  Entries whose magnitude
 // is below skip_rel * ||S||_F / k are left alone (and exact zeros always are, which keeps zero-padded
-// rows and columns decoupled).
-__device__ JacobiResult jacobi_lds(float *S, float *V, int k, int ld, int max_sweeps, float tol, float skip_rel,
-                                   float *red, float2 *cs, int *pp, int *qq, int *rotcount) {
+// rows and columns decoupled).  KC > 0 fixes k at compile time (index arithmetic becomes shifts and
+// each thread's column pair is loop invariant); KC == 0 takes k at run time.
+struct RotEntry { int p, q; float c, s; };
+
+template <int KC>
+__device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max_sweeps, float tol, float skip_rel,
+                                   float *red, RotEntry *rot, int *rotflag) {
     const int tid = threadIdx.x;
+    const int k = KC > 0 ? KC : k_rt;
     const int half = k >> 1;
     JacobiResult res{0, 0.f, 0.f, 0};
-    if (tid == 0) *rotcount = 0;
+    if (tid == 0) *rotflag = 0;
     for (int sweep = 0;; ++sweep) {
         float o2 = 0.f, d2 = 0.f;
         for (int e = tid; e < k * k; e += NT) {
@@ -94,60 +101,169 @@ __device__ JacobiResult jacobi_lds(float *S, float *V, int k, int ld, int max_sw
                     const double cd = 1.0 / sqrt(t * t + 1.0);
                     c = (float)cd;
                     s = (float)(t * cd);
-                    atomicAdd(rotcount, 1);
+                    *rotflag = 1;
                 }
-                cs[tid] = make_float2(c, s);
-                pp[tid] = p;
-                qq[tid] = q;
+                rot[tid] = RotEntry{p, q, c, s};
             }
             __syncthreads();
             // S <- J^T S J on 2x2 blocks (rows of pair j1, columns of pair j2)
-            for (int e = tid; e < half * half; e += NT) {
-                const int j1 = e / half, j2 = e - j1 * half;
-                const int p1 = pp[j1], q1 = qq[j1], p2 = pp[j2], q2 = qq[j2];
-                const float2 r1 = cs[j1], r2 = cs[j2];
-                float a = S[p1 * ld + p2], b = S[p1 * ld + q2], c_ = S[q1 * ld + p2], d = S[q1 * ld + q2];
-                // columns: [a b; c d] * [[c2, s2], [-s2, c2]]
-                const float a1 = r2.x * a - r2.y * b, b1 = r2.y * a + r2.x * b;
-                const float c1 = r2.x * c_ - r2.y * d, d1 = r2.y * c_ + r2.x * d;
-                // rows: [[c1, -s1], [s1, c1]] * [...]
-                S[p1 * ld + p2] = r1.x * a1 - r1.y * c1;
-                S[p1 * ld + q2] = r1.x * b1 - r1.y * d1;
-                S[q1 * ld + p2] = r1.y * a1 + r1.x * c1;
-                S[q1 * ld + q2] = r1.y * b1 + r1.x * d1;
-            }
-            // V <- V J
-            for (int e = tid; e < k * half; e += NT) {
-                const int j = e / k, i = e - j * k;
-                const int p = pp[j], q = qq[j];
-                const float2 rc = cs[j];
-                const float vp = V[i * ld + p], vq = V[i * ld + q];
-                V[i * ld + p] = rc.x * vp - rc.y * vq;
-                V[i * ld + q] = rc.y * vp + rc.x * vq;
+            if (KC == 128) {
+                const RotEntry r2 = rot[tid & 63];
+                const float *c0 = S + r2.p, *c1p = S + r2.q;
+                // loads of four blocks are issued together before any store, so they can overlap
+                for (int t0 = 0; t0 < 16; t0 += 4) {
+                    RotEntry r1[4];
+                    float a[4], b[4], c_[4], d[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        r1[u] = rot[(tid >> 6) + 4 * (t0 + u)];   // uniform across the wave
+                        a[u] = c0[r1[u].p * ld]; b[u] = c1p[r1[u].p * ld];
+                        c_[u] = c0[r1[u].q * ld]; d[u] = c1p[r1[u].q * ld];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const float a1 = r2.c * a[u] - r2.s * b[u], b1 = r2.s * a[u] + r2.c * b[u];
+                        const float cc1 = r2.c * c_[u] - r2.s * d[u], d1 = r2.s * c_[u] + r2.c * d[u];
+                        S[r1[u].p * ld + r2.p] = r1[u].c * a1 - r1[u].s * cc1;
+                        S[r1[u].p * ld + r2.q] = r1[u].c * b1 - r1[u].s * d1;
+                        S[r1[u].q * ld + r2.p] = r1[u].s * a1 + r1[u].c * cc1;
+                        S[r1[u].q * ld + r2.q] = r1[u].s * b1 + r1[u].c * d1;
+                    }
+                }
+                float *vrow = V + (tid & 127) * ld;
+                for (int t0 = 0; t0 < 32; t0 += 8) {
+                    RotEntry rc[8];
+                    float vp[8], vq[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        rc[u] = rot[(tid >> 7) + 2 * (t0 + u)];   // uniform across the wave
+                        vp[u] = vrow[rc[u].p]; vq[u] = vrow[rc[u].q];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        vrow[rc[u].p] = rc[u].c * vp[u] - rc[u].s * vq[u];
+                        vrow[rc[u].q] = rc[u].s * vp[u] + rc[u].c * vq[u];
+                    }
+                }
+            } else {
+                for (int e = tid; e < half * half; e += NT) {
+                    const int j1 = e / half, j2 = e - j1 * half;
+                    const RotEntry r1 = rot[j1], r2 = rot[j2];
+                    float a = S[r1.p * ld + r2.p], b = S[r1.p * ld + r2.q], c_ = S[r1.q * ld + r2.p], d = S[r1.q * ld + r2.q];
+                    // columns: [a b; c d] * [[c2, s2], [-s2, c2]]
+                    const float a1 = r2.c * a - r2.s * b, b1 = r2.s * a + r2.c * b;
+                    const float cc1 = r2.c * c_ - r2.s * d, d1 = r2.s * c_ + r2.c * d;
+                    // rows: [[c1, -s1], [s1, c1]] * [...]
+                    S[r1.p * ld + r2.p] = r1.c * a1 - r1.s * cc1;
+                    S[r1.p * ld + r2.q] = r1.c * b1 - r1.s * d1;
+                    S[r1.q * ld + r2.p] = r1.s * a1 + r1.c * cc1;
+                    S[r1.q * ld + r2.q] = r1.s * b1 + r1.c * d1;
+                }
+                // V <- V J
+                for (int e = tid; e < k * half; e += NT) {
+                    const int j = e / k, i = e - j * k;
+                    const RotEntry rc = rot[j];
+                    const float vp = V[i * ld + rc.p], vq = V[i * ld + rc.q];
+                    V[i * ld + rc.p] = rc.c * vp - rc.s * vq;
+                    V[i * ld + rc.q] = rc.s * vp + rc.c * vq;
+                }
             }
             __syncthreads();
         }
     }
-    res.rotations = *rotcount;
+    res.rotations = *rotflag;
     return res;
 }
 
 // Dynamic LDS layout shared by the small solver and the pivot solver.
 struct JacobiSmem {
     float *S, *V, *red;
-    float2 *cs;
-    int *pp, *qq, *rot;
+    RotEntry *rot;
+    int *rotflag, *rank;
+    float *diag;
     __device__ JacobiSmem(char *base, int k, int ld) {
         S = (float *)base;
         V = S + k * ld;
         red = V + k * ld;
-        cs = (float2 *)(red + 8);
-        pp = (int *)(cs + SK / 2);
-        qq = pp + SK / 2;
-        rot = qq + SK / 2;
+        rot = (RotEntry *)(red + 8);
+        rotflag = (int *)(rot + SK / 2);
+        rank = rotflag + 4;
+        diag = (float *)(rank + SK);
     }
-    static size_t bytes(int k, int ld) { return ((size_t)2 * k * ld + 8 + 4 * (SK / 2) + 4) * sizeof(float); }
+    static size_t bytes(int k, int ld) { return ((size_t)2 * k * ld + 8 + 4 * (SK / 2) + 4 + 2 * SK) * sizeof(float); }
 };
+
+// 128x128x128 product on LDS-resident operands: acc = A * B with A(m,k) = Am[m*am + k*ak],
+// B(k,n) = Bm[k*SLD + n].
+__device__ inline void lds_gemm128(const float *Am, int am, int ak, const float *Bm, floatx16 (&acc)[2][2]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lk = lane >> 5, lc = lane & 31;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll 4
+    for (int kk = 0; kk < SK; kk += 2) {
+        const float a0 = Am[(wm + lc) * am + (kk + lk) * ak];
+        const float a1 = Am[(wm + 32 + lc) * am + (kk + lk) * ak];
+        const float b0 = Bm[(kk + lk) * SLD + wn + lc];
+        const float b1 = Bm[(kk + lk) * SLD + wn + 32 + lc];
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+}
+
+__device__ inline void acc_to_lds(const floatx16 (&acc)[2][2], float *X) {
+    kfac::for_each_acc(acc, [&](int r, int c, float v) { X[r * SLD + c] = v; });
+}
+
+// The same Newton-Schulz step for the 128 x 128 pivot transform, as two MFMA products in LDS.
+__device__ void polish_lds_mfma(float *V, float *Y) {
+    floatx16 acc[2][2];
+    lds_gemm128(V, 1, SLD, V, acc);  // V^T V
+    kfac::for_each_acc(acc, [&](int r, int c, float v) { Y[r * SLD + c] = (r == c ? 1.5f : 0.f) - 0.5f * v; });
+    __syncthreads();
+    lds_gemm128(V, SLD, 1, Y, acc);  // V Y
+    __syncthreads();
+    acc_to_lds(acc, V);
+    __syncthreads();
+}
+
+// One Newton-Schulz step V <- V (3I - V^T V)/2 on the k x k matrix V in LDS (Y is k x k scratch, same
+// pitch): hundreds of fp32 rotations leave V orthogonal only to ~1e-6; this restores ~1e-7.
+__device__ void polish_lds_valu(float *V, float *Y, int k, int ld) {
+    const int tid = threadIdx.x;
+    for (int e = tid; e < k * k; e += NT) {
+        const int i = e / k, j = e - i * k;
+        float s = 0.f;
+        for (int r = 0; r < k; ++r) s = fmaf(V[r * ld + i], V[r * ld + j], s);
+        Y[i * ld + j] = (i == j ? 1.5f : 0.f) - 0.5f * s;
+    }
+    __syncthreads();
+    float out[SK * SK / NT];
+#pragma unroll
+    for (int t = 0; t < SK * SK / NT; ++t) {
+        const int e = tid + t * NT;
+        float s = 0.f;
+        if (e < k * k) {
+            const int i = e / k, j = e - i * k;
+            for (int r = 0; r < k; ++r) s = fmaf(V[i * ld + r], Y[r * ld + j], s);
+        }
+        out[t] = s;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < SK * SK / NT; ++t) {
+        const int e = tid + t * NT;
+        if (e < k * k) V[(e / k) * ld + (e % k)] = out[t];
+    }
+    __syncthreads();
+}
 
 // ------------------------------------------------------------------------------------------------
 // d <= 128: whole factor in LDS
@@ -167,22 +283,25 @@ __global__ __launch_bounds__(NT) void eig_small_kernel(const SmallItem *items, E
         sm.V[i * ld + j] = (i == j) ? 1.f : 0.f;
     }
     __syncthreads();
-    const JacobiResult res = jacobi_lds(sm.S, sm.V, k, ld, max_sweeps, tol, 1e-9f, sm.red, sm.cs, sm.pp, sm.qq, sm.rot);
+    const JacobiResult res = jacobi_lds<0>(sm.S, sm.V, k, ld, max_sweeps, tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
+    for (int i = tid; i < k; i += NT) sm.diag[i] = sm.S[i * ld + i];
+    __syncthreads();
+    if (res.rotations > 0) polish_lds_valu(sm.V, sm.S, k, ld);
     // rank of every eigenvalue (ascending, ties by index) -> pp[]
     for (int i = tid; i < n; i += NT) {
-        const float li = sm.S[i * ld + i];
+        const float li = sm.diag[i];
         int rank = 0;
         for (int j = 0; j < n; ++j) {
-            const float lj = sm.S[j * ld + j];
+            const float lj = sm.diag[j];
             rank += (lj < li) || (lj == li && j < i);
         }
-        sm.pp[i] = rank;
+        sm.rank[i] = rank;
         it.lam[rank] = li;
     }
     __syncthreads();
     for (int e = tid; e < n * n; e += NT) {
         const int i = e / n, j = e - i * n;
-        it.Q[(int64_t)i * n + sm.pp[j]] = sm.V[i * ld + j];
+        it.Q[(int64_t)i * n + sm.rank[j]] = sm.V[i * ld + j];
     }
     if (tid == 0) {
         EigStat st;
@@ -267,7 +386,8 @@ __global__ __launch_bounds__(NT) void blk_solve_kernel(BlkGroup g, int round, in
         sm.V[a * SLD + b] = (a == b) ? 1.f : 0.f;
     }
     __syncthreads();
-    const JacobiResult res = jacobi_lds(sm.S, sm.V, SK, SLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.cs, sm.pp, sm.qq, sm.rot);
+    const JacobiResult res = jacobi_lds<SK>(sm.S, sm.V, SK, SLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
+    if (res.rotations > 0) polish_lds_mfma(sm.V, sm.S);
     float *J = g.J + ((int64_t)m * g.npairs + pj) * (SK * SK);
     for (int e = tid; e < SK * SK; e += NT) {
         const int a = e / SK, b = e - a * SK;
@@ -282,35 +402,6 @@ __device__ inline void tri_decode(int idx, int &ti, int &tj) {
     while (t * (t + 1) / 2 > idx) --t;
     ti = t;
     tj = idx - t * (t + 1) / 2;
-}
-
-// 128x128x128 product on LDS-resident operands: acc = A * B with A(m,k) = Am[m*am + k*ak],
-// B(k,n) = Bm[k*SLD + n].
-__device__ inline void lds_gemm128(const float *Am, int am, int ak, const float *Bm, floatx16 (&acc)[2][2]) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-    const int lk = lane >> 5, lc = lane & 31;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-#pragma unroll 4
-    for (int kk = 0; kk < SK; kk += 2) {
-        const float a0 = Am[(wm + lc) * am + (kk + lk) * ak];
-        const float a1 = Am[(wm + 32 + lc) * am + (kk + lk) * ak];
-        const float b0 = Bm[(kk + lk) * SLD + wn + lc];
-        const float b1 = Bm[(kk + lk) * SLD + wn + 32 + lc];
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
-    }
-}
-
-__device__ inline void acc_to_lds(const floatx16 (&acc)[2][2], float *X) {
-    kfac::for_each_acc(acc, [&](int r, int c, float v) { X[r * SLD + c] = v; });
 }
 
 __device__ inline void load_J(float *Js, const float *J) {
@@ -391,33 +482,53 @@ __global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, in
     }
 }
 
-// perm[rank] = index of the rank-th smallest diagonal entry (ties by index); lam[rank] = that entry.
-__global__ __launch_bounds__(NT) void blk_rank_kernel(BlkGroup g, const BlkItem *items, int *perm) {
-    const int m = blockIdx.y;
-    const BlkItem it = items[m];
-    const float *W = g.W + (int64_t)m * g.npad * g.npad;
-    const int i = blockIdx.x * NT + threadIdx.x;
-    if (i >= it.n) return;
-    const float li = W[(int64_t)i * g.npad + i];
-    int rank = 0;
-    for (int j = 0; j < it.n; ++j) {
-        const float lj = W[(int64_t)j * g.npad + j];
-        rank += (lj < li) || (lj == li && j < i);
-    }
-    perm[m * g.npad + rank] = i;
-    it.lam[rank] = li;
+// ---- post-processing of a converged factor -------------------------------------------------------
+// Y = (3I - Q^T Q)/2 : epilogue of the Newton-Schulz orthogonalisation step Q <- Q Y.
+struct EpiNewtonSchulz {
+    float *Y;
+    int64_t ld;
+    __device__ void operator()(int r, int c, float v) const { Y[(int64_t)r * ld + c] = (r == c ? 1.5f : 0.f) - 0.5f * v; }
+};
+
+__global__ void blk_zero_f64_kernel(double *p, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0.0;
 }
 
-__global__ __launch_bounds__(NT) void blk_gather_kernel(BlkGroup g, const BlkItem *items, const int *perm) {
-    const int m = blockIdx.y;
-    const BlkItem it = items[m];
-    const float *Qw = g.Qw + (int64_t)m * g.npad * g.npad;
-    const int64_t n2 = (int64_t)it.n * it.n;
+// Rayleigh quotients lam[i] = q_i^T (F q_i) from Q [n][ldq] and Z = F Q [n][ldz]; rows split over blockIdx.y.
+__global__ __launch_bounds__(NT) void blk_rayleigh_kernel(const float *Q, int64_t ldq, const float *Z, int64_t ldz,
+                                                          int n, double *lam64) {
+    const int i = blockIdx.x * NT + threadIdx.x;
+    if (i >= n) return;
+    const int rows_per = (n + gridDim.y - 1) / gridDim.y;
+    const int r0 = blockIdx.y * rows_per, r1 = min(n, r0 + rows_per);
+    double s = 0.0;
+    for (int r = r0; r < r1; ++r) s += (double)Q[(int64_t)r * ldq + i] * (double)Z[(int64_t)r * ldz + i];
+    atomicAdd(&lam64[i], s);
+}
+
+// perm[rank] = index of the rank-th smallest eigenvalue (ties by index); lam[rank] = that eigenvalue.
+__global__ __launch_bounds__(NT) void blk_rank_kernel(const double *lam64, int n, int *perm, float *lam_out) {
+    const int i = blockIdx.x * NT + threadIdx.x;
+    if (i >= n) return;
+    const float li = (float)lam64[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+        const float lj = (float)lam64[j];
+        rank += (lj < li) || (lj == li && j < i);
+    }
+    perm[rank] = i;
+    lam_out[rank] = li;
+}
+
+// Qout[i][j] = Qin[i][perm[j]]
+__global__ __launch_bounds__(NT) void blk_gather_kernel(const float *Qin, int64_t ldin, float *Qout, int n, const int *perm) {
+    const int64_t n2 = (int64_t)n * n;
     for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < n2; e += (int64_t)gridDim.x * NT) {
-        const int i = (int)(e / it.n), j = (int)(e - (int64_t)i * it.n);
-        int c = perm[m * g.npad + j];
-        c = c < 0 ? 0 : (c >= it.n ? it.n - 1 : c);  // ranks collide only when the input holds NaNs
-        it.Q[e] = Qw[(int64_t)i * g.npad + c];
+        const int i = (int)(e / n), j = (int)(e - (int64_t)i * n);
+        int c = perm[j];
+        c = c < 0 ? 0 : (c >= n ? n - 1 : c);  // ranks collide only when the input holds NaNs
+        Qout[e] = Qin[(int64_t)i * ldin + c];
     }
 }
 
@@ -433,6 +544,7 @@ struct GroupPlan {
         b += kfac_align_up(nm * (size_t)npairs * sizeof(int), 256);                  // idt
         b += kfac_align_up(nm * 2 * sizeof(double), 256);                            // norms
         b += kfac_align_up(nm * (size_t)npad * sizeof(int), 256);                    // perm
+        b += kfac_align_up(nm * (size_t)npad * sizeof(double), 256);                 // Rayleigh quotients
         b += kfac_align_up(nm * sizeof(BlkItem), 256);                               // items
         return b;
     }
@@ -483,6 +595,10 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     if (kfac_eig_ws_bytes_impl(batch, d) > ctx->ws_bytes) return KFAC_EWORKSPACE;
     bool all_conv = true;
     hipStream_t st = ctx->stream;
+    int inner_cap = 1;
+    float inner_tol = 1e-7f;
+    if (const char *e = getenv("KFAC_DEBUG_INNER_SWEEPS")) inner_cap = atoi(e);
+    if (const char *e = getenv("KFAC_DEBUG_INNER_TOL")) inner_tol = (float)atof(e);
 
     if (!small.empty()) {
         const size_t ns = small.size();
@@ -498,7 +614,10 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         const size_t lds = JacobiSmem::bytes(kmax, kmax + 1);
         if ((int)lds > ctx->max_lds) return KFAC_EHIP;
         KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)eig_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(eig_small_kernel, dim3((unsigned)ns), dim3(NT), lds, st, d_items, d_stats, max_sweeps, tol);
+        {
+            KfacProfScope prof(ctx, KC_EIG_SMALL, 0.0, 0.0);
+            hipLaunchKernelGGL(eig_small_kernel, dim3((unsigned)ns), dim3(NT), lds, st, d_items, d_stats, max_sweeps, tol);
+        }
         KFAC_HIP_CHECK(hipGetLastError());
         std::vector<EigStat> stats(ns);
         KFAC_HIP_CHECK(hipMemcpyAsync(stats.data(), d_stats, ns * sizeof(EigStat), hipMemcpyDeviceToHost, st));
@@ -506,6 +625,8 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         for (size_t i = 0; i < ns; ++i) {
             const bool conv = stats[i].converged > 0.5f;
             all_conv &= conv;
+            const double k = (d[small[i]] + 1) & ~1;   // 9 flops per element per round: S twice, V once
+            if (ctx->prof_on && !ctx->prof.empty()) ctx->prof.back().flops += stats[i].sweeps * 9.0 * k * k * (k - 1);
             if (info) info[small[i]] = kfac_eig_info{(int)stats[i].sweeps, stats[i].off_rel, conv ? 1 : 0};
         }
     }
@@ -523,6 +644,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         g.idt = (int *)p; p += kfac_align_up((size_t)nm * gp.npairs * sizeof(int), 256);
         g.norms = (double *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(double), 256);
         int *perm = (int *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(int), 256);
+        double *lam64 = (double *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(double), 256);
         BlkItem *d_items = (BlkItem *)p;
         std::vector<BlkItem> items(nm);
         for (int i = 0; i < nm; ++i) {
@@ -531,7 +653,10 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         }
         KFAC_HIP_CHECK(hipMemcpyAsync(d_items, items.data(), nm * sizeof(BlkItem), hipMemcpyHostToDevice, st));
         const int fill_blocks = (int)std::min<size_t>((np2 + NT - 1) / NT, 4096);
-        hipLaunchKernelGGL(blk_init_kernel, dim3(fill_blocks, nm), dim3(NT), 0, st, g, d_items);
+        {
+            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0);
+            hipLaunchKernelGGL(blk_init_kernel, dim3(fill_blocks, nm), dim3(NT), 0, st, g, d_items);
+        }
         KFAC_HIP_CHECK(hipGetLastError());
 
         const size_t lds_solve = JacobiSmem::bytes(SK, SLD);
@@ -544,6 +669,10 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         for (int i = 0; i < nm; ++i) nmax = std::max(nmax, items[i].n);
         const int nrb = (nmax + SK - 1) / SK;
         const int ntiles = ntiles_w + nrb * gp.npairs;
+        // algorithmic work of one round: W <- J^T W J on half the (symmetric) matrix and Q <- Q J, each
+        // element a length-2B dot product: 8 n^2 B flops per factor
+        double apply_flops = 0.0;
+        for (int i = 0; i < nm; ++i) apply_flops += 8.0 * (double)items[i].n * items[i].n * EB;
 
         std::vector<double> norms(2 * nm);
         std::vector<int> sweeps_done(nm, 0);
@@ -551,8 +680,11 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         std::vector<float> offrel(nm, 0.f);
         int sweep = 0;
         for (;; ++sweep) {
-            hipLaunchKernelGGL(blk_zero_norms_kernel, dim3(1), dim3(256), 0, st, g.norms, 2 * nm);
-            hipLaunchKernelGGL(blk_offnorm_kernel, dim3(std::min(fill_blocks, 512), nm), dim3(NT), 0, st, g);
+            {
+                KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0);
+                hipLaunchKernelGGL(blk_zero_norms_kernel, dim3(1), dim3(256), 0, st, g.norms, 2 * nm);
+                hipLaunchKernelGGL(blk_offnorm_kernel, dim3(std::min(fill_blocks, 512), nm), dim3(NT), 0, st, g);
+            }
             KFAC_HIP_CHECK(hipGetLastError());
             KFAC_HIP_CHECK(hipMemcpyAsync(norms.data(), g.norms, 2 * nm * sizeof(double), hipMemcpyDeviceToHost, st));
             KFAC_HIP_CHECK(hipStreamSynchronize(st));
@@ -567,13 +699,55 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             }
             if (all || sweep >= max_sweeps) break;
             for (int r = 0; r < gp.players - 1; ++r) {
-                hipLaunchKernelGGL(blk_solve_kernel, dim3(gp.npairs, nm), dim3(NT), lds_solve, st, g, r, 6, 1e-7f);
-                hipLaunchKernelGGL(blk_apply_kernel, dim3(ntiles, nm), dim3(NT), lds_apply, st, g, r, ntiles_w, nrb);
+                {
+                    KfacProfScope prof(ctx, KC_EIG_SOLVE, 0.0, 0.0);
+                    hipLaunchKernelGGL(blk_solve_kernel, dim3(gp.npairs, nm), dim3(NT), lds_solve, st, g, r, inner_cap, inner_tol);
+                }
+                {
+                    KfacProfScope prof(ctx, KC_EIG_APPLY, apply_flops, 0.0);
+                    hipLaunchKernelGGL(blk_apply_kernel, dim3(ntiles, nm), dim3(NT), lds_apply, st, g, r, ntiles_w, nrb);
+                }
             }
             KFAC_HIP_CHECK(hipGetLastError());
         }
-        hipLaunchKernelGGL(blk_rank_kernel, dim3((nmax + NT - 1) / NT, nm), dim3(NT), 0, st, g, d_items, perm);
-        hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(fill_blocks, 2048), nm), dim3(NT), 0, st, g, d_items, perm);
+        // Post-processing per factor: one Newton-Schulz step restores the orthogonality that thousands of
+        // fp32 transforms have eroded, Rayleigh quotients against the caller's F give the eigenvalues,
+        // and the columns are put in ascending order.  W is dead by now and serves as scratch.
+        hipLaunchKernelGGL(blk_zero_f64_kernel, dim3((nm * gp.npad + 255) / 256), dim3(256), 0, st, lam64, nm * gp.npad);
+        for (int i = 0; i < nm; ++i) {
+            using namespace kfac;
+            const int n = items[i].n;
+            float *Wm = g.W + i * np2, *Qm = g.Qw + i * np2;
+            const int64_t ld = gp.npad;
+            const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
+            OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};          // elem(i,k) = Q[k][i]
+            {
+                KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0);
+                hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz>), grid, block, 0, st,
+                                   q_kn, q_kn, EpiNewtonSchulz{Wm, ld}, n, n, n);
+            }
+            OpStrided<float, true> q_mk{Qm, ld, 1, n, n, -1};           // elem(i,k) = Q[i][k]
+            OpStrided<float, false> y_kn{Wm, 1, ld, n, n, -1};
+            {
+                KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0);
+                hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_mk), decltype(y_kn), EpiStore>), grid, block, 0, st,
+                                   q_mk, y_kn, EpiStore{items[i].Q, n}, n, n, n);
+            }
+            OpStrided<float, true> f_mk{items[i].F, n, 1, n, n, -1};
+            OpStrided<float, false> qo_kn{items[i].Q, 1, n, n, n, -1};
+            {
+                KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0);
+                hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(qo_kn), EpiStore>), grid, block, 0, st,
+                                   f_mk, qo_kn, EpiStore{Qm, ld}, n, n, n);
+            }
+            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0);
+            double *l64 = lam64 + (size_t)i * gp.npad;
+            int *pm = perm + (size_t)i * gp.npad;
+            hipLaunchKernelGGL(blk_rayleigh_kernel, dim3((n + NT - 1) / NT, 32), dim3(NT), 0, st, items[i].Q, (int64_t)n, Qm, ld, n, l64);
+            hipLaunchKernelGGL(blk_rank_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, l64, n, pm, items[i].lam);
+            KFAC_HIP_CHECK(hipMemcpyAsync(Wm, items[i].Q, (size_t)n * n * sizeof(float), hipMemcpyDeviceToDevice, st));
+            hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(fill_blocks, 2048)), dim3(NT), 0, st, Wm, (int64_t)n, items[i].Q, n, pm);
+        }
         KFAC_HIP_CHECK(hipGetLastError());
         KFAC_HIP_CHECK(hipStreamSynchronize(st));  // the workspace is reused by the next group
         for (int i = 0; i < nm; ++i) {

@@ -1,6 +1,7 @@
 // C-ABI entry points: argument validation, workspace accounting, dispatch to the kernel launchers.
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <new>
 #include <string_view>
 #include <vector>
@@ -55,6 +56,7 @@ int kfac_create(kfac_ctx **out, int device, void *hip_stream, void *workspace_de
     c->ws = (char *)workspace_dev;
     c->ws_bytes = workspace_bytes;
     c->host_flags = nullptr;
+    c->prof_on = false;
     int lds = 0;
     if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) lds = 65536;
     c->max_lds = lds;
@@ -64,6 +66,8 @@ int kfac_create(kfac_ctx **out, int device, void *hip_stream, void *workspace_de
 
 int kfac_destroy(kfac_ctx *ctx) {
     if (!ctx) return KFAC_EINVAL;
+    for (auto &r : ctx->prof) { (void)hipEventDestroy(r.t0); (void)hipEventDestroy(r.t1); }
+    for (auto e : ctx->ev_pool) (void)hipEventDestroy(e);
     delete ctx;
     return KFAC_OK;
 }
@@ -128,6 +132,43 @@ int kfac_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA,
     if (dA < 1 || dG < 1 || dA > KFAC_MAX_D || dG > KFAC_MAX_D) return KFAC_EINVAL;
     if (!(damping > 0.f) || !std::isfinite(damping) || !valid_dtype(grad_dtype)) return KFAC_EINVAL;
     return kfac_launch_precondition(ctx, QA, lamA, dA, QG, lamG, dG, damping, grad, grad_dtype);
+}
+
+int kfac_profile_begin(kfac_ctx *ctx) {
+    if (!ctx) return KFAC_EINVAL;
+    for (auto &r : ctx->prof) { ctx->ev_pool.push_back(r.t0); ctx->ev_pool.push_back(r.t1); }
+    ctx->prof.clear();
+    ctx->prof_on = true;
+    return KFAC_OK;
+}
+
+int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out, int max, int *n) {
+    if (!ctx || !out || !n || max < 0) return KFAC_EINVAL;
+    static const char *names[KC_COUNT] = {"unfold", "syrk", "syrk_reduce", "precond_gemm", "eig_small",
+                                          "eig_pivot_solve", "eig_apply", "eig_misc", "eig_post_gemm"};
+    ctx->prof_on = false;
+    KFAC_HIP_CHECK(hipStreamSynchronize(ctx->stream));
+    kfac_kernel_stat acc[KC_COUNT] = {};
+    for (auto &r : ctx->prof) {
+        float ms = 0.f;
+        KFAC_HIP_CHECK(hipEventElapsedTime(&ms, r.t0, r.t1));
+        acc[r.cls].launches += 1;
+        acc[r.cls].ms += ms;
+        acc[r.cls].flops += r.flops;
+        acc[r.cls].bytes += r.bytes;
+        ctx->ev_pool.push_back(r.t0);
+        ctx->ev_pool.push_back(r.t1);
+    }
+    ctx->prof.clear();
+    int k = 0;
+    for (int c = 0; c < KC_COUNT && k < max; ++c) {
+        if (!acc[c].launches) continue;
+        out[k] = acc[c];
+        snprintf(out[k].name, sizeof(out[k].name), "%s", names[c]);
+        ++k;
+    }
+    *n = k;
+    return KFAC_OK;
 }
 
 int kfac_schedule_due(int64_t k, int f_fac, int f_eig, int *do_factors, int *do_eig) {

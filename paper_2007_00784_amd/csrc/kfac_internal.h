@@ -3,7 +3,15 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <vector>
 #include "../../include/kfac.h"
+
+// Kernel classes for the optional per-kernel timing (kfac_profile_begin / kfac_profile_end).
+enum KfacKernelClass {
+    KC_UNFOLD = 0, KC_SYRK, KC_SYRK_REDUCE, KC_PRECOND_GEMM, KC_EIG_SMALL, KC_EIG_SOLVE, KC_EIG_APPLY,
+    KC_EIG_MISC, KC_EIG_POST, KC_COUNT
+};
+struct KfacProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
 
 struct kfac_ctx {
     int device;
@@ -12,6 +20,31 @@ struct kfac_ctx {
     size_t ws_bytes;
     double *host_flags;  // pinned host scratch for the eigensolver's convergence read-back
     int max_lds;         // bytes of LDS one workgroup may use on this device
+    bool prof_on;        // bracket every kernel launch with events
+    std::vector<KfacProfRec> prof;
+    std::vector<hipEvent_t> ev_pool;
+};
+
+// Brackets one kernel launch with a pair of events when profiling is on; `flops` and `bytes` are the
+// algorithmic work of that launch.
+struct KfacProfScope {
+    kfac_ctx *c;
+    KfacProfRec r;
+    KfacProfScope(kfac_ctx *ctx, int cls, double flops, double bytes) : c(ctx) {
+        if (!c->prof_on) return;
+        r.cls = cls; r.flops = flops; r.bytes = bytes;
+        r.t0 = get(); r.t1 = get();
+        (void)hipEventRecord(r.t0, c->stream);
+    }
+    ~KfacProfScope() {
+        if (!c->prof_on) return;
+        (void)hipEventRecord(r.t1, c->stream);
+        c->prof.push_back(r);
+    }
+    hipEvent_t get() {
+        if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
+        hipEvent_t e; (void)hipEventCreate(&e); return e;
+    }
 };
 
 #define KFAC_HIP_CHECK(expr)                      \

@@ -176,4 +176,24 @@ __device__ inline void for_each_acc(const floatx16 (&acc)[2][2], F f) {
                 f(wm + 32 * i + 8 * (r >> 2) + 4 * lk + (r & 3), wn + 32 * j + lc, acc[i][j][r]);
 }
 
+// C = A * B over a rectangular grid of tiles (blockIdx.y: row tile, blockIdx.x: column tile); the
+// epilogue object is called as epi(row, col, value) for every in-range element.
+template <class OpA, class OpB, class Epi>
+__global__ __launch_bounds__(NTHREADS) void gemm_generic_kernel(OpA a, OpB b, Epi epi, int M, int N, int K) {
+    __shared__ TileSmem sm;
+    const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
+    floatx16 acc[2][2];
+    gemm_tile(a, b, i0, j0, 0, K, sm, acc);
+    for_each_acc(acc, [&](int r, int c, float v) {
+        const int gr = i0 + r, gc = j0 + c;
+        if (gr < M && gc < N) epi(gr, gc, v);
+    });
+}
+
+struct EpiStore {
+    float *C;
+    int64_t ld;
+    __device__ void operator()(int r, int c, float v) const { C[(int64_t)r * ld + c] = v; }
+};
+
 }  // namespace kfac

@@ -51,6 +51,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(OpA a, OpB b, GemmOut o,
 template <class OpA, class OpB, int EPI>
 int launch(kfac_ctx *ctx, OpA a, OpB b, GemmOut o, int K) {
     const dim3 grid((o.N + BM - 1) / BM, (o.M + BM - 1) / BM);
+    KfacProfScope prof(ctx, KC_PRECOND_GEMM, 2.0 * o.M * o.N * K, 4.0 * ((double)o.M * K + (double)K * o.N + (double)o.M * o.N));
     hipLaunchKernelGGL((gemm_kernel<OpA, OpB, EPI>), grid, dim3(NTHREADS), 0, ctx->stream, a, b, o, K);
     KFAC_HIP_CHECK(hipGetLastError());
     return KFAC_OK;

@@ -120,6 +120,11 @@ int kfac_launch_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layo
     if (g.nsplit > 1 && (size_t)g.nsplit * ntri * BM * BM * sizeof(float) > ctx->ws_bytes) return KFAC_EWORKSPACE;
     const dim3 grid(ntri, g.nsplit), block(NTHREADS);
     const int ones_i = append_ones ? d : -1;
+    const double esz = dtype == KFAC_F32 ? 4.0 : 2.0;
+    {
+    // useful flops of the symmetric update R*D*(D+1); bytes: the samples once, F read (if averaged) and written
+    KfacProfScope prof(ctx, KC_SYRK, (double)R * D * (D + 1.0),
+                       esz * (double)R * d + (g.nsplit == 1 ? (decay != 0.f ? 8.0 : 4.0) * D * D : 0.0));
     if (layout == KFAC_LAYOUT_NDT && T > 1) {
         if (dtype == KFAC_F32) {
             OpNDT<float> op{(const float *)X, d, T, 0, ones_i};
@@ -138,8 +143,10 @@ int kfac_launch_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layo
             hipLaunchKernelGGL((syrk_kernel<OpStrided<unsigned short, false>>), grid, block, 0, ctx->stream, op, g);
         }
     }
+    }
     KFAC_HIP_CHECK(hipGetLastError());
     if (g.nsplit > 1) {
+        KfacProfScope prof(ctx, KC_SYRK_REDUCE, 0.0, (decay != 0.f ? 8.0 : 4.0) * D * D);
         hipLaunchKernelGGL(syrk_reduce_kernel, dim3(ntri, 4), dim3(256), 0, ctx->stream, g);
         KFAC_HIP_CHECK(hipGetLastError());
     }

@@ -103,6 +103,9 @@ int kfac_launch_unfold(kfac_ctx *ctx, const kfac_conv_desc *d, const void *x, vo
     a.inv_Tc = 0.f;
     const dim3 grid((a.Ho + a.rows_out - 1) / a.rows_out, (d->C + a.cpb - 1) / a.cpb, d->N);
     if (grid.y > 65535 || grid.z > 65535) return KFAC_EINVAL;
+    const double esz = d->dtype == KFAC_F32 ? 4.0 : 2.0;
+    KfacProfScope prof(ctx, KC_UNFOLD, 0.0,
+                       esz * ((double)d->N * d->C * d->H * d->W + (double)d->N * d->C * d->kh * d->kw * a.Ho * a.Wo));
     if (d->dtype == KFAC_F32)
         hipLaunchKernelGGL(unfold_kernel<float>, grid, dim3(256), 0, ctx->stream, (const float *)x, (float *)patches, a);
     else

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libkfac_hip.so")
 EXPORTS = (
     "kfac_create", "kfac_destroy", "kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
     "kfac_unfold", "kfac_update_factors", "kfac_eig", "kfac_precondition", "kfac_schedule_due",
+    "kfac_profile_begin", "kfac_profile_end",
 )
 
 
@@ -32,6 +33,11 @@ class kfac_eig_opts(ctypes.Structure):
 
 class kfac_eig_info(ctypes.Structure):
     _fields_ = [("sweeps", ctypes.c_int), ("off_norm_rel", ctypes.c_float), ("converged", ctypes.c_int)]
+
+
+class kfac_kernel_stat(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 32), ("launches", ctypes.c_int), ("ms", ctypes.c_double),
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
 class KfacError(RuntimeError):
@@ -66,6 +72,8 @@ def lib():
                            ctypes.POINTER(kfac_eig_opts), ctypes.POINTER(kfac_eig_info)]
     L.kfac_precondition.argtypes = [vp, vp, vp, i, vp, vp, i, f, vp, i]
     L.kfac_schedule_due.argtypes = [i64, i, i, ip, ip]
+    L.kfac_profile_begin.argtypes = [vp]
+    L.kfac_profile_end.argtypes = [vp, ctypes.POINTER(kfac_kernel_stat), i, ip]
     for name in EXPORTS:
         if name not in ("kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror"):
             getattr(L, name).restype = i
@@ -169,3 +177,16 @@ def kfac_schedule_due(k, f_fac, f_eig):
     _check(lib().kfac_schedule_due(int(k), int(f_fac), int(f_eig), ctypes.byref(a), ctypes.byref(b)),
            "kfac_schedule_due")
     return bool(a.value), bool(b.value)
+
+
+def kfac_profile_begin(ctx):
+    _check(lib().kfac_profile_begin(ctx), "kfac_profile_begin")
+
+
+def kfac_profile_end(ctx):
+    """Returns {kernel class: dict(launches, ms, flops, bytes)} for the launches since kfac_profile_begin."""
+    out = (kfac_kernel_stat * 16)()
+    n = ctypes.c_int(0)
+    _check(lib().kfac_profile_end(ctx, out, 16, ctypes.byref(n)), "kfac_profile_end")
+    return {out[i].name.decode(): dict(launches=out[i].launches, ms=out[i].ms, flops=out[i].flops, bytes=out[i].bytes)
+            for i in range(n.value)}

@@ -1,0 +1,107 @@
+"""Drives a whole synthetic workload (a layer set) through the C-ABI library.
+
+Holds device buffers and call order only: every arithmetic step is a library call.  Used by the
+benchmark and by the full-size parity tests.
+"""
+import numpy as np
+import torch
+
+from . import kfac as K
+from . import synthetic as S
+
+
+class KfacRunner:
+    def __init__(self, wl, device="cuda:0", n_updates=2, batch=None, layers=None, verbose=False):
+        self.wl = wl
+        self.dev = torch.device(device)
+        self.N = wl.batch if batch is None else batch
+        self.layer_ids = list(range(len(wl.layers))) if layers is None else list(layers)
+        self.layers = [wl.layers[i] for i in self.layer_ids]
+        self.n_updates = n_updates
+        self.dt = torch.bfloat16 if wl.bf16 else torch.float32
+        self.x, self.g = [], []          # [update][layer] device tensors
+        self.gradw_master = []
+        for u in range(n_updates):
+            xs, gs = [], []
+            for li in self.layer_ids:
+                t = S.layer_inputs(wl, li, update=u, batch=self.N, want=("x", "g"))
+                xs.append(self._up(t["x"]))
+                gs.append(self._up(t["g"]))
+                if verbose:
+                    print("generated update %d layer %d" % (u, li), flush=True)
+            self.x.append(xs)
+            self.g.append(gs)
+        for li in self.layer_ids:
+            self.gradw_master.append(self._up(S.layer_inputs(wl, li, batch=self.N, want=("gradw",))["gradw"]))
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.A = [torch.zeros((l.d_a, l.d_a), **f32) for l in self.layers]
+        self.G = [torch.zeros((l.d_g, l.d_g), **f32) for l in self.layers]
+        self.QA = [torch.zeros_like(a) for a in self.A]
+        self.QG = [torch.zeros_like(g) for g in self.G]
+        self.lamA = [torch.zeros(l.d_a, **f32) for l in self.layers]
+        self.lamG = [torch.zeros(l.d_g, **f32) for l in self.layers]
+        self.grad = [torch.zeros_like(m) for m in self.gradw_master]
+        pmax = max([(l.d_a - 1) * l.T * self.N for l in self.layers if l.needs_unfold] + [1])
+        self.patches = torch.empty(pmax, dtype=self.dt, device=self.dev)
+        dims = [l.d_a for l in self.layers] + [l.d_g for l in self.layers]
+        need = K.kfac_eig_workspace_bytes(dims)
+        need = max(need, 2 * max(l.d_a * l.d_g for l in self.layers) * 4 + 1024)
+        need = max(need, (512 + 800) * 128 * 128 * 4)      # SYRK split partials (upper bound for d <= 4609)
+        self.ws = torch.empty(need + 4096, dtype=torch.uint8, device=self.dev)
+        self.stream = torch.cuda.current_stream(self.dev)
+        self.ctx = K.kfac_create(self.dev.index or 0, self.stream.cuda_stream, self.ws)
+        self.eig_info = None
+
+    def _up(self, a):
+        t = torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
+        return t.to(torch.bfloat16) if self.wl.bf16 else t
+
+    def close(self):
+        torch.cuda.synchronize()
+        if self.ctx is not None:
+            K.kfac_destroy(self.ctx)
+            self.ctx = None
+
+    # ---- phases ----
+    def update_factors(self, upd, decay):
+        N = self.N
+        for i, l in enumerate(self.layers):
+            x, g = self.x[upd][i], self.g[upd][i]
+            R = N * l.T
+            if l.fc:
+                K.kfac_update_factors(self.ctx, x, K.KFAC_LAYOUT_RD, N, l.d_a - 1, 1, 1, 1.0 / R, decay, self.A[i])
+                K.kfac_update_factors(self.ctx, g, K.KFAC_LAYOUT_RD, N, l.d_g, 1, 0, 1.0 / R, decay, self.G[i])
+                continue
+            if l.needs_unfold:
+                K.kfac_unfold(self.ctx, x, l.k, l.k, l.stride, l.pad, self.patches)
+                src = self.patches
+            else:
+                src = x                                  # [N][C][H*W] is already the patch slab
+            K.kfac_update_factors(self.ctx, src, K.KFAC_LAYOUT_NDT, N, l.d_a - 1, l.T, 1, 1.0 / R, decay, self.A[i],
+                                  dtype=K.KFAC_BF16 if self.wl.bf16 else K.KFAC_F32)
+            K.kfac_update_factors(self.ctx, g, K.KFAC_LAYOUT_NDT, N, l.d_g, l.T, 0, 1.0 / R, decay, self.G[i])
+
+    def eig(self, **kw):
+        self.eig_info = K.kfac_eig(self.ctx, self.A + self.G, self.QA + self.QG, self.lamA + self.lamG, **kw)
+        return self.eig_info
+
+    def precondition(self, damping=None):
+        gamma = self.wl.damping if damping is None else damping
+        for i in range(len(self.layers)):
+            self.grad[i].copy_(self.gradw_master[i])
+            K.kfac_precondition(self.ctx, self.QA[i], self.lamA[i], self.QG[i], self.lamG[i], gamma, self.grad[i])
+
+    # ---- algorithmic work of one step (flops, bytes) ----
+    def work(self):
+        N = self.N
+        esz = 2 if self.wl.bf16 else 4
+        w = dict(syrk_flops=0.0, precond_flops=0.0, unfold_bytes=0.0, ema_bytes=0.0, sum_d3=0.0)
+        for l in self.layers:
+            R = N * l.T
+            w["syrk_flops"] += R * (l.d_a * (l.d_a + 1.0) + l.d_g * (l.d_g + 1.0))
+            w["precond_flops"] += 4.0 * l.d_a * l.d_g * (l.d_a + l.d_g)
+            if l.needs_unfold:
+                w["unfold_bytes"] += esz * (N * l.c_in * l.h_in * l.h_in + R * (l.d_a - 1.0))
+            w["ema_bytes"] += 8.0 * (l.d_a ** 2 + l.d_g ** 2)
+            w["sum_d3"] += float(l.d_a) ** 3 + float(l.d_g) ** 3
+        return w
