@@ -404,20 +404,119 @@ __device__ inline void tri_decode(int idx, int &ti, int &tj) {
     tj = idx - t * (t + 1) / 2;
 }
 
-__device__ inline void load_J(float *Js, const float *J) {
-    for (int e = threadIdx.x; e < SK * SK; e += NT) Js[(e >> 7) * SLD + (e & 127)] = J[e];
+// ---- round application ---------------------------------------------------------------------------
+// A 128 x 128 tile X stays resident in LDS while the 128 x 128 pivot transform is streamed from global
+// memory (L2) in 8-row slabs through a small double buffer, so a workgroup needs 73 KB of LDS and two
+// of them share a compute unit: one loads while the other multiplies.
+constexpr int SLAB_K = 8;
+constexpr int SLAB_LD = SK + 4;
+constexpr size_t APPLY_LDS_BYTES = (size_t)(SK * SLD + 2 * SLAB_K * SLAB_LD) * sizeof(float);
+
+// acc = X * Jm (X_LEFT: A(m,k) = Xs[m][k], B(k,n) = Jm[k][n]) or acc = Jm^T * X (A(m,k) = Jm[k][m],
+// B(k,n) = Xs[k][n]); Jm is row-major [128][128] in global memory.
+template <bool X_LEFT>
+__device__ inline void stream_gemm128(const float *Xs, const float *__restrict__ Jm, float (*slab)[SLAB_K][SLAB_LD],
+                                      floatx16 (&acc)[2][2]) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lk = lane >> 5, lc = lane & 31;
+    const int srow = tid >> 5, scol = (tid & 31) * 4;   // this thread's float4 of every slab
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    float4 pre = *reinterpret_cast<const float4 *>(Jm + srow * SK + scol);
+    *reinterpret_cast<float4 *>(&slab[0][srow][scol]) = pre;
+    __syncthreads();
+    constexpr int NSLAB = SK / SLAB_K;
+    for (int sl = 0; sl < NSLAB; ++sl) {
+        const int cur = sl & 1;
+        if (sl + 1 < NSLAB) pre = *reinterpret_cast<const float4 *>(Jm + ((sl + 1) * SLAB_K + srow) * SK + scol);
+#pragma unroll
+        for (int kk = 0; kk < SLAB_K; kk += 2) {
+            const int k = sl * SLAB_K + kk + lk;
+            float a0, a1, b0, b1;
+            if (X_LEFT) {
+                a0 = Xs[(wm + lc) * SLD + k];
+                a1 = Xs[(wm + 32 + lc) * SLD + k];
+                b0 = slab[cur][kk + lk][wn + lc];
+                b1 = slab[cur][kk + lk][wn + 32 + lc];
+            } else {
+                a0 = slab[cur][kk + lk][wm + lc];
+                a1 = slab[cur][kk + lk][wm + 32 + lc];
+                b0 = Xs[k * SLD + wn + lc];
+                b1 = Xs[k * SLD + wn + 32 + lc];
+            }
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        if (sl + 1 < NSLAB) *reinterpret_cast<float4 *>(&slab[cur ^ 1][srow][scol]) = pre;
+        __syncthreads();
+    }
+}
+
+// Tile <-> global memory, four consecutive columns per access.  rowf(a) / colf(b) give the global row
+// and column of tile row a / tile column b (b a multiple of 4; the four columns are contiguous), or -1.
+template <class RowF, class ColF>
+__device__ inline void tile_load(float *Xs, const float *G, int64_t ld, RowF rowf, ColF colf) {
+    for (int t0 = 0; t0 < 16; t0 += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e4 = threadIdx.x + NT * (t0 + u);
+            const int a = e4 >> 5, b = (e4 & 31) * 4;
+            const int gi = rowf(a), gj = colf(b);
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gi >= 0 && gj >= 0) v[u] = *reinterpret_cast<const float4 *>(G + (int64_t)gi * ld + gj);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e4 = threadIdx.x + NT * (t0 + u);
+            float *dst = Xs + (e4 >> 5) * SLD + (e4 & 31) * 4;
+            dst[0] = v[u].x; dst[1] = v[u].y; dst[2] = v[u].z; dst[3] = v[u].w;
+        }
+    }
+}
+
+// TRANSPOSED: write Xs^T, i.e. global (colf(b), rowf(a..a+3)) <- Xs[a..a+3][b].
+template <bool TRANSPOSED, class RowF, class ColF>
+__device__ inline void tile_store(const float *Xs, float *G, int64_t ld, RowF rowf, ColF colf) {
+#pragma unroll 4
+    for (int t = 0; t < 16; ++t) {
+        const int e4 = threadIdx.x + NT * t;
+        if (!TRANSPOSED) {
+            const int a = e4 >> 5, b = (e4 & 31) * 4;
+            const int gi = rowf(a), gj = colf(b);
+            const float *src = Xs + a * SLD + b;
+            if (gi >= 0 && gj >= 0)
+                *reinterpret_cast<float4 *>(G + (int64_t)gi * ld + gj) = make_float4(src[0], src[1], src[2], src[3]);
+        } else {
+            const int b = e4 >> 5, a = (e4 & 31) * 4;
+            const int gi = rowf(a), gj = colf(b);
+            const float *src = Xs + a * SLD + b;
+            if (gi >= 0 && gj >= 0)
+                *reinterpret_cast<float4 *>(G + (int64_t)gj * ld + gi) =
+                    make_float4(src[0], src[SLD], src[2 * SLD], src[3 * SLD]);
+        }
+    }
 }
 
 // One round of transforms: W_IJ <- J_I^T W_IJ J_J for pair-tiles I >= J (mirrored into J,I), and
 // Qw[:, J] <- Qw[:, J] J_J for every 128-row slab of the accumulator.
-__global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, int ntiles_w, int nrb) {
+__global__ __launch_bounds__(NT, 2) void blk_apply_kernel(BlkGroup g, int round, int ntiles_w, int nrb) {
     extern __shared__ __align__(16) char smem[];
     float *Xs = (float *)smem;
-    float *Js = Xs + SK * SLD;
-    const int m = blockIdx.y, tid = threadIdx.x;
+    float(*slab)[SLAB_K][SLAB_LD] = reinterpret_cast<float(*)[SLAB_K][SLAB_LD]>(Xs + SK * SLD);
+    const int m = blockIdx.y;
     const int64_t np2 = (int64_t)g.npad * g.npad;
     const int *idt = g.idt + m * g.npairs;
     const float *Jall = g.J + (int64_t)m * g.npairs * (SK * SK);
+    const int nblk = g.nblk;
     floatx16 acc[2][2];
     if ((int)blockIdx.x < ntiles_w) {
         float *W = g.W + m * np2;
@@ -427,34 +526,18 @@ __global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, in
         int pi, qi, pj, qj;
         rr_pair(g.players, round, I, pi, qi);
         rr_pair(g.players, round, Jp, pj, qj);
-        for (int e = tid; e < SK * SK; e += NT) {
-            const int a = e >> 7, b = e & 127;
-            const int gi = pair_index(a, pi, qi, g.nblk), gj = pair_index(b, pj, qj, g.nblk);
-            Xs[a * SLD + b] = (gi >= 0 && gj >= 0) ? W[(int64_t)gi * g.npad + gj] : 0.f;
-        }
-        load_J(Js, Jall + (int64_t)Jp * (SK * SK));
+        auto rowf = [=](int a) { return pair_index(a, pi, qi, nblk); };
+        auto colf = [=](int b) { return pair_index(b, pj, qj, nblk); };
+        tile_load(Xs, W, g.npad, rowf, colf);
         __syncthreads();
-        lds_gemm128(Xs, SLD, 1, Js, acc);  // T = X J_J
+        stream_gemm128<true>(Xs, Jall + (int64_t)Jp * (SK * SK), slab, acc);   // T = X J_J
+        acc_to_lds(acc, Xs);   // every wave passed the last barrier of the product: X is dead
         __syncthreads();
-        acc_to_lds(acc, Xs);
-        load_J(Js, Jall + (int64_t)I * (SK * SK));
-        __syncthreads();
-        lds_gemm128(Js, 1, SLD, Xs, acc);  // W' = J_I^T T
-        __syncthreads();
+        stream_gemm128<false>(Xs, Jall + (int64_t)I * (SK * SK), slab, acc);   // W' = J_I^T T
         acc_to_lds(acc, Xs);
         __syncthreads();
-        for (int e = tid; e < SK * SK; e += NT) {
-            const int a = e >> 7, b = e & 127;
-            const int gi = pair_index(a, pi, qi, g.nblk), gj = pair_index(b, pj, qj, g.nblk);
-            if (gi >= 0 && gj >= 0) W[(int64_t)gi * g.npad + gj] = Xs[a * SLD + b];
-        }
-        if (I != Jp) {
-            for (int e = tid; e < SK * SK; e += NT) {
-                const int b = e >> 7, a = e & 127;  // a fastest: contiguous along the mirrored row
-                const int gi = pair_index(a, pi, qi, g.nblk), gj = pair_index(b, pj, qj, g.nblk);
-                if (gi >= 0 && gj >= 0) W[(int64_t)gj * g.npad + gi] = Xs[a * SLD + b];
-            }
-        }
+        tile_store<false>(Xs, W, g.npad, rowf, colf);
+        if (I != Jp) tile_store<true>(Xs, W, g.npad, rowf, colf);
     } else {
         float *Qw = g.Qw + m * np2;
         const int t = blockIdx.x - ntiles_w;
@@ -462,23 +545,15 @@ __global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, in
         if (idt[Jp]) return;
         int pj, qj;
         rr_pair(g.players, round, Jp, pj, qj);
-        const int row0 = rb * SK;
-        for (int e = tid; e < SK * SK; e += NT) {
-            const int a = e >> 7, b = e & 127;
-            const int gi = row0 + a, gj = pair_index(b, pj, qj, g.nblk);
-            Xs[a * SLD + b] = (gi < g.npad && gj >= 0) ? Qw[(int64_t)gi * g.npad + gj] : 0.f;
-        }
-        load_J(Js, Jall + (int64_t)Jp * (SK * SK));
+        const int row0 = rb * SK, npad = g.npad;
+        auto rowf = [=](int a) { return row0 + a < npad ? row0 + a : -1; };
+        auto colf = [=](int b) { return pair_index(b, pj, qj, nblk); };
+        tile_load(Xs, Qw, g.npad, rowf, colf);
         __syncthreads();
-        lds_gemm128(Xs, SLD, 1, Js, acc);
-        __syncthreads();
+        stream_gemm128<true>(Xs, Jall + (int64_t)Jp * (SK * SK), slab, acc);
         acc_to_lds(acc, Xs);
         __syncthreads();
-        for (int e = tid; e < SK * SK; e += NT) {
-            const int a = e >> 7, b = e & 127;
-            const int gi = row0 + a, gj = pair_index(b, pj, qj, g.nblk);
-            if (gi < g.npad && gj >= 0) Qw[(int64_t)gi * g.npad + gj] = Xs[a * SLD + b];
-        }
+        tile_store<false>(Xs, Qw, g.npad, rowf, colf);
     }
 }
 
@@ -574,14 +649,110 @@ size_t small_bytes(size_t nsmall) {
     return kfac_align_up(nsmall * sizeof(SmallItem), 256) + kfac_align_up(nsmall * sizeof(EigStat), 256);
 }
 
+// Everything one group of equally sized factors needs while it is in flight on its stream.
+struct GroupRun {
+    GroupPlan *plan;
+    BlkGroup g;
+    hipStream_t st;
+    hipEvent_t ev;
+    std::vector<BlkItem> items;
+    BlkItem *d_items;
+    int *perm;
+    double *lam64;
+    double *h_norms;      // pinned, 2 per factor
+    int nm, ntiles_w, nrb, ntiles, nmax, fill_blocks;
+    double apply_flops;
+    int sweep;
+    bool done;
+    std::vector<char> conv;
+    std::vector<int> sweeps_done;
+    std::vector<float> offrel;
+};
+
+int enqueue_offnorm(kfac_ctx *ctx, GroupRun &r) {
+    {
+        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
+        hipLaunchKernelGGL(blk_zero_f64_kernel, dim3(1), dim3(256), 0, r.st, r.g.norms, 2 * r.nm);
+        hipLaunchKernelGGL(blk_offnorm_kernel, dim3(std::min(r.fill_blocks, 512), r.nm), dim3(NT), 0, r.st, r.g);
+    }
+    KFAC_HIP_CHECK(hipGetLastError());
+    KFAC_HIP_CHECK(hipMemcpyAsync(r.h_norms, r.g.norms, 2 * r.nm * sizeof(double), hipMemcpyDeviceToHost, r.st));
+    KFAC_HIP_CHECK(hipEventRecord(r.ev, r.st));
+    return KFAC_OK;
+}
+
+int enqueue_sweep(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, size_t lds_apply, int inner_cap, float inner_tol) {
+    for (int rd = 0; rd < r.plan->players - 1; ++rd) {
+        {
+            KfacProfScope prof(ctx, KC_EIG_SOLVE, 0.0, 0.0, r.st);
+            hipLaunchKernelGGL(blk_solve_kernel, dim3(r.plan->npairs, r.nm), dim3(NT), lds_solve, r.st, r.g, rd, inner_cap, inner_tol);
+        }
+        {
+            KfacProfScope prof(ctx, KC_EIG_APPLY, r.apply_flops, 0.0, r.st);
+            hipLaunchKernelGGL(blk_apply_kernel, dim3(r.ntiles, r.nm), dim3(NT), lds_apply, r.st, r.g, rd, r.ntiles_w, r.nrb);
+        }
+    }
+    KFAC_HIP_CHECK(hipGetLastError());
+    return KFAC_OK;
+}
+
+// Post-processing per factor: one Newton-Schulz step restores the orthogonality that thousands of fp32
+// transforms have eroded, Rayleigh quotients against the caller's F give the eigenvalues, and the
+// columns are put in ascending order.  W is dead by now and serves as scratch.
+int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
+    using namespace kfac;
+    const GroupPlan &gp = *r.plan;
+    const size_t np2 = (size_t)gp.npad * gp.npad;
+    hipStream_t st = r.st;
+    hipLaunchKernelGGL(blk_zero_f64_kernel, dim3((r.nm * gp.npad + 255) / 256), dim3(256), 0, st, r.lam64, r.nm * gp.npad);
+    for (int i = 0; i < r.nm; ++i) {
+        const int n = r.items[i].n;
+        float *Wm = r.g.W + i * np2, *Qm = r.g.Qw + i * np2;
+        const int64_t ld = gp.npad;
+        const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
+        OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};          // elem(i,k) = Q[k][i]
+        {
+            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz>), grid, block, 0, st,
+                               q_kn, q_kn, EpiNewtonSchulz{Wm, ld}, n, n, n);
+        }
+        OpStrided<float, true> q_mk{Qm, ld, 1, n, n, -1};           // elem(i,k) = Q[i][k]
+        OpStrided<float, false> y_kn{Wm, 1, ld, n, n, -1};
+        {
+            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_mk), decltype(y_kn), EpiStore>), grid, block, 0, st,
+                               q_mk, y_kn, EpiStore{r.items[i].Q, n}, n, n, n);
+        }
+        OpStrided<float, true> f_mk{r.items[i].F, n, 1, n, n, -1};
+        OpStrided<float, false> qo_kn{r.items[i].Q, 1, n, n, n, -1};
+        {
+            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+            hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(qo_kn), EpiStore>), grid, block, 0, st,
+                               f_mk, qo_kn, EpiStore{Qm, ld}, n, n, n);
+        }
+        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+        double *l64 = r.lam64 + (size_t)i * gp.npad;
+        int *pm = r.perm + (size_t)i * gp.npad;
+        hipLaunchKernelGGL(blk_rayleigh_kernel, dim3((n + NT - 1) / NT, 32), dim3(NT), 0, st, r.items[i].Q, (int64_t)n, Qm, ld, n, l64);
+        hipLaunchKernelGGL(blk_rank_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, l64, n, pm, r.items[i].lam);
+        KFAC_HIP_CHECK(hipMemcpyAsync(Wm, r.items[i].Q, (size_t)n * n * sizeof(float), hipMemcpyDeviceToDevice, st));
+        hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, Wm, (int64_t)n, r.items[i].Q, n, pm);
+    }
+    KFAC_HIP_CHECK(hipGetLastError());
+    KFAC_HIP_CHECK(hipEventRecord(r.ev, st));
+    return KFAC_OK;
+}
+
 }  // namespace
 
+// All groups are in flight at once, each on one of the context's internal streams, so the workspace
+// holds every group's buffers side by side.
 size_t kfac_eig_ws_bytes_impl(int batch, const int *d) {
     std::vector<int> small;
     std::vector<GroupPlan> groups;
     make_plan(batch, d, small, groups);
     size_t need = small_bytes(small.size());
-    for (auto &g : groups) need = std::max(need, g.bytes());  // groups run one after another
+    for (auto &g : groups) need += g.bytes();
     return need;
 }
 
@@ -593,49 +764,69 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     std::vector<GroupPlan> groups;
     make_plan(batch, d, small, groups);
     if (kfac_eig_ws_bytes_impl(batch, d) > ctx->ws_bytes) return KFAC_EWORKSPACE;
+    size_t pinned_need = 0;
+    for (auto &gp : groups) pinned_need += 2 * gp.members.size() * sizeof(double);
+    if (pinned_need > ctx->pinned_bytes) return KFAC_EWORKSPACE;
+    const int inner_cap = 1;       // one Jacobi sweep over a pivot per visit: fewest total rotations
+    const float inner_tol = 1e-7f;
+    const size_t lds_solve = JacobiSmem::bytes(SK, SLD);
+    const size_t lds_apply = APPLY_LDS_BYTES;
+    if (!groups.empty()) {
+        if ((int)lds_solve > ctx->max_lds || (int)lds_apply > ctx->max_lds) return KFAC_EHIP;
+        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_solve));
+        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_apply));
+    }
     bool all_conv = true;
-    hipStream_t st = ctx->stream;
-    int inner_cap = 1;
-    float inner_tol = 1e-7f;
-    if (const char *e = getenv("KFAC_DEBUG_INNER_SWEEPS")) inner_cap = atoi(e);
-    if (const char *e = getenv("KFAC_DEBUG_INNER_TOL")) inner_tol = (float)atof(e);
 
+    // the internal streams start after everything already queued on the caller's stream
+    KFAC_HIP_CHECK(hipEventRecord(ctx->ev_fork, ctx->stream));
+    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) KFAC_HIP_CHECK(hipStreamWaitEvent(ctx->aux[i], ctx->ev_fork, 0));
+
+    char *wsp = ctx->ws;
+    // ---- small factors: one launch, on the last internal stream ----
+    std::vector<SmallItem> sitems;
+    std::vector<EigStat> sstats;
+    EigStat *d_stats = nullptr;
+    hipStream_t st_small = ctx->aux[KFAC_NUM_AUX_STREAMS - 1];
     if (!small.empty()) {
         const size_t ns = small.size();
-        std::vector<SmallItem> items(ns);
+        sitems.resize(ns);
+        sstats.resize(ns);
         int kmax = 2;
         for (size_t i = 0; i < ns; ++i) {
-            items[i] = SmallItem{F[small[i]], Q[small[i]], lam[small[i]], d[small[i]], 0};
+            sitems[i] = SmallItem{F[small[i]], Q[small[i]], lam[small[i]], d[small[i]], 0};
             kmax = std::max(kmax, (d[small[i]] + 1) & ~1);
         }
-        SmallItem *d_items = (SmallItem *)ctx->ws;
-        EigStat *d_stats = (EigStat *)(ctx->ws + kfac_align_up(ns * sizeof(SmallItem), 256));
-        KFAC_HIP_CHECK(hipMemcpyAsync(d_items, items.data(), ns * sizeof(SmallItem), hipMemcpyHostToDevice, st));
+        SmallItem *d_items = (SmallItem *)wsp;
+        d_stats = (EigStat *)(wsp + kfac_align_up(ns * sizeof(SmallItem), 256));
+        wsp += small_bytes(ns);
+        KFAC_HIP_CHECK(hipMemcpyAsync(d_items, sitems.data(), ns * sizeof(SmallItem), hipMemcpyHostToDevice, st_small));
         const size_t lds = JacobiSmem::bytes(kmax, kmax + 1);
         if ((int)lds > ctx->max_lds) return KFAC_EHIP;
         KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)eig_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         {
-            KfacProfScope prof(ctx, KC_EIG_SMALL, 0.0, 0.0);
-            hipLaunchKernelGGL(eig_small_kernel, dim3((unsigned)ns), dim3(NT), lds, st, d_items, d_stats, max_sweeps, tol);
+            KfacProfScope prof(ctx, KC_EIG_SMALL, 0.0, 0.0, st_small);
+            hipLaunchKernelGGL(eig_small_kernel, dim3((unsigned)ns), dim3(NT), lds, st_small, d_items, d_stats, max_sweeps, tol);
         }
         KFAC_HIP_CHECK(hipGetLastError());
-        std::vector<EigStat> stats(ns);
-        KFAC_HIP_CHECK(hipMemcpyAsync(stats.data(), d_stats, ns * sizeof(EigStat), hipMemcpyDeviceToHost, st));
-        KFAC_HIP_CHECK(hipStreamSynchronize(st));
-        for (size_t i = 0; i < ns; ++i) {
-            const bool conv = stats[i].converged > 0.5f;
-            all_conv &= conv;
-            const double k = (d[small[i]] + 1) & ~1;   // 9 flops per element per round: S twice, V once
-            if (ctx->prof_on && !ctx->prof.empty()) ctx->prof.back().flops += stats[i].sweeps * 9.0 * k * k * (k - 1);
-            if (info) info[small[i]] = kfac_eig_info{(int)stats[i].sweeps, stats[i].off_rel, conv ? 1 : 0};
-        }
+        KFAC_HIP_CHECK(hipMemcpyAsync(sstats.data(), d_stats, ns * sizeof(EigStat), hipMemcpyDeviceToHost, st_small));
     }
 
-    for (auto &gp : groups) {
-        const int nm = (int)gp.members.size();
+    // ---- blocked groups: set up, then drive them sweep by sweep as their norms arrive ----
+    std::vector<GroupRun> runs(groups.size());
+    double *pinned = ctx->pinned;
+    for (size_t gi = 0; gi < groups.size(); ++gi) {
+        GroupPlan &gp = groups[gi];
+        GroupRun &r = runs[gi];
+        r.plan = &gp;
+        r.nm = (int)gp.members.size();
+        r.st = ctx->aux[gi % KFAC_NUM_AUX_STREAMS];
+        r.ev = ctx->ev_group[gi % KFAC_MAX_GROUPS];
+        if (gi >= KFAC_MAX_GROUPS) return KFAC_EINVAL;
         const size_t np2 = (size_t)gp.npad * gp.npad;
-        char *p = ctx->ws;
-        BlkGroup g;
+        const int nm = r.nm;
+        char *p = wsp;
+        BlkGroup &g = r.g;
         g.nmat = nm; g.nblk = gp.nblk; g.npad = gp.npad; g.players = gp.players; g.npairs = gp.npairs;
         g.W = (float *)p;
         g.Qw = g.W + nm * np2;
@@ -643,116 +834,102 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         g.J = (float *)p; p += kfac_align_up((size_t)nm * gp.npairs * SK * SK * sizeof(float), 256);
         g.idt = (int *)p; p += kfac_align_up((size_t)nm * gp.npairs * sizeof(int), 256);
         g.norms = (double *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(double), 256);
-        int *perm = (int *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(int), 256);
-        double *lam64 = (double *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(double), 256);
-        BlkItem *d_items = (BlkItem *)p;
-        std::vector<BlkItem> items(nm);
+        r.perm = (int *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(int), 256);
+        r.lam64 = (double *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(double), 256);
+        r.d_items = (BlkItem *)p;
+        wsp += gp.bytes();
+        r.h_norms = pinned;
+        pinned += 2 * nm;
+        r.items.resize(nm);
+        r.nmax = 0;
+        r.apply_flops = 0.0;
         for (int i = 0; i < nm; ++i) {
             const int b = gp.members[i];
-            items[i] = BlkItem{F[b], Q[b], lam[b], d[b], 0};
+            r.items[i] = BlkItem{F[b], Q[b], lam[b], d[b], 0};
+            r.nmax = std::max(r.nmax, d[b]);
+            // algorithmic work of one round: W <- J^T W J on half the (symmetric) matrix and Q <- Q J,
+            // each element a length-2B dot product: 8 n^2 B flops per factor
+            r.apply_flops += 8.0 * (double)d[b] * d[b] * EB;
         }
-        KFAC_HIP_CHECK(hipMemcpyAsync(d_items, items.data(), nm * sizeof(BlkItem), hipMemcpyHostToDevice, st));
-        const int fill_blocks = (int)std::min<size_t>((np2 + NT - 1) / NT, 4096);
+        r.ntiles_w = gp.npairs * (gp.npairs + 1) / 2;
+        r.nrb = (r.nmax + SK - 1) / SK;
+        r.ntiles = r.ntiles_w + r.nrb * gp.npairs;
+        r.fill_blocks = (int)std::min<size_t>((np2 + NT - 1) / NT, 4096);
+        r.sweep = 0;
+        r.done = false;
+        r.conv.assign(nm, 0);
+        r.sweeps_done.assign(nm, 0);
+        r.offrel.assign(nm, 0.f);
+        KFAC_HIP_CHECK(hipMemcpyAsync(r.d_items, r.items.data(), nm * sizeof(BlkItem), hipMemcpyHostToDevice, r.st));
         {
-            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0);
-            hipLaunchKernelGGL(blk_init_kernel, dim3(fill_blocks, nm), dim3(NT), 0, st, g, d_items);
+            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
+            hipLaunchKernelGGL(blk_init_kernel, dim3(r.fill_blocks, nm), dim3(NT), 0, r.st, g, r.d_items);
         }
         KFAC_HIP_CHECK(hipGetLastError());
-
-        const size_t lds_solve = JacobiSmem::bytes(SK, SLD);
-        const size_t lds_apply = (size_t)2 * SK * SLD * sizeof(float);
-        if ((int)lds_solve > ctx->max_lds || (int)lds_apply > ctx->max_lds) return KFAC_EHIP;
-        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_solve));
-        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_apply));
-        const int ntiles_w = gp.npairs * (gp.npairs + 1) / 2;
-        int nmax = 0;
-        for (int i = 0; i < nm; ++i) nmax = std::max(nmax, items[i].n);
-        const int nrb = (nmax + SK - 1) / SK;
-        const int ntiles = ntiles_w + nrb * gp.npairs;
-        // algorithmic work of one round: W <- J^T W J on half the (symmetric) matrix and Q <- Q J, each
-        // element a length-2B dot product: 8 n^2 B flops per factor
-        double apply_flops = 0.0;
-        for (int i = 0; i < nm; ++i) apply_flops += 8.0 * (double)items[i].n * items[i].n * EB;
-
-        std::vector<double> norms(2 * nm);
-        std::vector<int> sweeps_done(nm, 0);
-        std::vector<char> conv(nm, 0);
-        std::vector<float> offrel(nm, 0.f);
-        int sweep = 0;
-        for (;; ++sweep) {
-            {
-                KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0);
-                hipLaunchKernelGGL(blk_zero_norms_kernel, dim3(1), dim3(256), 0, st, g.norms, 2 * nm);
-                hipLaunchKernelGGL(blk_offnorm_kernel, dim3(std::min(fill_blocks, 512), nm), dim3(NT), 0, st, g);
-            }
-            KFAC_HIP_CHECK(hipGetLastError());
-            KFAC_HIP_CHECK(hipMemcpyAsync(norms.data(), g.norms, 2 * nm * sizeof(double), hipMemcpyDeviceToHost, st));
-            KFAC_HIP_CHECK(hipStreamSynchronize(st));
+        int rc = enqueue_offnorm(ctx, r);
+        if (rc) return rc;
+    }
+    // state per group: waiting for norms (post == false) or for its post-processing (post == true)
+    std::vector<char> post(runs.size(), 0);
+    size_t remaining = runs.size();
+    while (remaining > 0) {
+        bool progressed = false;
+        for (size_t gi = 0; gi < runs.size(); ++gi) {
+            GroupRun &r = runs[gi];
+            if (r.done) continue;
+            const hipError_t q = hipEventQuery(r.ev);
+            if (q == hipErrorNotReady) continue;
+            if (q != hipSuccess) return KFAC_EHIP;
+            progressed = true;
+            if (post[gi]) { r.done = true; --remaining; continue; }
             bool all = true;
-            for (int i = 0; i < nm; ++i) {
-                const double o2 = norms[2 * i], n2 = o2 + norms[2 * i + 1];
-                offrel[i] = n2 > 0 ? (float)std::sqrt(o2 / n2) : 0.f;
+            for (int i = 0; i < r.nm; ++i) {
+                const double o2 = r.h_norms[2 * i], n2 = o2 + r.h_norms[2 * i + 1];
+                r.offrel[i] = n2 > 0 ? (float)std::sqrt(o2 / n2) : 0.f;
                 const bool c = o2 <= (double)tol * tol * n2;   // false for NaN
-                if (c && !conv[i]) sweeps_done[i] = sweep;
-                conv[i] = c;
+                if (c && !r.conv[i]) r.sweeps_done[i] = r.sweep;
+                r.conv[i] = c;
                 all &= c;
             }
-            if (all || sweep >= max_sweeps) break;
-            for (int r = 0; r < gp.players - 1; ++r) {
-                {
-                    KfacProfScope prof(ctx, KC_EIG_SOLVE, 0.0, 0.0);
-                    hipLaunchKernelGGL(blk_solve_kernel, dim3(gp.npairs, nm), dim3(NT), lds_solve, st, g, r, inner_cap, inner_tol);
-                }
-                {
-                    KfacProfScope prof(ctx, KC_EIG_APPLY, apply_flops, 0.0);
-                    hipLaunchKernelGGL(blk_apply_kernel, dim3(ntiles, nm), dim3(NT), lds_apply, st, g, r, ntiles_w, nrb);
-                }
+            int rc;
+            if (all || r.sweep >= max_sweeps) {
+                rc = enqueue_post(ctx, r);
+                post[gi] = 1;
+            } else {
+                rc = enqueue_sweep(ctx, r, lds_solve, lds_apply, inner_cap, inner_tol);
+                if (rc == KFAC_OK) rc = enqueue_offnorm(ctx, r);
+                ++r.sweep;
             }
-            KFAC_HIP_CHECK(hipGetLastError());
+            if (rc) return rc;
         }
-        // Post-processing per factor: one Newton-Schulz step restores the orthogonality that thousands of
-        // fp32 transforms have eroded, Rayleigh quotients against the caller's F give the eigenvalues,
-        // and the columns are put in ascending order.  W is dead by now and serves as scratch.
-        hipLaunchKernelGGL(blk_zero_f64_kernel, dim3((nm * gp.npad + 255) / 256), dim3(256), 0, st, lam64, nm * gp.npad);
-        for (int i = 0; i < nm; ++i) {
-            using namespace kfac;
-            const int n = items[i].n;
-            float *Wm = g.W + i * np2, *Qm = g.Qw + i * np2;
-            const int64_t ld = gp.npad;
-            const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
-            OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};          // elem(i,k) = Q[k][i]
-            {
-                KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0);
-                hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz>), grid, block, 0, st,
-                                   q_kn, q_kn, EpiNewtonSchulz{Wm, ld}, n, n, n);
-            }
-            OpStrided<float, true> q_mk{Qm, ld, 1, n, n, -1};           // elem(i,k) = Q[i][k]
-            OpStrided<float, false> y_kn{Wm, 1, ld, n, n, -1};
-            {
-                KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0);
-                hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_mk), decltype(y_kn), EpiStore>), grid, block, 0, st,
-                                   q_mk, y_kn, EpiStore{items[i].Q, n}, n, n, n);
-            }
-            OpStrided<float, true> f_mk{items[i].F, n, 1, n, n, -1};
-            OpStrided<float, false> qo_kn{items[i].Q, 1, n, n, n, -1};
-            {
-                KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0);
-                hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(qo_kn), EpiStore>), grid, block, 0, st,
-                                   f_mk, qo_kn, EpiStore{Qm, ld}, n, n, n);
-            }
-            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0);
-            double *l64 = lam64 + (size_t)i * gp.npad;
-            int *pm = perm + (size_t)i * gp.npad;
-            hipLaunchKernelGGL(blk_rayleigh_kernel, dim3((n + NT - 1) / NT, 32), dim3(NT), 0, st, items[i].Q, (int64_t)n, Qm, ld, n, l64);
-            hipLaunchKernelGGL(blk_rank_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, l64, n, pm, items[i].lam);
-            KFAC_HIP_CHECK(hipMemcpyAsync(Wm, items[i].Q, (size_t)n * n * sizeof(float), hipMemcpyDeviceToDevice, st));
-            hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(fill_blocks, 2048)), dim3(NT), 0, st, Wm, (int64_t)n, items[i].Q, n, pm);
+        if (!progressed) {
+            // nothing ready: block on the first unfinished group's event instead of spinning
+            for (auto &r : runs)
+                if (!r.done) { KFAC_HIP_CHECK(hipEventSynchronize(r.ev)); break; }
         }
-        KFAC_HIP_CHECK(hipGetLastError());
-        KFAC_HIP_CHECK(hipStreamSynchronize(st));  // the workspace is reused by the next group
-        for (int i = 0; i < nm; ++i) {
-            all_conv &= (bool)conv[i];
-            if (info) info[gp.members[i]] = kfac_eig_info{conv[i] ? sweeps_done[i] : sweep, offrel[i], conv[i] ? 1 : 0};
+    }
+    // join: the caller's stream continues after all internal streams
+    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) {
+        KFAC_HIP_CHECK(hipEventRecord(ctx->ev_join[i], ctx->aux[i]));
+        KFAC_HIP_CHECK(hipStreamWaitEvent(ctx->stream, ctx->ev_join[i], 0));
+    }
+    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) KFAC_HIP_CHECK(hipStreamSynchronize(ctx->aux[i]));
+
+    if (!small.empty()) {
+        for (size_t i = 0; i < small.size(); ++i) {
+            const bool conv = sstats[i].converged > 0.5f;
+            all_conv &= conv;
+            const double k = (d[small[i]] + 1) & ~1;   // 9 flops per element per round: S twice, V once
+            if (ctx->prof_on)
+                for (auto &pr : ctx->prof)
+                    if (pr.cls == KC_EIG_SMALL) { pr.flops += sstats[i].sweeps * 9.0 * k * k * (k - 1); break; }
+            if (info) info[small[i]] = kfac_eig_info{(int)sstats[i].sweeps, sstats[i].off_rel, conv ? 1 : 0};
+        }
+    }
+    for (auto &r : runs) {
+        for (int i = 0; i < r.nm; ++i) {
+            all_conv &= (bool)r.conv[i];
+            if (info) info[r.plan->members[i]] = kfac_eig_info{r.conv[i] ? r.sweeps_done[i] : r.sweep, r.offrel[i], r.conv[i] ? 1 : 0};
         }
     }
     return all_conv ? KFAC_OK : KFAC_ENOCONV;

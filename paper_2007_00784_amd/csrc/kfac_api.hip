@@ -55,7 +55,26 @@ int kfac_create(kfac_ctx **out, int device, void *hip_stream, void *workspace_de
     c->stream = (hipStream_t)hip_stream;
     c->ws = (char *)workspace_dev;
     c->ws_bytes = workspace_bytes;
-    c->host_flags = nullptr;
+    c->pinned = nullptr;
+    c->pinned_bytes = 1 << 16;
+    bool ok = hipHostMalloc((void **)&c->pinned, c->pinned_bytes, hipHostMallocDefault) == hipSuccess;
+    int made_streams = 0, made_events = 0;
+    hipEvent_t *evs[2 + KFAC_NUM_AUX_STREAMS + KFAC_MAX_GROUPS];
+    int ne = 0;
+    evs[ne++] = &c->ev_fork;
+    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) evs[ne++] = &c->ev_join[i];
+    for (int i = 0; i < KFAC_MAX_GROUPS; ++i) evs[ne++] = &c->ev_group[i];
+    for (; ok && made_streams < KFAC_NUM_AUX_STREAMS; ++made_streams)
+        ok = hipStreamCreateWithFlags(&c->aux[made_streams], hipStreamNonBlocking) == hipSuccess;
+    for (; ok && made_events < ne; ++made_events)
+        ok = hipEventCreateWithFlags(evs[made_events], hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+        for (int i = 0; i < made_events; ++i) (void)hipEventDestroy(*evs[i]);
+        for (int i = 0; i < made_streams; ++i) (void)hipStreamDestroy(c->aux[i]);
+        if (c->pinned) (void)hipHostFree(c->pinned);
+        delete c;
+        return KFAC_EHIP;
+    }
     c->prof_on = false;
     int lds = 0;
     if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, device) != hipSuccess) lds = 65536;
@@ -68,6 +87,11 @@ int kfac_destroy(kfac_ctx *ctx) {
     if (!ctx) return KFAC_EINVAL;
     for (auto &r : ctx->prof) { (void)hipEventDestroy(r.t0); (void)hipEventDestroy(r.t1); }
     for (auto e : ctx->ev_pool) (void)hipEventDestroy(e);
+    (void)hipEventDestroy(ctx->ev_fork);
+    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) (void)hipEventDestroy(ctx->ev_join[i]);
+    for (int i = 0; i < KFAC_MAX_GROUPS; ++i) (void)hipEventDestroy(ctx->ev_group[i]);
+    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) (void)hipStreamDestroy(ctx->aux[i]);
+    (void)hipHostFree(ctx->pinned);
     delete ctx;
     return KFAC_OK;
 }

@@ -13,12 +13,18 @@ enum KfacKernelClass {
 };
 struct KfacProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
 
+constexpr int KFAC_NUM_AUX_STREAMS = 4;   // internal streams of the eigensolver (default priority)
+constexpr int KFAC_MAX_GROUPS = 128;      // distinct block counts in one kfac_eig call (8192 / 64)
+
 struct kfac_ctx {
     int device;
     hipStream_t stream;
+    hipStream_t aux[KFAC_NUM_AUX_STREAMS];
+    hipEvent_t ev_fork, ev_join[KFAC_NUM_AUX_STREAMS], ev_group[KFAC_MAX_GROUPS];
+    double *pinned;      // pinned host scratch: the eigensolver's convergence read-back
+    size_t pinned_bytes;
     char *ws;            // caller-owned device workspace
     size_t ws_bytes;
-    double *host_flags;  // pinned host scratch for the eigensolver's convergence read-back
     int max_lds;         // bytes of LDS one workgroup may use on this device
     bool prof_on;        // bracket every kernel launch with events
     std::vector<KfacProfRec> prof;
@@ -30,15 +36,17 @@ struct kfac_ctx {
 struct KfacProfScope {
     kfac_ctx *c;
     KfacProfRec r;
-    KfacProfScope(kfac_ctx *ctx, int cls, double flops, double bytes) : c(ctx) {
+    hipStream_t s;
+    KfacProfScope(kfac_ctx *ctx, int cls, double flops, double bytes) : KfacProfScope(ctx, cls, flops, bytes, ctx->stream) {}
+    KfacProfScope(kfac_ctx *ctx, int cls, double flops, double bytes, hipStream_t st) : c(ctx), s(st) {
         if (!c->prof_on) return;
         r.cls = cls; r.flops = flops; r.bytes = bytes;
         r.t0 = get(); r.t1 = get();
-        (void)hipEventRecord(r.t0, c->stream);
+        (void)hipEventRecord(r.t0, s);
     }
     ~KfacProfScope() {
         if (!c->prof_on) return;
-        (void)hipEventRecord(r.t1, c->stream);
+        (void)hipEventRecord(r.t1, s);
         c->prof.push_back(r);
     }
     hipEvent_t get() {

@@ -67,25 +67,36 @@ __global__ __launch_bounds__(NTHREADS) void syrk_kernel(Op opA, SyrkArgs g) {
 }
 
 // Sum the split partials of each tile in split order, then apply the running average and mirror.
+// One thread per tile element (gridDim.y * 256 = 128 * 128); the loads of consecutive splits are
+// independent, so they are issued eight at a time.
 __global__ __launch_bounds__(256) void syrk_reduce_kernel(SyrkArgs g) {
     int ti, tj;
     tri_decode(blockIdx.x, ti, tj);
     const int ntri = gridDim.x;
     const bool diag = ti == tj;
-    for (int e = threadIdx.x + blockIdx.y * 256; e < BM * BM; e += 256 * gridDim.y) {
-        const int r = e / BM, c = e % BM;
-        const int gr = ti * BM + r, gc = tj * BM + c;
-        if (gr >= g.D || gc >= g.D || (diag && gc > gr)) continue;
-        float s = 0.f;
-        for (int sp = 0; sp < g.nsplit; ++sp) s += g.partial[((int64_t)sp * ntri + blockIdx.x) * (BM * BM) + e];
-        ema_store(g.F, g.D, gr, gc, s, g.alpha, g.decay, gr != gc);
+    const int e = threadIdx.x + blockIdx.y * 256;
+    const int r = e / BM, c = e % BM;
+    const int gr = ti * BM + r, gc = tj * BM + c;
+    if (gr >= g.D || gc >= g.D || (diag && gc > gr)) return;
+    const float *src = g.partial + (int64_t)blockIdx.x * (BM * BM) + e;
+    const int64_t stride = (int64_t)ntri * (BM * BM);
+    float s = 0.f;
+    int sp = 0;
+    for (; sp + 8 <= g.nsplit; sp += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(sp + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
     }
+    for (; sp < g.nsplit; ++sp) s += src[sp * stride];
+    ema_store(g.F, g.D, gr, gc, s, g.alpha, g.decay, gr != gc);
 }
 
 void plan(int D, int64_t R, int &ntile, int &ntri, int &nsplit, int &kchunk) {
     ntile = (D + BM - 1) / BM;
     ntri = ntile * (ntile + 1) / 2;
-    int want = (512 + ntri - 1) / ntri;                 // aim at >= 512 workgroups
+    int want = (256 + ntri - 1) / ntri;                 // aim at one workgroup per compute unit
     int64_t maxsplit = R / 256 > 0 ? R / 256 : 1;       // keep >= 256 rows per split
     nsplit = (int)(want < maxsplit ? want : maxsplit);
     if (nsplit < 1) nsplit = 1;
@@ -147,7 +158,7 @@ int kfac_launch_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layo
     KFAC_HIP_CHECK(hipGetLastError());
     if (g.nsplit > 1) {
         KfacProfScope prof(ctx, KC_SYRK_REDUCE, 0.0, (decay != 0.f ? 8.0 : 4.0) * D * D);
-        hipLaunchKernelGGL(syrk_reduce_kernel, dim3(ntri, 4), dim3(256), 0, ctx->stream, g);
+        hipLaunchKernelGGL(syrk_reduce_kernel, dim3(ntri, BM * BM / 256), dim3(256), 0, ctx->stream, g);
         KFAC_HIP_CHECK(hipGetLastError());
     }
     return KFAC_OK;
