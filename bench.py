@@ -30,6 +30,7 @@ BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
     "eig_apply": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
     "eig_misc": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "eig_post_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
+    "eig_copy": ("hbm", PEAK_HBM, "GB/s", "bytes"),
 }
 
 

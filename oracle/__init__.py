@@ -11,6 +11,7 @@ from .kfac_oracle import (  # noqa: F401
     unfold,
     gram,
     gram_entry,
+    conv_factor_entry,
     ema,
     eigh,
     eigh_jacobi,

@@ -127,6 +127,33 @@ double oracle_gram_entry(const double *X, int64_t R, int d, int append_ones, dou
     return scale * s;
 }
 
+/* One entry of the batch A factor of a conv layer without materialising the patch matrix, for spot
+ * checks at full size: scale * sum over examples and output locations of Pt[r][i] * Pt[r][j], where
+ * Pt[r][c] is the unfold entry defined above for c < C*kh*kw and the constant 1 for c == C*kh*kw. */
+static double patch_value(const double *x, int C, int H, int W, int kh, int kw, int sh, int sw, int ph, int pw,
+                          int n, int ho, int wo, int col)
+{
+    if (col == C * kh * kw) return 1.0;
+    const int c = col / (kh * kw), ky = (col / kw) % kh, kx = col % kw;
+    const int h = ho * sh - ph + ky, w = wo * sw - pw + kx;
+    if (h < 0 || h >= H || w < 0 || w >= W) return 0.0;
+    return x[(((int64_t)n * C + c) * H + h) * W + w];
+}
+
+double oracle_conv_factor_entry(const double *x, int N, int C, int H, int W, int kh, int kw,
+                                int sh, int sw, int ph, int pw, double scale, int i, int j)
+{
+    const int Ho = (H + 2 * ph - kh) / sh + 1;
+    const int Wo = (W + 2 * pw - kw) / sw + 1;
+    double s = 0.0;
+    for (int n = 0; n < N; ++n)
+        for (int ho = 0; ho < Ho; ++ho)
+            for (int wo = 0; wo < Wo; ++wo)
+                s += patch_value(x, C, H, W, kh, kw, sh, sw, ph, pw, n, ho, wo, i) *
+                     patch_value(x, C, H, W, kh, kw, sh, sw, ph, pw, n, ho, wo, j);
+    return scale * s;
+}
+
 /* ------------------------------------------------------------------------
  * Running average of a factor (Sec. IV-B): F <- xi * F + (1 - xi) * Fb,
  * xi the weight of the history (see the design notes for the reading of the

@@ -42,6 +42,8 @@ def _load():
     lib.oracle_gram.argtypes = [_dp, _i64, _i, _i, _d, _dp]
     lib.oracle_gram_entry.argtypes = [_dp, _i64, _i, _i, _d, _i, _i]
     lib.oracle_gram_entry.restype = _d
+    lib.oracle_conv_factor_entry.argtypes = [_dp, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i, _d, _i, _i]
+    lib.oracle_conv_factor_entry.restype = _d
     lib.oracle_ema.argtypes = [_dp, _dp, _i64, _d]
     for name in ("oracle_eigh", "oracle_eigh_jacobi", "oracle_eigh_tridiag"):
         getattr(lib, name).argtypes = [_dp, _i, _dp, _dp]
@@ -105,6 +107,13 @@ def gram_entry(X, append_ones, scale, i, j):
     X = _c(X)
     R, d = X.shape
     return float(_load().oracle_gram_entry(_p(X), R, d, int(bool(append_ones)), float(scale), int(i), int(j)))
+
+
+def conv_factor_entry(x, kh, kw, sh, sw, ph, pw, scale, i, j):
+    """Entry (i, j) of scale * [P|1]^T [P|1] for the unfold P of x, straight from the definition."""
+    x = _c(x)
+    N, C, H, W = x.shape
+    return float(_load().oracle_conv_factor_entry(_p(x), N, C, H, W, kh, kw, sh, sw, ph, pw, float(scale), int(i), int(j)))
 
 
 def ema(F, Fb, xi):

@@ -4,27 +4,35 @@
 //  * d <= 128: one workgroup per factor.  The rotated matrix and the accumulated eigenvectors both
 //    stay in LDS for the whole solve; every round applies d/2 disjoint plane rotations (round-robin
 //    tournament ordering), each computed by one lane and applied by the whole workgroup.
-//  * d  > 128: blocked Jacobi.  The matrix is cut into 64-wide blocks; a round pairs the blocks by
-//    the same tournament, solves each 128x128 pivot sub-problem with the LDS solver above (one
-//    workgroup per pair), and applies the resulting orthogonal 128x128 transforms to the whole
-//    matrix and to the eigenvector accumulator as fp32 MFMA products on LDS-resident tiles.  Only
+//  * d  > 128: blocked Jacobi.  The matrix is cut into EB-wide blocks; a round pairs the blocks by
+//    the same tournament, gives each 2EB x 2EB pivot sub-problem ONE sweep of the LDS solver above
+//    (one workgroup per pair), and applies the resulting orthogonal transforms to the whole matrix
+//    and to the eigenvector accumulator as fp32 MFMA products on LDS-resident 128 x 128 tiles.  Only
 //    the lower block-triangle is computed; the mirror image is written from LDS, so the working
-//    matrix stays exactly symmetric.  Factors of equal block count are advanced together.
+//    matrix stays exactly symmetric.  Factors of equal block count advance together, and all such
+//    groups are in flight at once on the context's internal streams.
+//  * When a factor has converged, one Newton-Schulz step re-orthogonalises the accumulated
+//    eigenvectors, Rayleigh quotients against the caller's matrix give the eigenvalues, and the
+//    columns are sorted.
 //
 // Convergence is decided on the host once per sweep from off(F)_F / ||F||_F.
 #include <algorithm>
-#include <cstdlib>
+#include <cmath>
 #include <vector>
 #include "kfac_internal.h"
 #include "mfma_gemm.h"
 
 namespace {
 
-constexpr int EB = KFAC_EIG_B;  // block width of the blocked path
-constexpr int SK = 2 * EB;      // pivot sub-problem size (128)
-constexpr int SLD = SK + 1;     // LDS pitch (odd: column walks are bank-conflict free)
+constexpr int EB = KFAC_EIG_B;       // block width of the blocked path
+constexpr int KP = 2 * EB;           // pivot sub-problem size
+constexpr int PLD = KP + 1;          // LDS pitch of a pivot (odd: column walks are conflict free)
+constexpr int TS = 128;              // edge of an apply tile
+constexpr int XLD = TS + 1;          // LDS pitch of an apply tile
+constexpr int PT = TS / KP;          // pivot pairs per tile edge
+constexpr int SMALL_MAX = KFAC_EIG_SMALL;
 constexpr int NT = 256;
-static_assert(NT == 256 && SK == 128, "the fixed-size Jacobi thread mapping assumes 256 threads and 128 x 128 pivots");
+static_assert(NT == 256 && (KP == 64 || KP == 128) && SMALL_MAX == 128, "thread mappings below assume these sizes");
 
 struct SmallItem { const float *F; float *Q; float *lam; int n; int pad_; };
 struct EigStat { float sweeps, off_rel, converged, rotations; };
@@ -57,6 +65,7 @@ __device__ inline float block_sum(float v, float *red) {
 }
 
 struct JacobiResult { int sweeps; float off2, nrm2; int rotations; };
+struct RotEntry { int p, q; float c, s; };
 
 // Two-sided Jacobi on the k x k symmetric matrix S (k even), accumulating V <- V J, both in LDS with
 // pitch ld.  Stops when off(S)^2 <= tol^2 * ||S||^2 or after max_sweeps.  Rotations use the smaller
@@ -64,8 +73,6 @@ struct JacobiResult { int sweeps; float off2, nrm2; int rotations; };
 // is below skip_rel * ||S||_F / k are left alone (and exact zeros always are, which keeps zero-padded
 // rows and columns decoupled).  KC > 0 fixes k at compile time (index arithmetic becomes shifts and
 // each thread's column pair is loop invariant); KC == 0 takes k at run time.
-struct RotEntry { int p, q; float c, s; };
-
 template <int KC>
 __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max_sweeps, float tol, float skip_rel,
                                    float *red, RotEntry *rot, int *rotflag) {
@@ -95,33 +102,40 @@ __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max
                 const float app = S[p * ld + p], aqq = S[q * ld + q], apq = S[p * ld + q];
                 float c = 1.f, s = 0.f;
                 if (fabsf(apq) > thr) {
-                    // rotation parameters in fp64, so that c^2 + s^2 = 1 to fp32 rounding without bias
-                    const double theta = ((double)aqq - (double)app) / (2.0 * (double)apq);
-                    const double t = copysign(1.0, theta) / (fabs(theta) + sqrt(theta * theta + 1.0));
-                    const double cd = 1.0 / sqrt(t * t + 1.0);
+                    // tangent of the smaller rotation angle in fp32; the normalisation in fp64, so that
+                    // c^2 + s^2 = 1 to fp32 rounding without bias (a biased rsqrt makes V drift)
+                    const float theta = (aqq - app) / (2.f * apq);
+                    const float t = copysignf(1.f, theta) / (fabsf(theta) + sqrtf(fmaf(theta, theta, 1.f)));
+                    const double td = (double)t;
+                    const double cd = 1.0 / sqrt(fma(td, td, 1.0));
                     c = (float)cd;
-                    s = (float)(t * cd);
+                    s = (float)(td * cd);
                     *rotflag = 1;
                 }
                 rot[tid] = RotEntry{p, q, c, s};
             }
             __syncthreads();
-            // S <- J^T S J on 2x2 blocks (rows of pair j1, columns of pair j2)
-            if (KC == 128) {
-                const RotEntry r2 = rot[tid & 63];
+            if constexpr (KC > 0) {
+                // S <- J^T S J on 2x2 blocks: this thread's column pair is fixed, its row pairs vary.
+                // Loads of a batch are issued together before any store, so they overlap.
+                constexpr int HALF = KC / 2;
+                constexpr int SB = 4;                                   // blocks per batch
+                constexpr int NSB = HALF * HALF / NT;                   // blocks per thread (16 or 4)
+                constexpr int JSTEP = NT / HALF;
+                const RotEntry r2 = rot[tid & (HALF - 1)];
                 const float *c0 = S + r2.p, *c1p = S + r2.q;
-                // loads of four blocks are issued together before any store, so they can overlap
-                for (int t0 = 0; t0 < 16; t0 += 4) {
-                    RotEntry r1[4];
-                    float a[4], b[4], c_[4], d[4];
+                for (int t0 = 0; t0 < NSB; t0 += SB) {
+                    RotEntry r1[SB];
+                    float a[SB], b[SB], c_[SB], d[SB];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        r1[u] = rot[(tid >> 6) + 4 * (t0 + u)];   // uniform across the wave
+                    for (int u = 0; u < SB; ++u) {
+                        r1[u] = rot[tid / HALF + JSTEP * (t0 + u)];
                         a[u] = c0[r1[u].p * ld]; b[u] = c1p[r1[u].p * ld];
                         c_[u] = c0[r1[u].q * ld]; d[u] = c1p[r1[u].q * ld];
                     }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
+                    for (int u = 0; u < SB; ++u) {
+                        // columns: [a b; c d] * [[c2, s2], [-s2, c2]], then rows: [[c1, -s1], [s1, c1]] * [...]
                         const float a1 = r2.c * a[u] - r2.s * b[u], b1 = r2.s * a[u] + r2.c * b[u];
                         const float cc1 = r2.c * c_[u] - r2.s * d[u], d1 = r2.s * c_[u] + r2.c * d[u];
                         S[r1[u].p * ld + r2.p] = r1[u].c * a1 - r1[u].s * cc1;
@@ -130,17 +144,21 @@ __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max
                         S[r1[u].q * ld + r2.q] = r1[u].s * b1 + r1[u].c * d1;
                     }
                 }
-                float *vrow = V + (tid & 127) * ld;
-                for (int t0 = 0; t0 < 32; t0 += 8) {
-                    RotEntry rc[8];
-                    float vp[8], vq[8];
+                // V <- V J: this thread's row is fixed, the column pairs vary
+                constexpr int VB = 8;
+                constexpr int NVB = KC * HALF / NT;                     // items per thread (32 or 8)
+                constexpr int VSTEP = NT / KC;
+                float *vrow = V + (tid & (KC - 1)) * ld;
+                for (int t0 = 0; t0 < NVB; t0 += VB) {
+                    RotEntry rc[VB];
+                    float vp[VB], vq[VB];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        rc[u] = rot[(tid >> 7) + 2 * (t0 + u)];   // uniform across the wave
+                    for (int u = 0; u < VB; ++u) {
+                        rc[u] = rot[tid / KC + VSTEP * (t0 + u)];
                         vp[u] = vrow[rc[u].p]; vq[u] = vrow[rc[u].q];
                     }
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
+                    for (int u = 0; u < VB; ++u) {
                         vrow[rc[u].p] = rc[u].c * vp[u] - rc[u].s * vq[u];
                         vrow[rc[u].q] = rc[u].s * vp[u] + rc[u].c * vq[u];
                     }
@@ -150,16 +168,13 @@ __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max
                     const int j1 = e / half, j2 = e - j1 * half;
                     const RotEntry r1 = rot[j1], r2 = rot[j2];
                     float a = S[r1.p * ld + r2.p], b = S[r1.p * ld + r2.q], c_ = S[r1.q * ld + r2.p], d = S[r1.q * ld + r2.q];
-                    // columns: [a b; c d] * [[c2, s2], [-s2, c2]]
                     const float a1 = r2.c * a - r2.s * b, b1 = r2.s * a + r2.c * b;
                     const float cc1 = r2.c * c_ - r2.s * d, d1 = r2.s * c_ + r2.c * d;
-                    // rows: [[c1, -s1], [s1, c1]] * [...]
                     S[r1.p * ld + r2.p] = r1.c * a1 - r1.s * cc1;
                     S[r1.p * ld + r2.q] = r1.c * b1 - r1.s * d1;
                     S[r1.q * ld + r2.p] = r1.s * a1 + r1.c * cc1;
                     S[r1.q * ld + r2.q] = r1.s * b1 + r1.c * d1;
                 }
-                // V <- V J
                 for (int e = tid; e < k * half; e += NT) {
                     const int j = e / k, i = e - j * k;
                     const RotEntry rc = rot[j];
@@ -175,7 +190,7 @@ __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max
     return res;
 }
 
-// Dynamic LDS layout shared by the small solver and the pivot solver.
+// Dynamic LDS layout shared by the small solver and the pivot solver (auxiliary arrays sized for 128).
 struct JacobiSmem {
     float *S, *V, *red;
     RotEntry *rot;
@@ -186,18 +201,24 @@ struct JacobiSmem {
         V = S + k * ld;
         red = V + k * ld;
         rot = (RotEntry *)(red + 8);
-        rotflag = (int *)(rot + SK / 2);
+        rotflag = (int *)(rot + SMALL_MAX / 2);
         rank = rotflag + 4;
-        diag = (float *)(rank + SK);
+        diag = (float *)(rank + SMALL_MAX);
     }
-    static size_t bytes(int k, int ld) { return ((size_t)2 * k * ld + 8 + 4 * (SK / 2) + 4 + 2 * SK) * sizeof(float); }
+    static size_t bytes(int k, int ld) {
+        return ((size_t)2 * k * ld + 8 + 4 * (SMALL_MAX / 2) + 4 + 2 * SMALL_MAX) * sizeof(float);
+    }
 };
 
-// 128x128x128 product on LDS-resident operands: acc = A * B with A(m,k) = Am[m*am + k*ak],
-// B(k,n) = Bm[k*SLD + n].
-__device__ inline void lds_gemm128(const float *Am, int am, int ak, const float *Bm, floatx16 (&acc)[2][2]) {
+// ---- Newton-Schulz step V <- V (3I - V^T V)/2 in LDS ------------------------------------------------
+// Hundreds of fp32 rotations leave V orthogonal only to ~1e-6; one step restores ~1e-7.
+
+// KP x KP x KP product on LDS operands for the pivot size: acc = A * B, A(m,k) = Am[m*am + k*ak],
+// B(k,n) = Bm[k*PLD + n].  KP = 128: 2x2 accumulators per wave; KP = 64: one (acc[0][0]).
+__device__ inline void lds_gemm_pivot(const float *Am, int am, int ak, const float *Bm, floatx16 (&acc)[2][2]) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    constexpr int Q = KP / 2;   // quadrant edge per wave
+    const int wm = (wave >> 1) * Q, wn = (wave & 1) * Q;
     const int lk = lane >> 5, lc = lane & 31;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -206,36 +227,48 @@ __device__ inline void lds_gemm128(const float *Am, int am, int ak, const float 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 #pragma unroll 4
-    for (int kk = 0; kk < SK; kk += 2) {
+    for (int kk = 0; kk < KP; kk += 2) {
         const float a0 = Am[(wm + lc) * am + (kk + lk) * ak];
-        const float a1 = Am[(wm + 32 + lc) * am + (kk + lk) * ak];
-        const float b0 = Bm[(kk + lk) * SLD + wn + lc];
-        const float b1 = Bm[(kk + lk) * SLD + wn + 32 + lc];
+        const float b0 = Bm[(kk + lk) * PLD + wn + lc];
         acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        if (KP == 128) {
+            const float a1 = Am[(wm + 32 + lc) * am + (kk + lk) * ak];
+            const float b1 = Bm[(kk + lk) * PLD + wn + 32 + lc];
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
     }
 }
 
-__device__ inline void acc_to_lds(const floatx16 (&acc)[2][2], float *X) {
-    kfac::for_each_acc(acc, [&](int r, int c, float v) { X[r * SLD + c] = v; });
+// f(row, col, value) over this thread's elements of the pivot-sized accumulators.
+template <class F>
+__device__ inline void for_each_pivot_acc(const floatx16 (&acc)[2][2], F f) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int Q = KP / 2, NI = KP / 64;
+    const int wm = (wave >> 1) * Q, wn = (wave & 1) * Q;
+    const int lk = lane >> 5, lc = lane & 31;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                f(wm + 32 * i + 8 * (r >> 2) + 4 * lk + (r & 3), wn + 32 * j + lc, acc[i][j][r]);
 }
 
-// The same Newton-Schulz step for the 128 x 128 pivot transform, as two MFMA products in LDS.
-__device__ void polish_lds_mfma(float *V, float *Y) {
+__device__ void polish_pivot_mfma(float *V, float *Y) {
     floatx16 acc[2][2];
-    lds_gemm128(V, 1, SLD, V, acc);  // V^T V
-    kfac::for_each_acc(acc, [&](int r, int c, float v) { Y[r * SLD + c] = (r == c ? 1.5f : 0.f) - 0.5f * v; });
+    lds_gemm_pivot(V, 1, PLD, V, acc);  // V^T V
+    for_each_pivot_acc(acc, [&](int r, int c, float v) { Y[r * PLD + c] = (r == c ? 1.5f : 0.f) - 0.5f * v; });
     __syncthreads();
-    lds_gemm128(V, SLD, 1, Y, acc);  // V Y
+    lds_gemm_pivot(V, PLD, 1, Y, acc);  // V Y
     __syncthreads();
-    acc_to_lds(acc, V);
+    for_each_pivot_acc(acc, [&](int r, int c, float v) { V[r * PLD + c] = v; });
     __syncthreads();
 }
 
-// One Newton-Schulz step V <- V (3I - V^T V)/2 on the k x k matrix V in LDS (Y is k x k scratch, same
-// pitch): hundreds of fp32 rotations leave V orthogonal only to ~1e-6; this restores ~1e-7.
+// The same step with plain FMAs for a run-time size k <= 128 (Y is k x k scratch, same pitch).
 __device__ void polish_lds_valu(float *V, float *Y, int k, int ld) {
     const int tid = threadIdx.x;
     for (int e = tid; e < k * k; e += NT) {
@@ -245,9 +278,9 @@ __device__ void polish_lds_valu(float *V, float *Y, int k, int ld) {
         Y[i * ld + j] = (i == j ? 1.5f : 0.f) - 0.5f * s;
     }
     __syncthreads();
-    float out[SK * SK / NT];
+    float out[SMALL_MAX * SMALL_MAX / NT];
 #pragma unroll
-    for (int t = 0; t < SK * SK / NT; ++t) {
+    for (int t = 0; t < SMALL_MAX * SMALL_MAX / NT; ++t) {
         const int e = tid + t * NT;
         float s = 0.f;
         if (e < k * k) {
@@ -258,7 +291,7 @@ __device__ void polish_lds_valu(float *V, float *Y, int k, int ld) {
     }
     __syncthreads();
 #pragma unroll
-    for (int t = 0; t < SK * SK / NT; ++t) {
+    for (int t = 0; t < SMALL_MAX * SMALL_MAX / NT; ++t) {
         const int e = tid + t * NT;
         if (e < k * k) V[(e / k) * ld + (e % k)] = out[t];
     }
@@ -287,7 +320,7 @@ __global__ __launch_bounds__(NT) void eig_small_kernel(const SmallItem *items, E
     for (int i = tid; i < k; i += NT) sm.diag[i] = sm.S[i * ld + i];
     __syncthreads();
     if (res.rotations > 0) polish_lds_valu(sm.V, sm.S, k, ld);
-    // rank of every eigenvalue (ascending, ties by index) -> pp[]
+    // rank of every eigenvalue (ascending, ties by index)
     for (int i = tid; i < n; i += NT) {
         const float li = sm.diag[i];
         int rank = 0;
@@ -314,15 +347,15 @@ __global__ __launch_bounds__(NT) void eig_small_kernel(const SmallItem *items, E
 }
 
 // ------------------------------------------------------------------------------------------------
-// d > 128: blocked path.  Per group of `nmat` factors with `nblk` 64-wide blocks (npad = 64*nblk):
+// d > 128: blocked path.  Per group of `nmat` factors with `nblk` EB-wide blocks (npad = EB*nblk):
 //   W  [nmat][npad][npad]   rotated matrix         Qw [nmat][npad][npad]  accumulated eigenvectors
-//   J  [nmat][npairs][128][128] pivot transforms   idt[nmat][npairs]      1 = transform is identity
+//   J  [nmat][npairs][KP][KP] pivot transforms     idt[nmat][npairs]      1 = transform is identity
 // ------------------------------------------------------------------------------------------------
 struct BlkGroup {
     float *W, *Qw, *J;
     int *idt;
     double *norms;   // [nmat][2] = off^2, diag^2
-    int nmat, nblk, npad, players, npairs;
+    int nmat, nblk, npad, players, npairs, npp;   // npp = tile rows = ceil(npairs / PT)
 };
 struct BlkItem { const float *F; float *Q; float *lam; int n; int pad_; };
 
@@ -338,9 +371,9 @@ __global__ void blk_init_kernel(BlkGroup g, const BlkItem *items) {
     }
 }
 
-__global__ void blk_zero_norms_kernel(double *norms, int count) {
+__global__ void blk_zero_f64_kernel(double *p, int count) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) norms[i] = 0.0;
+    if (i < count) p[i] = 0.0;
 }
 
 __global__ __launch_bounds__(NT) void blk_offnorm_kernel(BlkGroup g) {
@@ -362,37 +395,47 @@ __global__ __launch_bounds__(NT) void blk_offnorm_kernel(BlkGroup g) {
     }
 }
 
-// Row/column index in the padded matrix of element a (0..127) of the pair (p, q); -1 if the block is
+// Row/column index in the padded matrix of element a (0..KP-1) of the pair (p, q); -1 if the block is
 // the phantom one that completes an odd block count.
 __device__ inline int pair_index(int a, int p, int q, int nblk) {
     const int blk = a < EB ? p : q;
     return blk < nblk ? blk * EB + (a & (EB - 1)) : -1;
 }
 
+// One sweep of the LDS Jacobi solver over the pivot sub-problem of every pair of this round; writes
+// the accumulated (and re-orthogonalised) transform J and whether it is the identity.
 __global__ __launch_bounds__(NT) void blk_solve_kernel(BlkGroup g, int round, int inner_sweeps, float inner_tol) {
     extern __shared__ __align__(16) char smem[];
-    JacobiSmem sm(smem, SK, SLD);
+    JacobiSmem sm(smem, KP, PLD);
     const int m = blockIdx.y, pj = blockIdx.x, tid = threadIdx.x;
     const float *W = g.W + (int64_t)m * g.npad * g.npad;
     int p, q;
     rr_pair(g.players, round, pj, p, q);
-    for (int e = tid; e < SK * SK; e += NT) {
-        const int a = e / SK, b = e - a * SK;
-        const int gi = pair_index(a, p, q, g.nblk), gj = pair_index(b, p, q, g.nblk);
-        // read the lower triangle only, so the sub-problem is exactly symmetric
-        float v = 0.f;
-        if (gi >= 0 && gj >= 0) v = (gi >= gj) ? W[(int64_t)gi * g.npad + gj] : W[(int64_t)gj * g.npad + gi];
-        sm.S[a * SLD + b] = v;
-        sm.V[a * SLD + b] = (a == b) ? 1.f : 0.f;
+    constexpr int PER = KP * KP / NT;
+    for (int t0 = 0; t0 < PER; t0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e = tid + NT * (t0 + u);
+            const int a = e / KP, b = e % KP;
+            const int gi = pair_index(a, p, q, g.nblk), gj = pair_index(b, p, q, g.nblk);
+            // read the lower triangle only, so the sub-problem is exactly symmetric
+            v[u] = 0.f;
+            if (gi >= 0 && gj >= 0) v[u] = (gi >= gj) ? W[(int64_t)gi * g.npad + gj] : W[(int64_t)gj * g.npad + gi];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e = tid + NT * (t0 + u);
+            const int a = e / KP, b = e % KP;
+            sm.S[a * PLD + b] = v[u];
+            sm.V[a * PLD + b] = (a == b) ? 1.f : 0.f;
+        }
     }
     __syncthreads();
-    const JacobiResult res = jacobi_lds<SK>(sm.S, sm.V, SK, SLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
-    if (res.rotations > 0) polish_lds_mfma(sm.V, sm.S);
-    float *J = g.J + ((int64_t)m * g.npairs + pj) * (SK * SK);
-    for (int e = tid; e < SK * SK; e += NT) {
-        const int a = e / SK, b = e - a * SK;
-        J[e] = sm.V[a * SLD + b];
-    }
+    const JacobiResult res = jacobi_lds<KP>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
+    if (res.rotations > 0) polish_pivot_mfma(sm.V, sm.S);
+    float *J = g.J + ((int64_t)m * g.npairs + pj) * (KP * KP);
+    for (int e = tid; e < KP * KP; e += NT) J[e] = sm.V[(e / KP) * PLD + (e % KP)];
     if (tid == 0) g.idt[m * g.npairs + pj] = res.rotations == 0;
 }
 
@@ -405,59 +448,106 @@ __device__ inline void tri_decode(int idx, int &ti, int &tj) {
 }
 
 // ---- round application ---------------------------------------------------------------------------
-// A 128 x 128 tile X stays resident in LDS while the 128 x 128 pivot transform is streamed from global
-// memory (L2) in 8-row slabs through a small double buffer, so a workgroup needs 73 KB of LDS and two
-// of them share a compute unit: one loads while the other multiplies.
+// A 128 x 128 tile X (PT x PT pivot-pair blocks) stays resident in LDS while the pivot transforms of
+// its PT column pairs (then of its PT row pairs), laid side by side as a KP x 128 matrix, are
+// streamed from global memory (L2) in 8-row slabs through a small double buffer.  A workgroup needs
+// 73 KB of LDS, so two share a compute unit: one loads while the other multiplies.  Wave (a, b) owns
+// the 64 x 64 quadrant (a, b) of the tile; with KP = 64 that quadrant is one pair-block and its
+// product runs over that block's own 64 contraction indices.
 constexpr int SLAB_K = 8;
-constexpr int SLAB_LD = SK + 4;
-constexpr size_t APPLY_LDS_BYTES = (size_t)(SK * SLD + 2 * SLAB_K * SLAB_LD) * sizeof(float);
+constexpr int SLAB_LD = TS + 4;
+constexpr size_t APPLY_LDS_BYTES = (size_t)(TS * XLD + 2 * SLAB_K * SLAB_LD) * sizeof(float);
 
-// acc = X * Jm (X_LEFT: A(m,k) = Xs[m][k], B(k,n) = Jm[k][n]) or acc = Jm^T * X (A(m,k) = Jm[k][m],
-// B(k,n) = Xs[k][n]); Jm is row-major [128][128] in global memory.
+struct TilePairs {      // the PT pivot pairs along one edge of a tile
+    int p[PT], q[PT];
+    bool valid[PT];
+};
+
+__device__ inline TilePairs tile_pairs(const BlkGroup &g, int round, int tile) {
+    TilePairs tp;
+#pragma unroll
+    for (int u = 0; u < PT; ++u) {
+        const int pair = tile * PT + u;
+        tp.valid[u] = pair < g.npairs;
+        tp.p[u] = tp.q[u] = 0;
+        if (tp.valid[u]) rr_pair(g.players, round, pair, tp.p[u], tp.q[u]);
+    }
+    return tp;
+}
+
+// global row/column of tile coordinate a (0..127), or -1
+__device__ inline int tile_index(const TilePairs &tp, int a, int nblk) {
+    const int u = a / KP;
+    return tp.valid[u] ? pair_index(a % KP, tp.p[u], tp.q[u], nblk) : -1;
+}
+
+// The KP x 128 panel [J_0 | J_1 ..] of a tile edge (row-major KP x KP transforms of its PT pairs, first
+// pair `pair0`), fetched whole into registers: thread t holds float4 number t of every 8-row slab.
+constexpr int NSLAB = KP / SLAB_K;
+struct Panel { float4 v[NSLAB]; };
+
+__device__ inline void panel_fetch(Panel &pan, const float *__restrict__ Jall, int pair0, int npairs) {
+    const int tid = threadIdx.x;
+    const int srow = tid >> 5, scol = (tid & 31) * 4;
+    const int spair = pair0 + scol / KP;
+    const bool sval = spair < npairs;
+    const float *src = Jall + (int64_t)(sval ? spair : pair0) * (KP * KP) + (scol % KP) + srow * KP;
+#pragma unroll
+    for (int sl = 0; sl < NSLAB; ++sl)
+        pan.v[sl] = sval ? *reinterpret_cast<const float4 *>(src + sl * SLAB_K * KP) : make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// acc = X * panel (X_LEFT: A(m,k) = Xs[m][k], B(k,n) = panel[k][n]) or acc = panel^T * X (A(m,k) =
+// panel[k][m], B(k,n) = Xs[k][n]); the panel goes through LDS slab by slab from registers, so no global
+// latency sits inside the product.
 template <bool X_LEFT>
-__device__ inline void stream_gemm128(const float *Xs, const float *__restrict__ Jm, float (*slab)[SLAB_K][SLAB_LD],
-                                      floatx16 (&acc)[2][2]) {
+__device__ inline void panel_gemm(const float *Xs, const Panel &pan, float (*slab)[SLAB_K][SLAB_LD],
+                                  floatx16 (&acc)[2][2]) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int lk = lane >> 5, lc = lane & 31;
-    const int srow = tid >> 5, scol = (tid & 31) * 4;   // this thread's float4 of every slab
+    const int srow = tid >> 5, scol = (tid & 31) * 4;
+    // contraction offset inside the resident tile: with KP = 64 each quadrant multiplies its own block
+    const int koff = (KP == TS) ? 0 : (X_LEFT ? wn : wm);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    float4 pre = *reinterpret_cast<const float4 *>(Jm + srow * SK + scol);
-    *reinterpret_cast<float4 *>(&slab[0][srow][scol]) = pre;
+    *reinterpret_cast<float4 *>(&slab[0][srow][scol]) = pan.v[0];
     __syncthreads();
-    constexpr int NSLAB = SK / SLAB_K;
+#pragma unroll
     for (int sl = 0; sl < NSLAB; ++sl) {
         const int cur = sl & 1;
-        if (sl + 1 < NSLAB) pre = *reinterpret_cast<const float4 *>(Jm + ((sl + 1) * SLAB_K + srow) * SK + scol);
+        if (sl + 1 < NSLAB) *reinterpret_cast<float4 *>(&slab[cur ^ 1][srow][scol]) = pan.v[sl + 1];
 #pragma unroll
         for (int kk = 0; kk < SLAB_K; kk += 2) {
-            const int k = sl * SLAB_K + kk + lk;
+            const int k = koff + sl * SLAB_K + kk + lk;
             float a0, a1, b0, b1;
             if (X_LEFT) {
-                a0 = Xs[(wm + lc) * SLD + k];
-                a1 = Xs[(wm + 32 + lc) * SLD + k];
+                a0 = Xs[(wm + lc) * XLD + k];
+                a1 = Xs[(wm + 32 + lc) * XLD + k];
                 b0 = slab[cur][kk + lk][wn + lc];
                 b1 = slab[cur][kk + lk][wn + 32 + lc];
             } else {
                 a0 = slab[cur][kk + lk][wm + lc];
                 a1 = slab[cur][kk + lk][wm + 32 + lc];
-                b0 = Xs[k * SLD + wn + lc];
-                b1 = Xs[k * SLD + wn + 32 + lc];
+                b0 = Xs[k * XLD + wn + lc];
+                b1 = Xs[k * XLD + wn + 32 + lc];
             }
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
         }
-        if (sl + 1 < NSLAB) *reinterpret_cast<float4 *>(&slab[cur ^ 1][srow][scol]) = pre;
         __syncthreads();
     }
+}
+
+__device__ inline void acc_to_tile(const floatx16 (&acc)[2][2], float *X) {
+    kfac::for_each_acc(acc, [&](int r, int c, float v) { X[r * XLD + c] = v; });
 }
 
 // Tile <-> global memory, four consecutive columns per access.  rowf(a) / colf(b) give the global row
@@ -477,7 +567,7 @@ __device__ inline void tile_load(float *Xs, const float *G, int64_t ld, RowF row
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int e4 = threadIdx.x + NT * (t0 + u);
-            float *dst = Xs + (e4 >> 5) * SLD + (e4 & 31) * 4;
+            float *dst = Xs + (e4 >> 5) * XLD + (e4 & 31) * 4;
             dst[0] = v[u].x; dst[1] = v[u].y; dst[2] = v[u].z; dst[3] = v[u].w;
         }
     }
@@ -492,66 +582,84 @@ __device__ inline void tile_store(const float *Xs, float *G, int64_t ld, RowF ro
         if (!TRANSPOSED) {
             const int a = e4 >> 5, b = (e4 & 31) * 4;
             const int gi = rowf(a), gj = colf(b);
-            const float *src = Xs + a * SLD + b;
+            const float *src = Xs + a * XLD + b;
             if (gi >= 0 && gj >= 0)
                 *reinterpret_cast<float4 *>(G + (int64_t)gi * ld + gj) = make_float4(src[0], src[1], src[2], src[3]);
         } else {
             const int b = e4 >> 5, a = (e4 & 31) * 4;
             const int gi = rowf(a), gj = colf(b);
-            const float *src = Xs + a * SLD + b;
+            const float *src = Xs + a * XLD + b;
             if (gi >= 0 && gj >= 0)
                 *reinterpret_cast<float4 *>(G + (int64_t)gj * ld + gi) =
-                    make_float4(src[0], src[SLD], src[2 * SLD], src[3 * SLD]);
+                    make_float4(src[0], src[XLD], src[2 * XLD], src[3 * XLD]);
         }
     }
 }
 
-// One round of transforms: W_IJ <- J_I^T W_IJ J_J for pair-tiles I >= J (mirrored into J,I), and
+// One round of transforms: W_IJ <- J_I^T W_IJ J_J for tiles I >= J (mirrored into J,I), and
 // Qw[:, J] <- Qw[:, J] J_J for every 128-row slab of the accumulator.
 __global__ __launch_bounds__(NT, 2) void blk_apply_kernel(BlkGroup g, int round, int ntiles_w, int nrb) {
     extern __shared__ __align__(16) char smem[];
     float *Xs = (float *)smem;
-    float(*slab)[SLAB_K][SLAB_LD] = reinterpret_cast<float(*)[SLAB_K][SLAB_LD]>(Xs + SK * SLD);
+    float(*slab)[SLAB_K][SLAB_LD] = reinterpret_cast<float(*)[SLAB_K][SLAB_LD]>(Xs + TS * XLD);
     const int m = blockIdx.y;
     const int64_t np2 = (int64_t)g.npad * g.npad;
     const int *idt = g.idt + m * g.npairs;
-    const float *Jall = g.J + (int64_t)m * g.npairs * (SK * SK);
+    const float *Jall = g.J + (int64_t)m * g.npairs * (KP * KP);
     const int nblk = g.nblk;
     floatx16 acc[2][2];
+    auto all_identity = [&](int tile) {
+        bool idn = true;
+        for (int u = 0; u < PT; ++u) {
+            const int pair = tile * PT + u;
+            if (pair < g.npairs) idn = idn && idt[pair];
+        }
+        return idn;
+    };
     if ((int)blockIdx.x < ntiles_w) {
         float *W = g.W + m * np2;
-        int I, Jp;
-        tri_decode(blockIdx.x, I, Jp);
-        if (idt[I] && idt[Jp]) return;
-        int pi, qi, pj, qj;
-        rr_pair(g.players, round, I, pi, qi);
-        rr_pair(g.players, round, Jp, pj, qj);
-        auto rowf = [=](int a) { return pair_index(a, pi, qi, nblk); };
-        auto colf = [=](int b) { return pair_index(b, pj, qj, nblk); };
+        int I, Jt;
+        tri_decode(blockIdx.x, I, Jt);
+        if (all_identity(I) && all_identity(Jt)) return;
+        const TilePairs rows = tile_pairs(g, round, I), cols = tile_pairs(g, round, Jt);
+        auto rowf = [&](int a) { return tile_index(rows, a, nblk); };
+        auto colf = [&](int b) { return tile_index(cols, b, nblk); };
+        Panel pc, pr;
+        panel_fetch(pc, Jall, Jt * PT, g.npairs);
         tile_load(Xs, W, g.npad, rowf, colf);
+        panel_fetch(pr, Jall, I * PT, g.npairs);    // in flight during the first product
         __syncthreads();
-        stream_gemm128<true>(Xs, Jall + (int64_t)Jp * (SK * SK), slab, acc);   // T = X J_J
-        acc_to_lds(acc, Xs);   // every wave passed the last barrier of the product: X is dead
+        panel_gemm<true>(Xs, pc, slab, acc);    // T = X J_cols
+        acc_to_tile(acc, Xs);   // every wave passed the last barrier of the product: X is dead
         __syncthreads();
-        stream_gemm128<false>(Xs, Jall + (int64_t)I * (SK * SK), slab, acc);   // W' = J_I^T T
-        acc_to_lds(acc, Xs);
+        panel_gemm<false>(Xs, pr, slab, acc);   // W' = J_rows^T T
+        acc_to_tile(acc, Xs);
         __syncthreads();
+        if (I == Jt) {
+            // a diagonal tile holds both halves of its off-diagonal pair blocks: keep the lower one
+            for (int e = threadIdx.x; e < TS * TS; e += NT) {
+                const int a = e >> 7, b = e & 127;
+                if (b > a) Xs[a * XLD + b] = Xs[b * XLD + a];
+            }
+            __syncthreads();
+        }
         tile_store<false>(Xs, W, g.npad, rowf, colf);
-        if (I != Jp) tile_store<true>(Xs, W, g.npad, rowf, colf);
+        if (I != Jt) tile_store<true>(Xs, W, g.npad, rowf, colf);
     } else {
         float *Qw = g.Qw + m * np2;
         const int t = blockIdx.x - ntiles_w;
-        const int rb = t % nrb, Jp = t / nrb;
-        if (idt[Jp]) return;
-        int pj, qj;
-        rr_pair(g.players, round, Jp, pj, qj);
-        const int row0 = rb * SK, npad = g.npad;
-        auto rowf = [=](int a) { return row0 + a < npad ? row0 + a : -1; };
-        auto colf = [=](int b) { return pair_index(b, pj, qj, nblk); };
+        const int rb = t % nrb, Jt = t / nrb;
+        if (all_identity(Jt)) return;
+        const TilePairs cols = tile_pairs(g, round, Jt);
+        const int row0 = rb * TS, npad = g.npad;
+        auto rowf = [&](int a) { return row0 + a < npad ? row0 + a : -1; };
+        auto colf = [&](int b) { return tile_index(cols, b, nblk); };
+        Panel pc;
+        panel_fetch(pc, Jall, Jt * PT, g.npairs);
         tile_load(Xs, Qw, g.npad, rowf, colf);
         __syncthreads();
-        stream_gemm128<true>(Xs, Jall + (int64_t)Jp * (SK * SK), slab, acc);
-        acc_to_lds(acc, Xs);
+        panel_gemm<true>(Xs, pc, slab, acc);
+        acc_to_tile(acc, Xs);
         __syncthreads();
         tile_store<false>(Xs, Qw, g.npad, rowf, colf);
     }
@@ -564,11 +672,6 @@ struct EpiNewtonSchulz {
     int64_t ld;
     __device__ void operator()(int r, int c, float v) const { Y[(int64_t)r * ld + c] = (r == c ? 1.5f : 0.f) - 0.5f * v; }
 };
-
-__global__ void blk_zero_f64_kernel(double *p, int count) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) p[i] = 0.0;
-}
 
 // Rayleigh quotients lam[i] = q_i^T (F q_i) from Q [n][ldq] and Z = F Q [n][ldz]; rows split over blockIdx.y.
 __global__ __launch_bounds__(NT) void blk_rayleigh_kernel(const float *Q, int64_t ldq, const float *Z, int64_t ldz,
@@ -596,6 +699,10 @@ __global__ __launch_bounds__(NT) void blk_rank_kernel(const double *lam64, int n
     lam_out[rank] = li;
 }
 
+__global__ __launch_bounds__(NT) void blk_copy_kernel(const float *src, float *dst, int64_t count) {
+    for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < count; e += (int64_t)gridDim.x * NT) dst[e] = src[e];
+}
+
 // Qout[i][j] = Qin[i][perm[j]]
 __global__ __launch_bounds__(NT) void blk_gather_kernel(const float *Qin, int64_t ldin, float *Qout, int n, const int *perm) {
     const int64_t n2 = (int64_t)n * n;
@@ -609,13 +716,13 @@ __global__ __launch_bounds__(NT) void blk_gather_kernel(const float *Qin, int64_
 
 // ---- host side ---------------------------------------------------------------------------------
 struct GroupPlan {
-    int nblk, npad, players, npairs;
+    int nblk, npad, players, npairs, npp;
     std::vector<int> members;
     size_t bytes() const {
         const size_t nm = members.size();
         size_t b = 0;
         b += kfac_align_up(nm * 2 * (size_t)npad * npad * sizeof(float), 256);       // W, Qw
-        b += kfac_align_up(nm * (size_t)npairs * SK * SK * sizeof(float), 256);      // J
+        b += kfac_align_up(nm * (size_t)npairs * KP * KP * sizeof(float), 256);      // J
         b += kfac_align_up(nm * (size_t)npairs * sizeof(int), 256);                  // idt
         b += kfac_align_up(nm * 2 * sizeof(double), 256);                            // norms
         b += kfac_align_up(nm * (size_t)npad * sizeof(int), 256);                    // perm
@@ -627,7 +734,7 @@ struct GroupPlan {
 
 void make_plan(int batch, const int *d, std::vector<int> &small, std::vector<GroupPlan> &groups) {
     for (int i = 0; i < batch; ++i) {
-        if (d[i] <= KFAC_EIG_SMALL) { small.push_back(i); continue; }
+        if (d[i] <= SMALL_MAX) { small.push_back(i); continue; }
         const int nblk = (d[i] + EB - 1) / EB;
         GroupPlan *gp = nullptr;
         for (auto &g : groups) if (g.nblk == nblk) gp = &g;
@@ -637,6 +744,7 @@ void make_plan(int batch, const int *d, std::vector<int> &small, std::vector<Gro
             g.npad = nblk * EB;
             g.players = (nblk + 1) & ~1;
             g.npairs = g.players / 2;
+            g.npp = (g.npairs + PT - 1) / PT;
             groups.push_back(g);
             gp = &groups.back();
         }
@@ -661,7 +769,7 @@ struct GroupRun {
     double *lam64;
     double *h_norms;      // pinned, 2 per factor
     int nm, ntiles_w, nrb, ntiles, nmax, fill_blocks;
-    double apply_flops;
+    double apply_flops, solve_flops;
     int sweep;
     bool done;
     std::vector<char> conv;
@@ -681,15 +789,15 @@ int enqueue_offnorm(kfac_ctx *ctx, GroupRun &r) {
     return KFAC_OK;
 }
 
-int enqueue_sweep(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, size_t lds_apply, int inner_cap, float inner_tol) {
+int enqueue_sweep(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int inner_cap, float inner_tol) {
     for (int rd = 0; rd < r.plan->players - 1; ++rd) {
         {
-            KfacProfScope prof(ctx, KC_EIG_SOLVE, 0.0, 0.0, r.st);
+            KfacProfScope prof(ctx, KC_EIG_SOLVE, r.solve_flops, 0.0, r.st);
             hipLaunchKernelGGL(blk_solve_kernel, dim3(r.plan->npairs, r.nm), dim3(NT), lds_solve, r.st, r.g, rd, inner_cap, inner_tol);
         }
         {
             KfacProfScope prof(ctx, KC_EIG_APPLY, r.apply_flops, 0.0, r.st);
-            hipLaunchKernelGGL(blk_apply_kernel, dim3(r.ntiles, r.nm), dim3(NT), lds_apply, r.st, r.g, rd, r.ntiles_w, r.nrb);
+            hipLaunchKernelGGL(blk_apply_kernel, dim3(r.ntiles, r.nm), dim3(NT), APPLY_LDS_BYTES, r.st, r.g, rd, r.ntiles_w, r.nrb);
         }
     }
     KFAC_HIP_CHECK(hipGetLastError());
@@ -730,12 +838,19 @@ int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
             hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(qo_kn), EpiStore>), grid, block, 0, st,
                                f_mk, qo_kn, EpiStore{Qm, ld}, n, n, n);
         }
-        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
         double *l64 = r.lam64 + (size_t)i * gp.npad;
         int *pm = r.perm + (size_t)i * gp.npad;
-        hipLaunchKernelGGL(blk_rayleigh_kernel, dim3((n + NT - 1) / NT, 32), dim3(NT), 0, st, r.items[i].Q, (int64_t)n, Qm, ld, n, l64);
-        hipLaunchKernelGGL(blk_rank_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, l64, n, pm, r.items[i].lam);
-        KFAC_HIP_CHECK(hipMemcpyAsync(Wm, r.items[i].Q, (size_t)n * n * sizeof(float), hipMemcpyDeviceToDevice, st));
+        {
+            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+            hipLaunchKernelGGL(blk_rayleigh_kernel, dim3((n + NT - 1) / NT, 32), dim3(NT), 0, st, r.items[i].Q, (int64_t)n, Qm, ld, n, l64);
+            hipLaunchKernelGGL(blk_rank_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, l64, n, pm, r.items[i].lam);
+        }
+        {
+            // plain copy of n*n floats (read + write): also the reference point for HBM traffic counters
+            KfacProfScope prof(ctx, KC_EIG_COPY, 0.0, 8.0 * n * n, st);
+            hipLaunchKernelGGL(blk_copy_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, r.items[i].Q, Wm, (int64_t)n * n);
+        }
+        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
         hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, Wm, (int64_t)n, r.items[i].Q, n, pm);
     }
     KFAC_HIP_CHECK(hipGetLastError());
@@ -764,17 +879,17 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     std::vector<GroupPlan> groups;
     make_plan(batch, d, small, groups);
     if (kfac_eig_ws_bytes_impl(batch, d) > ctx->ws_bytes) return KFAC_EWORKSPACE;
+    if (groups.size() > (size_t)KFAC_MAX_GROUPS) return KFAC_EINVAL;
     size_t pinned_need = 0;
     for (auto &gp : groups) pinned_need += 2 * gp.members.size() * sizeof(double);
     if (pinned_need > ctx->pinned_bytes) return KFAC_EWORKSPACE;
     const int inner_cap = 1;       // one Jacobi sweep over a pivot per visit: fewest total rotations
     const float inner_tol = 1e-7f;
-    const size_t lds_solve = JacobiSmem::bytes(SK, SLD);
-    const size_t lds_apply = APPLY_LDS_BYTES;
+    const size_t lds_solve = JacobiSmem::bytes(KP, PLD);
     if (!groups.empty()) {
-        if ((int)lds_solve > ctx->max_lds || (int)lds_apply > ctx->max_lds) return KFAC_EHIP;
+        if ((int)lds_solve > ctx->max_lds || (int)APPLY_LDS_BYTES > ctx->max_lds) return KFAC_EHIP;
         KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_solve));
-        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_apply));
+        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)APPLY_LDS_BYTES));
     }
     bool all_conv = true;
 
@@ -786,7 +901,6 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     // ---- small factors: one launch, on the last internal stream ----
     std::vector<SmallItem> sitems;
     std::vector<EigStat> sstats;
-    EigStat *d_stats = nullptr;
     hipStream_t st_small = ctx->aux[KFAC_NUM_AUX_STREAMS - 1];
     if (!small.empty()) {
         const size_t ns = small.size();
@@ -798,7 +912,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             kmax = std::max(kmax, (d[small[i]] + 1) & ~1);
         }
         SmallItem *d_items = (SmallItem *)wsp;
-        d_stats = (EigStat *)(wsp + kfac_align_up(ns * sizeof(SmallItem), 256));
+        EigStat *d_stats = (EigStat *)(wsp + kfac_align_up(ns * sizeof(SmallItem), 256));
         wsp += small_bytes(ns);
         KFAC_HIP_CHECK(hipMemcpyAsync(d_items, sitems.data(), ns * sizeof(SmallItem), hipMemcpyHostToDevice, st_small));
         const size_t lds = JacobiSmem::bytes(kmax, kmax + 1);
@@ -821,17 +935,16 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         r.plan = &gp;
         r.nm = (int)gp.members.size();
         r.st = ctx->aux[gi % KFAC_NUM_AUX_STREAMS];
-        r.ev = ctx->ev_group[gi % KFAC_MAX_GROUPS];
-        if (gi >= KFAC_MAX_GROUPS) return KFAC_EINVAL;
+        r.ev = ctx->ev_group[gi];
         const size_t np2 = (size_t)gp.npad * gp.npad;
         const int nm = r.nm;
         char *p = wsp;
         BlkGroup &g = r.g;
-        g.nmat = nm; g.nblk = gp.nblk; g.npad = gp.npad; g.players = gp.players; g.npairs = gp.npairs;
+        g.nmat = nm; g.nblk = gp.nblk; g.npad = gp.npad; g.players = gp.players; g.npairs = gp.npairs; g.npp = gp.npp;
         g.W = (float *)p;
         g.Qw = g.W + nm * np2;
         p += kfac_align_up(nm * 2 * np2 * sizeof(float), 256);
-        g.J = (float *)p; p += kfac_align_up((size_t)nm * gp.npairs * SK * SK * sizeof(float), 256);
+        g.J = (float *)p; p += kfac_align_up((size_t)nm * gp.npairs * KP * KP * sizeof(float), 256);
         g.idt = (int *)p; p += kfac_align_up((size_t)nm * gp.npairs * sizeof(int), 256);
         g.norms = (double *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(double), 256);
         r.perm = (int *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(int), 256);
@@ -848,12 +961,14 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             r.items[i] = BlkItem{F[b], Q[b], lam[b], d[b], 0};
             r.nmax = std::max(r.nmax, d[b]);
             // algorithmic work of one round: W <- J^T W J on half the (symmetric) matrix and Q <- Q J,
-            // each element a length-2B dot product: 8 n^2 B flops per factor
+            // each element a length-2*EB dot product: 8 n^2 EB flops per factor
             r.apply_flops += 8.0 * (double)d[b] * d[b] * EB;
         }
-        r.ntiles_w = gp.npairs * (gp.npairs + 1) / 2;
-        r.nrb = (r.nmax + SK - 1) / SK;
-        r.ntiles = r.ntiles_w + r.nrb * gp.npairs;
+        // one inner sweep per pivot: KP-1 rounds, 9 flops per element per round (S rotated twice, V once)
+        r.solve_flops = (double)nm * gp.npairs * 9.0 * KP * KP * (KP - 1);
+        r.ntiles_w = gp.npp * (gp.npp + 1) / 2;
+        r.nrb = (r.nmax + TS - 1) / TS;
+        r.ntiles = r.ntiles_w + r.nrb * gp.npp;
         r.fill_blocks = (int)std::min<size_t>((np2 + NT - 1) / NT, 4096);
         r.sweep = 0;
         r.done = false;
@@ -869,7 +984,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         int rc = enqueue_offnorm(ctx, r);
         if (rc) return rc;
     }
-    // state per group: waiting for norms (post == false) or for its post-processing (post == true)
+    // state per group: waiting for norms (post == 0) or for its post-processing (post == 1)
     std::vector<char> post(runs.size(), 0);
     size_t remaining = runs.size();
     while (remaining > 0) {
@@ -896,7 +1011,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
                 rc = enqueue_post(ctx, r);
                 post[gi] = 1;
             } else {
-                rc = enqueue_sweep(ctx, r, lds_solve, lds_apply, inner_cap, inner_tol);
+                rc = enqueue_sweep(ctx, r, lds_solve, inner_cap, inner_tol);
                 if (rc == KFAC_OK) rc = enqueue_offnorm(ctx, r);
                 ++r.sweep;
             }
@@ -915,16 +1030,14 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     }
     for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) KFAC_HIP_CHECK(hipStreamSynchronize(ctx->aux[i]));
 
-    if (!small.empty()) {
-        for (size_t i = 0; i < small.size(); ++i) {
-            const bool conv = sstats[i].converged > 0.5f;
-            all_conv &= conv;
-            const double k = (d[small[i]] + 1) & ~1;   // 9 flops per element per round: S twice, V once
-            if (ctx->prof_on)
-                for (auto &pr : ctx->prof)
-                    if (pr.cls == KC_EIG_SMALL) { pr.flops += sstats[i].sweeps * 9.0 * k * k * (k - 1); break; }
-            if (info) info[small[i]] = kfac_eig_info{(int)sstats[i].sweeps, sstats[i].off_rel, conv ? 1 : 0};
-        }
+    for (size_t i = 0; i < small.size(); ++i) {
+        const bool conv = sstats[i].converged > 0.5f;
+        all_conv &= conv;
+        const double k = (d[small[i]] + 1) & ~1;   // 9 flops per element per round: S twice, V once
+        if (ctx->prof_on)
+            for (auto it = ctx->prof.rbegin(); it != ctx->prof.rend(); ++it)
+                if (it->cls == KC_EIG_SMALL) { it->flops += sstats[i].sweeps * 9.0 * k * k * (k - 1); break; }
+        if (info) info[small[i]] = kfac_eig_info{(int)sstats[i].sweeps, sstats[i].off_rel, conv ? 1 : 0};
     }
     for (auto &r : runs) {
         for (int i = 0; i < r.nm; ++i) {

@@ -9,7 +9,7 @@
 // Kernel classes for the optional per-kernel timing (kfac_profile_begin / kfac_profile_end).
 enum KfacKernelClass {
     KC_UNFOLD = 0, KC_SYRK, KC_SYRK_REDUCE, KC_PRECOND_GEMM, KC_EIG_SMALL, KC_EIG_SOLVE, KC_EIG_APPLY,
-    KC_EIG_MISC, KC_EIG_POST, KC_COUNT
+    KC_EIG_MISC, KC_EIG_POST, KC_EIG_COPY, KC_COUNT
 };
 struct KfacProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
 
@@ -66,7 +66,7 @@ static inline size_t kfac_align_up(size_t x, size_t a) { return (x + a - 1) / a 
 // Tiling constants shared between host-side sizing and kernels.
 constexpr int KFAC_TILE = 128;       // GEMM / SYRK output tile edge
 constexpr int KFAC_EIG_SMALL = 128;  // factors up to this size are solved inside one workgroup's LDS
-constexpr int KFAC_EIG_B = 64;       // block size of the blocked Jacobi path (sub-problems are 2B x 2B)
+constexpr int KFAC_EIG_B = 32;       // block size of the blocked Jacobi path (sub-problems are 2B x 2B)
 constexpr int KFAC_MAX_D = 8192;
 
 // ---- launchers implemented in the kernel files (all enqueue on ctx->stream) ----

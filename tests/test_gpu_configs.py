@@ -1,0 +1,298 @@
+"""GPU parity on the five benchmark configurations, in the launch configuration bench.py times
+(paper_2007_00784_amd.runner.KfacRunner over the whole layer set).
+
+Small configurations are compared with the oracle element by element.  At the ResNet-50 sizes the
+oracle is used where it can finish in seconds -- sampled factor entries, one mid-size layer end to end,
+the largest factor once -- and everything else is checked through properties that hold at any size and
+need only fp64 matrix products: symmetry, ||F - Q diag(lam) Q^T||, Q^T Q = I, and the defining equation
+of the preconditioned gradient  G X A + gamma X = grad  (Sec. IV-A: X = (G (x) A + gamma I)^-1 grad).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2007_00784_amd import kfac as K
+from paper_2007_00784_amd import synthetic as S
+from paper_2007_00784_amd.runner import KfacRunner
+from gpu_util import relfro
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32, TOL_BF16, TOL_RES, TOL_LAM = 1e-4, 2e-2, 1e-5, 1e-5
+
+
+def f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def rows_of(t, fc):
+    """device activation / gradient tensor -> [R, d] float64 sample rows."""
+    a = f64(t)
+    return a if fc else a.reshape(a.shape[0], a.shape[1], -1).transpose(0, 2, 1).reshape(-1, a.shape[1])
+
+
+def oracle_factors(run, i, n_updates):
+    """Oracle A and G of runner layer i after n_updates factor updates (first with decay 0)."""
+    l = run.layers[i]
+    A = G = None
+    for u in range(n_updates):
+        x = f64(run.x[u][i])
+        P = x if l.fc else oracle.unfold(x, l.k, l.k, l.stride, l.stride, l.pad, l.pad)
+        g = rows_of(run.g[u][i], l.fc)
+        R = P.shape[0]
+        Ab, Gb = oracle.gram(P, 1, 1.0 / R), oracle.gram(g, 0, 1.0 / R)
+        A = Ab if A is None else oracle.ema(A, Ab, run.wl.decay)
+        G = Gb if G is None else oracle.ema(G, Gb, run.wl.decay)
+    return A, G
+
+
+def eig_properties(F, lam, Q, label):
+    F, lam, Q = f64(F), f64(lam), f64(Q)
+    n = F.shape[0]
+    res = np.linalg.norm(F - (Q * lam) @ Q.T) / np.linalg.norm(F)
+    orth = np.linalg.norm(Q.T @ Q - np.eye(n), 2)
+    print("%s d=%d residual=%.2e orth=%.2e" % (label, n, res, orth))
+    assert np.all(np.diff(lam) >= 0), label
+    assert res <= TOL_RES, (label, res)
+    assert orth <= 2e-5, (label, orth)
+
+
+def precondition_equation_residual(run, i, gamma):
+    """|| G X A + gamma X - grad || / || grad || with the GPU's own factors, in fp64."""
+    A, G, X, g0 = f64(run.A[i]), f64(run.G[i]), f64(run.grad[i]), f64(run.gradw_master[i])
+    return np.linalg.norm(G @ X @ A + gamma * X - g0) / np.linalg.norm(g0)
+
+
+def check_scaled_damping(run, i, lamA, QA, lamG, QG):
+    """Parity-only variant with a damping of 1e-3 * mean(lamA) * mean(lamG), far below the spectra, so the
+    step is almost the undamped G^-1 grad A^-1.  Its condition number is that of the factors (>= 1e3: the
+    ReLU mean gives A one eigenvalue ~ 0.16 d_A against a bulk of ~0.3), and an eigendecomposition that
+    is accurate to 1e-5 ||F|| -- the stated tolerance -- moves the result by up to that condition number
+    times 1e-5.  So the preconditioner kernel is held to 1e-4 against the oracle's formula on the same
+    eigenpairs, and the end-to-end difference to the oracle's own eigenpairs to 1e-3."""
+    gamma = 1e-3 * lamA.mean() * lamG.mean()
+    g0 = f64(run.gradw_master[i])
+    g = run.gradw_master[i].clone()
+    K.kfac_precondition(run.ctx, run.QA[i], run.lamA[i], run.QG[i], run.lamG[i], gamma, g)
+    torch.cuda.synchronize()
+    same_pairs = oracle.precondition(f64(run.QA[i]), f64(run.lamA[i]), f64(run.QG[i]), f64(run.lamG[i]), gamma, g0)
+    assert relfro(f64(g), same_pairs) <= TOL_F32
+    assert relfro(f64(g), oracle.precondition(QA, lamA, QG, lamG, gamma, g0)) <= 1e-3
+
+
+@pytest.mark.timeout(600)
+def test_config2_resnet32_cifar_full_parity():
+    """ResNet-32-CIFAR layer set, batch 128, two factor updates: every layer's factors, eigenpairs and
+    preconditioned gradient against the oracle (one layer of each distinct shape for the O(d^3) parts)."""
+    wl = S.workload("resnet32_cifar")
+    run = KfacRunner(wl, n_updates=2)
+    run.update_factors(0, 0.0)
+    run.update_factors(1, wl.decay)
+    info = run.eig()
+    run.precondition()
+    torch.cuda.synchronize()
+    assert all(c for (_, _, c) in info)
+    seen = set()
+    for i, l in enumerate(run.layers):
+        shape = (l.c_in, l.c_out, l.k, l.stride, l.h_in)
+        A, G = oracle_factors(run, i, 2)
+        assert relfro(f64(run.A[i]), A) <= TOL_F32, l.name
+        assert relfro(f64(run.G[i]), G) <= TOL_F32, l.name
+        assert precondition_equation_residual(run, i, wl.damping) <= TOL_F32, l.name
+        if shape in seen:
+            continue
+        seen.add(shape)
+        eig_properties(run.A[i], run.lamA[i], run.QA[i], l.name + ".A")
+        eig_properties(run.G[i], run.lamG[i], run.QG[i], l.name + ".G")
+        lamA, QA = oracle.eigh(A)
+        lamG, QG = oracle.eigh(G)
+        assert np.abs(f64(run.lamA[i]) - lamA).max() <= TOL_LAM * lamA.max(), l.name
+        assert np.abs(f64(run.lamG[i]) - lamG).max() <= TOL_LAM * lamG.max(), l.name
+        ref = oracle.precondition(QA, lamA, QG, lamG, wl.damping, f64(run.gradw_master[i]))
+        assert relfro(f64(run.grad[i]), ref) <= TOL_F32, l.name
+    # same layers with a damping scaled to the spectra, so that the eigenvalues really enter the result
+    for i in (1, 12, 23, 33):
+        A, G = oracle_factors(run, i, 2)
+        lamA, QA = oracle.eigh(A)
+        lamG, QG = oracle.eigh(G)
+        gamma = 1e-3 * lamA.mean() * lamG.mean()
+        g = run.gradw_master[i].clone()
+        K.kfac_precondition(run.ctx, run.QA[i], run.lamA[i], run.QG[i], run.lamG[i], gamma, g)
+        torch.cuda.synchronize()
+        ref = oracle.precondition(QA, lamA, QG, lamG, gamma, f64(run.gradw_master[i]))
+        assert relfro(f64(g), ref) <= TOL_F32, run.layers[i].name
+    run.close()
+
+
+@pytest.fixture(scope="module")
+def resnet50_run():
+    wl = S.workload("resnet50")
+    run = KfacRunner(wl, n_updates=2)
+    run.update_factors(0, 0.0)
+    run.update_factors(1, wl.decay)
+    info = run.eig()
+    run.precondition()
+    torch.cuda.synchronize()
+    yield run, info
+    run.close()
+
+
+def test_config3_resnet50_factors_sampled(resnet50_run):
+    """All 108 factors of the ResNet-50 set: symmetric, finite, unit bias corner, and 12 sampled entries
+    per factor against the oracle's one-entry routine (after two updates: EMA of two batch entries)."""
+    run, _ = resnet50_run
+    wl = run.wl
+    rng = np.random.default_rng(0)
+    for i, l in enumerate(run.layers):
+        A, G = f64(run.A[i]), f64(run.G[i])
+        assert np.isfinite(A).all() and np.isfinite(G).all()
+        assert np.array_equal(A, A.T) and np.array_equal(G, G.T)
+        assert abs(A[-1, -1] - 1.0) < 1e-5
+        if i % 3:       # sampled entries on every third layer keep the host time in seconds
+            continue
+        rows = []
+        for u in range(2):
+            x = f64(run.x[u][i])
+            P = x if l.fc else None
+            g = rows_of(run.g[u][i], l.fc)
+            rows.append((x, P, g))
+        for F, d, is_a in ((A, l.d_a, True), (G, l.d_g, False)):
+            nf = np.abs(F).max()
+            for _ in range(12):
+                a, b = int(rng.integers(d)), int(rng.integers(d))
+                val = None
+                for u in range(2):
+                    x, P, g = rows[u]
+                    if is_a:
+                        e = (oracle.conv_factor_entry(x, l.k, l.k, l.stride, l.stride, l.pad, l.pad, 1.0 / (x.shape[0] * l.T), a, b)
+                             if P is None else oracle.gram_entry(P, 1, 1.0 / P.shape[0], a, b))
+                    else:
+                        e = oracle.gram_entry(g, 0, 1.0 / g.shape[0], a, b)
+                    val = e if val is None else wl.decay * val + (1 - wl.decay) * e
+                assert abs(F[a, b] - val) <= 2e-5 * nf + 1e-4 * abs(val), (l.name, is_a, a, b)
+
+
+def test_config3_resnet50_eig_and_precondition_properties(resnet50_run):
+    """Eigenpairs of every factor size class and the preconditioned gradient of every layer through
+    properties computed in fp64 from the GPU's own factors."""
+    run, info = resnet50_run
+    assert all(c for (_, _, c) in info), [x for x in info if not x[2]]
+    assert max(s for (s, _, _) in info) <= 20
+    seen = set()
+    for i, l in enumerate(run.layers):
+        assert precondition_equation_residual(run, i, run.wl.damping) <= TOL_F32, l.name
+        for F, lam, Q, d, tag in ((run.A[i], run.lamA[i], run.QA[i], l.d_a, "A"), (run.G[i], run.lamG[i], run.QG[i], l.d_g, "G")):
+            if d in seen:
+                continue
+            seen.add(d)
+            eig_properties(F, lam, Q, "%s.%s" % (l.name, tag))
+
+
+@pytest.mark.timeout(600)
+def test_config3_resnet50_one_layer_against_oracle(resnet50_run):
+    """A mid-size layer of the set (3x3 conv 256->256 on 14x14: d_A = 2305, d_G = 256) end to end against
+    the oracle, at the reported damping and at a damping scaled to the spectra."""
+    run, _ = resnet50_run
+    i = [k for k, l in enumerate(run.layers) if l.name == "s3b1.conv3"][0]
+    A, G = oracle_factors(run, i, 2)
+    assert relfro(f64(run.A[i]), A) <= TOL_F32
+    assert relfro(f64(run.G[i]), G) <= TOL_F32
+    lamA, QA = oracle.eigh(A)
+    lamG, QG = oracle.eigh(G)
+    assert np.abs(f64(run.lamA[i]) - lamA).max() <= TOL_LAM * lamA.max()
+    assert np.abs(f64(run.lamG[i]) - lamG).max() <= TOL_LAM * lamG.max()
+    g0 = f64(run.gradw_master[i])
+    assert relfro(f64(run.grad[i]), oracle.precondition(QA, lamA, QG, lamG, run.wl.damping, g0)) <= TOL_F32
+    check_scaled_damping(run, i, lamA, QA, lamG, QG)
+
+
+@pytest.mark.timeout(900)
+def test_config4_largest_factor_ill_conditioned():
+    """3x3 conv 512->512 on 7x7, batch 64, activation channels scaled over 1e-3..1e1: A is 4609 x 4609 of
+    rank <= 3136; full parity with the oracle (its Householder + QR eigensolver at d = 4609)."""
+    wl = S.workload("largest_factor")
+    run = KfacRunner(wl, n_updates=1)
+    run.update_factors(0, 0.0)
+    info = run.eig()
+    run.precondition()
+    torch.cuda.synchronize()
+    assert all(c for (_, _, c) in info), info
+    A, G = oracle_factors(run, 0, 1)
+    assert relfro(f64(run.A[0]), A) <= TOL_F32
+    assert relfro(f64(run.G[0]), G) <= TOL_F32
+    eig_properties(run.A[0], run.lamA[0], run.QA[0], "A")
+    eig_properties(run.G[0], run.lamG[0], run.QG[0], "G")
+    lamA, QA = oracle.eigh(A)
+    lamG, QG = oracle.eigh(G)
+    gl = f64(run.lamA[0])
+    assert np.abs(gl - lamA).max() <= TOL_LAM * lamA.max()
+    assert np.abs(f64(run.lamG[0]) - lamG).max() <= TOL_LAM * lamG.max()
+    # rank deficiency: at least d - R eigenvalues at noise level on both sides
+    R = wl.batch * wl.layers[0].T
+    assert (np.abs(gl) <= 1e-5 * gl.max()).sum() >= 4609 - R
+    assert (np.abs(lamA) <= 1e-9 * lamA.max()).sum() >= 4609 - R - 1
+    g0 = f64(run.gradw_master[0])
+    assert relfro(f64(run.grad[0]), oracle.precondition(QA, lamA, QG, lamG, wl.damping, g0)) <= TOL_F32
+    assert precondition_equation_residual(run, 0, wl.damping) <= TOL_F32
+    check_scaled_damping(run, 0, lamA, QA, lamG, QG)
+    run.close()
+
+
+@pytest.mark.timeout(600)
+def test_config5_bf16_schedule():
+    """ResNet-50 set, batch 64, bf16 activations / gradients, fp32 factors and eigensolve, update-decoupled
+    schedule (factors every 10 iterations, eigendecompositions every 100, precondition always), run for
+    the first 21 iterations of the 200 (the pattern repeats); parity at iterations 0, 10 and 20 on three
+    layers against the oracle fed the same bf16-rounded inputs, and against the unrounded fp32 masters."""
+    wl = S.workload("resnet50_bf16")
+    names = ["s3b1.reduce", "s4b0.proj", "fc"]       # a 1x1 (no unfold), a strided 1x1 (unfold), the FC layer
+    layers = [i for i, l in enumerate(wl.layers) if l.name in names]
+    run = KfacRunner(wl, n_updates=2, layers=layers)
+    counts = dict(f=0, e=0, p=0)
+    n_fac = 0
+    ref = {}
+    for k in range(21):
+        do_f, do_e = K.kfac_schedule_due(k, 10, 100)
+        if do_f:
+            run.update_factors(n_fac % 2, 0.0 if n_fac == 0 else wl.decay)
+            n_fac += 1
+            counts["f"] += 1
+        if do_e:
+            info = run.eig()
+            counts["e"] += 1
+            assert all(c for (_, _, c) in info)
+        run.precondition()
+        counts["p"] += 1
+        if k in (0, 10, 20):
+            torch.cuda.synchronize()
+            for jj, li in enumerate(layers):
+                l = run.layers[jj]
+                # oracle on the rounded inputs: replay the factor updates so far
+                A = G = None
+                for u in range(n_fac):
+                    x = f64(run.x[u % 2][jj])
+                    P = x if l.fc else oracle.unfold(x, l.k, l.k, l.stride, l.stride, l.pad, l.pad)
+                    g = rows_of(run.g[u % 2][jj], l.fc)
+                    Rr = P.shape[0]
+                    Ab, Gb = oracle.gram(P, 1, 1.0 / Rr), oracle.gram(g, 0, 1.0 / Rr)
+                    A = Ab if A is None else oracle.ema(A, Ab, wl.decay)
+                    G = Gb if G is None else oracle.ema(G, Gb, wl.decay)
+                assert relfro(f64(run.A[jj]), A) <= TOL_F32, (k, l.name)
+                assert relfro(f64(run.G[jj]), G) <= TOL_F32, (k, l.name)
+                if k == 0:
+                    lamA, QA = oracle.eigh(A)
+                    lamG, QG = oracle.eigh(G)
+                    ref[jj] = (lamA, QA, lamG, QG)
+                    # quantisation included: against the oracle on the unrounded fp32 masters
+                    t = S.layer_inputs(wl, li, update=0, batch=wl.batch)
+                    xm = t["x"].astype(np.float64)
+                    Pm = xm if l.fc else oracle.unfold(xm, l.k, l.k, l.stride, l.stride, l.pad, l.pad)
+                    Am = oracle.gram(Pm, 1, 1.0 / Pm.shape[0])
+                    assert relfro(f64(run.A[jj]), Am) <= TOL_BF16, l.name
+                # the eigenbasis in use is the stale one of iteration 0 (eig is due every 100 iterations)
+                lamA, QA, lamG, QG = ref[jj]
+                want = oracle.precondition(QA, lamA, QG, lamG, wl.damping, f64(run.gradw_master[jj]))
+                assert relfro(f64(run.grad[jj]), want) <= TOL_BF16, (k, l.name)
+    assert counts == dict(f=3, e=1, p=21)
+    run.close()

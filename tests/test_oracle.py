@@ -189,6 +189,18 @@ def test_gram_invariants():
     assert v @ F @ v >= 0
 
 
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_factor_entry_matches_gram_of_unfold(case):
+    N, C, H, W, kh, kw, sh, sw, ph, pw = case
+    x = np.maximum(rng(20).standard_normal((N, C, H, W)), 0)
+    P = oracle.unfold(x, kh, kw, sh, sw, ph, pw)
+    F = oracle.gram(P, 1, 1.0 / P.shape[0])
+    d = F.shape[0]
+    for (i, j) in [(0, 0), (d - 1, d - 1), (d - 1, 0), (d // 2, d // 3), (1, d - 2)]:
+        got = oracle.conv_factor_entry(x, kh, kw, sh, sw, ph, pw, 1.0 / P.shape[0], i, j)
+        assert abs(got - F[i, j]) <= 1e-13 * max(1.0, abs(F[i, j]))
+
+
 def test_ema_closed_form_and_limits():
     r = rng(8)
     F0 = r.standard_normal((6, 6)); F0 = F0 @ F0.T
