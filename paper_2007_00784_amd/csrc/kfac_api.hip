@@ -107,7 +107,7 @@ size_t kfac_workspace_bytes(int max_d, int max_batch_factors, int64_t max_R) {
     if (max_d < 1 || max_d > KFAC_MAX_D || max_batch_factors < 1 || max_R < 1) return 0;
     // SYRK split partials: at most 512 + one tile per lower-triangular tile, 64 KB each
     const size_t nt = (max_d + KFAC_TILE) / KFAC_TILE + 1;
-    size_t need = (512 + nt * (nt + 1) / 2) * (size_t)KFAC_TILE * KFAC_TILE * sizeof(float);
+    size_t need = (2048 + 2 * nt * (nt + 1) / 2) * (size_t)(KFAC_TILE * KFAC_TILE + KFAC_TILE) * sizeof(float);
     // precondition: two dG x dA temporaries
     need = std::max(need, 2 * kfac_align_up((size_t)max_d * max_d, 64) * sizeof(float));
     // eig: every factor of the batch at the largest size, advanced together

@@ -32,31 +32,46 @@ __device__ inline float to_float(unsigned short v) { return __uint_as_float(((un
 //                 IFAST : ii = tid & 127, kk = (tid >> 7) + 2*s          (s = 0..7)
 
 // elem(i,k) = p[i*si + k*sk] for i < I, k < K; 1.0 on row ones_i (if >= 0); else 0.
+// Loads are branch free: an out-of-range element reads p[0] and is replaced by a select, so the
+// compiler can issue a slab's loads back to back and interleave them with the MFMAs.
 template <typename E, bool KFAST_>
 struct OpStrided {
     static constexpr bool KFAST = KFAST_;
     const E *p;
     int64_t si, sk;
     int I, K, ones_i;
-    int i_t, k_t;  // thread state: first element's (i, k)
+    // thread state
+    int64_t off[EPT];   // element offset of each of this thread's slots in the current slab
+    int k_t;            // k of slot 0
+    unsigned in_mask, ones_mask;   // per slot: row index inside the operand / is the ones row
     __device__ void start(int tid, int i0, int k0) {
-        if (KFAST) { i_t = i0 + (tid >> 4); k_t = k0 + (tid & 15); }
-        else       { i_t = i0 + (tid & 127); k_t = k0 + (tid >> 7); }
-    }
-    __device__ void fetch(float (&r)[EPT]) const {
+        const int i_t = KFAST ? i0 + (tid >> 4) : i0 + (tid & 127);
+        k_t = KFAST ? k0 + (tid & 15) : k0 + (tid >> 7);
+        in_mask = ones_mask = 0;
 #pragma unroll
         for (int s = 0; s < EPT; ++s) {
             const int i = KFAST ? i_t + 16 * s : i_t;
             const int k = KFAST ? k_t : k_t + 2 * s;
-            float v = 0.f;
-            if (k < K) {
-                if (i < I) v = to_float(p[(int64_t)i * si + (int64_t)k * sk]);
-                else if (i == ones_i) v = 1.f;
-            }
-            r[s] = v;
+            off[s] = (int64_t)i * si + (int64_t)k * sk;
+            in_mask |= (i < I ? 1u : 0u) << s;
+            ones_mask |= (i == ones_i ? 1u : 0u) << s;
         }
     }
-    __device__ void next() { k_t += BK; }
+    __device__ void fetch(float (&r)[EPT]) const {
+#pragma unroll
+        for (int s = 0; s < EPT; ++s) {
+            const int k = KFAST ? k_t : k_t + 2 * s;
+            const bool kv = k < K;
+            const bool ld = kv && ((in_mask >> s) & 1u);
+            const float v = to_float(p[ld ? off[s] : 0]);
+            r[s] = ld ? v : ((kv && ((ones_mask >> s) & 1u)) ? 1.f : 0.f);
+        }
+    }
+    __device__ void next() {
+        k_t += BK;
+#pragma unroll
+        for (int s = 0; s < EPT; ++s) off[s] += (int64_t)BK * sk;
+    }
 };
 
 // Samples in [N][d][T] layout with the contraction index k = n*T + t running over all sample rows:
@@ -66,30 +81,40 @@ struct OpNDT {
     static constexpr bool KFAST = true;
     const E *p;
     int d, T, K, ones_i;
-    int i_t, k_t, n_t, t_t;
+    // thread state
+    int64_t base;       // n*d*T + t of this thread's k
+    int ioff[EPT];      // i*T per slot (d*T < 2^31 is checked on the host)
+    int k_t, t_t;
+    unsigned in_mask, ones_mask;
     __device__ void start(int tid, int i0, int k0) {
-        i_t = i0 + (tid >> 4);
+        const int i_t = i0 + (tid >> 4);
         k_t = k0 + (tid & 15);
-        n_t = k_t / T;
+        const int n_t = k_t / T;
         t_t = k_t - n_t * T;
-    }
-    __device__ void fetch(float (&r)[EPT]) const {
-        const E *base = p + ((int64_t)n_t * d) * T + t_t;
+        base = (int64_t)n_t * d * T + t_t;
+        in_mask = ones_mask = 0;
 #pragma unroll
         for (int s = 0; s < EPT; ++s) {
             const int i = i_t + 16 * s;
-            float v = 0.f;
-            if (k_t < K) {
-                if (i < d) v = to_float(base[(int64_t)i * T]);
-                else if (i == ones_i) v = 1.f;
-            }
-            r[s] = v;
+            ioff[s] = i * T;
+            in_mask |= (i < d ? 1u : 0u) << s;
+            ones_mask |= (i == ones_i ? 1u : 0u) << s;
+        }
+    }
+    __device__ void fetch(float (&r)[EPT]) const {
+        const bool kv = k_t < K;
+#pragma unroll
+        for (int s = 0; s < EPT; ++s) {
+            const bool ld = kv && ((in_mask >> s) & 1u);
+            const float v = to_float(p[ld ? base + ioff[s] : 0]);
+            r[s] = ld ? v : ((kv && ((ones_mask >> s) & 1u)) ? 1.f : 0.f);
         }
     }
     __device__ void next() {
         k_t += BK;
         t_t += BK;
-        while (t_t >= T) { t_t -= T; ++n_t; }
+        base += BK;
+        while (t_t >= T) { t_t -= T; base += (int64_t)(d - 1) * T; }
     }
 };
 
@@ -109,9 +134,11 @@ struct TileSmem {
 
 // acc[i][j] accumulates rows wm+32i.., cols wn+32j.. of the tile; element r of a 32x32 accumulator
 // sits at row 8*(r/4) + 4*(lane/32) + r%4, column lane%32.
-template <class OpA, class OpB>
+// With COLSUM the thread also accumulates, per load slot, the sum over k of the A-operand elements it
+// fetches (csum[s]); summed over the threads that share a row index this is sum_k elem_A(i, k).
+template <class OpA, class OpB, bool COLSUM = false>
 __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int kend, TileSmem &sm,
-                                 floatx16 (&acc)[2][2]) {
+                                 floatx16 (&acc)[2][2], float *csum = nullptr) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -129,6 +156,10 @@ __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int k
     B.start(tid, j0, kbeg);
     A.fetch(ra);
     B.fetch(rb);
+    if (COLSUM) {
+#pragma unroll
+        for (int t = 0; t < EPT; ++t) csum[t] += ra[t];
+    }
     store_slab<OpA::KFAST>(sm.a[0], ra, tid);
     store_slab<OpB::KFAST>(sm.b[0], rb, tid);
     __syncthreads();
@@ -140,17 +171,28 @@ __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int k
             B.next();
             A.fetch(ra);
             B.fetch(rb);
-        }
+            if (COLSUM) {
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            float a0 = sm.a[cur][kk + lk][wm + lc];
-            float a1 = sm.a[cur][kk + lk][wm + 32 + lc];
-            float b0 = sm.b[cur][kk + lk][wn + lc];
-            float b1 = sm.b[cur][kk + lk][wn + 32 + lc];
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+                for (int t = 0; t < EPT; ++t) csum[t] += ra[t];
+            }
+        }
+        // all MFMA operands of the slab are read from LDS up front (32 registers), so the LDS latency is
+        // paid once per slab instead of once per k-step and the 32 MFMAs issue back to back
+        float a0[BK / 2], a1[BK / 2], b0[BK / 2], b1[BK / 2];
+#pragma unroll
+        for (int j = 0; j < BK / 2; ++j) {
+            a0[j] = sm.a[cur][2 * j + lk][wm + lc];
+            a1[j] = sm.a[cur][2 * j + lk][wm + 32 + lc];
+            b0[j] = sm.b[cur][2 * j + lk][wn + lc];
+            b1[j] = sm.b[cur][2 * j + lk][wn + 32 + lc];
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the reads above ahead of the MFMAs below
+#pragma unroll
+        for (int j = 0; j < BK / 2; ++j) {
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[j], b0[j], acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[j], b1[j], acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b0[j], acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b1[j], acc[1][1], 0, 0, 0);
         }
         if (more) {
             store_slab<OpA::KFAST>(sm.a[cur ^ 1], ra, tid);

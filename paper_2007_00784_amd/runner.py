@@ -46,7 +46,7 @@ class KfacRunner:
         dims = [l.d_a for l in self.layers] + [l.d_g for l in self.layers]
         need = K.kfac_eig_workspace_bytes(dims)
         need = max(need, 2 * max(l.d_a * l.d_g for l in self.layers) * 4 + 1024)
-        need = max(need, (512 + 800) * 128 * 128 * 4)      # SYRK split partials (upper bound for d <= 4609)
+        need = max(need, K.kfac_workspace_bytes(max(dims), 1, max(l.rows(self.N) for l in self.layers)))  # SYRK partials, precondition
         self.ws = torch.empty(need + 4096, dtype=torch.uint8, device=self.dev)
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = K.kfac_create(self.dev.index or 0, self.stream.cuda_stream, self.ws)
