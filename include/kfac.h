@@ -123,6 +123,23 @@ int kfac_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, floa
 int kfac_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,
                       const float *lamG, int dG, float damping, void *grad, int grad_dtype);
 
+/* The same operation for a batch of layers in four launches (one per GEMM stage, covering the output
+ * tiles of every layer): what a training step calls once per iteration (Algorithm 1, step 3).
+ *   items : HOST array of n records; every pointer in a record is a device pointer with the meaning
+ *           and shape of the kfac_precondition() argument of the same name.  Gradients must not alias
+ *           one another.  kfac_precondition_workspace_bytes() gives the workspace the batch needs.  */
+typedef struct {
+    const float *QA, *lamA;
+    int dA;
+    const float *QG, *lamG;
+    int dG;
+    float damping;
+    void *grad;
+    int grad_dtype;
+} kfac_precond_item;
+int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items /* host */);
+size_t kfac_precondition_workspace_bytes(int n, const kfac_precond_item *items /* host; only dA, dG are read */);
+
 /* Update-decoupled schedule (Sec. IV-C, Sec. V-C), host only: at iteration k refresh the factors
  * when k % f_fac == 0 and the eigendecompositions when k % f_eig == 0; precondition always.  */
 int kfac_schedule_due(int64_t k, int f_fac, int f_eig, int *do_factors, int *do_eig);

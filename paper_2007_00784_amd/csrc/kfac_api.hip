@@ -109,7 +109,7 @@ size_t kfac_workspace_bytes(int max_d, int max_batch_factors, int64_t max_R) {
     const size_t nt = (max_d + KFAC_TILE) / KFAC_TILE + 1;
     size_t need = (2048 + 2 * nt * (nt + 1) / 2) * (size_t)(KFAC_TILE * KFAC_TILE + KFAC_TILE) * sizeof(float);
     // precondition: two dG x dA temporaries
-    need = std::max(need, 2 * kfac_align_up((size_t)max_d * max_d, 64) * sizeof(float));
+    need = std::max(need, 2 * kfac_align_up((size_t)max_d * max_d, 64) * sizeof(float) + (size_t)(1 << 20));
     // eig: every factor of the batch at the largest size, advanced together
     std::vector<int> d((size_t)max_batch_factors, max_d);
     need = std::max(need, kfac_eig_ws_bytes_impl(max_batch_factors, d.data()));
@@ -193,6 +193,27 @@ int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out, int max, int *n) {
     }
     *n = k;
     return KFAC_OK;
+}
+
+static bool valid_precond_item(const kfac_precond_item &p) {
+    if (!p.QA || !p.lamA || !p.QG || !p.lamG || !p.grad) return false;
+    if (p.dA < 1 || p.dG < 1 || p.dA > KFAC_MAX_D || p.dG > KFAC_MAX_D) return false;
+    return p.damping > 0.f && std::isfinite(p.damping) && valid_dtype(p.grad_dtype);
+}
+
+int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items) {
+    if (!ctx || n < 0 || (n > 0 && !items)) return KFAC_EINVAL;
+    for (int i = 0; i < n; ++i)
+        if (!valid_precond_item(items[i])) return KFAC_EINVAL;
+    if (n == 0) return KFAC_OK;
+    return kfac_launch_precondition_batched(ctx, n, items);
+}
+
+size_t kfac_precondition_workspace_bytes(int n, const kfac_precond_item *items) {
+    if (n <= 0 || !items) return 0;
+    for (int i = 0; i < n; ++i)
+        if (items[i].dA < 1 || items[i].dG < 1 || items[i].dA > KFAC_MAX_D || items[i].dG > KFAC_MAX_D) return 0;
+    return kfac_precond_ws_bytes_impl(n, items);
 }
 
 int kfac_schedule_due(int64_t k, int f_fac, int f_eig, int *do_factors, int *do_eig) {

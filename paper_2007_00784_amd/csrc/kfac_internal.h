@@ -76,6 +76,8 @@ int kfac_launch_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layo
                                int append_ones, float scale, float decay, float *F);
 int kfac_launch_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,
                              const float *lamG, int dG, float damping, void *grad, int grad_dtype);
+int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items);
+size_t kfac_precond_ws_bytes_impl(int n, const kfac_precond_item *items);
 size_t kfac_eig_ws_bytes_impl(int batch, const int *d);
 int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,
                     float *const *lam, const kfac_eig_opts *opts, kfac_eig_info *info);

@@ -1,9 +1,15 @@
-// Eigenbasis preconditioning of one layer's gradient, Eqs. (v1), (v2), (kfac-eigen) of Sec. IV-A:
+// Eigenbasis preconditioning, Eqs. (v1), (v2), (kfac-eigen) of Sec. IV-A, for one layer or a batch of
+// layers:
 //   T  = QG^T grad            (dG x dA, K = dG)
 //   V2 = (T QA) / (lamG lamA^T + damping)     (K = dA, divide fused into the epilogue)
 //   T  = QG V2                (K = dG)
 //   grad = T QA^T             (K = dA)
-// Four dependent GEMMs on the fp32 MFMA tile engine; T and V2 live in the context workspace.
+// Four dependent GEMM stages on the fp32 MFMA tile engine.  Each stage is ONE launch over the 128x128
+// output tiles of every layer in the batch (a device table maps a workgroup to its layer and tile,
+// longest contraction first), so small layers do not leave the machine idle and a 54-layer network
+// costs four launches instead of 216.  T and V2 live in the context workspace.
+#include <algorithm>
+#include <vector>
 #include "kfac_internal.h"
 #include "mfma_gemm.h"
 
@@ -11,16 +17,15 @@ using namespace kfac;
 
 namespace {
 
-enum { EPI_STORE = 0, EPI_DIVIDE = 1, EPI_STORE_BF16 = 2 };
-
-struct GemmOut {
-    float *C;
-    unsigned short *Cb;
-    int M, N;
-    int64_t ldc;
-    const float *lamG, *lamA;
+struct LayerDev {
+    const float *QA, *lamA, *QG, *lamG;
+    void *grad;
+    float *T, *V;
+    int dA, dG;
     float damping;
+    int grad_bf16;
 };
+struct TileRef { int layer, tile; };   // tile = ti * tiles_n + tj
 
 __device__ inline unsigned short f32_to_bf16_rne(float v) {
     unsigned u = __float_as_uint(v);
@@ -29,76 +34,138 @@ __device__ inline unsigned short f32_to_bf16_rne(float v) {
     return (unsigned short)(u >> 16);
 }
 
-template <class OpA, class OpB, int EPI>
-__global__ __launch_bounds__(NTHREADS) void gemm_kernel(OpA a, OpB b, GemmOut o, int K) {
-    __shared__ TileSmem sm;
-    const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
+template <class OpA, class OpB, class Epi>
+__device__ inline void run_tile(OpA a, OpB b, int i0, int j0, int K, int M, int N, TileSmem &sm, Epi epi) {
     floatx16 acc[2][2];
     gemm_tile(a, b, i0, j0, 0, K, sm, acc);
     for_each_acc(acc, [&](int r, int c, float v) {
         const int gr = i0 + r, gc = j0 + c;
-        if (gr < o.M && gc < o.N) {
-            if (EPI == EPI_DIVIDE) {
-                const float lg = fmaxf(o.lamG[gr], 0.f), la = fmaxf(o.lamA[gc], 0.f);
-                v = v / (lg * la + o.damping);
-            }
-            if (EPI == EPI_STORE_BF16) o.Cb[(int64_t)gr * o.ldc + gc] = f32_to_bf16_rne(v);
-            else o.C[(int64_t)gr * o.ldc + gc] = v;
-        }
+        if (gr < M && gc < N) epi(gr, gc, v);
     });
 }
 
-template <class OpA, class OpB, int EPI>
-int launch(kfac_ctx *ctx, OpA a, OpB b, GemmOut o, int K) {
-    const dim3 grid((o.N + BM - 1) / BM, (o.M + BM - 1) / BM);
-    KfacProfScope prof(ctx, KC_PRECOND_GEMM, 2.0 * o.M * o.N * K, 4.0 * ((double)o.M * K + (double)K * o.N + (double)o.M * o.N));
-    hipLaunchKernelGGL((gemm_kernel<OpA, OpB, EPI>), grid, dim3(NTHREADS), 0, ctx->stream, a, b, o, K);
-    KFAC_HIP_CHECK(hipGetLastError());
-    return KFAC_OK;
+template <int STAGE>
+__global__ __launch_bounds__(NTHREADS) void precond_stage_kernel(const LayerDev *layers, const TileRef *tiles) {
+    __shared__ TileSmem sm;
+    const TileRef tr = tiles[blockIdx.x];
+    const LayerDev L = layers[tr.layer];
+    const int dA = L.dA, dG = L.dG;
+    const int tn = (dA + BM - 1) / BM;
+    const int i0 = (tr.tile / tn) * BM, j0 = (tr.tile % tn) * BM;
+    if (STAGE == 0) {
+        // T = QG^T grad : A(m,k) = QG[k][m] (m contiguous), B(k,n) = grad[k][n] (n contiguous)
+        OpStrided<float, false> qgt{L.QG, 1, dG, dG, dG, -1};
+        float *T = L.T;
+        auto epi = [=](int r, int c, float v) { T[(int64_t)r * dA + c] = v; };
+        if (L.grad_bf16) {
+            OpStrided<unsigned short, false> g{(const unsigned short *)L.grad, 1, dA, dA, dG, -1};
+            run_tile(qgt, g, i0, j0, dG, dG, dA, sm, epi);
+        } else {
+            OpStrided<float, false> g{(const float *)L.grad, 1, dA, dA, dG, -1};
+            run_tile(qgt, g, i0, j0, dG, dG, dA, sm, epi);
+        }
+    } else if (STAGE == 1) {
+        // V = (T QA) / (lamG lamA^T + damping) : A(m,k) = T[m][k] (k contiguous), B(k,n) = QA[k][n]
+        OpStrided<float, true> t_mk{L.T, dA, 1, dG, dA, -1};
+        OpStrided<float, false> qa_kn{L.QA, 1, dA, dA, dA, -1};
+        float *V = L.V;
+        const float *lamG = L.lamG, *lamA = L.lamA;
+        const float damping = L.damping;
+        run_tile(t_mk, qa_kn, i0, j0, dA, dG, dA, sm, [=](int r, int c, float v) {
+            const float lg = fmaxf(lamG[r], 0.f), la = fmaxf(lamA[c], 0.f);
+            V[(int64_t)r * dA + c] = v / (lg * la + damping);
+        });
+    } else if (STAGE == 2) {
+        // T = QG V : A(m,k) = QG[m][k] (k contiguous), B(k,n) = V[k][n]
+        OpStrided<float, true> qg_mk{L.QG, dG, 1, dG, dG, -1};
+        OpStrided<float, false> v_kn{L.V, 1, dA, dA, dG, -1};
+        float *T = L.T;
+        run_tile(qg_mk, v_kn, i0, j0, dG, dG, dA, sm, [=](int r, int c, float v) { T[(int64_t)r * dA + c] = v; });
+    } else {
+        // grad = T QA^T : A(m,k) = T[m][k], B(k,n) = QA[n][k] (k contiguous)
+        OpStrided<float, true> t_mk{L.T, dA, 1, dG, dA, -1};
+        OpStrided<float, true> qa_nk{L.QA, dA, 1, dA, dA, -1};
+        void *grad = L.grad;
+        if (L.grad_bf16)
+            run_tile(t_mk, qa_nk, i0, j0, dA, dG, dA, sm,
+                     [=](int r, int c, float v) { ((unsigned short *)grad)[(int64_t)r * dA + c] = f32_to_bf16_rne(v); });
+        else
+            run_tile(t_mk, qa_nk, i0, j0, dA, dG, dA, sm, [=](int r, int c, float v) { ((float *)grad)[(int64_t)r * dA + c] = v; });
+    }
+}
+
+size_t layout(int n, const kfac_precond_item *it, size_t &off_tiles, size_t &off_tv, size_t &ntiles) {
+    ntiles = 0;
+    size_t tv = 0;
+    for (int i = 0; i < n; ++i) {
+        ntiles += (size_t)((it[i].dG + BM - 1) / BM) * ((it[i].dA + BM - 1) / BM);
+        tv += 2 * kfac_align_up((size_t)it[i].dG * it[i].dA, 64);
+    }
+    off_tiles = kfac_align_up((size_t)n * sizeof(LayerDev), 256);
+    off_tv = off_tiles + kfac_align_up(2 * ntiles * sizeof(TileRef), 256);
+    return off_tv + tv * sizeof(float);
 }
 
 }  // namespace
 
+size_t kfac_precond_ws_bytes_impl(int n, const kfac_precond_item *items) {
+    size_t a, b, c;
+    return layout(n, items, a, b, c);
+}
+
+int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items) {
+    size_t off_tiles, off_tv, ntiles;
+    const size_t need = layout(n, items, off_tiles, off_tv, ntiles);
+    if (need > ctx->ws_bytes) return KFAC_EWORKSPACE;
+    std::vector<LayerDev> dev(n);
+    float *tv = (float *)(ctx->ws + off_tv);
+    double flops = 0.0, bytes = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const kfac_precond_item &p = items[i];
+        const size_t e = kfac_align_up((size_t)p.dG * p.dA, 64);
+        dev[i] = LayerDev{p.QA, p.lamA, p.QG, p.lamG, p.grad, tv, tv + e, p.dA, p.dG, p.damping, p.grad_dtype == KFAC_BF16};
+        tv += 2 * e;
+        flops += 4.0 * p.dA * p.dG * ((double)p.dA + p.dG);
+        bytes += 4.0 * ((double)p.dA * p.dA + (double)p.dG * p.dG) * 2 + 4.0 * 8 * p.dA * p.dG;
+    }
+    // tile lists, longest contraction first: stages 0 and 2 contract over dG, stages 1 and 3 over dA
+    std::vector<TileRef> byG, byA;
+    byG.reserve(ntiles);
+    for (int i = 0; i < n; ++i) {
+        const int nt = ((items[i].dG + BM - 1) / BM) * ((items[i].dA + BM - 1) / BM);
+        for (int t = 0; t < nt; ++t) byG.push_back(TileRef{i, t});
+    }
+    byA = byG;
+    std::stable_sort(byG.begin(), byG.end(), [&](const TileRef &a, const TileRef &b) { return items[a.layer].dG > items[b.layer].dG; });
+    std::stable_sort(byA.begin(), byA.end(), [&](const TileRef &a, const TileRef &b) { return items[a.layer].dA > items[b.layer].dA; });
+    LayerDev *d_layers = (LayerDev *)ctx->ws;
+    TileRef *d_byG = (TileRef *)(ctx->ws + off_tiles), *d_byA = d_byG + ntiles;
+    KFAC_HIP_CHECK(hipMemcpyAsync(d_layers, dev.data(), n * sizeof(LayerDev), hipMemcpyHostToDevice, ctx->stream));
+    KFAC_HIP_CHECK(hipMemcpyAsync(d_byG, byG.data(), ntiles * sizeof(TileRef), hipMemcpyHostToDevice, ctx->stream));
+    KFAC_HIP_CHECK(hipMemcpyAsync(d_byA, byA.data(), ntiles * sizeof(TileRef), hipMemcpyHostToDevice, ctx->stream));
+    const dim3 grid((unsigned)ntiles), block(NTHREADS);
+    {
+        KfacProfScope prof(ctx, KC_PRECOND_GEMM, flops / 4, bytes / 4);
+        hipLaunchKernelGGL(precond_stage_kernel<0>, grid, block, 0, ctx->stream, d_layers, d_byG);
+    }
+    {
+        KfacProfScope prof(ctx, KC_PRECOND_GEMM, flops / 4, bytes / 4);
+        hipLaunchKernelGGL(precond_stage_kernel<1>, grid, block, 0, ctx->stream, d_layers, d_byA);
+    }
+    {
+        KfacProfScope prof(ctx, KC_PRECOND_GEMM, flops / 4, bytes / 4);
+        hipLaunchKernelGGL(precond_stage_kernel<2>, grid, block, 0, ctx->stream, d_layers, d_byG);
+    }
+    {
+        KfacProfScope prof(ctx, KC_PRECOND_GEMM, flops / 4, bytes / 4);
+        hipLaunchKernelGGL(precond_stage_kernel<3>, grid, block, 0, ctx->stream, d_layers, d_byA);
+    }
+    KFAC_HIP_CHECK(hipGetLastError());
+    return KFAC_OK;
+}
+
 int kfac_launch_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,
                              const float *lamG, int dG, float damping, void *grad, int grad_dtype) {
-    const size_t elems = (size_t)dG * dA;
-    if (2 * elems * sizeof(float) > ctx->ws_bytes) return KFAC_EWORKSPACE;
-    float *T = (float *)ctx->ws;
-    float *V = T + kfac_align_up(elems, 64);
-    if (2 * kfac_align_up(elems, 64) * sizeof(float) > ctx->ws_bytes) return KFAC_EWORKSPACE;
-    GemmOut o{nullptr, nullptr, dG, dA, dA, lamG, lamA, damping};
-    int rc;
-    // T = QG^T grad : A(m,k) = QG[k][m] (m contiguous), B(k,n) = grad[k][n] (n contiguous)
-    o.C = T;
-    OpStrided<float, false> qgt{QG, 1, dG, dG, dG, -1};
-    if (grad_dtype == KFAC_F32) {
-        OpStrided<float, false> g{(const float *)grad, 1, dA, dA, dG, -1};
-        rc = launch<decltype(qgt), decltype(g), EPI_STORE>(ctx, qgt, g, o, dG);
-    } else {
-        OpStrided<unsigned short, false> g{(const unsigned short *)grad, 1, dA, dA, dG, -1};
-        rc = launch<decltype(qgt), decltype(g), EPI_STORE>(ctx, qgt, g, o, dG);
-    }
-    if (rc) return rc;
-    // V = (T QA) / (lamG lamA^T + damping) : A(m,k) = T[m][k] (k contiguous), B(k,n) = QA[k][n]
-    o.C = V;
-    OpStrided<float, true> t_mk{T, dA, 1, dG, dA, -1};
-    OpStrided<float, false> qa_kn{QA, 1, dA, dA, dA, -1};
-    rc = launch<decltype(t_mk), decltype(qa_kn), EPI_DIVIDE>(ctx, t_mk, qa_kn, o, dA);
-    if (rc) return rc;
-    // T = QG V : A(m,k) = QG[m][k] (k contiguous), B(k,n) = V[k][n]
-    o.C = T;
-    OpStrided<float, true> qg_mk{QG, dG, 1, dG, dG, -1};
-    OpStrided<float, false> v_kn{V, 1, dA, dA, dG, -1};
-    rc = launch<decltype(qg_mk), decltype(v_kn), EPI_STORE>(ctx, qg_mk, v_kn, o, dG);
-    if (rc) return rc;
-    // grad = T QA^T : A(m,k) = T[m][k], B(k,n) = QA[n][k] (k contiguous)
-    OpStrided<float, true> qa_nk{QA, dA, 1, dA, dA, -1};
-    if (grad_dtype == KFAC_F32) {
-        o.C = (float *)grad;
-        rc = launch<decltype(t_mk), decltype(qa_nk), EPI_STORE>(ctx, t_mk, qa_nk, o, dA);
-    } else {
-        o.Cb = (unsigned short *)grad;
-        rc = launch<decltype(t_mk), decltype(qa_nk), EPI_STORE_BF16>(ctx, t_mk, qa_nk, o, dA);
-    }
-    return rc;
+    kfac_precond_item it{QA, lamA, dA, QG, lamG, dG, damping, grad, grad_dtype};
+    return kfac_launch_precondition_batched(ctx, 1, &it);
 }

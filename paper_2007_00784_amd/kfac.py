@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libkfac_hip.so")
 EXPORTS = (
     "kfac_create", "kfac_destroy", "kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
     "kfac_unfold", "kfac_update_factors", "kfac_eig", "kfac_precondition", "kfac_schedule_due",
-    "kfac_profile_begin", "kfac_profile_end",
+    "kfac_profile_begin", "kfac_profile_end", "kfac_precondition_batched", "kfac_precondition_workspace_bytes",
 )
 
 
@@ -38,6 +38,12 @@ class kfac_eig_info(ctypes.Structure):
 class kfac_kernel_stat(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char * 32), ("launches", ctypes.c_int), ("ms", ctypes.c_double),
                 ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
+
+
+class kfac_precond_item(ctypes.Structure):
+    _fields_ = [("QA", ctypes.c_void_p), ("lamA", ctypes.c_void_p), ("dA", ctypes.c_int),
+                ("QG", ctypes.c_void_p), ("lamG", ctypes.c_void_p), ("dG", ctypes.c_int),
+                ("damping", ctypes.c_float), ("grad", ctypes.c_void_p), ("grad_dtype", ctypes.c_int)]
 
 
 class KfacError(RuntimeError):
@@ -72,10 +78,14 @@ def lib():
                            ctypes.POINTER(kfac_eig_opts), ctypes.POINTER(kfac_eig_info)]
     L.kfac_precondition.argtypes = [vp, vp, vp, i, vp, vp, i, f, vp, i]
     L.kfac_schedule_due.argtypes = [i64, i, i, ip, ip]
+    L.kfac_precondition_batched.argtypes = [vp, i, ctypes.POINTER(kfac_precond_item)]
+    L.kfac_precondition_workspace_bytes.argtypes = [i, ctypes.POINTER(kfac_precond_item)]
+    L.kfac_precondition_workspace_bytes.restype = sz
     L.kfac_profile_begin.argtypes = [vp]
     L.kfac_profile_end.argtypes = [vp, ctypes.POINTER(kfac_kernel_stat), i, ip]
     for name in EXPORTS:
-        if name not in ("kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror"):
+        if name not in ("kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
+                        "kfac_precondition_workspace_bytes"):
             getattr(L, name).restype = i
     _lib = L
     return L
@@ -170,6 +180,32 @@ def kfac_precondition(ctx, QA, lamA, QG, lamG, damping, grad):
         raise ValueError("grad must be [dG, dA]")
     _check(lib().kfac_precondition(ctx, _ptr(QA), _ptr(lamA), dA, _ptr(QG), _ptr(lamG), dG, float(damping),
                                    _ptr(grad), _dtype_code(grad)), "kfac_precondition")
+
+
+def _precond_items(QA, lamA, QG, lamG, damping, grad):
+    n = len(grad)
+    arr = (kfac_precond_item * n)()
+    for j in range(n):
+        dA, dG = int(QA[j].shape[0]), int(QG[j].shape[0])
+        if tuple(grad[j].shape) != (dG, dA):
+            raise ValueError("grad[%d] must be [dG, dA]" % j)
+        arr[j] = kfac_precond_item(_ptr(QA[j]), _ptr(lamA[j]), dA, _ptr(QG[j]), _ptr(lamG[j]), dG, float(damping),
+                                   _ptr(grad[j]), _dtype_code(grad[j]))
+    return arr
+
+
+def kfac_precondition_batched(ctx, QA, lamA, QG, lamG, damping, grad):
+    """Lists of per-layer device tensors; every grad[j] is preconditioned in place."""
+    arr = _precond_items(QA, lamA, QG, lamG, damping, grad)
+    _check(lib().kfac_precondition_batched(ctx, len(grad), arr), "kfac_precondition_batched")
+
+
+def kfac_precondition_workspace_bytes(dims):
+    """dims: list of (dA, dG)."""
+    arr = (kfac_precond_item * len(dims))()
+    for j, (dA, dG) in enumerate(dims):
+        arr[j].dA, arr[j].dG = int(dA), int(dG)
+    return int(lib().kfac_precondition_workspace_bytes(len(dims), arr))
 
 
 def kfac_schedule_due(k, f_fac, f_eig):

@@ -45,7 +45,7 @@ class KfacRunner:
         self.patches = torch.empty(pmax, dtype=self.dt, device=self.dev)
         dims = [l.d_a for l in self.layers] + [l.d_g for l in self.layers]
         need = K.kfac_eig_workspace_bytes(dims)
-        need = max(need, 2 * max(l.d_a * l.d_g for l in self.layers) * 4 + 1024)
+        need = max(need, K.kfac_precondition_workspace_bytes([(l.d_a, l.d_g) for l in self.layers]))
         need = max(need, K.kfac_workspace_bytes(max(dims), 1, max(l.rows(self.N) for l in self.layers)))  # SYRK partials, precondition
         self.ws = torch.empty(need + 4096, dtype=torch.uint8, device=self.dev)
         self.stream = torch.cuda.current_stream(self.dev)
@@ -89,7 +89,7 @@ class KfacRunner:
         gamma = self.wl.damping if damping is None else damping
         for i in range(len(self.layers)):
             self.grad[i].copy_(self.gradw_master[i])
-            K.kfac_precondition(self.ctx, self.QA[i], self.lamA[i], self.QG[i], self.lamG[i], gamma, self.grad[i])
+        K.kfac_precondition_batched(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad)
 
     # ---- algorithmic work of one step (flops, bytes) ----
     def work(self):
