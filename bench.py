@@ -31,40 +31,70 @@ BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
     "eig_misc": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "eig_post_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
     "eig_copy": ("hbm", PEAK_HBM, "GB/s", "bytes"),
+    "eig_outer_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
 }
 
 
-def cpu_baseline(wl_name, seconds_hint=20.0):
-    """The fp64 oracle, as it stands, timed on this host on one mid-size layer of the workload
-    (unfold + both factors + both eigendecompositions + preconditioning)."""
-    import numpy as np
+SAMPLE_LAYERS = ("s3b1.conv3", "s4b1.reduce", "fc")   # d_A/d_G = 2305/256, 2049/512, 2049/1000
+
+
+def sample_layer_ids(wl):
+    ids = [i for i, l in enumerate(wl.layers) if l.name in SAMPLE_LAYERS]
+    return ids if ids else [0]
+
+
+def cpu_baseline(wl_name):
+    """The fp64 oracle, as it stands, timed on this host on a bounded sample of the workload: three
+    layers of the set, one K-FAC step each (unfold + both factors + both eigendecompositions +
+    preconditioning)."""
     import oracle
     from paper_2007_00784_amd import synthetic as S
     wl = S.workload(wl_name)
-    name = "s3b1.conv3" if len(wl.layers) > 1 else wl.layers[0].name
-    li = [i for i, l in enumerate(wl.layers) if l.name == name][0]
-    lay = wl.layers[li]
-    t = S.layer_inputs(wl, li, update=0)
-    R = wl.batch * lay.T
-    t0 = time.perf_counter()
-    P = oracle.unfold(t["x"], lay.k, lay.k, lay.stride, lay.stride, lay.pad, lay.pad)
-    A = oracle.gram(P, 1, 1.0 / R)
-    G = oracle.gram(t["g"].transpose(0, 2, 3, 1).reshape(R, lay.c_out), 0, 1.0 / R)
-    t1 = time.perf_counter()
-    la, qa = oracle.eigh(A)
-    lg, qg = oracle.eigh(G)
-    t2 = time.perf_counter()
-    oracle.precondition(qa, la, qg, lg, wl.damping, t["gradw"])
-    t3 = time.perf_counter()
+    ids = sample_layer_ids(wl)
+    ph = {"factors": 0.0, "eig": 0.0, "precondition": 0.0}
+    desc = []
+    for li in ids:
+        lay = wl.layers[li]
+        t = S.layer_inputs(wl, li, update=0)
+        R = wl.batch * lay.T
+        t0 = time.perf_counter()
+        if lay.fc:
+            P, g = t["x"], t["g"]
+        else:
+            P = oracle.unfold(t["x"], lay.k, lay.k, lay.stride, lay.stride, lay.pad, lay.pad)
+            g = t["g"].transpose(0, 2, 3, 1).reshape(R, lay.c_out)
+        A = oracle.gram(P, 1, 1.0 / R)
+        G = oracle.gram(g, 0, 1.0 / R)
+        t1 = time.perf_counter()
+        la, qa = oracle.eigh(A)
+        lg, qg = oracle.eigh(G)
+        t2 = time.perf_counter()
+        oracle.precondition(qa, la, qg, lg, wl.damping, t["gradw"])
+        t3 = time.perf_counter()
+        ph["factors"] += (t1 - t0) * 1e3
+        ph["eig"] += (t2 - t1) * 1e3
+        ph["precondition"] += (t3 - t2) * 1e3
+        desc.append("%s (d_A=%d, d_G=%d, R=%d)" % (lay.name, lay.d_a, lay.d_g, R))
     return {
-        "value": round((t3 - t0) * 1e3, 1), "unit": "ms", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": "one layer of the set (%s: %dx%d conv %d->%d on %dx%d, batch %d; d_A=%d, d_G=%d), "
-                  "one K-FAC step of that layer" % (name, lay.k, lay.k, lay.c_in, lay.c_out, lay.h_in, lay.h_in,
-                                                    wl.batch, lay.d_a, lay.d_g),
-        "phases_ms": {"factors": round((t1 - t0) * 1e3, 1), "eig": round((t2 - t1) * 1e3, 1),
-                      "precondition": round((t3 - t2) * 1e3, 1)},
-        "layer_index": li,
+        "value": round(sum(ph.values()), 1), "unit": "ms", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "one K-FAC step of %d of the %d layers: %s" % (len(ids), len(wl.layers), ", ".join(desc)),
+        "phases_ms": {k: round(v, 1) for k, v in ph.items()},
     }
+
+
+def gpu_same_sample_ms(wl, torch, KfacRunner):
+    """The HIP path on exactly the layers the CPU baseline times (one step, after one warm-up step)."""
+    run = KfacRunner(wl, "cuda:0", n_updates=1, layers=sample_layer_ids(wl))
+    for _ in range(2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run.update_factors(0, 0.0)
+        run.eig(raise_on_noconv=False)
+        run.precondition()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3
+    run.close()
+    return round(ms, 3)
 
 
 def main():
@@ -175,6 +205,7 @@ def main():
     run.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
+        out["cpu_baseline"]["gpu_same_sample_ms"] = gpu_same_sample_ms(wl, torch, KfacRunner)
     print(json.dumps(out))
 
 

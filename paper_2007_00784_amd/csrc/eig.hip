@@ -356,7 +356,20 @@ struct BlkGroup {
     int *idt;
     double *norms;   // [nmat][2] = off^2, diag^2
     int nmat, nblk, npad, players, npairs, npp;   // npp = tile rows = ceil(npairs / PT)
+    int bipartite;   // 0: tournament over all blocks; 1: block j of the first half with a block of the second
 };
+
+// Pair j of round `round`: tournament over `players` blocks, or (bipartite) block j with block
+// half + (j + round) % half, which meets every cross pair of the two halves in `half` rounds.
+__device__ inline void sched_pair(const BlkGroup &g, int round, int j, int &p, int &q) {
+    if (g.bipartite) {
+        const int half = g.players >> 1;
+        p = j;
+        q = half + (j + round) % half;
+    } else {
+        rr_pair(g.players, round, j, p, q);
+    }
+}
 struct BlkItem { const float *F; float *Q; float *lam; int n; int pad_; };
 
 __global__ void blk_init_kernel(BlkGroup g, const BlkItem *items) {
@@ -410,7 +423,7 @@ __global__ __launch_bounds__(NT) void blk_solve_kernel(BlkGroup g, int round, in
     const int m = blockIdx.y, pj = blockIdx.x, tid = threadIdx.x;
     const float *W = g.W + (int64_t)m * g.npad * g.npad;
     int p, q;
-    rr_pair(g.players, round, pj, p, q);
+    sched_pair(g, round, pj, p, q);
     constexpr int PER = KP * KP / NT;
     for (int t0 = 0; t0 < PER; t0 += 8) {
         float v[8];
@@ -470,7 +483,7 @@ __device__ inline TilePairs tile_pairs(const BlkGroup &g, int round, int tile) {
         const int pair = tile * PT + u;
         tp.valid[u] = pair < g.npairs;
         tp.p[u] = tp.q[u] = 0;
-        if (tp.valid[u]) rr_pair(g.players, round, pair, tp.p[u], tp.q[u]);
+        if (tp.valid[u]) sched_pair(g, round, pair, tp.p[u], tp.q[u]);
     }
     return tp;
 }
@@ -714,16 +727,181 @@ __global__ __launch_bounds__(NT) void blk_gather_kernel(const float *Qin, int64_
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// d >= 2048: two-level blocked Jacobi.  At these sizes the round application above is bound by HBM
+// traffic (a 64-wide contraction per pass over the matrix), so rounds are grouped: 128-wide
+// super-blocks are paired by an outer tournament; each 256 x 256 super-pair is gathered into a compact
+// buffer that stays in L2, where the block rounds above run on it alone (4 bipartite rounds meet every
+// cross pair of its 4 + 4 small blocks) and accumulate its 256 x 256 orthogonal transform; that
+// transform is then applied to the whole matrix and to the eigenvector accumulator in two passes of
+// ordinary 128 x 128 x 256 GEMM tiles (columns, then rows), which are MFMA bound.  Pairs of small
+// blocks inside one super-block are met in a "diagonal" phase once per sweep, so every pair of small
+// blocks is still visited exactly once per sweep.
+// ------------------------------------------------------------------------------------------------
+constexpr int SB = 128;                 // super-block width
+constexpr int LDI = 2 * SB;             // edge of a gathered super-pair
+constexpr int TWO_LEVEL_MIN = 2048;     // factors at least this large take the two-level path
+
+struct SpGroup {
+    float *W, *T;          // [nmat][npad][npad]: rotated matrix, column-pass result
+    float *Wi, *Vi;        // gathered units and their accumulated transforms: [nmat*U][s][s]
+    int nmat, npad, nsuper, players;
+};
+
+// Super-blocks of unit u: outer tournament pair of round `round`, or super-block u alone in the
+// diagonal phase (round < 0).  b1 = -1 when the unit has a single super-block.
+__device__ inline void unit_blocks(const SpGroup &g, int round, int u, int &b0, int &b1) {
+    if (round < 0) { b0 = u; b1 = -1; return; }
+    int p, q;
+    rr_pair(g.players, round, u, p, q);
+    b0 = p;
+    b1 = q < g.nsuper ? q : -1;
+}
+
+// Wi[unit] <- W[{b0,b1},{b0,b1}] (zero where a super-block is absent), Vi[unit] <- I.  s = unit edge.
+__global__ __launch_bounds__(NT) void sp_gather_kernel(SpGroup g, int round, int s) {
+    const int u = blockIdx.y, m = blockIdx.z, U = gridDim.y;
+    int b0, b1;
+    unit_blocks(g, round, u, b0, b1);
+    const float *W = g.W + (int64_t)m * g.npad * g.npad;
+    float *Wi = g.Wi + ((int64_t)m * U + u) * s * s;
+    float *Vi = g.Vi + ((int64_t)m * U + u) * s * s;
+    for (int e4 = blockIdx.x * NT + threadIdx.x; e4 < s * s / 4; e4 += gridDim.x * NT) {
+        const int a = (e4 * 4) / s, b = (e4 * 4) % s;
+        const int ba = a < SB ? b0 : b1, bb = b < SB ? b0 : b1;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ba >= 0 && bb >= 0)
+            v = *reinterpret_cast<const float4 *>(W + (int64_t)(ba * SB + (a & (SB - 1))) * g.npad + bb * SB + (b & (SB - 1)));
+        *reinterpret_cast<float4 *>(Wi + a * s + b) = v;
+        *reinterpret_cast<float4 *>(Vi + a * s + b) =
+            make_float4(a == b ? 1.f : 0.f, a == b + 1 ? 1.f : 0.f, a == b + 2 ? 1.f : 0.f, a == b + 3 ? 1.f : 0.f);
+    }
+}
+
+// W[{b0,b1},{b0,b1}] <- Wi[unit]: the unit's own blocks after its inner rounds.
+__global__ __launch_bounds__(NT) void sp_scatter_kernel(SpGroup g, int round, int s) {
+    const int u = blockIdx.y, m = blockIdx.z, U = gridDim.y;
+    int b0, b1;
+    unit_blocks(g, round, u, b0, b1);
+    float *W = g.W + (int64_t)m * g.npad * g.npad;
+    const float *Wi = g.Wi + ((int64_t)m * U + u) * s * s;
+    for (int e4 = blockIdx.x * NT + threadIdx.x; e4 < s * s / 4; e4 += gridDim.x * NT) {
+        const int a = (e4 * 4) / s, b = (e4 * 4) % s;
+        const int ba = a < SB ? b0 : b1, bb = b < SB ? b0 : b1;
+        if (ba >= 0 && bb >= 0)
+            *reinterpret_cast<float4 *>(W + (int64_t)(ba * SB + (a & (SB - 1))) * g.npad + bb * SB + (b & (SB - 1))) =
+                *reinterpret_cast<const float4 *>(Wi + a * s + b);
+    }
+}
+
+// Column pass.  W part: T[blk(I,a), blk(J,b)] = sum_c W[blk(I,a), blk(J,c)] V_J[c, b] for unit pairs I > J;
+// accumulator part: Qout[rb, blk(J,b)] = sum_c Qin[rb, blk(J,c)] V_J[c, b] for every 128-row slab rb.
+__global__ __launch_bounds__(kfac::NTHREADS) void sp_pass_cols_kernel(SpGroup g, int round, int U, int s, int nW, int nrb,
+                                                                      const float *Qin, float *Qout) {
+    using namespace kfac;
+    __shared__ TileSmem sm;
+    const int m = blockIdx.y;
+    const int64_t np2 = (int64_t)g.npad * g.npad;
+    const int ld = g.npad;
+    int J, b, rowblk;          // unit and column part; global row super-block of the output tile
+    const float *src;          // matrix whose rows [rowblk] are multiplied
+    float *dst;
+    if ((int)blockIdx.x < nW) {
+        const int idx = blockIdx.x;
+        const int a = (idx >> 1) & 1;
+        b = idx & 1;
+        int i1;
+        tri_decode(idx >> 2, i1, J);
+        int I0, I1;
+        unit_blocks(g, round, i1 + 1, I0, I1);
+        rowblk = a ? I1 : I0;
+        if (rowblk < 0) return;
+        src = g.W + m * np2;
+        dst = g.T + m * np2;
+    } else {
+        const int idx = blockIdx.x - nW;
+        rowblk = idx % nrb;
+        J = (idx / nrb) >> 1;
+        b = (idx / nrb) & 1;
+        src = Qin + m * np2;
+        dst = Qout + m * np2;
+    }
+    int J0, J1;
+    unit_blocks(g, round, J, J0, J1);
+    const int cb = b ? J1 : J0;
+    if (cb < 0) return;
+    const float *V = g.Vi + ((int64_t)m * U + J) * s * s;
+    floatx16 acc[2][2];
+    bool first = true;
+    for (int c = 0; c < 2; ++c) {
+        const int kb = c ? J1 : J0;
+        if (kb < 0) continue;
+        OpStrided<float, true> A{src + (int64_t)rowblk * SB * ld + kb * SB, ld, 1, SB, SB, -1};
+        OpStrided<float, false> B{V + c * SB * s + b * SB, 1, s, SB, SB, -1};
+        gemm_tile(A, B, 0, 0, 0, SB, sm, acc, nullptr, first);
+        first = false;
+    }
+    float *out = dst + (int64_t)rowblk * SB * ld + cb * SB;
+    for_each_acc(acc, [&](int r, int c, float v) { out[(int64_t)r * ld + c] = v; });
+}
+
+// Row pass: W[blk(I,a), blk(J,b)] = sum_c V_I[c, a]^T T[blk(I,c), blk(J,b)] for unit pairs I > J, mirrored.
+__global__ __launch_bounds__(kfac::NTHREADS) void sp_pass_rows_kernel(SpGroup g, int round, int U, int s) {
+    using namespace kfac;
+    __shared__ TileSmem sm;
+    const int m = blockIdx.y;
+    const int64_t np2 = (int64_t)g.npad * g.npad;
+    const int ld = g.npad;
+    const int idx = blockIdx.x;
+    const int a = (idx >> 1) & 1, b = idx & 1;
+    int i1, J;
+    tri_decode(idx >> 2, i1, J);
+    const int I = i1 + 1;
+    int I0, I1, J0, J1;
+    unit_blocks(g, round, I, I0, I1);
+    unit_blocks(g, round, J, J0, J1);
+    const int rb = a ? I1 : I0, cb = b ? J1 : J0;
+    if (rb < 0 || cb < 0) return;
+    const float *V = g.Vi + ((int64_t)m * U + I) * s * s;
+    const float *T = g.T + m * np2;
+    float *W = g.W + m * np2;
+    floatx16 acc[2][2];
+    bool first = true;
+    for (int c = 0; c < 2; ++c) {
+        const int kb = c ? I1 : I0;
+        if (kb < 0) continue;
+        OpStrided<float, false> A{V + c * SB * s + a * SB, 1, s, SB, SB, -1};                          // elem(m,k) = V[k][m]
+        OpStrided<float, false> B{T + (int64_t)kb * SB * ld + cb * SB, 1, ld, SB, SB, -1};            // elem(n,k) = T[k][n]
+        gemm_tile(A, B, 0, 0, 0, SB, sm, acc, nullptr, first);
+        first = false;
+    }
+    float *out = W + (int64_t)rb * SB * ld + cb * SB;
+    float *mir = W + (int64_t)cb * SB * ld + rb * SB;
+    for_each_acc(acc, [&](int r, int c, float v) {
+        out[(int64_t)r * ld + c] = v;
+        mir[(int64_t)c * ld + r] = v;
+    });
+}
+
 // ---- host side ---------------------------------------------------------------------------------
 struct GroupPlan {
     int nblk, npad, players, npairs, npp;
+    bool two_level;
+    int nsuper, splayers, U;      // two-level: super-blocks, outer players (even), units per outer round
     std::vector<int> members;
+    size_t inner_mats() const { return members.size() * (size_t)std::max(U, nsuper); }
     size_t bytes() const {
         const size_t nm = members.size();
         size_t b = 0;
-        b += kfac_align_up(nm * 2 * (size_t)npad * npad * sizeof(float), 256);       // W, Qw
-        b += kfac_align_up(nm * (size_t)npairs * KP * KP * sizeof(float), 256);      // J
-        b += kfac_align_up(nm * (size_t)npairs * sizeof(int), 256);                  // idt
+        b += kfac_align_up(nm * (two_level ? 4 : 2) * (size_t)npad * npad * sizeof(float), 256);   // W, Qw (+ T, Qw')
+        if (two_level) {
+            b += kfac_align_up(nm * (size_t)U * 2 * LDI * LDI * sizeof(float), 256);              // Wi, Vi
+            b += kfac_align_up(inner_mats() * 4 * KP * KP * sizeof(float), 256);                   // inner J
+            b += kfac_align_up(inner_mats() * 4 * sizeof(int), 256);                               // inner idt
+        } else {
+            b += kfac_align_up(nm * (size_t)npairs * KP * KP * sizeof(float), 256);                // J
+            b += kfac_align_up(nm * (size_t)npairs * sizeof(int), 256);                            // idt
+        }
         b += kfac_align_up(nm * 2 * sizeof(double), 256);                            // norms
         b += kfac_align_up(nm * (size_t)npad * sizeof(int), 256);                    // perm
         b += kfac_align_up(nm * (size_t)npad * sizeof(double), 256);                 // Rayleigh quotients
@@ -735,16 +913,23 @@ struct GroupPlan {
 void make_plan(int batch, const int *d, std::vector<int> &small, std::vector<GroupPlan> &groups) {
     for (int i = 0; i < batch; ++i) {
         if (d[i] <= SMALL_MAX) { small.push_back(i); continue; }
-        const int nblk = (d[i] + EB - 1) / EB;
+        const bool two = d[i] >= TWO_LEVEL_MIN;
+        const int unit = two ? SB : EB;
+        const int npad = (d[i] + unit - 1) / unit * unit;
+        const int nblk = npad / EB;
         GroupPlan *gp = nullptr;
-        for (auto &g : groups) if (g.nblk == nblk) gp = &g;
+        for (auto &g : groups) if (g.nblk == nblk && g.two_level == two) gp = &g;
         if (!gp) {
             GroupPlan g;
+            g.two_level = two;
             g.nblk = nblk;
-            g.npad = nblk * EB;
+            g.npad = npad;
             g.players = (nblk + 1) & ~1;
             g.npairs = g.players / 2;
             g.npp = (g.npairs + PT - 1) / PT;
+            g.nsuper = npad / SB;
+            g.splayers = (g.nsuper + 1) & ~1;
+            g.U = g.splayers / 2;
             groups.push_back(g);
             gp = &groups.back();
         }
@@ -760,7 +945,10 @@ size_t small_bytes(size_t nsmall) {
 // Everything one group of equally sized factors needs while it is in flight on its stream.
 struct GroupRun {
     GroupPlan *plan;
-    BlkGroup g;
+    BlkGroup g;           // flat view: W, Qw (current accumulator), J, idt, norms
+    SpGroup sp;           // two-level view
+    BlkGroup gi, gd;      // two-level: inner groups of the regular rounds and of the diagonal phase
+    float *Qalt;          // two-level: the other accumulator buffer
     hipStream_t st;
     hipEvent_t ev;
     std::vector<BlkItem> items;
@@ -789,17 +977,69 @@ int enqueue_offnorm(kfac_ctx *ctx, GroupRun &r) {
     return KFAC_OK;
 }
 
-int enqueue_sweep(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int inner_cap, float inner_tol) {
-    for (int rd = 0; rd < r.plan->players - 1; ++rd) {
-        {
-            KfacProfScope prof(ctx, KC_EIG_SOLVE, r.solve_flops, 0.0, r.st);
-            hipLaunchKernelGGL(blk_solve_kernel, dim3(r.plan->npairs, r.nm), dim3(NT), lds_solve, r.st, r.g, rd, inner_cap, inner_tol);
-        }
-        {
-            KfacProfScope prof(ctx, KC_EIG_APPLY, r.apply_flops, 0.0, r.st);
-            hipLaunchKernelGGL(blk_apply_kernel, dim3(r.ntiles, r.nm), dim3(NT), APPLY_LDS_BYTES, r.st, r.g, rd, r.ntiles_w, r.nrb);
-        }
+// One round of (pivot solves, application) on a block group.
+void enqueue_round(kfac_ctx *ctx, hipStream_t st, const BlkGroup &g, int rd, int ntiles, int ntiles_w, int nrb,
+                   size_t lds_solve, int inner_cap, float inner_tol, double solve_flops, double apply_flops) {
+    {
+        KfacProfScope prof(ctx, KC_EIG_SOLVE, solve_flops, 0.0, st);
+        hipLaunchKernelGGL(blk_solve_kernel, dim3(g.npairs, g.nmat), dim3(NT), lds_solve, st, g, rd, inner_cap, inner_tol);
     }
+    {
+        KfacProfScope prof(ctx, KC_EIG_APPLY, apply_flops, 0.0, st);
+        hipLaunchKernelGGL(blk_apply_kernel, dim3(ntiles, g.nmat), dim3(NT), APPLY_LDS_BYTES, st, g, rd, ntiles_w, nrb);
+    }
+}
+
+int enqueue_sweep_flat(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int inner_cap, float inner_tol) {
+    for (int rd = 0; rd < r.plan->players - 1; ++rd)
+        enqueue_round(ctx, r.st, r.g, rd, r.ntiles, r.ntiles_w, r.nrb, lds_solve, inner_cap, inner_tol, r.solve_flops, r.apply_flops);
+    KFAC_HIP_CHECK(hipGetLastError());
+    return KFAC_OK;
+}
+
+// One phase of the two-level sweep: gather the units, run their inner rounds, apply their transforms.
+void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int inner_cap, float inner_tol) {
+    const GroupPlan &gp = *r.plan;
+    hipStream_t st = r.st;
+    const bool diag = round < 0;
+    const int U = diag ? gp.nsuper : gp.U;
+    const int s = diag ? SB : LDI;
+    const BlkGroup &gin = diag ? r.gd : r.gi;
+    const int inner_rounds = diag ? gin.players - 1 : gin.players / 2;
+    {
+        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+        hipLaunchKernelGGL(sp_gather_kernel, dim3(s * s / 4 / NT, U, r.nm), dim3(NT), 0, st, r.sp, round, s);
+    }
+    const int in_tw = gin.npp * (gin.npp + 1) / 2, in_nrb = s / TS, in_tiles = in_tw + in_nrb * gin.npp;
+    const double in_solve = (double)gin.nmat * gin.npairs * 9.0 * KP * KP * (KP - 1);
+    const double in_apply = (double)gin.nmat * 8.0 * s * s * EB;
+    for (int ri = 0; ri < inner_rounds; ++ri)
+        enqueue_round(ctx, st, gin, ri, in_tiles, in_tw, in_nrb, lds_solve, inner_cap, inner_tol, in_solve, in_apply);
+    const int nW = 4 * (U * (U - 1) / 2);
+    const int nrb = gp.npad / SB;
+    // algorithmic work of the two passes: every element of half the symmetric matrix and of the
+    // accumulator gets two (one) dot products of the unit edge s
+    double fl = 0.0;
+    for (int i = 0; i < r.nm; ++i) fl += 4.0 * (double)r.items[i].n * r.items[i].n * s;
+    {
+        KfacProfScope prof(ctx, KC_EIG_OUTER, 0.75 * fl, 0.0, st);
+        hipLaunchKernelGGL(sp_pass_cols_kernel, dim3(nW + nrb * U * 2, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s, nW, nrb,
+                           (const float *)r.g.Qw, r.Qalt);
+    }
+    if (nW > 0) {
+        KfacProfScope prof(ctx, KC_EIG_OUTER, 0.25 * fl, 0.0, st);
+        hipLaunchKernelGGL(sp_pass_rows_kernel, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
+    }
+    {
+        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+        hipLaunchKernelGGL(sp_scatter_kernel, dim3(s * s / 4 / NT, U, r.nm), dim3(NT), 0, st, r.sp, round, s);
+    }
+    std::swap(r.g.Qw, r.Qalt);
+}
+
+int enqueue_sweep_two_level(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int inner_cap, float inner_tol) {
+    enqueue_phase(ctx, r, -1, lds_solve, inner_cap, inner_tol);
+    for (int rd = 0; rd < r.plan->splayers - 1; ++rd) enqueue_phase(ctx, r, rd, lds_solve, inner_cap, inner_tol);
     KFAC_HIP_CHECK(hipGetLastError());
     return KFAC_OK;
 }
@@ -941,11 +1181,34 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         char *p = wsp;
         BlkGroup &g = r.g;
         g.nmat = nm; g.nblk = gp.nblk; g.npad = gp.npad; g.players = gp.players; g.npairs = gp.npairs; g.npp = gp.npp;
+        g.bipartite = 0;
         g.W = (float *)p;
         g.Qw = g.W + nm * np2;
-        p += kfac_align_up(nm * 2 * np2 * sizeof(float), 256);
-        g.J = (float *)p; p += kfac_align_up((size_t)nm * gp.npairs * KP * KP * sizeof(float), 256);
-        g.idt = (int *)p; p += kfac_align_up((size_t)nm * gp.npairs * sizeof(int), 256);
+        r.Qalt = nullptr;
+        if (gp.two_level) {
+            SpGroup &sp = r.sp;
+            sp.W = g.W;
+            sp.T = g.W + 2 * nm * np2;
+            r.Qalt = g.W + 3 * nm * np2;
+            sp.nmat = nm; sp.npad = gp.npad; sp.nsuper = gp.nsuper; sp.players = gp.splayers;
+            p += kfac_align_up(nm * 4 * np2 * sizeof(float), 256);
+            sp.Wi = (float *)p;
+            sp.Vi = sp.Wi + (size_t)nm * gp.U * LDI * LDI;
+            p += kfac_align_up((size_t)nm * gp.U * 2 * LDI * LDI * sizeof(float), 256);
+            float *Jin = (float *)p; p += kfac_align_up(gp.inner_mats() * 4 * KP * KP * sizeof(float), 256);
+            int *idtin = (int *)p; p += kfac_align_up(gp.inner_mats() * 4 * sizeof(int), 256);
+            g.J = Jin; g.idt = idtin;   // unused by the flat kernels for this group
+            // inner group of a regular outer round: units of 4 + 4 small blocks, bipartite pairing
+            r.gi = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.U, 2 * SB / EB, LDI, 2 * SB / EB, SB / EB,
+                            (SB / EB + PT - 1) / PT, 1};
+            // inner group of the diagonal phase: one super-block of 4 small blocks each, tournament pairing
+            r.gd = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.nsuper, SB / EB, SB, SB / EB, SB / EB / 2,
+                            (SB / EB / 2 + PT - 1) / PT, 0};
+        } else {
+            p += kfac_align_up(nm * 2 * np2 * sizeof(float), 256);
+            g.J = (float *)p; p += kfac_align_up((size_t)nm * gp.npairs * KP * KP * sizeof(float), 256);
+            g.idt = (int *)p; p += kfac_align_up((size_t)nm * gp.npairs * sizeof(int), 256);
+        }
         g.norms = (double *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(double), 256);
         r.perm = (int *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(int), 256);
         r.lam64 = (double *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(double), 256);
@@ -1011,7 +1274,8 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
                 rc = enqueue_post(ctx, r);
                 post[gi] = 1;
             } else {
-                rc = enqueue_sweep(ctx, r, lds_solve, inner_cap, inner_tol);
+                rc = r.plan->two_level ? enqueue_sweep_two_level(ctx, r, lds_solve, inner_cap, inner_tol)
+                                       : enqueue_sweep_flat(ctx, r, lds_solve, inner_cap, inner_tol);
                 if (rc == KFAC_OK) rc = enqueue_offnorm(ctx, r);
                 ++r.sweep;
             }

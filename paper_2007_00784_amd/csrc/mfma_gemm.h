@@ -138,17 +138,19 @@ struct TileSmem {
 // fetches (csum[s]); summed over the threads that share a row index this is sum_k elem_A(i, k).
 template <class OpA, class OpB, bool COLSUM = false>
 __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int kend, TileSmem &sm,
-                                 floatx16 (&acc)[2][2], float *csum = nullptr) {
+                                 floatx16 (&acc)[2][2], float *csum = nullptr, bool zero_acc = true) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int lk = lane >> 5, lc = lane & 31;
+    if (zero_acc) {   // false: keep accumulating into acc (a contraction given in several segments)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    }
     const int nslab = (kend - kbeg + BK - 1) / BK;
     if (nslab <= 0) return;
     float ra[EPT], rb[EPT];
