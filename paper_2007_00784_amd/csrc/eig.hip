@@ -73,7 +73,9 @@ struct RotEntry { int p, q; float c, s; };
 // is below skip_rel * ||S||_F / k are left alone (and exact zeros always are, which keeps zero-padded
 // rows and columns decoupled).  KC > 0 fixes k at compile time (index arithmetic becomes shifts and
 // each thread's column pair is loop invariant); KC == 0 takes k at run time.
-template <int KC>
+// CROSS: a sweep visits only the pairs (i, k/2 + j) between the two halves, in k/2 rounds (the pairs inside
+// each half are left to the caller's schedule).
+template <int KC, bool CROSS = false>
 __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max_sweeps, float tol, float skip_rel,
                                    float *red, RotEntry *rot, int *rotflag) {
     const int tid = threadIdx.x;
@@ -95,21 +97,30 @@ __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max
         res.sweeps = sweep;
         if (!(o2 > tol * tol * res.nrm2) || sweep >= max_sweeps) break;
         const float thr = skip_rel * sqrtf(res.nrm2) / (float)k;
-        for (int r = 0; r < k - 1; ++r) {
+        const int nrounds = CROSS ? half : k - 1;
+        for (int r = 0; r < nrounds; ++r) {
             if (tid < half) {
                 int p, q;
-                rr_pair(k, r, tid, p, q);
+                if (CROSS) { p = tid; q = half + (tid + r) % half; }
+                else rr_pair(k, r, tid, p, q);
                 const float app = S[p * ld + p], aqq = S[q * ld + q], apq = S[p * ld + q];
                 float c = 1.f, s = 0.f;
                 if (fabsf(apq) > thr) {
-                    // tangent of the smaller rotation angle in fp32; the normalisation in fp64, so that
-                    // c^2 + s^2 = 1 to fp32 rounding without bias (a biased rsqrt makes V drift)
-                    const float theta = (aqq - app) / (2.f * apq);
-                    const float t = copysignf(1.f, theta) / (fabsf(theta) + sqrtf(fmaf(theta, theta, 1.f)));
-                    const double td = (double)t;
-                    const double cd = 1.0 / sqrt(fma(td, td, 1.0));
-                    c = (float)cd;
-                    s = (float)(td * cd);
+                    // smaller rotation angle: with dd = aqq - app, b = 2 apq,
+                    //   tan = sign(dd b) |b| / (|dd| + sqrt(dd^2 + b^2)),  c = 1/sqrt(1 + tan^2),  s = tan c
+                    // on operands scaled by max(|dd|, |b|), with the hardware reciprocal, square root and
+                    // reciprocal square root; one Newton step on c removes the bias of the 1 ulp reciprocal
+                    // square root, which would otherwise scale S and V a little at every rotation
+                    const float dd = aqq - app, b = 2.f * apq;
+                    const float rm = __builtin_amdgcn_rcpf(fmaxf(fabsf(dd), fabsf(b)));
+                    const float dn = fabsf(dd) * rm, bn = fabsf(b) * rm;
+                    const float h = __builtin_amdgcn_sqrtf(fmaf(dn, dn, bn * bn));
+                    const float ta = bn * __builtin_amdgcn_rcpf(dn + h);
+                    const float t = copysignf(ta, __uint_as_float(__float_as_uint(dd) ^ (__float_as_uint(b) & 0x80000000u)));
+                    const float w = fmaf(t, t, 1.f);
+                    c = __builtin_amdgcn_rsqf(w);
+                    c = c * fmaf(-0.5f * w, c * c, 1.5f);
+                    s = t * c;
                     *rotflag = 1;
                 }
                 rot[tid] = RotEntry{p, q, c, s};
@@ -445,7 +456,12 @@ __global__ __launch_bounds__(NT) void blk_solve_kernel(BlkGroup g, int round, in
         }
     }
     __syncthreads();
-    const JacobiResult res = jacobi_lds<KP>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
+    // The pairs inside a block need one visit per sweep: a tournament gives it in its round 0 (where every
+    // block plays, possibly against the phantom), a bipartite schedule leaves it to its caller.  Every
+    // other visit rotates only the pairs between the two blocks.
+    const JacobiResult res =
+        (g.bipartite || round > 0) ? jacobi_lds<KP, true>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag)
+                    : jacobi_lds<KP, false>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
     if (res.rotations > 0) polish_pivot_mfma(sm.V, sm.S);
     float *J = g.J + ((int64_t)m * g.npairs + pj) * (KP * KP);
     for (int e = tid; e < KP * KP; e += NT) J[e] = sm.V[(e / KP) * PLD + (e % KP)];
@@ -796,7 +812,7 @@ __global__ __launch_bounds__(NT) void sp_scatter_kernel(SpGroup g, int round, in
 
 // Column pass.  W part: T[blk(I,a), blk(J,b)] = sum_c W[blk(I,a), blk(J,c)] V_J[c, b] for unit pairs I > J;
 // accumulator part: Qout[rb, blk(J,b)] = sum_c Qin[rb, blk(J,c)] V_J[c, b] for every 128-row slab rb.
-__global__ __launch_bounds__(kfac::NTHREADS) void sp_pass_cols_kernel(SpGroup g, int round, int U, int s, int nW, int nrb,
+__global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void sp_pass_cols_kernel(SpGroup g, int round, int U, int s, int nW, int nrb,
                                                                       const float *Qin, float *Qout) {
     using namespace kfac;
     __shared__ TileSmem sm;
@@ -831,22 +847,20 @@ __global__ __launch_bounds__(kfac::NTHREADS) void sp_pass_cols_kernel(SpGroup g,
     const int cb = b ? J1 : J0;
     if (cb < 0) return;
     const float *V = g.Vi + ((int64_t)m * U + J) * s * s;
+    // one contraction over both column blocks of the unit: the A operand jumps from block J0 to block J1
+    // half way, the rows of V are contiguous
     floatx16 acc[2][2];
-    bool first = true;
-    for (int c = 0; c < 2; ++c) {
-        const int kb = c ? J1 : J0;
-        if (kb < 0) continue;
-        OpStrided<float, true> A{src + (int64_t)rowblk * SB * ld + kb * SB, ld, 1, SB, SB, -1};
-        OpStrided<float, false> B{V + c * SB * s + b * SB, 1, s, SB, SB, -1};
-        gemm_tile(A, B, 0, 0, 0, SB, sm, acc, nullptr, first);
-        first = false;
-    }
+    const int K = J1 >= 0 ? 2 * SB : SB;
+    OpStrided<float, true> A{src + (int64_t)rowblk * SB * ld + J0 * SB, ld, 1, SB, K, -1};
+    if (J1 >= 0) A.set_segment(SB, (int64_t)(J1 - J0 - 1) * SB);
+    OpStrided<float, false> B{V + b * SB, 1, s, SB, K, -1};
+    gemm_tile(A, B, 0, 0, 0, K, sm, acc);
     float *out = dst + (int64_t)rowblk * SB * ld + cb * SB;
     for_each_acc(acc, [&](int r, int c, float v) { out[(int64_t)r * ld + c] = v; });
 }
 
 // Row pass: W[blk(I,a), blk(J,b)] = sum_c V_I[c, a]^T T[blk(I,c), blk(J,b)] for unit pairs I > J, mirrored.
-__global__ __launch_bounds__(kfac::NTHREADS) void sp_pass_rows_kernel(SpGroup g, int round, int U, int s) {
+__global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void sp_pass_rows_kernel(SpGroup g, int round, int U, int s) {
     using namespace kfac;
     __shared__ TileSmem sm;
     const int m = blockIdx.y;
@@ -866,15 +880,11 @@ __global__ __launch_bounds__(kfac::NTHREADS) void sp_pass_rows_kernel(SpGroup g,
     const float *T = g.T + m * np2;
     float *W = g.W + m * np2;
     floatx16 acc[2][2];
-    bool first = true;
-    for (int c = 0; c < 2; ++c) {
-        const int kb = c ? I1 : I0;
-        if (kb < 0) continue;
-        OpStrided<float, false> A{V + c * SB * s + a * SB, 1, s, SB, SB, -1};                          // elem(m,k) = V[k][m]
-        OpStrided<float, false> B{T + (int64_t)kb * SB * ld + cb * SB, 1, ld, SB, SB, -1};            // elem(n,k) = T[k][n]
-        gemm_tile(A, B, 0, 0, 0, SB, sm, acc, nullptr, first);
-        first = false;
-    }
+    const int K = I1 >= 0 ? 2 * SB : SB;
+    OpStrided<float, false> A{V + a * SB, 1, s, SB, K, -1};                                    // elem(m,k) = V[k][m]
+    OpStrided<float, false> B{T + (int64_t)I0 * SB * ld + cb * SB, 1, ld, SB, K, -1};         // elem(n,k) = T[k][n]
+    if (I1 >= 0) B.set_segment(SB, (int64_t)(I1 - I0 - 1) * SB * ld);
+    gemm_tile(A, B, 0, 0, 0, K, sm, acc);
     float *out = W + (int64_t)rb * SB * ld + cb * SB;
     float *mir = W + (int64_t)cb * SB * ld + rb * SB;
     for_each_acc(acc, [&](int r, int c, float v) {

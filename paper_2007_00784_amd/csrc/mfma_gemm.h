@@ -31,46 +31,56 @@ __device__ inline float to_float(unsigned short v) { return __uint_as_float(((un
 // Thread mapping, KFAST : kk = tid & 15,  ii = (tid >> 4) + 16*s
 //                 IFAST : ii = tid & 127, kk = (tid >> 7) + 2*s          (s = 0..7)
 
-// elem(i,k) = p[i*si + k*sk] for i < I, k < K; 1.0 on row ones_i (if >= 0); else 0.
-// Loads are branch free: an out-of-range element reads p[0] and is replaced by a select, so the
-// compiler can issue a slab's loads back to back and interleave them with the MFMAs.
+// elem(i,k) = p[i*si + k*sk] for i < I, k < K, else 0  (ones_i is unused and kept at -1).
+// Addressing: one base pointer that is uniform over the workgroup (it advances by a whole slab, so it
+// lives in scalar registers) plus an unsigned 32-bit offset per load slot that never changes.  Loads
+// are branch free: an out-of-range element reads the base and is replaced by a select, so a slab's
+// loads issue back to back and interleave with the MFMAs.
+// A contraction index may run over two separate memory ranges: set_segment(k, delta) moves the base by
+// `delta` more elements when the slab starting at contraction index k is entered (k a multiple of BK).
 template <typename E, bool KFAST_>
 struct OpStrided {
     static constexpr bool KFAST = KFAST_;
     const E *p;
     int64_t si, sk;
     int I, K, ones_i;
+    int seg_k;
+    int64_t seg_delta;
     // thread state
-    int64_t off[EPT];   // element offset of each of this thread's slots in the current slab
-    int k_t;            // k of slot 0
-    unsigned in_mask, ones_mask;   // per slot: row index inside the operand / is the ones row
+    const E *pb;          // tile base for the current slab (uniform)
+    unsigned off[EPT];    // slot offsets relative to pb
+    int k_t, k_slab;      // k of slot 0; first k of the current slab
+    unsigned in_mask;     // per slot: row index inside the operand
+    __device__ void set_segment(int k, int64_t delta) { seg_k = k; seg_delta = delta; }
     __device__ void start(int tid, int i0, int k0) {
-        const int i_t = KFAST ? i0 + (tid >> 4) : i0 + (tid & 127);
-        k_t = KFAST ? k0 + (tid & 15) : k0 + (tid >> 7);
-        in_mask = ones_mask = 0;
+        const int di = KFAST ? (tid >> 4) : (tid & 127);
+        const int dk = KFAST ? (tid & 15) : (tid >> 7);
+        pb = p + (int64_t)i0 * si + (int64_t)k0 * sk;
+        k_t = k0 + dk;
+        k_slab = k0;
+        in_mask = 0;
 #pragma unroll
         for (int s = 0; s < EPT; ++s) {
-            const int i = KFAST ? i_t + 16 * s : i_t;
-            const int k = KFAST ? k_t : k_t + 2 * s;
-            off[s] = (int64_t)i * si + (int64_t)k * sk;
-            in_mask |= (i < I ? 1u : 0u) << s;
-            ones_mask |= (i == ones_i ? 1u : 0u) << s;
+            const int i = KFAST ? di + 16 * s : di;
+            const int k = KFAST ? dk : dk + 2 * s;
+            off[s] = (unsigned)((int64_t)i * si + (int64_t)k * sk);
+            in_mask |= (i0 + i < I ? 1u : 0u) << s;
         }
     }
     __device__ void fetch(float (&r)[EPT]) const {
 #pragma unroll
         for (int s = 0; s < EPT; ++s) {
             const int k = KFAST ? k_t : k_t + 2 * s;
-            const bool kv = k < K;
-            const bool ld = kv && ((in_mask >> s) & 1u);
-            const float v = to_float(p[ld ? off[s] : 0]);
-            r[s] = ld ? v : ((kv && ((ones_mask >> s) & 1u)) ? 1.f : 0.f);
+            const bool ld = (k < K) && ((in_mask >> s) & 1u);
+            const float v = to_float(pb[ld ? off[s] : 0u]);
+            r[s] = ld ? v : 0.f;
         }
     }
     __device__ void next() {
         k_t += BK;
-#pragma unroll
-        for (int s = 0; s < EPT; ++s) off[s] += (int64_t)BK * sk;
+        k_slab += BK;
+        pb += (int64_t)BK * sk;
+        if (seg_k != 0 && k_slab == seg_k) pb += seg_delta;
     }
 };
 
@@ -173,10 +183,6 @@ __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int k
             B.next();
             A.fetch(ra);
             B.fetch(rb);
-            if (COLSUM) {
-#pragma unroll
-                for (int t = 0; t < EPT; ++t) csum[t] += ra[t];
-            }
         }
         // all MFMA operands of the slab are read from LDS up front (32 registers), so the LDS latency is
         // paid once per slab instead of once per k-step and the 32 MFMAs issue back to back
@@ -197,6 +203,10 @@ __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int k
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b1[j], acc[1][1], 0, 0, 0);
         }
         if (more) {
+            if (COLSUM) {   // here, not at the fetch: the loads stay in flight behind the MFMAs
+#pragma unroll
+                for (int t = 0; t < EPT; ++t) csum[t] += ra[t];
+            }
             store_slab<OpA::KFAST>(sm.a[cur ^ 1], ra, tid);
             store_slab<OpB::KFAST>(sm.b[cur ^ 1], rb, tid);
         }
@@ -223,7 +233,7 @@ __device__ inline void for_each_acc(const floatx16 (&acc)[2][2], F f) {
 // C = A * B over a rectangular grid of tiles (blockIdx.y: row tile, blockIdx.x: column tile); the
 // epilogue object is called as epi(row, col, value) for every in-range element.
 template <class OpA, class OpB, class Epi>
-__global__ __launch_bounds__(NTHREADS) void gemm_generic_kernel(OpA a, OpB b, Epi epi, int M, int N, int K) {
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void gemm_generic_kernel(OpA a, OpB b, Epi epi, int M, int N, int K) {
     __shared__ TileSmem sm;
     const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
     floatx16 acc[2][2];

@@ -45,7 +45,7 @@ __device__ inline void run_tile(OpA a, OpB b, int i0, int j0, int K, int M, int 
 }
 
 template <int STAGE>
-__global__ __launch_bounds__(NTHREADS) void precond_stage_kernel(const LayerDev *layers, const TileRef *tiles) {
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void precond_stage_kernel(const LayerDev *layers, const TileRef *tiles) {
     __shared__ TileSmem sm;
     const TileRef tr = tiles[blockIdx.x];
     const LayerDev L = layers[tr.layer];

@@ -72,7 +72,7 @@ __device__ inline void reduce_colsum(const float (&csum)[EPT], float *scratch /*
 }
 
 template <class Op>
-__global__ __launch_bounds__(NTHREADS) void syrk_kernel(Op opA, SyrkArgs g) {
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void syrk_kernel(Op opA, SyrkArgs g) {
     __shared__ TileSmem sm;
     __shared__ float cs[BM];
     int ti, tj;
