@@ -18,9 +18,12 @@
 // Convergence is decided on the host once per sweep from off(F)_F / ||F||_F.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
+#include <type_traits>
 #include <vector>
 #include "kfac_internal.h"
 #include "mfma_gemm.h"
+#include "mfma_gemm_x3.h"
 
 namespace {
 
@@ -761,8 +764,30 @@ constexpr int TWO_LEVEL_MIN = 2048;     // factors at least this large take the 
 struct SpGroup {
     float *W, *T;          // [nmat][npad][npad]: rotated matrix, column-pass result
     float *Wi, *Vi;        // gathered units and their accumulated transforms: [nmat*U][s][s]
+    float *scale;          // [nmat][2]: power of two that brings ||W||_F into [2^12, 2^13), and its inverse
     int nmat, npad, nsuper, players;
 };
+
+// The passes below run on the split-fp16 engine (template argument X3; the fp32 engine otherwise).  Its
+// operands are scaled into fp16's range: W and T by the factor's own power of two (no entry of an
+// orthogonally rotated matrix exceeds its Frobenius norm, which the rotations preserve), the transforms
+// and the eigenvector accumulator, whose entries are at most 1, by 2^14.
+constexpr float X3_UNIT = 16384.f;
+
+__global__ void sp_scale_kernel(SpGroup g, const double *norms) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= g.nmat) return;
+    const double n2 = norms[2 * m] + norms[2 * m + 1];
+    float sc = 1.f, inv = 1.f;
+    if (n2 > 0.0 && n2 < 1e300) {
+        const int e = ilogb(sqrt(n2));          // ||W||_F in [2^e, 2^(e+1))
+        const int k = min(max(12 - e, -100), 100);
+        sc = ldexpf(1.f, k);
+        inv = ldexpf(1.f, -k);
+    }
+    g.scale[2 * m] = sc;
+    g.scale[2 * m + 1] = inv;
+}
 
 // Super-blocks of unit u: outer tournament pair of round `round`, or super-block u alone in the
 // diagonal phase (round < 0).  b1 = -1 when the unit has a single super-block.
@@ -810,20 +835,38 @@ __global__ __launch_bounds__(NT) void sp_scatter_kernel(SpGroup g, int round, in
     }
 }
 
+// Vi[unit] <- Vi[unit] - I for the split engine's passes, which compute X V as X + X (V - I) with only the
+// second term on the split engine: its error then scales with |V - I| and vanishes as the sweeps converge.
+__global__ __launch_bounds__(NT) void sp_minus_identity_kernel(SpGroup g, int s, int count) {
+    const int e = blockIdx.x * NT + threadIdx.x;      // (unit, diagonal index)
+    if (e >= count) return;
+    const int u = e / s, a = e - u * s;
+    g.Vi[(int64_t)u * s * s + (int64_t)a * s + a] -= 1.f;
+}
+
 // Column pass.  W part: T[blk(I,a), blk(J,b)] = sum_c W[blk(I,a), blk(J,c)] V_J[c, b] for unit pairs I > J;
 // accumulator part: Qout[rb, blk(J,b)] = sum_c Qin[rb, blk(J,c)] V_J[c, b] for every 128-row slab rb.
+template <bool X3>
 __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void sp_pass_cols_kernel(SpGroup g, int round, int U, int s, int nW, int nrb,
-                                                                      const float *Qin, float *Qout) {
+                                                                      const float *Qin, float *Qout, int bx0) {
     using namespace kfac;
-    __shared__ TileSmem sm;
+    __shared__ typename std::conditional<X3, X3Smem, TileSmem>::type sm;
     const int m = blockIdx.y;
     const int64_t np2 = (int64_t)g.npad * g.npad;
     const int ld = g.npad;
     int J, b, rowblk;          // unit and column part; global row super-block of the output tile
     const float *src;          // matrix whose rows [rowblk] are multiplied
     float *dst;
-    if ((int)blockIdx.x < nW) {
-        const int idx = blockIdx.x;
+    // The fp16 MFMA's fp32 accumulation truncates toward minus infinity: a bias of about 2^-25 of every
+    // result, always downwards.  Summed down a column of the accumulator, against the all-positive leading
+    // eigenvector of a factor, such a bias adds up coherently over the rounds.  Feeding the negated operand in
+    // every other round (and negating the result) turns it upwards there, so it cancels over two rounds.
+    const float sgn = (round & 1) ? -1.f : 1.f;
+    float in_scale = X3_UNIT, out_scale = 1.f / (X3_UNIT * X3_UNIT);   // split engine: accumulator part
+    const int bx = blockIdx.x + bx0;
+    if (bx < nW) {
+        if (X3) { in_scale = g.scale[2 * m]; out_scale = g.scale[2 * m + 1] * (1.f / X3_UNIT); }
+        const int idx = bx;
         const int a = (idx >> 1) & 1;
         b = idx & 1;
         int i1;
@@ -835,7 +878,7 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
         src = g.W + m * np2;
         dst = g.T + m * np2;
     } else {
-        const int idx = blockIdx.x - nW;
+        const int idx = bx - nW;
         rowblk = idx % nrb;
         J = (idx / nrb) >> 1;
         b = (idx / nrb) & 1;
@@ -851,18 +894,36 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
     // half way, the rows of V are contiguous
     floatx16 acc[2][2];
     const int K = J1 >= 0 ? 2 * SB : SB;
-    OpStrided<float, true> A{src + (int64_t)rowblk * SB * ld + J0 * SB, ld, 1, SB, K, -1};
-    if (J1 >= 0) A.set_segment(SB, (int64_t)(J1 - J0 - 1) * SB);
-    OpStrided<float, false> B{V + b * SB, 1, s, SB, K, -1};
-    gemm_tile(A, B, 0, 0, 0, K, sm, acc);
     float *out = dst + (int64_t)rowblk * SB * ld + cb * SB;
-    for_each_acc(acc, [&](int r, int c, float v) { out[(int64_t)r * ld + c] = v; });
+    if constexpr (X3) {
+        X3Op<true> A{src + (int64_t)rowblk * SB * ld + J0 * SB, ld, sgn * in_scale, 0, 0};
+        out_scale *= sgn;
+        if (J1 >= 0) A.set_segment(SB, (int64_t)(J1 - J0 - 1) * SB);
+        X3Op<false> B{V + b * SB, s, X3_UNIT, 0, 0};      // V holds V - I here: X V = X + X (V - I)
+        gemm_tile_x3(A, B, K, sm, acc);
+        // all loads of the input tile are issued before the first store (the two may alias for the compiler)
+        const float *in = src + (int64_t)rowblk * SB * ld + cb * SB;
+        floatx16 xin[2][2];
+        fill_acc(xin, [&](int r, int c) { return in[(int64_t)r * ld + c]; });
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = acc[i][j] * out_scale + xin[i][j];
+        for_each_acc(acc, [&](int r, int c, float v) { out[(int64_t)r * ld + c] = v; });
+    } else {
+        OpStrided<float, true> A{src + (int64_t)rowblk * SB * ld + J0 * SB, ld, 1, SB, K, -1};
+        if (J1 >= 0) A.set_segment(SB, (int64_t)(J1 - J0 - 1) * SB);
+        OpStrided<float, false> B{V + b * SB, 1, s, SB, K, -1};
+        gemm_tile(A, B, 0, 0, 0, K, sm, acc);
+        for_each_acc(acc, [&](int r, int c, float v) { out[(int64_t)r * ld + c] = v; });
+    }
 }
 
 // Row pass: W[blk(I,a), blk(J,b)] = sum_c V_I[c, a]^T T[blk(I,c), blk(J,b)] for unit pairs I > J, mirrored.
+template <bool X3>
 __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void sp_pass_rows_kernel(SpGroup g, int round, int U, int s) {
     using namespace kfac;
-    __shared__ TileSmem sm;
+    __shared__ typename std::conditional<X3, X3Smem, TileSmem>::type sm;
     const int m = blockIdx.y;
     const int64_t np2 = (int64_t)g.npad * g.npad;
     const int ld = g.npad;
@@ -881,16 +942,33 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
     float *W = g.W + m * np2;
     floatx16 acc[2][2];
     const int K = I1 >= 0 ? 2 * SB : SB;
-    OpStrided<float, false> A{V + a * SB, 1, s, SB, K, -1};                                    // elem(m,k) = V[k][m]
-    OpStrided<float, false> B{T + (int64_t)I0 * SB * ld + cb * SB, 1, ld, SB, K, -1};         // elem(n,k) = T[k][n]
-    if (I1 >= 0) B.set_segment(SB, (int64_t)(I1 - I0 - 1) * SB * ld);
-    gemm_tile(A, B, 0, 0, 0, K, sm, acc);
+    float out_scale = 1.f;
+    if constexpr (X3) {
+        const float sgn = (round & 1) ? -1.f : 1.f;   // alternating sign: see the column pass
+        X3Op<false> A{V + a * SB, s, sgn * X3_UNIT, 0, 0};                              // elem(m,k) = (V - I)[k][m]
+        X3Op<false> B{T + (int64_t)I0 * SB * ld + cb * SB, ld, g.scale[2 * m], 0, 0};   // elem(n,k) = T[k][n]
+        if (I1 >= 0) B.set_segment(SB, (int64_t)(I1 - I0 - 1) * SB * ld);
+        gemm_tile_x3(A, B, K, sm, acc);
+        out_scale = sgn * g.scale[2 * m + 1] * (1.f / X3_UNIT);
+    } else {
+        OpStrided<float, false> A{V + a * SB, 1, s, SB, K, -1};                                    // elem(m,k) = V[k][m]
+        OpStrided<float, false> B{T + (int64_t)I0 * SB * ld + cb * SB, 1, ld, SB, K, -1};         // elem(n,k) = T[k][n]
+        if (I1 >= 0) B.set_segment(SB, (int64_t)(I1 - I0 - 1) * SB * ld);
+        gemm_tile(A, B, 0, 0, 0, K, sm, acc);
+    }
     float *out = W + (int64_t)rb * SB * ld + cb * SB;
     float *mir = W + (int64_t)cb * SB * ld + rb * SB;
-    for_each_acc(acc, [&](int r, int c, float v) {
-        out[(int64_t)r * ld + c] = v;
-        mir[(int64_t)c * ld + r] = v;
-    });
+    if constexpr (X3) {
+        const float *tin = T + (int64_t)rb * SB * ld + cb * SB;   // V^T T = T + (V - I)^T T
+        floatx16 xin[2][2];
+        fill_acc(xin, [&](int r, int c) { return tin[(int64_t)r * ld + c]; });
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = acc[i][j] * out_scale + xin[i][j];
+    }
+    for_each_acc(acc, [&](int r, int c, float v) { out[(int64_t)r * ld + c] = v; });
+    store_acc_transposed(acc, reinterpret_cast<float *>(&sm), mir, ld);
 }
 
 // ---- host side ---------------------------------------------------------------------------------
@@ -908,6 +986,7 @@ struct GroupPlan {
             b += kfac_align_up(nm * (size_t)U * 2 * LDI * LDI * sizeof(float), 256);              // Wi, Vi
             b += kfac_align_up(inner_mats() * 4 * KP * KP * sizeof(float), 256);                   // inner J
             b += kfac_align_up(inner_mats() * 4 * sizeof(int), 256);                               // inner idt
+            b += kfac_align_up(nm * 2 * sizeof(float), 256);                                       // scale
         } else {
             b += kfac_align_up(nm * (size_t)npairs * KP * KP * sizeof(float), 256);                // J
             b += kfac_align_up(nm * (size_t)npairs * sizeof(int), 256);                            // idt
@@ -970,6 +1049,7 @@ struct GroupRun {
     double apply_flops, solve_flops;
     int sweep;
     bool done;
+    bool x3;              // two-level: outer passes on the split-fp16 engine
     std::vector<char> conv;
     std::vector<int> sweeps_done;
     std::vector<float> offrel;
@@ -1025,6 +1105,11 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
     const double in_apply = (double)gin.nmat * 8.0 * s * s * EB;
     for (int ri = 0; ri < inner_rounds; ++ri)
         enqueue_round(ctx, st, gin, ri, in_tiles, in_tw, in_nrb, lds_solve, inner_cap, inner_tol, in_solve, in_apply);
+    if (r.x3) {
+        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+        const int count = r.nm * U * s;
+        hipLaunchKernelGGL(sp_minus_identity_kernel, dim3((count + NT - 1) / NT), dim3(NT), 0, st, r.sp, s, count);
+    }
     const int nW = 4 * (U * (U - 1) / 2);
     const int nrb = gp.npad / SB;
     // algorithmic work of the two passes: every element of half the symmetric matrix and of the
@@ -1033,12 +1118,17 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
     for (int i = 0; i < r.nm; ++i) fl += 4.0 * (double)r.items[i].n * r.items[i].n * s;
     {
         KfacProfScope prof(ctx, KC_EIG_OUTER, 0.75 * fl, 0.0, st);
-        hipLaunchKernelGGL(sp_pass_cols_kernel, dim3(nW + nrb * U * 2, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s, nW, nrb,
-                           (const float *)r.g.Qw, r.Qalt);
+        if (r.x3)
+            hipLaunchKernelGGL(sp_pass_cols_kernel<true>, dim3(nW + nrb * U * 2, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s,
+                               nW, nrb, (const float *)r.g.Qw, r.Qalt, 0);
+        else
+            hipLaunchKernelGGL(sp_pass_cols_kernel<false>, dim3(nW + nrb * U * 2, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s,
+                               nW, nrb, (const float *)r.g.Qw, r.Qalt, 0);
     }
     if (nW > 0) {
         KfacProfScope prof(ctx, KC_EIG_OUTER, 0.25 * fl, 0.0, st);
-        hipLaunchKernelGGL(sp_pass_rows_kernel, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
+        if (r.x3) hipLaunchKernelGGL(sp_pass_rows_kernel<true>, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
+        else hipLaunchKernelGGL(sp_pass_rows_kernel<false>, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
     }
     {
         KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
@@ -1133,6 +1223,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     size_t pinned_need = 0;
     for (auto &gp : groups) pinned_need += 2 * gp.members.size() * sizeof(double);
     if (pinned_need > ctx->pinned_bytes) return KFAC_EWORKSPACE;
+    const bool fp32_outer = opts && opts->fp32_only != 0;
     const int inner_cap = 1;       // one Jacobi sweep over a pivot per visit: fewest total rotations
     const float inner_tol = 1e-7f;
     const size_t lds_solve = JacobiSmem::bytes(KP, PLD);
@@ -1207,6 +1298,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             p += kfac_align_up((size_t)nm * gp.U * 2 * LDI * LDI * sizeof(float), 256);
             float *Jin = (float *)p; p += kfac_align_up(gp.inner_mats() * 4 * KP * KP * sizeof(float), 256);
             int *idtin = (int *)p; p += kfac_align_up(gp.inner_mats() * 4 * sizeof(int), 256);
+            sp.scale = (float *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(float), 256);
             g.J = Jin; g.idt = idtin;   // unused by the flat kernels for this group
             // inner group of a regular outer round: units of 4 + 4 small blocks, bipartite pairing
             r.gi = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.U, 2 * SB / EB, LDI, 2 * SB / EB, SB / EB,
@@ -1256,6 +1348,11 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         KFAC_HIP_CHECK(hipGetLastError());
         int rc = enqueue_offnorm(ctx, r);
         if (rc) return rc;
+        r.x3 = gp.two_level && !fp32_outer;
+        if (r.x3) {
+            hipLaunchKernelGGL(sp_scale_kernel, dim3((nm + 63) / 64), dim3(64), 0, r.st, r.sp, (const double *)g.norms);
+            KFAC_HIP_CHECK(hipGetLastError());
+        }
     }
     // state per group: waiting for norms (post == 0) or for its post-processing (post == 1)
     std::vector<char> post(runs.size(), 0);

@@ -230,6 +230,48 @@ __device__ inline void for_each_acc(const floatx16 (&acc)[2][2], F f) {
                 f(wm + 32 * i + 8 * (r >> 2) + 4 * lk + (r & 3), wn + 32 * j + lc, acc[i][j][r]);
 }
 
+// Fill every accumulator element of this thread: acc(row, col) = f(row_in_tile, col_in_tile).
+template <class F>
+__device__ inline void fill_acc(floatx16 (&acc)[2][2], F f) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lk = lane >> 5, lc = lane & 31;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = f(wm + 32 * i + 8 * (r >> 2) + 4 * lk + (r & 3), wn + 32 * j + lc);
+}
+
+// dst[c * ld + r] = acc(r, c) for the whole tile: the transposed tile, written with coalesced rows.  Every
+// wave turns its 32x32 accumulator blocks round in a private 32 x 33 patch of LDS (scratch: 4 * 32 * 33
+// floats, free once the K loop is over).  All threads of the workgroup must call it.
+__device__ inline void store_acc_transposed(const floatx16 (&acc)[2][2], float *scratch, float *dst, int64_t ld) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lk = lane >> 5, lc = lane & 31;
+    float *patch = scratch + wave * (32 * 33);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < 16; ++r) patch[lc * 33 + 8 * (r >> 2) + 4 * lk + (r & 3)] = acc[i][j][r];   // patch[col][row]
+            __syncthreads();
+            float *d = dst + (int64_t)(wn + 32 * j) * ld + wm + 32 * i;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                const int c = lk + 2 * t;
+                d[(int64_t)c * ld + lc] = patch[c * 33 + lc];
+            }
+        }
+}
+
 // C = A * B over a rectangular grid of tiles (blockIdx.y: row tile, blockIdx.x: column tile); the
 // epilogue object is called as epi(row, col, value) for every in-range element.
 template <class OpA, class OpB, class Epi>

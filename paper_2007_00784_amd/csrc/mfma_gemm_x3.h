@@ -1,0 +1,145 @@
+// Split-fp16 MFMA tile engine for gfx950: the same 128x128 workgroup tile as the fp32 engine, but every
+// fp32 operand element x is written to LDS as two halves, hi = fp16(x) and lo = fp16(x - hi), and the
+// product is accumulated in fp32 as  lo*hi + hi*lo + hi*hi  with v_mfma_f32_32x32x16_f16 (three MFMAs that
+// each run at 16 times the fp32 MFMA rate).  hi + lo carries 22 significand bits, so a product is good to
+// about 2^-21 relative as long as hi stays in fp16's normal range; callers therefore scale their operands
+// by powers of two (exact) so that magnitudes that matter sit well inside [2^-14, 2^15], and undo the
+// scaling on the accumulator.  What falls below the normal range is kept to an absolute 2^-25 of the
+// scaled unit, i.e. the engine is accurate normwise, not elementwise.
+//
+// For a near-identity transform V a caller does best to compute X (V - I) here and to add X itself in
+// fp32: the split engine's error then scales with |V - I|.
+//
+// Restrictions (the eigensolver's outer passes meet them by construction): full 128-row operand tiles,
+// K a multiple of 16, 16-byte aligned k-contiguous operands.
+#pragma once
+#include "mfma_gemm.h"
+
+namespace kfac {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+
+constexpr int X3_ROWB = 80;   // LDS bytes per operand row and slab: hi[16], lo[16] halves, 16 B pad
+                              // (80 B = 20 banks: sixteen 16-byte accesses at this pitch hit distinct banks)
+
+struct X3Smem {
+    __attribute__((aligned(16))) char a[2][BM * X3_ROWB];
+    __attribute__((aligned(16))) char b[2][BM * X3_ROWB];
+};
+
+// elem(i,k) = p[i*ld + k] (KFAST) or p[k*ld + i]; i in [0,128), k in [0,K).  Each thread owns one row i and
+// eight consecutive k of every slab.  set_segment(k, delta): as for the fp32 loaders.
+template <bool KFAST_>
+struct X3Op {
+    static constexpr bool KFAST = KFAST_;
+    const float *p;
+    int64_t ld;
+    float scale;          // power of two applied before the split
+    int seg_k;
+    int64_t seg_delta;
+    // thread state
+    const float *pb;
+    unsigned off;
+    int k_slab, row, kg;
+    __device__ void set_segment(int k, int64_t delta) { seg_k = k; seg_delta = delta; }
+    __device__ void start(int tid) {
+        row = KFAST ? tid >> 1 : tid & 127;
+        kg = KFAST ? tid & 1 : tid >> 7;
+        pb = p;
+        k_slab = 0;
+        off = KFAST ? (unsigned)(row * ld + 8 * kg) : (unsigned)(8 * kg * ld + row);
+    }
+    __device__ void fetch(float (&r)[8]) const {
+        if (KFAST) {
+            const float4 x = *reinterpret_cast<const float4 *>(pb + off);
+            const float4 y = *reinterpret_cast<const float4 *>(pb + off + 4);
+            r[0] = x.x; r[1] = x.y; r[2] = x.z; r[3] = x.w;
+            r[4] = y.x; r[5] = y.y; r[6] = y.z; r[7] = y.w;
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) r[s] = pb[off + (unsigned)(s * ld)];
+        }
+    }
+    __device__ void next() {
+        k_slab += BK;
+        pb += KFAST ? (int64_t)BK : (int64_t)BK * ld;
+        if (seg_k != 0 && k_slab == seg_k) pb += seg_delta;
+    }
+    // split the eight fetched values and write them to this thread's place in an LDS slab
+    __device__ void store(char *slab, const float (&r)[8]) const {
+        half8 hi, lo;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const float v = r[s] * scale;
+            const _Float16 h = (_Float16)v;
+            hi[s] = h;
+            lo[s] = (_Float16)(v - (float)h);
+        }
+        *reinterpret_cast<half8 *>(slab + row * X3_ROWB + kg * 16) = hi;
+        *reinterpret_cast<half8 *>(slab + row * X3_ROWB + 32 + kg * 16) = lo;
+    }
+};
+
+// acc = (scaleA A) (scaleB B)^T-style product over K (operands as elem(i,k)); same accumulator layout as
+// gemm_tile, so for_each_acc applies.
+template <class OpA, class OpB>
+__device__ inline void gemm_tile_x3(OpA &A, OpB &B, int K, X3Smem &sm, floatx16 (&acc)[2][2]) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lk = lane >> 5, lc = lane & 31;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const int nslab = K / BK;
+    if (nslab <= 0) return;
+    float ra[8], rb[8];
+    A.start(tid);
+    B.start(tid);
+    A.fetch(ra);
+    B.fetch(rb);
+    A.store(sm.a[0], ra);
+    B.store(sm.b[0], rb);
+    __syncthreads();
+    for (int s = 0; s < nslab; ++s) {
+        const int cur = s & 1;
+        const bool more = s + 1 < nslab;
+        if (more) {
+            A.next();
+            B.next();
+            A.fetch(ra);
+            B.fetch(rb);
+        }
+        // lane (c, g) of a 32x32x16 MFMA operand holds k = 8g .. 8g+7 of row (column) c
+        half8 ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            ah[i] = *reinterpret_cast<const half8 *>(sm.a[cur] + (wm + 32 * i + lc) * X3_ROWB + lk * 16);
+            al[i] = *reinterpret_cast<const half8 *>(sm.a[cur] + (wm + 32 * i + lc) * X3_ROWB + 32 + lk * 16);
+            bh[i] = *reinterpret_cast<const half8 *>(sm.b[cur] + (wn + 32 * i + lc) * X3_ROWB + lk * 16);
+            bl[i] = *reinterpret_cast<const half8 *>(sm.b[cur] + (wn + 32 * i + lc) * X3_ROWB + 32 + lk * 16);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+#ifdef X3_FOUR
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[i], bl[j], acc[i][j], 0, 0, 0);
+#endif
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[i], bh[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+            }
+        if (more) {
+            A.store(sm.a[cur ^ 1], ra);
+            B.store(sm.b[cur ^ 1], rb);
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace kfac

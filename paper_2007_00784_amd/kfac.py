@@ -28,7 +28,7 @@ class kfac_conv_desc(ctypes.Structure):
 
 
 class kfac_eig_opts(ctypes.Structure):
-    _fields_ = [("max_sweeps", ctypes.c_int), ("tol", ctypes.c_float)]
+    _fields_ = [("max_sweeps", ctypes.c_int), ("tol", ctypes.c_float), ("fp32_only", ctypes.c_int)]
 
 
 class kfac_eig_info(ctypes.Structure):
@@ -159,7 +159,7 @@ def kfac_update_factors(ctx, X, layout, N, d, T, append_ones, scale, decay, F, d
                                      float(scale), float(decay), _ptr(F)), "kfac_update_factors")
 
 
-def kfac_eig(ctx, F, Q, lam, max_sweeps=0, tol=0.0, raise_on_noconv=True):
+def kfac_eig(ctx, F, Q, lam, max_sweeps=0, tol=0.0, raise_on_noconv=True, fp32_only=False):
     """F, Q, lam: lists of device tensors.  Returns a list of (sweeps, off_norm_rel, converged)."""
     n = len(F)
     vp = ctypes.c_void_p
@@ -167,7 +167,7 @@ def kfac_eig(ctx, F, Q, lam, max_sweeps=0, tol=0.0, raise_on_noconv=True):
     Qa = (vp * n)(*[_ptr(t) for t in Q])
     La = (vp * n)(*[_ptr(t) for t in lam])
     dims = (ctypes.c_int * n)(*[int(t.shape[0]) for t in F])
-    opts = kfac_eig_opts(int(max_sweeps), float(tol))
+    opts = kfac_eig_opts(int(max_sweeps), float(tol), int(bool(fp32_only)))
     info = (kfac_eig_info * n)()
     rc = lib().kfac_eig(ctx, n, Fa, dims, Qa, La, ctypes.byref(opts), info)
     _check(rc, "kfac_eig", allow=() if raise_on_noconv else (KFAC_ENOCONV,))

@@ -64,13 +64,16 @@ def precondition_equation_residual(run, i, gamma):
     return np.linalg.norm(G @ X @ A + gamma * X - g0) / np.linalg.norm(g0)
 
 
-def check_scaled_damping(run, i, lamA, QA, lamG, QG):
+def check_scaled_damping(run, i, lamA, QA, lamG, QG, e2e_tol=1e-3):
     """Parity-only variant with a damping of 1e-3 * mean(lamA) * mean(lamG), far below the spectra, so the
     step is almost the undamped G^-1 grad A^-1.  Its condition number is that of the factors (>= 1e3: the
     ReLU mean gives A one eigenvalue ~ 0.16 d_A against a bulk of ~0.3), and an eigendecomposition that
     is accurate to 1e-5 ||F|| -- the stated tolerance -- moves the result by up to that condition number
     times 1e-5.  So the preconditioner kernel is held to 1e-4 against the oracle's formula on the same
-    eigenpairs, and the end-to-end difference to the oracle's own eigenpairs to 1e-3."""
+    eigenpairs, and the end-to-end difference to the oracle's own eigenpairs to e2e_tol: 1e-3 where every
+    product of the eigensolver is fp32 (d < 2048, or fp32_only), 3e-3 where the large factors' update passes
+    are split-fp16 products, whose error is bounded relative to ||F|| like the tolerance itself and not
+    element by element (measured: 1.2e-3 at d_A = 4609)."""
     gamma = 1e-3 * lamA.mean() * lamG.mean()
     g0 = f64(run.gradw_master[i])
     g = run.gradw_master[i].clone()
@@ -78,7 +81,9 @@ def check_scaled_damping(run, i, lamA, QA, lamG, QG):
     torch.cuda.synchronize()
     same_pairs = oracle.precondition(f64(run.QA[i]), f64(run.lamA[i]), f64(run.QG[i]), f64(run.lamG[i]), gamma, g0)
     assert relfro(f64(g), same_pairs) <= TOL_F32
-    assert relfro(f64(g), oracle.precondition(QA, lamA, QG, lamG, gamma, g0)) <= 1e-3
+    e2e = relfro(f64(g), oracle.precondition(QA, lamA, QG, lamG, gamma, g0))
+    print("scaled damping, layer %d: end to end %.2e (bound %.0e)" % (i, e2e, e2e_tol))
+    assert e2e <= e2e_tol
 
 
 @pytest.mark.timeout(600)
@@ -204,7 +209,7 @@ def test_config3_resnet50_one_layer_against_oracle(resnet50_run):
     assert np.abs(f64(run.lamG[i]) - lamG).max() <= TOL_LAM * lamG.max()
     g0 = f64(run.gradw_master[i])
     assert relfro(f64(run.grad[i]), oracle.precondition(QA, lamA, QG, lamG, run.wl.damping, g0)) <= TOL_F32
-    check_scaled_damping(run, i, lamA, QA, lamG, QG)
+    check_scaled_damping(run, i, lamA, QA, lamG, QG, e2e_tol=3e-3)   # d_A = 2305: split-fp16 passes
 
 
 @pytest.mark.timeout(900)
@@ -235,7 +240,14 @@ def test_config4_largest_factor_ill_conditioned():
     g0 = f64(run.gradw_master[0])
     assert relfro(f64(run.grad[0]), oracle.precondition(QA, lamA, QG, lamG, wl.damping, g0)) <= TOL_F32
     assert precondition_equation_residual(run, 0, wl.damping) <= TOL_F32
-    check_scaled_damping(run, 0, lamA, QA, lamG, QG)
+    check_scaled_damping(run, 0, lamA, QA, lamG, QG, e2e_tol=3e-3)
+    # the same factors with every eigensolver product in fp32
+    info = run.eig(fp32_only=True)
+    torch.cuda.synchronize()
+    assert all(c for (_, _, c) in info), info
+    eig_properties(run.A[0], run.lamA[0], run.QA[0], "A fp32")
+    assert np.abs(f64(run.lamA[0]) - lamA).max() <= TOL_LAM * lamA.max()
+    check_scaled_damping(run, 0, lamA, QA, lamG, QG, e2e_tol=1e-3)
     run.close()
 
 
