@@ -56,14 +56,14 @@ __device__ inline float wave_sum(float v) {
     return v;
 }
 
-// Sum over the workgroup (NT threads); result valid in all threads.  red: >= 5 floats of LDS.
+// Sum over the workgroup; result valid in all threads.  red: one float of LDS per wave.
 __device__ inline float block_sum(float v, float *red) {
     v = wave_sum(v);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
     float s = 0.f;
-    for (int w = 0; w < NT / 64; ++w) s += red[w];
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) s += red[w];
     return s;
 }
 
@@ -78,7 +78,7 @@ struct RotEntry { int p, q; float c, s; };
 // each thread's column pair is loop invariant); KC == 0 takes k at run time.
 // CROSS: a sweep visits only the pairs (i, k/2 + j) between the two halves, in k/2 rounds (the pairs inside
 // each half are left to the caller's schedule).
-template <int KC, bool CROSS = false>
+template <int KC, bool CROSS = false, int NTH = NT>
 __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max_sweeps, float tol, float skip_rel,
                                    float *red, RotEntry *rot, int *rotflag) {
     const int tid = threadIdx.x;
@@ -88,7 +88,7 @@ __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max
     if (tid == 0) *rotflag = 0;
     for (int sweep = 0;; ++sweep) {
         float o2 = 0.f, d2 = 0.f;
-        for (int e = tid; e < k * k; e += NT) {
+        for (int e = tid; e < k * k; e += NTH) {
             const int i = e / k, j = e - i * k;
             const float v = S[i * ld + j];
             if (i == j) d2 += v * v; else o2 += v * v;
@@ -130,51 +130,61 @@ __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max
             }
             __syncthreads();
             if constexpr (KC > 0) {
-                // S <- J^T S J on 2x2 blocks: this thread's column pair is fixed, its row pairs vary.
-                // Loads of a batch are issued together before any store, so they overlap.
+                // S <- J^T S J on 2x2 blocks (a thread's column pair is fixed, its row pairs vary) and V <- V J
+                // (a thread's row is fixed, the column pairs vary).  Loads of a batch are issued together before
+                // any store, so they overlap.  With NTH = NT every thread does its share of both; with more
+                // threads the lower half of the workgroup takes S and the upper half V, which run side by side
+                // (the rounds are bound by LDS latency, not by its throughput).
                 constexpr int HALF = KC / 2;
-                constexpr int SB = 4;                                   // blocks per batch
-                constexpr int NSB = HALF * HALF / NT;                   // blocks per thread (16 or 4)
-                constexpr int JSTEP = NT / HALF;
-                const RotEntry r2 = rot[tid & (HALF - 1)];
-                const float *c0 = S + r2.p, *c1p = S + r2.q;
-                for (int t0 = 0; t0 < NSB; t0 += SB) {
-                    RotEntry r1[SB];
-                    float a[SB], b[SB], c_[SB], d[SB];
+                constexpr bool SPLIT = NTH > NT;
+                constexpr int NS = SPLIT ? NTH / 2 : NTH;               // threads on S, threads on V
+                constexpr int NSB = HALF * HALF / NS;                   // blocks per thread
+                constexpr int SB = NSB < 4 ? NSB : 4;                   // blocks per batch
+                constexpr int JSTEP = NS / HALF;
+                constexpr int NVB = KC * HALF / NS;                     // items per thread
+                constexpr int VB = NVB < 8 ? NVB : 8;
+                constexpr int VSTEP = NS / KC;
+                static_assert(NSB >= 1 && NVB >= 1 && NS % HALF == 0 && NS % KC == 0, "thread counts");
+                if (!SPLIT || tid < NS) {
+                    const RotEntry r2 = rot[tid & (HALF - 1)];
+                    const float *c0 = S + r2.p, *c1p = S + r2.q;
+                    for (int t0 = 0; t0 < NSB; t0 += SB) {
+                        RotEntry r1[SB];
+                        float a[SB], b[SB], c_[SB], d[SB];
 #pragma unroll
-                    for (int u = 0; u < SB; ++u) {
-                        r1[u] = rot[tid / HALF + JSTEP * (t0 + u)];
-                        a[u] = c0[r1[u].p * ld]; b[u] = c1p[r1[u].p * ld];
-                        c_[u] = c0[r1[u].q * ld]; d[u] = c1p[r1[u].q * ld];
-                    }
+                        for (int u = 0; u < SB; ++u) {
+                            r1[u] = rot[tid / HALF + JSTEP * (t0 + u)];
+                            a[u] = c0[r1[u].p * ld]; b[u] = c1p[r1[u].p * ld];
+                            c_[u] = c0[r1[u].q * ld]; d[u] = c1p[r1[u].q * ld];
+                        }
 #pragma unroll
-                    for (int u = 0; u < SB; ++u) {
-                        // columns: [a b; c d] * [[c2, s2], [-s2, c2]], then rows: [[c1, -s1], [s1, c1]] * [...]
-                        const float a1 = r2.c * a[u] - r2.s * b[u], b1 = r2.s * a[u] + r2.c * b[u];
-                        const float cc1 = r2.c * c_[u] - r2.s * d[u], d1 = r2.s * c_[u] + r2.c * d[u];
-                        S[r1[u].p * ld + r2.p] = r1[u].c * a1 - r1[u].s * cc1;
-                        S[r1[u].p * ld + r2.q] = r1[u].c * b1 - r1[u].s * d1;
-                        S[r1[u].q * ld + r2.p] = r1[u].s * a1 + r1[u].c * cc1;
-                        S[r1[u].q * ld + r2.q] = r1[u].s * b1 + r1[u].c * d1;
+                        for (int u = 0; u < SB; ++u) {
+                            // columns: [a b; c d] * [[c2, s2], [-s2, c2]], then rows: [[c1, -s1], [s1, c1]] * [...]
+                            const float a1 = r2.c * a[u] - r2.s * b[u], b1 = r2.s * a[u] + r2.c * b[u];
+                            const float cc1 = r2.c * c_[u] - r2.s * d[u], d1 = r2.s * c_[u] + r2.c * d[u];
+                            S[r1[u].p * ld + r2.p] = r1[u].c * a1 - r1[u].s * cc1;
+                            S[r1[u].p * ld + r2.q] = r1[u].c * b1 - r1[u].s * d1;
+                            S[r1[u].q * ld + r2.p] = r1[u].s * a1 + r1[u].c * cc1;
+                            S[r1[u].q * ld + r2.q] = r1[u].s * b1 + r1[u].c * d1;
+                        }
                     }
                 }
-                // V <- V J: this thread's row is fixed, the column pairs vary
-                constexpr int VB = 8;
-                constexpr int NVB = KC * HALF / NT;                     // items per thread (32 or 8)
-                constexpr int VSTEP = NT / KC;
-                float *vrow = V + (tid & (KC - 1)) * ld;
-                for (int t0 = 0; t0 < NVB; t0 += VB) {
-                    RotEntry rc[VB];
-                    float vp[VB], vq[VB];
+                if (!SPLIT || tid >= NS) {
+                    const int vt = SPLIT ? tid - NS : tid;
+                    float *vrow = V + (vt & (KC - 1)) * ld;
+                    for (int t0 = 0; t0 < NVB; t0 += VB) {
+                        RotEntry rc[VB];
+                        float vp[VB], vq[VB];
 #pragma unroll
-                    for (int u = 0; u < VB; ++u) {
-                        rc[u] = rot[tid / KC + VSTEP * (t0 + u)];
-                        vp[u] = vrow[rc[u].p]; vq[u] = vrow[rc[u].q];
-                    }
+                        for (int u = 0; u < VB; ++u) {
+                            rc[u] = rot[vt / KC + VSTEP * (t0 + u)];
+                            vp[u] = vrow[rc[u].p]; vq[u] = vrow[rc[u].q];
+                        }
 #pragma unroll
-                    for (int u = 0; u < VB; ++u) {
-                        vrow[rc[u].p] = rc[u].c * vp[u] - rc[u].s * vq[u];
-                        vrow[rc[u].q] = rc[u].s * vp[u] + rc[u].c * vq[u];
+                        for (int u = 0; u < VB; ++u) {
+                            vrow[rc[u].p] = rc[u].c * vp[u] - rc[u].s * vq[u];
+                            vrow[rc[u].q] = rc[u].s * vp[u] + rc[u].c * vq[u];
+                        }
                     }
                 }
             } else {
@@ -214,13 +224,13 @@ struct JacobiSmem {
         S = (float *)base;
         V = S + k * ld;
         red = V + k * ld;
-        rot = (RotEntry *)(red + 8);
+        rot = (RotEntry *)(red + 16);
         rotflag = (int *)(rot + SMALL_MAX / 2);
         rank = rotflag + 4;
         diag = (float *)(rank + SMALL_MAX);
     }
     static size_t bytes(int k, int ld) {
-        return ((size_t)2 * k * ld + 8 + 4 * (SMALL_MAX / 2) + 4 + 2 * SMALL_MAX) * sizeof(float);
+        return ((size_t)2 * k * ld + 16 + 4 * (SMALL_MAX / 2) + 4 + 2 * SMALL_MAX) * sizeof(float);
     }
 };
 
@@ -271,14 +281,18 @@ __device__ inline void for_each_pivot_acc(const floatx16 (&acc)[2][2], F f) {
                 f(wm + 32 * i + 8 * (r >> 2) + 4 * lk + (r & 3), wn + 32 * j + lc, acc[i][j][r]);
 }
 
+// Called by the whole workgroup; the first four waves do the products.
 __device__ void polish_pivot_mfma(float *V, float *Y) {
+    const bool act = threadIdx.x < NT;
     floatx16 acc[2][2];
-    lds_gemm_pivot(V, 1, PLD, V, acc);  // V^T V
-    for_each_pivot_acc(acc, [&](int r, int c, float v) { Y[r * PLD + c] = (r == c ? 1.5f : 0.f) - 0.5f * v; });
+    if (act) {
+        lds_gemm_pivot(V, 1, PLD, V, acc);  // V^T V
+        for_each_pivot_acc(acc, [&](int r, int c, float v) { Y[r * PLD + c] = (r == c ? 1.5f : 0.f) - 0.5f * v; });
+    }
     __syncthreads();
-    lds_gemm_pivot(V, PLD, 1, Y, acc);  // V Y
+    if (act) lds_gemm_pivot(V, PLD, 1, Y, acc);  // V Y
     __syncthreads();
-    for_each_pivot_acc(acc, [&](int r, int c, float v) { V[r * PLD + c] = v; });
+    if (act) for_each_pivot_acc(acc, [&](int r, int c, float v) { V[r * PLD + c] = v; });
     __syncthreads();
 }
 
@@ -431,43 +445,43 @@ __device__ inline int pair_index(int a, int p, int q, int nblk) {
 
 // One sweep of the LDS Jacobi solver over the pivot sub-problem of every pair of this round; writes
 // the accumulated (and re-orthogonalised) transform J and whether it is the identity.
-__global__ __launch_bounds__(NT) void blk_solve_kernel(BlkGroup g, int round, int inner_sweeps, float inner_tol) {
+constexpr int SOLVE_NT = 1024;   // threads of a pivot solve: half of them rotate S, the other half V
+
+__global__ __launch_bounds__(SOLVE_NT) void blk_solve_kernel(BlkGroup g, int round, int inner_sweeps, float inner_tol) {
     extern __shared__ __align__(16) char smem[];
     JacobiSmem sm(smem, KP, PLD);
     const int m = blockIdx.y, pj = blockIdx.x, tid = threadIdx.x;
     const float *W = g.W + (int64_t)m * g.npad * g.npad;
     int p, q;
     sched_pair(g, round, pj, p, q);
-    constexpr int PER = KP * KP / NT;
-    for (int t0 = 0; t0 < PER; t0 += 8) {
-        float v[8];
+    constexpr int PER = KP * KP / SOLVE_NT;
+    float v[PER];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int e = tid + NT * (t0 + u);
-            const int a = e / KP, b = e % KP;
-            const int gi = pair_index(a, p, q, g.nblk), gj = pair_index(b, p, q, g.nblk);
-            // read the lower triangle only, so the sub-problem is exactly symmetric
-            v[u] = 0.f;
-            if (gi >= 0 && gj >= 0) v[u] = (gi >= gj) ? W[(int64_t)gi * g.npad + gj] : W[(int64_t)gj * g.npad + gi];
-        }
+    for (int u = 0; u < PER; ++u) {
+        const int e = tid + SOLVE_NT * u;
+        const int a = e / KP, b = e % KP;
+        const int gi = pair_index(a, p, q, g.nblk), gj = pair_index(b, p, q, g.nblk);
+        // read the lower triangle only, so the sub-problem is exactly symmetric
+        v[u] = 0.f;
+        if (gi >= 0 && gj >= 0) v[u] = (gi >= gj) ? W[(int64_t)gi * g.npad + gj] : W[(int64_t)gj * g.npad + gi];
+    }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int e = tid + NT * (t0 + u);
-            const int a = e / KP, b = e % KP;
-            sm.S[a * PLD + b] = v[u];
-            sm.V[a * PLD + b] = (a == b) ? 1.f : 0.f;
-        }
+    for (int u = 0; u < PER; ++u) {
+        const int e = tid + SOLVE_NT * u;
+        const int a = e / KP, b = e % KP;
+        sm.S[a * PLD + b] = v[u];
+        sm.V[a * PLD + b] = (a == b) ? 1.f : 0.f;
     }
     __syncthreads();
     // The pairs inside a block need one visit per sweep: a tournament gives it in its round 0 (where every
     // block plays, possibly against the phantom), a bipartite schedule leaves it to its caller.  Every
     // other visit rotates only the pairs between the two blocks.
     const JacobiResult res =
-        (g.bipartite || round > 0) ? jacobi_lds<KP, true>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag)
-                    : jacobi_lds<KP, false>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
+        (g.bipartite || round > 0) ? jacobi_lds<KP, true, SOLVE_NT>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag)
+                                   : jacobi_lds<KP, false, SOLVE_NT>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
     if (res.rotations > 0) polish_pivot_mfma(sm.V, sm.S);
     float *J = g.J + ((int64_t)m * g.npairs + pj) * (KP * KP);
-    for (int e = tid; e < KP * KP; e += NT) J[e] = sm.V[(e / KP) * PLD + (e % KP)];
+    for (int e = tid; e < KP * KP; e += SOLVE_NT) J[e] = sm.V[(e / KP) * PLD + (e % KP)];
     if (tid == 0) g.idt[m * g.npairs + pj] = res.rotations == 0;
 }
 
@@ -1072,7 +1086,7 @@ void enqueue_round(kfac_ctx *ctx, hipStream_t st, const BlkGroup &g, int rd, int
                    size_t lds_solve, int inner_cap, float inner_tol, double solve_flops, double apply_flops) {
     {
         KfacProfScope prof(ctx, KC_EIG_SOLVE, solve_flops, 0.0, st);
-        hipLaunchKernelGGL(blk_solve_kernel, dim3(g.npairs, g.nmat), dim3(NT), lds_solve, st, g, rd, inner_cap, inner_tol);
+        hipLaunchKernelGGL(blk_solve_kernel, dim3(g.npairs, g.nmat), dim3(SOLVE_NT), lds_solve, st, g, rd, inner_cap, inner_tol);
     }
     {
         KfacProfScope prof(ctx, KC_EIG_APPLY, apply_flops, 0.0, st);
@@ -1269,13 +1283,38 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
 
     // ---- blocked groups: set up, then drive them sweep by sweep as their norms arrive ----
     std::vector<GroupRun> runs(groups.size());
+    // A group's sweeps are one dependent chain of launches on one stream.  Groups are dealt to the internal
+    // streams longest chain first, each to the stream with the least work so far; the estimate per round is
+    // a launch-latency floor plus the round's products at the rate those kernels reach.
+    std::vector<int> stream_of(groups.size(), 0);
+    {
+        std::vector<std::pair<double, size_t>> cost(groups.size());
+        for (size_t gi = 0; gi < groups.size(); ++gi) {
+            const GroupPlan &gp = groups[gi];
+            double n2 = 0.0;
+            for (int b : gp.members) n2 += (double)d[b] * d[b];
+            double t;
+            if (gp.two_level) t = gp.splayers * (350e-6 + 4.0 * n2 * LDI / 130e12);
+            else t = (gp.players - 1) * std::max(90e-6, 8.0 * n2 * EB / 20e12);
+            cost[gi] = {t, gi};
+        }
+        std::sort(cost.begin(), cost.end(), [](const std::pair<double, size_t> &a, const std::pair<double, size_t> &b) { return a.first > b.first; });
+        double load[KFAC_NUM_AUX_STREAMS] = {0};
+        if (!small.empty()) load[KFAC_NUM_AUX_STREAMS - 1] += 0.5e-3;   // the small factors' one launch
+        for (auto &c : cost) {
+            int best = 0;
+            for (int i = 1; i < KFAC_NUM_AUX_STREAMS; ++i) if (load[i] < load[best]) best = i;
+            stream_of[c.second] = best;
+            load[best] += c.first;
+        }
+    }
     double *pinned = ctx->pinned;
     for (size_t gi = 0; gi < groups.size(); ++gi) {
         GroupPlan &gp = groups[gi];
         GroupRun &r = runs[gi];
         r.plan = &gp;
         r.nm = (int)gp.members.size();
-        r.st = ctx->aux[gi % KFAC_NUM_AUX_STREAMS];
+        r.st = ctx->aux[stream_of[gi]];
         r.ev = ctx->ev_group[gi];
         const size_t np2 = (size_t)gp.npad * gp.npad;
         const int nm = r.nm;
