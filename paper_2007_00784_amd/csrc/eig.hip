@@ -861,7 +861,7 @@ __global__ __launch_bounds__(NT) void sp_minus_identity_kernel(SpGroup g, int s,
 // Column pass.  W part: T[blk(I,a), blk(J,b)] = sum_c W[blk(I,a), blk(J,c)] V_J[c, b] for unit pairs I > J;
 // accumulator part: Qout[rb, blk(J,b)] = sum_c Qin[rb, blk(J,c)] V_J[c, b] for every 128-row slab rb.
 template <bool X3>
-__global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void sp_pass_cols_kernel(SpGroup g, int round, int U, int s, int nW, int nrb,
+__global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(3))) void sp_pass_cols_kernel(SpGroup g, int round, int U, int s, int nW, int nrb,
                                                                       const float *Qin, float *Qout, int bx0) {
     using namespace kfac;
     __shared__ typename std::conditional<X3, X3Smem, TileSmem>::type sm;
@@ -935,7 +935,7 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
 
 // Row pass: W[blk(I,a), blk(J,b)] = sum_c V_I[c, a]^T T[blk(I,c), blk(J,b)] for unit pairs I > J, mirrored.
 template <bool X3>
-__global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void sp_pass_rows_kernel(SpGroup g, int round, int U, int s) {
+__global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(3))) void sp_pass_rows_kernel(SpGroup g, int round, int U, int s) {
     using namespace kfac;
     __shared__ typename std::conditional<X3, X3Smem, TileSmem>::type sm;
     const int m = blockIdx.y;
