@@ -17,6 +17,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32 = 157.3e12   # MI355X dense fp32 matrix FLOP/s
+PEAK_MFMA_F16 = 2.5e15     # dense fp16 matrix FLOP/s
 PEAK_VALU_F32 = 157.3e12   # fp32 vector FLOP/s (256 CUs x 128 lanes x 2 flops x 2.4 GHz)
 PEAK_HBM = 8.0e12          # bytes/s
 
@@ -27,12 +28,29 @@ BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
     "precond_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
     "eig_small": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
     "eig_pivot_solve": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
-    "eig_apply": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
+    # K = 64 contraction per pass over W and Q: 16 flop/byte, below the fp32 ridge of 19.7
+    "eig_apply": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "eig_misc": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "eig_post_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
     "eig_copy": ("hbm", PEAK_HBM, "GB/s", "bytes"),
-    "eig_outer_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
+    # split-fp16 engine: three fp16 MFMA products per algorithmic fp32 product ("achieved" counts the
+    # algorithmic flops once, against the fp16 matrix peak)
+    "eig_outer_gemm": ("mfma", PEAK_MFMA_F16, "TFLOP/s", "flops"),
 }
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of a kernel class on the default workload, from the committed counter summary
+    (rocprofv3 FETCH_SIZE / WRITE_SIZE runs); None where no figure was taken."""
+    path = os.path.join(ROOT, "profiles", "resnet50_step_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 3 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
 
 
 SAMPLE_LAYERS = ("s3b1.conv3", "s4b1.reduce", "fc")   # d_A/d_G = 2305/256, 2049/512, 2049/1000
@@ -100,8 +118,8 @@ def gpu_same_sample_ms(wl, torch, KfacRunner):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -156,6 +174,7 @@ def main():
         phases["factors"] += m[0].elapsed_time(m[1]) / args.steps
         phases["eig"] += m[1].elapsed_time(m[2]) / args.steps
         phases["precondition"] += m[2].elapsed_time(m[3]) / args.steps
+    step_ms = sorted(m[0].elapsed_time(m[3]) for m in all_marks)
     info = run.eig_info
     sweeps = [s for (s, _, _) in info]
     nconv = sum(1 for (_, _, c) in info if c)
@@ -177,7 +196,7 @@ def main():
     dom = max(stats, key=lambda k: stats[k]["ms"])
     roofline = dict(kernels[dom])
     roofline["kernel"] = dom
-    roofline["traffic"] = None
+    roofline["traffic"] = measured_traffic(dom) if args.workload == "resnet50" else None
     roofline = {k: roofline[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic",
                                          "launches", "avg_ms", "total_ms")}
     w = run.work()
@@ -198,6 +217,7 @@ def main():
                                % (wl.name, len(wl.layers), wl.batch, "bf16 in / fp32 factors" if wl.bf16 else "fp32",
                                   2 * len(wl.layers))},
         "phases_ms": {k: round(v, 3) for k, v in phases.items()},
+        "step_ms_median": round(step_ms[len(step_ms) // 2], 3), "step_ms_min": round(step_ms[0], 3),
         "derived": derived,
         "roofline": roofline,
         "kernels": kernels,

@@ -109,6 +109,21 @@ int kfac_unfold(kfac_ctx *ctx, const kfac_conv_desc *desc, const void *x, void *
 int kfac_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layout, int N, int d, int T,
                         int append_ones, float scale, float decay, float *F);
 
+/* The same update for a batch of factors in as few launches as there are operand forms (layout x dtype):
+ * every factor is cut into jobs of similar length that fill the machine together, so small layers cost
+ * no launch of their own.  items: host array; fields as the arguments of kfac_update_factors.  The
+ * factors of one call must be distinct.  Workspace: kfac_update_factors_workspace_bytes().  */
+typedef struct {
+    const void *X;
+    int dtype, layout;
+    int N, d, T;
+    int append_ones;
+    float scale, decay;
+    float *F;
+} kfac_factor_item;
+int kfac_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_item *items /* host */);
+size_t kfac_update_factors_workspace_bytes(int n, const kfac_factor_item *items /* host; X, F not read */);
+
 /* Symmetric eigendecompositions F_i = Q_i diag(lam_i) Q_i^T (Sec. IV-A, Algorithm 1 step 2) of a
  * batch of factors by (block) Jacobi iteration; lam ascending, eigenvectors in the columns of Q.
  *   F, Q, lam : HOST arrays of `batch` device pointers; F_i is [d_i][d_i] (read only),

@@ -17,7 +17,11 @@
 //
 // Convergence is decided on the host once per sweep from off(F)_F / ||F||_F.
 #include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
 #include <cmath>
+#include <thread>
 #include <cstdlib>
 #include <type_traits>
 #include <vector>
@@ -30,9 +34,6 @@ namespace {
 constexpr int EB = KFAC_EIG_B;       // block width of the blocked path
 constexpr int KP = 2 * EB;           // pivot sub-problem size
 constexpr int PLD = KP + 1;          // LDS pitch of a pivot (odd: column walks are conflict free)
-constexpr int TS = 128;              // edge of an apply tile
-constexpr int XLD = TS + 1;          // LDS pitch of an apply tile
-constexpr int PT = TS / KP;          // pivot pairs per tile edge
 constexpr int SMALL_MAX = KFAC_EIG_SMALL;
 constexpr int NT = 256;
 static_assert(NT == 256 && (KP == 64 || KP == 128) && SMALL_MAX == 128, "thread mappings below assume these sizes");
@@ -383,9 +384,12 @@ struct BlkGroup {
     float *W, *Qw, *J;
     int *idt;
     double *norms;   // [nmat][2] = off^2, diag^2
-    int nmat, nblk, npad, players, npairs, npp;   // npp = tile rows = ceil(npairs / PT)
+    int nmat, nblk, npad, players, npairs, npp;   // npp: unused
     int bipartite;   // 0: tournament over all blocks; 1: block j of the first half with a block of the second
+    const int *done; // [factors]: 1 once a factor has met the tolerance; its workgroups return at once
+    int per_factor;  // matrices of this group per factor (units of a two-level group; 1 otherwise)
 };
+__device__ inline bool blk_done(const BlkGroup &g, int m) { return g.done[m / g.per_factor] != 0; }
 
 // Pair j of round `round`: tournament over `players` blocks, or (bipartite) block j with block
 // half + (j + round) % half, which meets every cross pair of the two halves in `half` rounds.
@@ -436,6 +440,14 @@ __global__ __launch_bounds__(NT) void blk_offnorm_kernel(BlkGroup g) {
     }
 }
 
+// done[m] = the factor met the tolerance (same test, on the same sums, as the host's).
+__global__ void blk_flag_kernel(const double *norms, int *done, int nmat, double tol2) {
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= nmat) return;
+    const double o2 = norms[2 * m], n2 = o2 + norms[2 * m + 1];
+    done[m] = (o2 <= tol2 * n2) ? 1 : 0;
+}
+
 // Row/column index in the padded matrix of element a (0..KP-1) of the pair (p, q); -1 if the block is
 // the phantom one that completes an odd block count.
 __device__ inline int pair_index(int a, int p, int q, int nblk) {
@@ -445,12 +457,14 @@ __device__ inline int pair_index(int a, int p, int q, int nblk) {
 
 // One sweep of the LDS Jacobi solver over the pivot sub-problem of every pair of this round; writes
 // the accumulated (and re-orthogonalised) transform J and whether it is the identity.
-constexpr int SOLVE_NT = 1024;   // threads of a pivot solve: half of them rotate S, the other half V
+constexpr int SOLVE_NT = 512;    // threads of a pivot solve: half of them rotate S, the other half V (more threads
+                                 // are no faster, and a smaller workgroup leaves room for other groups' kernels)
 
 __global__ __launch_bounds__(SOLVE_NT) void blk_solve_kernel(BlkGroup g, int round, int inner_sweeps, float inner_tol) {
     extern __shared__ __align__(16) char smem[];
     JacobiSmem sm(smem, KP, PLD);
     const int m = blockIdx.y, pj = blockIdx.x, tid = threadIdx.x;
+    if (blk_done(g, m)) return;
     const float *W = g.W + (int64_t)m * g.npad * g.npad;
     int p, q;
     sched_pair(g, round, pj, p, q);
@@ -494,220 +508,154 @@ __device__ inline void tri_decode(int idx, int &ti, int &tj) {
 }
 
 // ---- round application ---------------------------------------------------------------------------
-// A 128 x 128 tile X (PT x PT pivot-pair blocks) stays resident in LDS while the pivot transforms of
-// its PT column pairs (then of its PT row pairs), laid side by side as a KP x 128 matrix, are
-// streamed from global memory (L2) in 8-row slabs through a small double buffer.  A workgroup needs
-// 73 KB of LDS, so two share a compute unit: one loads while the other multiplies.  Wave (a, b) owns
-// the 64 x 64 quadrant (a, b) of the tile; with KP = 64 that quadrant is one pair-block and its
-// product runs over that block's own 64 contraction indices.
-constexpr int SLAB_K = 8;
-constexpr int SLAB_LD = TS + 4;
-constexpr size_t APPLY_LDS_BYTES = (size_t)(TS * XLD + 2 * SLAB_K * SLAB_LD) * sizeof(float);
+// One workgroup per KP x KP block of pivot pairs: block (I, J) of W becomes J_I^T W_IJ J_J (pairs I >= J;
+// the mirror image is written from LDS, so W stays exactly symmetric), and every KP-row slab of the
+// accumulator is multiplied by the transform of its column pair.  The work of a round is bound by latency,
+// not by arithmetic, so the blocks are small and many share a compute unit (17 KB of LDS, one 32 x 32
+// accumulator per wave): the transforms are read from global memory (L2) straight into MFMA operand
+// registers while the block itself is on its way into LDS.
+constexpr int BLD = KP + 1;          // LDS pitch of a block
+static_assert(KP == 64, "the block application assumes 64 x 64 pivots (four 32 x 32 wave quadrants)");
 
-struct TilePairs {      // the PT pivot pairs along one edge of a tile
-    int p[PT], q[PT];
-    bool valid[PT];
-};
-
-__device__ inline TilePairs tile_pairs(const BlkGroup &g, int round, int tile) {
-    TilePairs tp;
+// acc = A * B over KP: A(m,k) from LDS (Xs[m][k]) and B(k,n) in registers (bj[j] = B[2j + lk][n]), or
+// A(m,k) in registers (aj[j] = A[m][2j + lk]) and B(k,n) from LDS (Xs[k][n]).
+template <bool A_IN_LDS>
+__device__ inline floatx16 block_gemm(const float *Xs, const float (&reg)[KP / 2], int wm, int wn, int lk, int lc) {
+    floatx16 acc;
 #pragma unroll
-    for (int u = 0; u < PT; ++u) {
-        const int pair = tile * PT + u;
-        tp.valid[u] = pair < g.npairs;
-        tp.p[u] = tp.q[u] = 0;
-        if (tp.valid[u]) sched_pair(g, round, pair, tp.p[u], tp.q[u]);
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int j = 0; j < KP / 2; ++j) {
+        const int k = 2 * j + lk;
+        if (A_IN_LDS) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Xs[(wm + lc) * BLD + k], reg[j], acc, 0, 0, 0);
+        else acc = __builtin_amdgcn_mfma_f32_32x32x2f32(reg[j], Xs[k * BLD + wn + lc], acc, 0, 0, 0);
     }
-    return tp;
+    return acc;
 }
 
-// global row/column of tile coordinate a (0..127), or -1
-__device__ inline int tile_index(const TilePairs &tp, int a, int nblk) {
-    const int u = a / KP;
-    return tp.valid[u] ? pair_index(a % KP, tp.p[u], tp.q[u], nblk) : -1;
-}
-
-// The KP x 128 panel [J_0 | J_1 ..] of a tile edge (row-major KP x KP transforms of its PT pairs, first
-// pair `pair0`), fetched whole into registers: thread t holds float4 number t of every 8-row slab.
-constexpr int NSLAB = KP / SLAB_K;
-struct Panel { float4 v[NSLAB]; };
-
-__device__ inline void panel_fetch(Panel &pan, const float *__restrict__ Jall, int pair0, int npairs) {
-    const int tid = threadIdx.x;
-    const int srow = tid >> 5, scol = (tid & 31) * 4;
-    const int spair = pair0 + scol / KP;
-    const bool sval = spair < npairs;
-    const float *src = Jall + (int64_t)(sval ? spair : pair0) * (KP * KP) + (scol % KP) + srow * KP;
-#pragma unroll
-    for (int sl = 0; sl < NSLAB; ++sl)
-        pan.v[sl] = sval ? *reinterpret_cast<const float4 *>(src + sl * SLAB_K * KP) : make_float4(0.f, 0.f, 0.f, 0.f);
-}
-
-// acc = X * panel (X_LEFT: A(m,k) = Xs[m][k], B(k,n) = panel[k][n]) or acc = panel^T * X (A(m,k) =
-// panel[k][m], B(k,n) = Xs[k][n]); the panel goes through LDS slab by slab from registers, so no global
-// latency sits inside the product.
-template <bool X_LEFT>
-__device__ inline void panel_gemm(const float *Xs, const Panel &pan, float (*slab)[SLAB_K][SLAB_LD],
-                                  floatx16 (&acc)[2][2]) {
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-    const int lk = lane >> 5, lc = lane & 31;
-    const int srow = tid >> 5, scol = (tid & 31) * 4;
-    // contraction offset inside the resident tile: with KP = 64 each quadrant multiplies its own block
-    const int koff = (KP == TS) ? 0 : (X_LEFT ? wn : wm);
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    *reinterpret_cast<float4 *>(&slab[0][srow][scol]) = pan.v[0];
-    __syncthreads();
-#pragma unroll
-    for (int sl = 0; sl < NSLAB; ++sl) {
-        const int cur = sl & 1;
-        if (sl + 1 < NSLAB) *reinterpret_cast<float4 *>(&slab[cur ^ 1][srow][scol]) = pan.v[sl + 1];
-#pragma unroll
-        for (int kk = 0; kk < SLAB_K; kk += 2) {
-            const int k = koff + sl * SLAB_K + kk + lk;
-            float a0, a1, b0, b1;
-            if (X_LEFT) {
-                a0 = Xs[(wm + lc) * XLD + k];
-                a1 = Xs[(wm + 32 + lc) * XLD + k];
-                b0 = slab[cur][kk + lk][wn + lc];
-                b1 = slab[cur][kk + lk][wn + 32 + lc];
-            } else {
-                a0 = slab[cur][kk + lk][wm + lc];
-                a1 = slab[cur][kk + lk][wm + 32 + lc];
-                b0 = Xs[k * XLD + wn + lc];
-                b1 = Xs[k * XLD + wn + 32 + lc];
-            }
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
-        }
-        __syncthreads();
-    }
-}
-
-__device__ inline void acc_to_tile(const floatx16 (&acc)[2][2], float *X) {
-    kfac::for_each_acc(acc, [&](int r, int c, float v) { X[r * XLD + c] = v; });
-}
-
-// Tile <-> global memory, four consecutive columns per access.  rowf(a) / colf(b) give the global row
-// and column of tile row a / tile column b (b a multiple of 4; the four columns are contiguous), or -1.
+// Block <-> global memory, four consecutive columns per access.  rowf(a) / colf(b) give the global row and
+// column of block row a / block column b (b a multiple of 4; the four columns are contiguous), or -1.
 template <class RowF, class ColF>
-__device__ inline void tile_load(float *Xs, const float *G, int64_t ld, RowF rowf, ColF colf) {
-    for (int t0 = 0; t0 < 16; t0 += 8) {
-        float4 v[8];
+__device__ inline void block_load(float *Xs, const float *G, int64_t ld, RowF rowf, ColF colf) {
+    float4 v[KP * KP / 4 / NT];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int e4 = threadIdx.x + NT * (t0 + u);
-            const int a = e4 >> 5, b = (e4 & 31) * 4;
-            const int gi = rowf(a), gj = colf(b);
-            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (gi >= 0 && gj >= 0) v[u] = *reinterpret_cast<const float4 *>(G + (int64_t)gi * ld + gj);
-        }
+    for (int u = 0; u < KP * KP / 4 / NT; ++u) {
+        const int e4 = threadIdx.x + NT * u;
+        const int a = e4 >> 4, b = (e4 & 15) * 4;
+        const int gi = rowf(a), gj = colf(b);
+        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gi >= 0 && gj >= 0) v[u] = *reinterpret_cast<const float4 *>(G + (int64_t)gi * ld + gj);
+    }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int e4 = threadIdx.x + NT * (t0 + u);
-            float *dst = Xs + (e4 >> 5) * XLD + (e4 & 31) * 4;
-            dst[0] = v[u].x; dst[1] = v[u].y; dst[2] = v[u].z; dst[3] = v[u].w;
-        }
+    for (int u = 0; u < KP * KP / 4 / NT; ++u) {
+        const int e4 = threadIdx.x + NT * u;
+        float *dst = Xs + (e4 >> 4) * BLD + (e4 & 15) * 4;
+        dst[0] = v[u].x; dst[1] = v[u].y; dst[2] = v[u].z; dst[3] = v[u].w;
     }
 }
 
 // TRANSPOSED: write Xs^T, i.e. global (colf(b), rowf(a..a+3)) <- Xs[a..a+3][b].
 template <bool TRANSPOSED, class RowF, class ColF>
-__device__ inline void tile_store(const float *Xs, float *G, int64_t ld, RowF rowf, ColF colf) {
-#pragma unroll 4
-    for (int t = 0; t < 16; ++t) {
-        const int e4 = threadIdx.x + NT * t;
+__device__ inline void block_store(const float *Xs, float *G, int64_t ld, RowF rowf, ColF colf) {
+#pragma unroll
+    for (int u = 0; u < KP * KP / 4 / NT; ++u) {
+        const int e4 = threadIdx.x + NT * u;
         if (!TRANSPOSED) {
-            const int a = e4 >> 5, b = (e4 & 31) * 4;
+            const int a = e4 >> 4, b = (e4 & 15) * 4;
             const int gi = rowf(a), gj = colf(b);
-            const float *src = Xs + a * XLD + b;
+            const float *src = Xs + a * BLD + b;
             if (gi >= 0 && gj >= 0)
                 *reinterpret_cast<float4 *>(G + (int64_t)gi * ld + gj) = make_float4(src[0], src[1], src[2], src[3]);
         } else {
-            const int b = e4 >> 5, a = (e4 & 31) * 4;
+            const int b = e4 >> 4, a = (e4 & 15) * 4;
             const int gi = rowf(a), gj = colf(b);
-            const float *src = Xs + a * XLD + b;
+            const float *src = Xs + a * BLD + b;
             if (gi >= 0 && gj >= 0)
                 *reinterpret_cast<float4 *>(G + (int64_t)gj * ld + gi) =
-                    make_float4(src[0], src[XLD], src[2 * XLD], src[3 * XLD]);
+                    make_float4(src[0], src[BLD], src[2 * BLD], src[3 * BLD]);
         }
     }
 }
 
-// One round of transforms: W_IJ <- J_I^T W_IJ J_J for tiles I >= J (mirrored into J,I), and
-// Qw[:, J] <- Qw[:, J] J_J for every 128-row slab of the accumulator.
-__global__ __launch_bounds__(NT, 2) void blk_apply_kernel(BlkGroup g, int round, int ntiles_w, int nrb) {
-    extern __shared__ __align__(16) char smem[];
-    float *Xs = (float *)smem;
-    float(*slab)[SLAB_K][SLAB_LD] = reinterpret_cast<float(*)[SLAB_K][SLAB_LD]>(Xs + TS * XLD);
+__device__ inline void acc_to_block(const floatx16 &acc, float *Xs, int wm, int wn, int lk, int lc) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) Xs[(wm + 8 * (r >> 2) + 4 * lk + (r & 3)) * BLD + wn + lc] = acc[r];
+}
+
+// grid.x: nblocks_w lower-triangular blocks of W, then nrb row slabs x npairs column pairs of the accumulator.
+__global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, int nblocks_w, int nrb) {
+    __shared__ float Xs[KP * BLD];
     const int m = blockIdx.y;
+    if (blk_done(g, m)) return;
     const int64_t np2 = (int64_t)g.npad * g.npad;
     const int *idt = g.idt + m * g.npairs;
     const float *Jall = g.J + (int64_t)m * g.npairs * (KP * KP);
     const int nblk = g.nblk;
-    floatx16 acc[2][2];
-    auto all_identity = [&](int tile) {
-        bool idn = true;
-        for (int u = 0; u < PT; ++u) {
-            const int pair = tile * PT + u;
-            if (pair < g.npairs) idn = idn && idt[pair];
-        }
-        return idn;
-    };
-    if ((int)blockIdx.x < ntiles_w) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32, lk = lane >> 5, lc = lane & 31;
+    if ((int)blockIdx.x < nblocks_w) {
         float *W = g.W + m * np2;
-        int I, Jt;
-        tri_decode(blockIdx.x, I, Jt);
-        if (all_identity(I) && all_identity(Jt)) return;
-        const TilePairs rows = tile_pairs(g, round, I), cols = tile_pairs(g, round, Jt);
-        auto rowf = [&](int a) { return tile_index(rows, a, nblk); };
-        auto colf = [&](int b) { return tile_index(cols, b, nblk); };
-        Panel pc, pr;
-        panel_fetch(pc, Jall, Jt * PT, g.npairs);
-        tile_load(Xs, W, g.npad, rowf, colf);
-        panel_fetch(pr, Jall, I * PT, g.npairs);    // in flight during the first product
+        int I, Jp;
+        tri_decode(blockIdx.x, I, Jp);
+        const bool idI = idt[I] != 0, idJ = idt[Jp] != 0;
+        if (idI && idJ) return;
+        int pI, qI, pJ, qJ;
+        sched_pair(g, round, I, pI, qI);
+        sched_pair(g, round, Jp, pJ, qJ);
+        auto rowf = [&](int a) { return pair_index(a, pI, qI, nblk); };
+        auto colf = [&](int b) { return pair_index(b, pJ, qJ, nblk); };
+        // operands of both products in registers: bj[j] = J_J[2j + lk][wn + lc], aj[j] = J_I[2j + lk][wm + lc]
+        float bj[KP / 2], aj[KP / 2];
+        const float *Jc = Jall + (int64_t)Jp * (KP * KP) + wn + lc, *Jr = Jall + (int64_t)I * (KP * KP) + wm + lc;
+#pragma unroll
+        for (int j = 0; j < KP / 2; ++j) bj[j] = Jc[(2 * j + lk) * KP];
+        block_load(Xs, W, g.npad, rowf, colf);
+#pragma unroll
+        for (int j = 0; j < KP / 2; ++j) aj[j] = Jr[(2 * j + lk) * KP];
         __syncthreads();
-        panel_gemm<true>(Xs, pc, slab, acc);    // T = X J_cols
-        acc_to_tile(acc, Xs);   // every wave passed the last barrier of the product: X is dead
-        __syncthreads();
-        panel_gemm<false>(Xs, pr, slab, acc);   // W' = J_rows^T T
-        acc_to_tile(acc, Xs);
-        __syncthreads();
-        if (I == Jt) {
-            // a diagonal tile holds both halves of its off-diagonal pair blocks: keep the lower one
-            for (int e = threadIdx.x; e < TS * TS; e += NT) {
-                const int a = e >> 7, b = e & 127;
-                if (b > a) Xs[a * XLD + b] = Xs[b * XLD + a];
+        if (!idJ) {
+            const floatx16 t = block_gemm<true>(Xs, bj, wm, wn, lk, lc);    // T = X J_J
+            __syncthreads();
+            acc_to_block(t, Xs, wm, wn, lk, lc);
+            __syncthreads();
+        }
+        if (!idI) {
+            const floatx16 w = block_gemm<false>(Xs, aj, wm, wn, lk, lc);   // W' = J_I^T T
+            __syncthreads();
+            acc_to_block(w, Xs, wm, wn, lk, lc);
+            __syncthreads();
+        }
+        if (I == Jp) {
+            // a diagonal block holds both halves of itself: keep the lower one
+            for (int e = threadIdx.x; e < KP * KP; e += NT) {
+                const int a = e >> 6, b = e & 63;
+                if (b > a) Xs[a * BLD + b] = Xs[b * BLD + a];
             }
             __syncthreads();
         }
-        tile_store<false>(Xs, W, g.npad, rowf, colf);
-        if (I != Jt) tile_store<true>(Xs, W, g.npad, rowf, colf);
+        block_store<false>(Xs, W, g.npad, rowf, colf);
+        if (I != Jp) block_store<true>(Xs, W, g.npad, rowf, colf);
     } else {
         float *Qw = g.Qw + m * np2;
-        const int t = blockIdx.x - ntiles_w;
-        const int rb = t % nrb, Jt = t / nrb;
-        if (all_identity(Jt)) return;
-        const TilePairs cols = tile_pairs(g, round, Jt);
-        const int row0 = rb * TS, npad = g.npad;
+        const int t = blockIdx.x - nblocks_w;
+        const int rb = t % nrb, Jp = t / nrb;
+        if (idt[Jp]) return;
+        int pJ, qJ;
+        sched_pair(g, round, Jp, pJ, qJ);
+        const int row0 = rb * KP, npad = g.npad;
         auto rowf = [&](int a) { return row0 + a < npad ? row0 + a : -1; };
-        auto colf = [&](int b) { return tile_index(cols, b, nblk); };
-        Panel pc;
-        panel_fetch(pc, Jall, Jt * PT, g.npairs);
-        tile_load(Xs, Qw, g.npad, rowf, colf);
+        auto colf = [&](int b) { return pair_index(b, pJ, qJ, nblk); };
+        float bj[KP / 2];
+        const float *Jc = Jall + (int64_t)Jp * (KP * KP) + wn + lc;
+#pragma unroll
+        for (int j = 0; j < KP / 2; ++j) bj[j] = Jc[(2 * j + lk) * KP];
+        block_load(Xs, Qw, g.npad, rowf, colf);
         __syncthreads();
-        panel_gemm<true>(Xs, pc, slab, acc);
-        acc_to_tile(acc, Xs);
+        const floatx16 t2 = block_gemm<true>(Xs, bj, wm, wn, lk, lc);
         __syncthreads();
-        tile_store<false>(Xs, Qw, g.npad, rowf, colf);
+        acc_to_block(t2, Xs, wm, wn, lk, lc);
+        __syncthreads();
+        block_store<false>(Xs, Qw, g.npad, rowf, colf);
     }
 }
 
@@ -779,6 +727,7 @@ struct SpGroup {
     float *W, *T;          // [nmat][npad][npad]: rotated matrix, column-pass result
     float *Wi, *Vi;        // gathered units and their accumulated transforms: [nmat*U][s][s]
     float *scale;          // [nmat][2]: power of two that brings ||W||_F into [2^12, 2^13), and its inverse
+    const int *done;       // [nmat]: as in BlkGroup
     int nmat, npad, nsuper, players;
 };
 
@@ -816,6 +765,7 @@ __device__ inline void unit_blocks(const SpGroup &g, int round, int u, int &b0, 
 // Wi[unit] <- W[{b0,b1},{b0,b1}] (zero where a super-block is absent), Vi[unit] <- I.  s = unit edge.
 __global__ __launch_bounds__(NT) void sp_gather_kernel(SpGroup g, int round, int s) {
     const int u = blockIdx.y, m = blockIdx.z, U = gridDim.y;
+    if (g.done[m]) return;
     int b0, b1;
     unit_blocks(g, round, u, b0, b1);
     const float *W = g.W + (int64_t)m * g.npad * g.npad;
@@ -836,6 +786,7 @@ __global__ __launch_bounds__(NT) void sp_gather_kernel(SpGroup g, int round, int
 // W[{b0,b1},{b0,b1}] <- Wi[unit]: the unit's own blocks after its inner rounds.
 __global__ __launch_bounds__(NT) void sp_scatter_kernel(SpGroup g, int round, int s) {
     const int u = blockIdx.y, m = blockIdx.z, U = gridDim.y;
+    if (g.done[m]) return;
     int b0, b1;
     unit_blocks(g, round, u, b0, b1);
     float *W = g.W + (int64_t)m * g.npad * g.npad;
@@ -851,10 +802,11 @@ __global__ __launch_bounds__(NT) void sp_scatter_kernel(SpGroup g, int round, in
 
 // Vi[unit] <- Vi[unit] - I for the split engine's passes, which compute X V as X + X (V - I) with only the
 // second term on the split engine: its error then scales with |V - I| and vanishes as the sweeps converge.
-__global__ __launch_bounds__(NT) void sp_minus_identity_kernel(SpGroup g, int s, int count) {
+__global__ __launch_bounds__(NT) void sp_minus_identity_kernel(SpGroup g, int s, int U, int count) {
     const int e = blockIdx.x * NT + threadIdx.x;      // (unit, diagonal index)
     if (e >= count) return;
     const int u = e / s, a = e - u * s;
+    if (g.done[u / U]) return;
     g.Vi[(int64_t)u * s * s + (int64_t)a * s + a] -= 1.f;
 }
 
@@ -866,6 +818,7 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
     using namespace kfac;
     __shared__ typename std::conditional<X3, X3Smem, TileSmem>::type sm;
     const int m = blockIdx.y;
+    if (g.done[m]) return;
     const int64_t np2 = (int64_t)g.npad * g.npad;
     const int ld = g.npad;
     int J, b, rowblk;          // unit and column part; global row super-block of the output tile
@@ -939,6 +892,7 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
     using namespace kfac;
     __shared__ typename std::conditional<X3, X3Smem, TileSmem>::type sm;
     const int m = blockIdx.y;
+    if (g.done[m]) return;
     const int64_t np2 = (int64_t)g.npad * g.npad;
     const int ld = g.npad;
     const int idx = blockIdx.x;
@@ -1006,6 +960,7 @@ struct GroupPlan {
             b += kfac_align_up(nm * (size_t)npairs * sizeof(int), 256);                            // idt
         }
         b += kfac_align_up(nm * 2 * sizeof(double), 256);                            // norms
+        b += kfac_align_up(nm * sizeof(int), 256);                                   // done flags
         b += kfac_align_up(nm * (size_t)npad * sizeof(int), 256);                    // perm
         b += kfac_align_up(nm * (size_t)npad * sizeof(double), 256);                 // Rayleigh quotients
         b += kfac_align_up(nm * sizeof(BlkItem), 256);                               // items
@@ -1013,12 +968,25 @@ struct GroupPlan {
     }
 };
 
+// Factors of similar size advance together as one group, each padded with zero blocks (which no rotation
+// ever touches) to the group's block count: one chain of launches serves them all, and a round's launches
+// are large enough to fill the machine.  Block counts are rounded up along a ladder of odd numbers about
+// 15 % apart (odd: the tournament then needs no phantom block).
+int bucket(int n) {
+    static const int ladder[] = {3, 5, 7, 9, 11, 13, 15, 19, 23, 27, 33, 37, 45, 53, 65, 75, 87, 101, 117, 135, 155, 179, 205, 235, 257};
+    for (int b : ladder) if (b >= n) return b;
+    return n | 1;
+}
+
 void make_plan(int batch, const int *d, std::vector<int> &small, std::vector<GroupPlan> &groups) {
     for (int i = 0; i < batch; ++i) {
         if (d[i] <= SMALL_MAX) { small.push_back(i); continue; }
         const bool two = d[i] >= TWO_LEVEL_MIN;
         const int unit = two ? SB : EB;
-        const int npad = (d[i] + unit - 1) / unit * unit;
+        // small blocks along the ladder; super-blocks only up to the next odd count (padding a large factor
+        // by 15 % would cost more than a chain of its own)
+        const int nunit = (d[i] + unit - 1) / unit;
+        const int npad = (two ? (nunit | 1) : bucket(nunit)) * unit;
         const int nblk = npad / EB;
         GroupPlan *gp = nullptr;
         for (auto &g : groups) if (g.nblk == nblk && g.two_level == two) gp = &g;
@@ -1029,7 +997,7 @@ void make_plan(int batch, const int *d, std::vector<int> &small, std::vector<Gro
             g.npad = npad;
             g.players = (nblk + 1) & ~1;
             g.npairs = g.players / 2;
-            g.npp = (g.npairs + PT - 1) / PT;
+            g.npp = 0;
             g.nsuper = npad / SB;
             g.splayers = (g.nsuper + 1) & ~1;
             g.U = g.splayers / 2;
@@ -1064,6 +1032,8 @@ struct GroupRun {
     int sweep;
     bool done;
     bool x3;              // two-level: outer passes on the split-fp16 engine
+    int *d_done;          // device flags, one per factor
+    double tol2;
     std::vector<char> conv;
     std::vector<int> sweeps_done;
     std::vector<float> offrel;
@@ -1074,6 +1044,7 @@ int enqueue_offnorm(kfac_ctx *ctx, GroupRun &r) {
         KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
         hipLaunchKernelGGL(blk_zero_f64_kernel, dim3(1), dim3(256), 0, r.st, r.g.norms, 2 * r.nm);
         hipLaunchKernelGGL(blk_offnorm_kernel, dim3(std::min(r.fill_blocks, 512), r.nm), dim3(NT), 0, r.st, r.g);
+        hipLaunchKernelGGL(blk_flag_kernel, dim3((r.nm + 63) / 64), dim3(64), 0, r.st, (const double *)r.g.norms, r.d_done, r.nm, r.tol2);
     }
     KFAC_HIP_CHECK(hipGetLastError());
     KFAC_HIP_CHECK(hipMemcpyAsync(r.h_norms, r.g.norms, 2 * r.nm * sizeof(double), hipMemcpyDeviceToHost, r.st));
@@ -1083,20 +1054,21 @@ int enqueue_offnorm(kfac_ctx *ctx, GroupRun &r) {
 
 // One round of (pivot solves, application) on a block group.
 void enqueue_round(kfac_ctx *ctx, hipStream_t st, const BlkGroup &g, int rd, int ntiles, int ntiles_w, int nrb,
-                   size_t lds_solve, int inner_cap, float inner_tol, double solve_flops, double apply_flops) {
+                   size_t lds_solve, int inner_cap, float inner_tol, double solve_flops, double apply_flops, double apply_bytes) {
     {
         KfacProfScope prof(ctx, KC_EIG_SOLVE, solve_flops, 0.0, st);
         hipLaunchKernelGGL(blk_solve_kernel, dim3(g.npairs, g.nmat), dim3(SOLVE_NT), lds_solve, st, g, rd, inner_cap, inner_tol);
     }
     {
-        KfacProfScope prof(ctx, KC_EIG_APPLY, apply_flops, 0.0, st);
-        hipLaunchKernelGGL(blk_apply_kernel, dim3(ntiles, g.nmat), dim3(NT), APPLY_LDS_BYTES, st, g, rd, ntiles_w, nrb);
+        KfacProfScope prof(ctx, KC_EIG_APPLY, apply_flops, apply_bytes, st);
+        hipLaunchKernelGGL(blk_apply_kernel, dim3(ntiles, g.nmat), dim3(NT), 0, st, g, rd, ntiles_w, nrb);
     }
 }
 
 int enqueue_sweep_flat(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int inner_cap, float inner_tol) {
     for (int rd = 0; rd < r.plan->players - 1; ++rd)
-        enqueue_round(ctx, r.st, r.g, rd, r.ntiles, r.ntiles_w, r.nrb, lds_solve, inner_cap, inner_tol, r.solve_flops, r.apply_flops);
+        enqueue_round(ctx, r.st, r.g, rd, r.ntiles, r.ntiles_w, r.nrb, lds_solve, inner_cap, inner_tol, r.solve_flops, r.apply_flops,
+                      2.0 * r.apply_flops / EB);   // W and the accumulator read and written once: 16 n^2 bytes per factor
     KFAC_HIP_CHECK(hipGetLastError());
     return KFAC_OK;
 }
@@ -1114,15 +1086,15 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
         KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
         hipLaunchKernelGGL(sp_gather_kernel, dim3(s * s / 4 / NT, U, r.nm), dim3(NT), 0, st, r.sp, round, s);
     }
-    const int in_tw = gin.npp * (gin.npp + 1) / 2, in_nrb = s / TS, in_tiles = in_tw + in_nrb * gin.npp;
-    const double in_solve = (double)gin.nmat * gin.npairs * 9.0 * KP * KP * (KP - 1);
+    const int in_tw = gin.npairs * (gin.npairs + 1) / 2, in_nrb = s / KP, in_tiles = in_tw + in_nrb * gin.npairs;
+    const double in_solve = (double)gin.nmat * gin.npairs * 9.0 * KP * KP * (KP / 2);
     const double in_apply = (double)gin.nmat * 8.0 * s * s * EB;
     for (int ri = 0; ri < inner_rounds; ++ri)
-        enqueue_round(ctx, st, gin, ri, in_tiles, in_tw, in_nrb, lds_solve, inner_cap, inner_tol, in_solve, in_apply);
+        enqueue_round(ctx, st, gin, ri, in_tiles, in_tw, in_nrb, lds_solve, inner_cap, inner_tol, in_solve, in_apply, 2.0 * in_apply / EB);
     if (r.x3) {
         KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
         const int count = r.nm * U * s;
-        hipLaunchKernelGGL(sp_minus_identity_kernel, dim3((count + NT - 1) / NT), dim3(NT), 0, st, r.sp, s, count);
+        hipLaunchKernelGGL(sp_minus_identity_kernel, dim3((count + NT - 1) / NT), dim3(NT), 0, st, r.sp, s, U, count);
     }
     const int nW = 4 * (U * (U - 1) / 2);
     const int nrb = gp.npad / SB;
@@ -1242,9 +1214,8 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     const float inner_tol = 1e-7f;
     const size_t lds_solve = JacobiSmem::bytes(KP, PLD);
     if (!groups.empty()) {
-        if ((int)lds_solve > ctx->max_lds || (int)APPLY_LDS_BYTES > ctx->max_lds) return KFAC_EHIP;
+        if ((int)lds_solve > ctx->max_lds) return KFAC_EHIP;
         KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_solve));
-        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)blk_apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)APPLY_LDS_BYTES));
     }
     bool all_conv = true;
 
@@ -1314,7 +1285,9 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         GroupRun &r = runs[gi];
         r.plan = &gp;
         r.nm = (int)gp.members.size();
+        r.tol2 = (double)tol * tol;
         r.st = ctx->aux[stream_of[gi]];
+        if (getenv("KFAC_DEBUG")) fprintf(stderr, "[kfac] group %zu nblk=%d nm=%d two=%d -> stream %d (%p)\n", gi, gp.nblk, (int)gp.members.size(), (int)gp.two_level, stream_of[gi], (void *)r.st);
         r.ev = ctx->ev_group[gi];
         const size_t np2 = (size_t)gp.npad * gp.npad;
         const int nm = r.nm;
@@ -1341,16 +1314,26 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             g.J = Jin; g.idt = idtin;   // unused by the flat kernels for this group
             // inner group of a regular outer round: units of 4 + 4 small blocks, bipartite pairing
             r.gi = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.U, 2 * SB / EB, LDI, 2 * SB / EB, SB / EB,
-                            (SB / EB + PT - 1) / PT, 1};
+                            0, 1, nullptr, 1};
             // inner group of the diagonal phase: one super-block of 4 small blocks each, tournament pairing
             r.gd = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.nsuper, SB / EB, SB, SB / EB, SB / EB / 2,
-                            (SB / EB / 2 + PT - 1) / PT, 0};
+                            0, 0, nullptr, 1};
         } else {
             p += kfac_align_up(nm * 2 * np2 * sizeof(float), 256);
             g.J = (float *)p; p += kfac_align_up((size_t)nm * gp.npairs * KP * KP * sizeof(float), 256);
             g.idt = (int *)p; p += kfac_align_up((size_t)nm * gp.npairs * sizeof(int), 256);
         }
         g.norms = (double *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(double), 256);
+        int *done = (int *)p; p += kfac_align_up((size_t)nm * sizeof(int), 256);
+        g.done = done;
+        g.per_factor = 1;
+        r.d_done = done;
+        if (gp.two_level) {
+            r.sp.done = done;
+            r.gi.done = done; r.gi.per_factor = gp.U;
+            r.gd.done = done; r.gd.per_factor = gp.nsuper;
+        }
+        KFAC_HIP_CHECK(hipMemsetAsync(done, 0, (size_t)nm * sizeof(int), r.st));
         r.perm = (int *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(int), 256);
         r.lam64 = (double *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(double), 256);
         r.d_items = (BlkItem *)p;
@@ -1368,11 +1351,12 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             // each element a length-2*EB dot product: 8 n^2 EB flops per factor
             r.apply_flops += 8.0 * (double)d[b] * d[b] * EB;
         }
-        // one inner sweep per pivot: KP-1 rounds, 9 flops per element per round (S rotated twice, V once)
-        r.solve_flops = (double)nm * gp.npairs * 9.0 * KP * KP * (KP - 1);
-        r.ntiles_w = gp.npp * (gp.npp + 1) / 2;
-        r.nrb = (r.nmax + TS - 1) / TS;
-        r.ntiles = r.ntiles_w + r.nrb * gp.npp;
+        // one visit of a pivot: KP/2 rounds over the cross pairs (the first round of a sweep also does the
+        // pairs inside the blocks; not counted), 9 flops per element per round (S rotated twice, V once)
+        r.solve_flops = (double)nm * gp.npairs * 9.0 * KP * KP * (KP / 2);
+        r.ntiles_w = gp.npairs * (gp.npairs + 1) / 2;
+        r.nrb = (r.nmax + KP - 1) / KP;
+        r.ntiles = r.ntiles_w + r.nrb * gp.npairs;
         r.fill_blocks = (int)std::min<size_t>((np2 + NT - 1) / NT, 4096);
         r.sweep = 0;
         r.done = false;
@@ -1427,11 +1411,9 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             }
             if (rc) return rc;
         }
-        if (!progressed) {
-            // nothing ready: block on the first unfinished group's event instead of spinning
-            for (auto &r : runs)
-                if (!r.done) { KFAC_HIP_CHECK(hipEventSynchronize(r.ev)); break; }
-        }
+        // nothing ready: poll again shortly.  (Blocking on one group's event would leave every other group
+        // that finishes its sweep earlier waiting for the host.)
+        if (!progressed) std::this_thread::sleep_for(std::chrono::microseconds(20));
     }
     // join: the caller's stream continues after all internal streams
     for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) {

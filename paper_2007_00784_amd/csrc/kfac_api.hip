@@ -108,6 +108,7 @@ size_t kfac_workspace_bytes(int max_d, int max_batch_factors, int64_t max_R) {
     // SYRK split partials: at most 512 + one tile per lower-triangular tile, 64 KB each
     const size_t nt = (max_d + KFAC_TILE) / KFAC_TILE + 1;
     size_t need = (2048 + 2 * nt * (nt + 1) / 2) * (size_t)(KFAC_TILE * KFAC_TILE + KFAC_TILE) * sizeof(float);
+    need = std::max(need, kfac_syrk_workspace_bytes(max_d, max_R)) + (size_t)(1 << 20);   // + job tables
     // precondition: two dG x dA temporaries
     need = std::max(need, 2 * kfac_align_up((size_t)max_d * max_d, 64) * sizeof(float) + (size_t)(1 << 20));
     // eig: every factor of the batch at the largest size, advanced together
@@ -128,15 +129,41 @@ int kfac_unfold(kfac_ctx *ctx, const kfac_conv_desc *desc, const void *x, void *
     return kfac_launch_unfold(ctx, desc, x, patches);
 }
 
+static bool valid_factor_item(const kfac_factor_item &it, bool pointers) {
+    if (pointers && (!it.X || !it.F || (const void *)it.F == it.X)) return false;
+    if (!valid_dtype(it.dtype) || (it.layout != KFAC_LAYOUT_RD && it.layout != KFAC_LAYOUT_NDT)) return false;
+    if (it.N < 1 || it.d < 1 || it.T < 1 || (it.append_ones != 0 && it.append_ones != 1)) return false;
+    if (it.d + it.append_ones > KFAC_MAX_D) return false;
+    if ((int64_t)it.N * it.T >= (int64_t)1 << 30) return false;
+    if ((int64_t)it.d * it.T >= (int64_t)1 << 31) return false;   // 32-bit offsets inside one example's slab
+    if (pointers && (!(it.decay >= 0.f && it.decay <= 1.f) || !std::isfinite(it.scale))) return false;
+    return true;
+}
+
 int kfac_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layout, int N, int d, int T,
                         int append_ones, float scale, float decay, float *F) {
-    if (!ctx || !X || !F || (const void *)F == X) return KFAC_EINVAL;
-    if (!valid_dtype(dtype) || (layout != KFAC_LAYOUT_RD && layout != KFAC_LAYOUT_NDT)) return KFAC_EINVAL;
-    if (N < 1 || d < 1 || T < 1 || (append_ones != 0 && append_ones != 1)) return KFAC_EINVAL;
-    if (d + append_ones > KFAC_MAX_D) return KFAC_EINVAL;
-    if ((int64_t)N * T >= (int64_t)1 << 30) return KFAC_EINVAL;
-    if (!(decay >= 0.f && decay <= 1.f) || !std::isfinite(scale)) return KFAC_EINVAL;
-    return kfac_launch_update_factors(ctx, X, dtype, layout, N, d, T, append_ones, scale, decay, F);
+    if (!ctx) return KFAC_EINVAL;
+    const kfac_factor_item it{X, dtype, layout, N, d, T, append_ones, scale, decay, F};
+    if (!valid_factor_item(it, true)) return KFAC_EINVAL;
+    return kfac_launch_update_factors_batched(ctx, 1, &it);
+}
+
+int kfac_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_item *items) {
+    if (!ctx || n < 0 || (n > 0 && !items)) return KFAC_EINVAL;
+    for (int i = 0; i < n; ++i) {
+        if (!valid_factor_item(items[i], true)) return KFAC_EINVAL;
+        for (int j = 0; j < i; ++j)
+            if (items[j].F == items[i].F) return KFAC_EINVAL;
+    }
+    if (n == 0) return KFAC_OK;
+    return kfac_launch_update_factors_batched(ctx, n, items);
+}
+
+size_t kfac_update_factors_workspace_bytes(int n, const kfac_factor_item *items) {
+    if (n <= 0 || !items) return 0;
+    for (int i = 0; i < n; ++i)
+        if (!valid_factor_item(items[i], false)) return 0;
+    return kfac_syrk_ws_bytes_impl(n, items);
 }
 
 int kfac_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,

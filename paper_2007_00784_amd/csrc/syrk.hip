@@ -7,7 +7,9 @@
 // The appended ones column is not materialised and costs no MFMA tile: its row of the factor is the
 // vector of column sums of X, which every diagonal tile accumulates for its own 128 columns from the
 // operand elements it loads anyway; the corner entry is scale * R.
+#include <algorithm>
 #include <cmath>
+#include <vector>
 #include "kfac_internal.h"
 #include "mfma_gemm.h"
 
@@ -17,18 +19,22 @@ namespace {
 
 constexpr int PART = BM * BM + BM;   // floats per split partial: the tile, then 128 column sums
 
-struct SyrkArgs {
+struct SyrkArgs {     // one factor update of a batch
+    const void *X;
     int d;            // features (tile grid covers d x d)
     int D;            // factor dimension (d + append_ones), leading dimension of F
     int ones;         // 1: also produce the bias row/column
     int nsplit;       // workgroups along K per tile
     int kchunk;       // K rows per split (multiple of BK)
     int K;            // total sample rows
+    int T;            // [N][d][T] layout: positions per example
+    int ntri;         // lower-triangular tiles
     float alpha;      // (1-decay)*scale
     float decay;
     float *F;
     float *partial;   // [nsplit][ntri][PART] when nsplit > 1
 };
+struct SyrkJob { int item, tri, split; };   // one workgroup's share: tile `tri` of factor `item`, K split `split`
 
 __device__ inline void tri_decode(int idx, int &ti, int &tj) {
     // idx = ti*(ti+1)/2 + tj, tj <= ti
@@ -71,18 +77,34 @@ __device__ inline void reduce_colsum(const float (&csum)[EPT], float *scratch /*
     __syncthreads();
 }
 
+template <class Op> __device__ inline Op make_op(const SyrkArgs &g);
+template <> __device__ inline OpNDT<float> make_op(const SyrkArgs &g) { return OpNDT<float>{(const float *)g.X, g.d, g.T, 0, -1}; }
+template <> __device__ inline OpNDT<unsigned short> make_op(const SyrkArgs &g) {
+    return OpNDT<unsigned short>{(const unsigned short *)g.X, g.d, g.T, 0, -1};
+}
+// [R][d]: feature index contiguous, sample index strided by d
+template <> __device__ inline OpStrided<float, false> make_op(const SyrkArgs &g) {
+    return OpStrided<float, false>{(const float *)g.X, 1, g.d, g.d, 0, -1};
+}
+template <> __device__ inline OpStrided<unsigned short, false> make_op(const SyrkArgs &g) {
+    return OpStrided<unsigned short, false>{(const unsigned short *)g.X, 1, g.d, g.d, 0, -1};
+}
+
+// One launch serves every factor of a batch that shares an operand form: workgroup b takes jobs[b].
 template <class Op>
-__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void syrk_kernel(Op opA, SyrkArgs g) {
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void syrk_kernel(const SyrkArgs *items, const SyrkJob *jobs) {
     __shared__ TileSmem sm;
     __shared__ float cs[BM];
+    const SyrkJob job = jobs[blockIdx.x];
+    const SyrkArgs g = items[job.item];
     int ti, tj;
-    tri_decode(blockIdx.x, ti, tj);
-    const int split = blockIdx.y;
+    tri_decode(job.tri, ti, tj);
+    const int split = job.split;
     const int kbeg = split * g.kchunk;
     const int kend = min(g.K, kbeg + g.kchunk);
     const bool diag = ti == tj;
     const bool want_cs = diag && g.ones;
-    Op a = opA, b = opA;
+    Op a = make_op<Op>(g), b = a;
     a.K = kend;
     b.K = kend;
     floatx16 acc[2][2];
@@ -104,11 +126,10 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
         if (want_cs) {
             const int gc = ti * BM + threadIdx.x;
             if (threadIdx.x < BM && gc < g.d) ema_store(g.F, g.D, g.d, gc, cs[threadIdx.x], g.alpha, g.decay, true);
-            if (blockIdx.x == 0 && threadIdx.x == 0) ema_store(g.F, g.D, g.d, g.d, (float)g.K, g.alpha, g.decay, false);
+            if (job.tri == 0 && threadIdx.x == 0) ema_store(g.F, g.D, g.d, g.d, (float)g.K, g.alpha, g.decay, false);
         }
     } else {
-        const int ntri = gridDim.x;
-        float *dst = g.partial + ((int64_t)split * ntri + blockIdx.x) * PART;
+        float *dst = g.partial + ((int64_t)split * g.ntri + job.tri) * PART;
         for_each_acc(acc, [&](int r, int c, float v) { dst[r * BM + c] = v; });
         if (want_cs && threadIdx.x < BM) dst[BM * BM + threadIdx.x] = cs[threadIdx.x];
     }
@@ -116,11 +137,12 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
 
 // Sum the split partials of each tile in split order, then apply the running average and mirror.
 // One thread per tile element (plus 128 for the column sums of diagonal tiles); the loads of
-// consecutive splits are independent, so they are issued eight at a time.
-__global__ __launch_bounds__(256) void syrk_reduce_kernel(SyrkArgs g) {
+// consecutive splits are independent, so they are issued eight at a time.  jobs: (item, tile) pairs.
+__global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkArgs *items, const SyrkJob *jobs) {
+    const SyrkJob job = jobs[blockIdx.x];
+    const SyrkArgs g = items[job.item];
     int ti, tj;
-    tri_decode(blockIdx.x, ti, tj);
-    const int ntri = gridDim.x;
+    tri_decode(job.tri, ti, tj);
     const bool diag = ti == tj;
     const int e = threadIdx.x + blockIdx.y * 256;          // 0 .. PART-1 (grid covers PART rounded up)
     if (e >= PART) return;
@@ -138,8 +160,8 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(SyrkArgs g) {
         if (gc >= g.d) return;
         mirror = true;
     }
-    const float *src = g.partial + (int64_t)blockIdx.x * PART + e;
-    const int64_t stride = (int64_t)ntri * PART;
+    const float *src = g.partial + (int64_t)job.tri * PART + e;
+    const int64_t stride = (int64_t)g.ntri * PART;
     float s = 0.f;
     int sp = 0;
     for (; sp + 8 <= g.nsplit; sp += 8) {
@@ -151,14 +173,14 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(SyrkArgs g) {
     }
     for (; sp < g.nsplit; ++sp) s += src[sp * stride];
     ema_store(g.F, g.D, gr, gc, s, g.alpha, g.decay, mirror);
-    if (g.ones && blockIdx.x == 0 && e == 0) ema_store(g.F, g.D, g.d, g.d, (float)g.K, g.alpha, g.decay, false);
+    if (g.ones && job.tri == 0 && e == 0) ema_store(g.F, g.D, g.d, g.d, (float)g.K, g.alpha, g.decay, false);
 }
 
-// Choose the number of K splits.  Two workgroups share a compute unit (register budget), so the
-// machine has 512 slots; a launch takes ceil(workgroups / 512) rounds of (slabs per split + a fixed
-// per-workgroup cost of about 12 slabs for prologue, epilogue and partial traffic).
-void plan(int d, int64_t R, int &ntile, int &ntri, int &nsplit, int &kchunk) {
-    ntile = (d + BM - 1) / BM;
+// Choose the number of K splits of one factor launched alone.  Two workgroups share a compute unit
+// (register budget), so the machine has 512 slots; a launch takes ceil(workgroups / 512) rounds of (slabs
+// per split + a fixed per-workgroup cost of about 12 slabs for prologue, epilogue and partial traffic).
+void plan_single(int d, int64_t R, int &ntri, int &nsplit, int &kchunk) {
+    const int ntile = (d + BM - 1) / BM;
     ntri = ntile * (ntile + 1) / 2;
     const int64_t slabs = (R + BK - 1) / BK;
     int best = 1;
@@ -176,60 +198,134 @@ void plan(int d, int64_t R, int &ntile, int &ntri, int &nsplit, int &kchunk) {
     nsplit = (int)((R + chunk - 1) / chunk);
 }
 
+// In a batch the other factors fill the machine, so a factor is cut into jobs of about JOB_SLABS slabs
+// each: long enough to amortise a job's fixed cost and its 64 KB partial, short enough that the longest
+// job is a small part of the launch.
+constexpr int JOB_SLABS = 256;
+void plan_batched(int d, int64_t R, int &ntri, int &nsplit, int &kchunk) {
+    const int ntile = (d + BM - 1) / BM;
+    ntri = ntile * (ntile + 1) / 2;
+    const int64_t slabs = (R + BK - 1) / BK;
+    nsplit = (int)std::max<int64_t>(1, (slabs + JOB_SLABS / 2) / JOB_SLABS);
+    int64_t chunk = (R + nsplit - 1) / nsplit;
+    chunk = (chunk + BK - 1) / BK * BK;
+    kchunk = (int)chunk;
+    nsplit = (int)((R + chunk - 1) / chunk);
+}
+
+void plan_item(int n, const kfac_factor_item &it, int &ntri, int &nsplit, int &kchunk) {
+    const int64_t R = (int64_t)it.N * it.T;
+    if (n == 1) plan_single(it.d, R, ntri, nsplit, kchunk);
+    else plan_batched(it.d, R, ntri, nsplit, kchunk);
+}
+
+// Workspace layout: SyrkArgs[n], the job table, the reducer's job table, then every factor's partials.
+size_t layout(int n, const kfac_factor_item *items, size_t &off_jobs, size_t &off_rjobs, size_t &off_part, size_t &njobs, size_t &nrjobs) {
+    njobs = nrjobs = 0;
+    size_t part = 0;
+    for (int i = 0; i < n; ++i) {
+        int ntri, nsplit, kchunk;
+        plan_item(n, items[i], ntri, nsplit, kchunk);
+        njobs += (size_t)ntri * nsplit;
+        if (nsplit > 1) {
+            nrjobs += ntri;
+            part += (size_t)nsplit * ntri * PART;
+        }
+    }
+    off_jobs = kfac_align_up((size_t)n * sizeof(SyrkArgs), 256);
+    off_rjobs = off_jobs + kfac_align_up(njobs * sizeof(SyrkJob), 256);
+    off_part = off_rjobs + kfac_align_up(nrjobs * sizeof(SyrkJob), 256);
+    return off_part + part * sizeof(float);
+}
+
+template <class Op>
+void launch_class(kfac_ctx *ctx, const SyrkArgs *d_items, const SyrkJob *d_jobs, size_t count, double flops, double bytes) {
+    if (count == 0) return;
+    KfacProfScope prof(ctx, KC_SYRK, flops, bytes);
+    hipLaunchKernelGGL((syrk_kernel<Op>), dim3((unsigned)count), dim3(NTHREADS), 0, ctx->stream, d_items, d_jobs);
+}
+
 }  // namespace
 
+size_t kfac_syrk_ws_bytes_impl(int n, const kfac_factor_item *items) {
+    size_t a, b, c, d, e;
+    return layout(n, items, a, b, c, d, e);
+}
+
 size_t kfac_syrk_workspace_bytes(int D, int64_t R) {
-    int ntile, ntri, nsplit, kchunk;
-    plan(D, R, ntile, ntri, nsplit, kchunk);
-    return nsplit > 1 ? (size_t)nsplit * ntri * PART * sizeof(float) : 0;
+    kfac_factor_item it{};
+    it.N = 1;
+    it.T = (int)std::min<int64_t>(R, (int64_t)1 << 30);
+    it.d = D;
+    return kfac_syrk_ws_bytes_impl(1, &it);
+}
+
+int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_item *items) {
+    size_t off_jobs, off_rjobs, off_part, njobs, nrjobs;
+    const size_t need = layout(n, items, off_jobs, off_rjobs, off_part, njobs, nrjobs);
+    if (need > ctx->ws_bytes) return KFAC_EWORKSPACE;
+    std::vector<SyrkArgs> args(n);
+    // jobs grouped by operand form (0: [N][d][T] fp32, 1: [N][d][T] bf16, 2: [R][d] fp32, 3: [R][d] bf16), inside
+    // a form the longest contraction first
+    std::vector<SyrkJob> jobs[4], rjobs;
+    double flops[4] = {0, 0, 0, 0}, bytes[4] = {0, 0, 0, 0}, rbytes = 0.0;
+    float *part = (float *)(ctx->ws + off_part);
+    for (int i = 0; i < n; ++i) {
+        const kfac_factor_item &it = items[i];
+        SyrkArgs &g = args[i];
+        const int64_t R = (int64_t)it.N * it.T;
+        plan_item(n, it, g.ntri, g.nsplit, g.kchunk);
+        g.X = it.X;
+        g.d = it.d;
+        g.D = it.d + (it.append_ones ? 1 : 0);
+        g.ones = it.append_ones ? 1 : 0;
+        g.K = (int)R;
+        g.T = it.T;
+        g.alpha = (1.f - it.decay) * it.scale;
+        g.decay = it.decay;
+        g.F = it.F;
+        g.partial = part;
+        if (g.nsplit > 1) part += (size_t)g.nsplit * g.ntri * PART;
+        const int form = ((it.layout == KFAC_LAYOUT_NDT && it.T > 1) ? 0 : 2) + (it.dtype == KFAC_F32 ? 0 : 1);
+        for (int t = 0; t < g.ntri; ++t)
+            for (int sp = 0; sp < g.nsplit; ++sp) jobs[form].push_back(SyrkJob{i, t, sp});
+        if (g.nsplit > 1)
+            for (int t = 0; t < g.ntri; ++t) rjobs.push_back(SyrkJob{i, t, 0});
+        // useful flops of the symmetric update R*D*(D+1); bytes: the samples once, F read (if averaged) and written
+        const double esz = it.dtype == KFAC_F32 ? 4.0 : 2.0, D = g.D;
+        const double fbytes = (it.decay != 0.f ? 8.0 : 4.0) * D * D;
+        flops[form] += (double)R * D * (D + 1.0);
+        bytes[form] += esz * (double)R * it.d + (g.nsplit == 1 ? fbytes : 0.0);
+        if (g.nsplit > 1) rbytes += fbytes;
+    }
+    SyrkArgs *d_items = (SyrkArgs *)ctx->ws;
+    SyrkJob *d_jobs = (SyrkJob *)(ctx->ws + off_jobs), *d_rjobs = (SyrkJob *)(ctx->ws + off_rjobs);
+    KFAC_HIP_CHECK(hipMemcpyAsync(d_items, args.data(), n * sizeof(SyrkArgs), hipMemcpyHostToDevice, ctx->stream));
+    size_t at[4], pos = 0;
+    for (int f = 0; f < 4; ++f) {
+        std::stable_sort(jobs[f].begin(), jobs[f].end(), [&](const SyrkJob &a, const SyrkJob &b) { return args[a.item].kchunk > args[b.item].kchunk; });
+        at[f] = pos;
+        if (!jobs[f].empty())
+            KFAC_HIP_CHECK(hipMemcpyAsync(d_jobs + pos, jobs[f].data(), jobs[f].size() * sizeof(SyrkJob), hipMemcpyHostToDevice, ctx->stream));
+        pos += jobs[f].size();
+    }
+    if (!rjobs.empty())
+        KFAC_HIP_CHECK(hipMemcpyAsync(d_rjobs, rjobs.data(), rjobs.size() * sizeof(SyrkJob), hipMemcpyHostToDevice, ctx->stream));
+    launch_class<OpNDT<float>>(ctx, d_items, d_jobs + at[0], jobs[0].size(), flops[0], bytes[0]);
+    launch_class<OpNDT<unsigned short>>(ctx, d_items, d_jobs + at[1], jobs[1].size(), flops[1], bytes[1]);
+    launch_class<OpStrided<float, false>>(ctx, d_items, d_jobs + at[2], jobs[2].size(), flops[2], bytes[2]);
+    launch_class<OpStrided<unsigned short, false>>(ctx, d_items, d_jobs + at[3], jobs[3].size(), flops[3], bytes[3]);
+    KFAC_HIP_CHECK(hipGetLastError());
+    if (!rjobs.empty()) {
+        KfacProfScope prof(ctx, KC_SYRK_REDUCE, 0.0, rbytes);
+        hipLaunchKernelGGL(syrk_reduce_kernel, dim3((unsigned)rjobs.size(), (PART + 255) / 256), dim3(256), 0, ctx->stream, d_items, d_rjobs);
+        KFAC_HIP_CHECK(hipGetLastError());
+    }
+    return KFAC_OK;
 }
 
 int kfac_launch_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layout, int N, int d, int T,
                                int append_ones, float scale, float decay, float *F) {
-    const int64_t R = (int64_t)N * T;
-    SyrkArgs g;
-    int ntile, ntri;
-    plan(d, R, ntile, ntri, g.nsplit, g.kchunk);
-    g.d = d;
-    g.D = d + (append_ones ? 1 : 0);
-    g.ones = append_ones ? 1 : 0;
-    g.K = (int)R;
-    g.alpha = (1.f - decay) * scale;
-    g.decay = decay;
-    g.F = F;
-    g.partial = (float *)ctx->ws;
-    if (g.nsplit > 1 && (size_t)g.nsplit * ntri * PART * sizeof(float) > ctx->ws_bytes) return KFAC_EWORKSPACE;
-    const dim3 grid(ntri, g.nsplit), block(NTHREADS);
-    const double esz = dtype == KFAC_F32 ? 4.0 : 2.0;
-    const double D = g.D;
-    {
-        // useful flops of the symmetric update R*D*(D+1); bytes: the samples once, F read (if averaged) and written
-        KfacProfScope prof(ctx, KC_SYRK, (double)R * D * (D + 1.0),
-                           esz * (double)R * d + (g.nsplit == 1 ? (decay != 0.f ? 8.0 : 4.0) * D * D : 0.0));
-        if (layout == KFAC_LAYOUT_NDT && T > 1) {
-            if (dtype == KFAC_F32) {
-                OpNDT<float> op{(const float *)X, d, T, 0, -1};
-                hipLaunchKernelGGL(syrk_kernel<OpNDT<float>>, grid, block, 0, ctx->stream, op, g);
-            } else {
-                OpNDT<unsigned short> op{(const unsigned short *)X, d, T, 0, -1};
-                hipLaunchKernelGGL(syrk_kernel<OpNDT<unsigned short>>, grid, block, 0, ctx->stream, op, g);
-            }
-        } else {
-            // [R][d]: feature index contiguous, sample index strided by d
-            if (dtype == KFAC_F32) {
-                OpStrided<float, false> op{(const float *)X, 1, d, d, 0, -1};
-                hipLaunchKernelGGL((syrk_kernel<OpStrided<float, false>>), grid, block, 0, ctx->stream, op, g);
-            } else {
-                OpStrided<unsigned short, false> op{(const unsigned short *)X, 1, d, d, 0, -1};
-                hipLaunchKernelGGL((syrk_kernel<OpStrided<unsigned short, false>>), grid, block, 0, ctx->stream, op, g);
-            }
-        }
-    }
-    KFAC_HIP_CHECK(hipGetLastError());
-    if (g.nsplit > 1) {
-        KfacProfScope prof(ctx, KC_SYRK_REDUCE, 0.0, (decay != 0.f ? 8.0 : 4.0) * D * D);
-        hipLaunchKernelGGL(syrk_reduce_kernel, dim3(ntri, (PART + 255) / 256), dim3(256), 0, ctx->stream, g);
-        KFAC_HIP_CHECK(hipGetLastError());
-    }
-    return KFAC_OK;
+    kfac_factor_item it{X, dtype, layout, N, d, T, append_ones, scale, decay, F};
+    return kfac_launch_update_factors_batched(ctx, 1, &it);
 }

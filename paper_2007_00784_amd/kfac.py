@@ -19,6 +19,7 @@ EXPORTS = (
     "kfac_create", "kfac_destroy", "kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
     "kfac_unfold", "kfac_update_factors", "kfac_eig", "kfac_precondition", "kfac_schedule_due",
     "kfac_profile_begin", "kfac_profile_end", "kfac_precondition_batched", "kfac_precondition_workspace_bytes",
+    "kfac_update_factors_batched", "kfac_update_factors_workspace_bytes",
 )
 
 
@@ -44,6 +45,12 @@ class kfac_precond_item(ctypes.Structure):
     _fields_ = [("QA", ctypes.c_void_p), ("lamA", ctypes.c_void_p), ("dA", ctypes.c_int),
                 ("QG", ctypes.c_void_p), ("lamG", ctypes.c_void_p), ("dG", ctypes.c_int),
                 ("damping", ctypes.c_float), ("grad", ctypes.c_void_p), ("grad_dtype", ctypes.c_int)]
+
+
+class kfac_factor_item(ctypes.Structure):
+    _fields_ = [("X", ctypes.c_void_p), ("dtype", ctypes.c_int), ("layout", ctypes.c_int),
+                ("N", ctypes.c_int), ("d", ctypes.c_int), ("T", ctypes.c_int), ("append_ones", ctypes.c_int),
+                ("scale", ctypes.c_float), ("decay", ctypes.c_float), ("F", ctypes.c_void_p)]
 
 
 class KfacError(RuntimeError):
@@ -81,11 +88,14 @@ def lib():
     L.kfac_precondition_batched.argtypes = [vp, i, ctypes.POINTER(kfac_precond_item)]
     L.kfac_precondition_workspace_bytes.argtypes = [i, ctypes.POINTER(kfac_precond_item)]
     L.kfac_precondition_workspace_bytes.restype = sz
+    L.kfac_update_factors_batched.argtypes = [vp, i, ctypes.POINTER(kfac_factor_item)]
+    L.kfac_update_factors_workspace_bytes.argtypes = [i, ctypes.POINTER(kfac_factor_item)]
+    L.kfac_update_factors_workspace_bytes.restype = sz
     L.kfac_profile_begin.argtypes = [vp]
     L.kfac_profile_end.argtypes = [vp, ctypes.POINTER(kfac_kernel_stat), i, ip]
     for name in EXPORTS:
         if name not in ("kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
-                        "kfac_precondition_workspace_bytes"):
+                        "kfac_precondition_workspace_bytes", "kfac_update_factors_workspace_bytes"):
             getattr(L, name).restype = i
     _lib = L
     return L
@@ -157,6 +167,29 @@ def kfac_update_factors(ctx, X, layout, N, d, T, append_ones, scale, decay, F, d
     code = _dtype_code(X) if dtype is None else dtype
     _check(lib().kfac_update_factors(ctx, _ptr(X), code, int(layout), int(N), int(d), int(T), int(append_ones),
                                      float(scale), float(decay), _ptr(F)), "kfac_update_factors")
+
+
+def _factor_items(items):
+    """items: list of dicts with the arguments of kfac_update_factors (X and F may be None for sizing)."""
+    arr = (kfac_factor_item * len(items))()
+    for j, it in enumerate(items):
+        X, F = it.get("X"), it.get("F")
+        code = it.get("dtype")
+        if code is None:
+            code = _dtype_code(X) if X is not None else KFAC_F32
+        arr[j] = kfac_factor_item(_ptr(X), int(code), int(it["layout"]), int(it["N"]), int(it["d"]), int(it["T"]),
+                                  int(it["append_ones"]), float(it.get("scale", 1.0)), float(it.get("decay", 0.0)), _ptr(F))
+    return arr
+
+
+def kfac_update_factors_batched(ctx, items):
+    """items: list of dicts(X, layout, N, d, T, append_ones, scale, decay, F[, dtype]); all updated in one call."""
+    arr = _factor_items(items)
+    _check(lib().kfac_update_factors_batched(ctx, len(items), arr), "kfac_update_factors_batched")
+
+
+def kfac_update_factors_workspace_bytes(items):
+    return int(lib().kfac_update_factors_workspace_bytes(len(items), _factor_items(items)))
 
 
 def kfac_eig(ctx, F, Q, lam, max_sweeps=0, tol=0.0, raise_on_noconv=True, fp32_only=False):

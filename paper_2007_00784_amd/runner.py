@@ -31,8 +31,16 @@ class KfacRunner:
                     print("generated update %d layer %d" % (u, li), flush=True)
             self.x.append(xs)
             self.g.append(gs)
-        for li in self.layer_ids:
-            self.gradw_master.append(self._up(S.layer_inputs(wl, li, batch=self.N, want=("gradw",))["gradw"]))
+        # all gradients live in one flat buffer (and so do their masters), so that restoring them before an
+        # in-place preconditioning is a single device copy
+        gw = [S.layer_inputs(wl, li, batch=self.N, want=("gradw",))["gradw"] for li in self.layer_ids]
+        offs = np.cumsum([0] + [(g.size + 63) // 64 * 64 for g in gw])
+        self.gradw_master_flat = torch.zeros(int(offs[-1]), dtype=self.dt, device=self.dev)
+        self.grad_flat = torch.zeros_like(self.gradw_master_flat)
+        for j, g in enumerate(gw):
+            view = self.gradw_master_flat[int(offs[j]):int(offs[j]) + g.size].view(g.shape)
+            view.copy_(self._up(g))
+            self.gradw_master.append(view)
         f32 = dict(dtype=torch.float32, device=self.dev)
         self.A = [torch.zeros((l.d_a, l.d_a), **f32) for l in self.layers]
         self.G = [torch.zeros((l.d_g, l.d_g), **f32) for l in self.layers]
@@ -40,11 +48,13 @@ class KfacRunner:
         self.QG = [torch.zeros_like(g) for g in self.G]
         self.lamA = [torch.zeros(l.d_a, **f32) for l in self.layers]
         self.lamG = [torch.zeros(l.d_g, **f32) for l in self.layers]
-        self.grad = [torch.zeros_like(m) for m in self.gradw_master]
-        pmax = max([(l.d_a - 1) * l.T * self.N for l in self.layers if l.needs_unfold] + [1])
-        self.patches = torch.empty(pmax, dtype=self.dt, device=self.dev)
+        self.grad = [self.grad_flat[int(offs[j]):int(offs[j]) + g.size].view(g.shape) for j, g in enumerate(gw)]
+        # every unfolded layer keeps its own patch slab, so all factor updates go out as one batch
+        self.patches = [torch.empty((l.d_a - 1) * l.T * self.N, dtype=self.dt, device=self.dev) if l.needs_unfold else None
+                        for l in self.layers]
         dims = [l.d_a for l in self.layers] + [l.d_g for l in self.layers]
         need = K.kfac_eig_workspace_bytes(dims)
+        need = max(need, K.kfac_update_factors_workspace_bytes(self._factor_items(0, 0.0, sizing=True)))
         need = max(need, K.kfac_precondition_workspace_bytes([(l.d_a, l.d_g) for l in self.layers]))
         need = max(need, K.kfac_workspace_bytes(max(dims), 1, max(l.rows(self.N) for l in self.layers)))  # SYRK partials, precondition
         self.ws = torch.empty(need + 4096, dtype=torch.uint8, device=self.dev)
@@ -63,23 +73,36 @@ class KfacRunner:
             self.ctx = None
 
     # ---- phases ----
-    def update_factors(self, upd, decay):
+    def _factor_items(self, upd, decay, sizing=False):
         N = self.N
+        code = K.KFAC_BF16 if self.wl.bf16 else K.KFAC_F32
+        items = []
         for i, l in enumerate(self.layers):
-            x, g = self.x[upd][i], self.g[upd][i]
             R = N * l.T
-            if l.fc:
-                K.kfac_update_factors(self.ctx, x, K.KFAC_LAYOUT_RD, N, l.d_a - 1, 1, 1, 1.0 / R, decay, self.A[i])
-                K.kfac_update_factors(self.ctx, g, K.KFAC_LAYOUT_RD, N, l.d_g, 1, 0, 1.0 / R, decay, self.G[i])
-                continue
-            if l.needs_unfold:
-                K.kfac_unfold(self.ctx, x, l.k, l.k, l.stride, l.pad, self.patches)
-                src = self.patches
+            lay = K.KFAC_LAYOUT_RD if l.fc else K.KFAC_LAYOUT_NDT
+            T = 1 if l.fc else l.T
+            if sizing:
+                src = g = FA = FG = None
             else:
-                src = x                                  # [N][C][H*W] is already the patch slab
-            K.kfac_update_factors(self.ctx, src, K.KFAC_LAYOUT_NDT, N, l.d_a - 1, l.T, 1, 1.0 / R, decay, self.A[i],
-                                  dtype=K.KFAC_BF16 if self.wl.bf16 else K.KFAC_F32)
-            K.kfac_update_factors(self.ctx, g, K.KFAC_LAYOUT_NDT, N, l.d_g, l.T, 0, 1.0 / R, decay, self.G[i])
+                src = self.patches[i] if l.needs_unfold else self.x[upd][i]   # [N][C][H*W] is already the patch slab
+                g, FA, FG = self.g[upd][i], self.A[i], self.G[i]
+            items.append(dict(X=src, dtype=code, layout=lay, N=N, d=l.d_a - 1, T=T, append_ones=1, scale=1.0 / R,
+                              decay=decay, F=FA))
+            items.append(dict(X=g, dtype=code, layout=lay, N=N, d=l.d_g, T=T, append_ones=0, scale=1.0 / R,
+                              decay=decay, F=FG))
+        return items
+
+    def update_factors(self, upd, decay, batched=True):
+        for i, l in enumerate(self.layers):
+            if l.needs_unfold:
+                K.kfac_unfold(self.ctx, self.x[upd][i], l.k, l.k, l.stride, l.pad, self.patches[i])
+        items = self._factor_items(upd, decay)
+        if batched:
+            K.kfac_update_factors_batched(self.ctx, items)
+        else:
+            for it in items:
+                K.kfac_update_factors(self.ctx, it["X"], it["layout"], it["N"], it["d"], it["T"], it["append_ones"],
+                                      it["scale"], it["decay"], it["F"], dtype=it["dtype"])
 
     def eig(self, **kw):
         self.eig_info = K.kfac_eig(self.ctx, self.A + self.G, self.QA + self.QG, self.lamA + self.lamG, **kw)
@@ -87,8 +110,7 @@ class KfacRunner:
 
     def precondition(self, damping=None):
         gamma = self.wl.damping if damping is None else damping
-        for i in range(len(self.layers)):
-            self.grad[i].copy_(self.gradw_master[i])
+        self.grad_flat.copy_(self.gradw_master_flat)
         K.kfac_precondition_batched(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad)
 
     # ---- algorithmic work of one step (flops, bytes) ----

@@ -101,6 +101,43 @@ def test_update_factors_matches_oracle(ctx, case, bf16):
         assert abs(got[D - 1, D - 1] - 1.0) < 1e-6
 
 
+def test_update_factors_batched_matches_oracle(ctx):
+    """Every case above, fp32 and bf16 operands mixed, in ONE batched call per update (all four operand forms
+    in the same call; job tables, per-factor partial buffers, the shared reducer), two updates so the
+    running average of each factor is exercised, plus an empty batch."""
+    rng = np.random.default_rng(5)
+    K.kfac_update_factors_batched(ctx.h, [])
+    F = [None] * (2 * len(FACTOR_CASES))
+    Fd = [torch.full((d + ones, d + ones), float("nan"), dtype=torch.float32, device=ctx.dev)
+          for (_, _, d, _, ones) in FACTOR_CASES for _ in range(2)]
+    for upd, decay in enumerate([0.0, 0.9]):
+        items = []
+        for ci, (layout, N, d, T, ones) in enumerate(FACTOR_CASES):
+            for bf16 in (False, True):
+                j = 2 * ci + int(bf16)
+                X = np.maximum(rng.standard_normal((N, d, T)), 0).astype(np.float32) if layout == "NDT" else \
+                    np.maximum(rng.standard_normal((N * T, d)), 0).astype(np.float32)
+                if bf16:
+                    X = S.bf16_bits_to_f32(S.to_bf16_bits(X)).reshape(X.shape)
+                rows = ndt_to_rows(X) if layout == "NDT" else X.astype(np.float64)
+                R = rows.shape[0]
+                Fb = oracle.gram(rows, ones, 1.0 / R)
+                F[j] = Fb if upd == 0 else oracle.ema(F[j], Fb, decay)
+                items.append(dict(X=ctx.to_dev(X, bf16), layout=K.KFAC_LAYOUT_NDT if layout == "NDT" else K.KFAC_LAYOUT_RD,
+                                  N=N, d=d, T=T, append_ones=ones, scale=1.0 / R, decay=decay, F=Fd[j]))
+        assert K.kfac_update_factors_workspace_bytes(items) <= ctx.ws.numel()
+        K.kfac_update_factors_batched(ctx.h, items)
+        torch.cuda.synchronize()
+        for j in range(len(F)):
+            got = Fd[j].cpu().numpy()
+            assert np.isfinite(got).all(), j
+            assert np.array_equal(got, got.T), j
+            assert relfro(got, F[j]) <= TOL_F32, (j, relfro(got, F[j]))
+    # the same factor twice in one batch is rejected
+    with pytest.raises(K.KfacError):
+        K.kfac_update_factors_batched(ctx.h, [items[0], items[0]])
+
+
 def test_update_factors_deterministic(ctx):
     rng = np.random.default_rng(3)
     X = ctx.to_dev(rng.standard_normal((20000, 70)).astype(np.float32))
