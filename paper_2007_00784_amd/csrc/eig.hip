@@ -6,11 +6,17 @@
 //    tournament ordering), each computed by one lane and applied by the whole workgroup.
 //  * d  > 128: blocked Jacobi.  The matrix is cut into EB-wide blocks; a round pairs the blocks by
 //    the same tournament, gives each 2EB x 2EB pivot sub-problem ONE sweep of the LDS solver above
-//    (one workgroup per pair), and applies the resulting orthogonal transforms to the whole matrix
-//    and to the eigenvector accumulator as fp32 MFMA products on LDS-resident 128 x 128 tiles.  Only
-//    the lower block-triangle is computed; the mirror image is written from LDS, so the working
-//    matrix stays exactly symmetric.  Factors of equal block count advance together, and all such
-//    groups are in flight at once on the context's internal streams.
+//    (one workgroup per pair; only the pairs between the two blocks after a block's first visit of the
+//    sweep), and applies the resulting orthogonal transforms to the whole matrix and to the eigenvector
+//    accumulator as fp32 MFMA products, one workgroup per 2EB x 2EB block.  Only the lower
+//    block-triangle is computed; the mirror image is written from LDS, so the working matrix stays
+//    exactly symmetric.
+//  * d >= 2048: two-level.  128-wide super-blocks are paired by an outer tournament; each 256 x 256
+//    super-pair runs the rounds above on a compact copy that stays in L2 and accumulates its transform,
+//    which is then applied to the whole matrix and accumulator by two passes of 128 x 128 x 256 GEMM
+//    tiles on split-fp16 MFMAs (or fp32 MFMAs on request).
+//  * Factors of similar size are padded into common groups that advance together; all groups are in
+//    flight at once on the context's internal streams.
 //  * When a factor has converged, one Newton-Schulz step re-orthogonalises the accumulated
 //    eigenvectors, Rayleigh quotients against the caller's matrix give the eigenvalues, and the
 //    columns are sorted.
@@ -1100,10 +1106,15 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
     const int nrb = gp.npad / SB;
     // algorithmic work of the two passes: every element of half the symmetric matrix and of the
     // accumulator gets two (one) dot products of the unit edge s
-    double fl = 0.0;
-    for (int i = 0; i < r.nm; ++i) fl += 4.0 * (double)r.items[i].n * r.items[i].n * s;
+    // algorithmic bytes: the column pass reads Q and the lower half of W and writes as much (12 n^2 bytes), the
+    // row pass reads the half-size T and writes W with its mirror image (6 n^2)
+    double fl = 0.0, n2 = 0.0;
+    for (int i = 0; i < r.nm; ++i) {
+        fl += 4.0 * (double)r.items[i].n * r.items[i].n * s;
+        n2 += (double)r.items[i].n * r.items[i].n;
+    }
     {
-        KfacProfScope prof(ctx, KC_EIG_OUTER, 0.75 * fl, 0.0, st);
+        KfacProfScope prof(ctx, KC_EIG_OUTER, 0.75 * fl, 12.0 * n2, st);
         if (r.x3)
             hipLaunchKernelGGL(sp_pass_cols_kernel<true>, dim3(nW + nrb * U * 2, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s,
                                nW, nrb, (const float *)r.g.Qw, r.Qalt, 0);
@@ -1112,7 +1123,7 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
                                nW, nrb, (const float *)r.g.Qw, r.Qalt, 0);
     }
     if (nW > 0) {
-        KfacProfScope prof(ctx, KC_EIG_OUTER, 0.25 * fl, 0.0, st);
+        KfacProfScope prof(ctx, KC_EIG_OUTER, 0.25 * fl, 6.0 * n2, st);
         if (r.x3) hipLaunchKernelGGL(sp_pass_rows_kernel<true>, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
         else hipLaunchKernelGGL(sp_pass_rows_kernel<false>, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
     }
