@@ -61,7 +61,7 @@ typedef struct {
 
 typedef struct {
     int max_sweeps;          /* cap on Jacobi sweeps (<=0: 30)                    */
-    float tol;               /* stop when off(F)_F <= tol * ||F||_F (<=0: 1e-6)   */
+    float tol;               /* stop when off(F)_F <= tol * ||F||_F (<=0: 2e-6)   */
     int fp32_only;           /* 0 (default): for d >= 2048 the rank-256 update passes run as split-fp16
                                 MFMA products (hi + lo halves, three products per fp32 product, fp32
                                 accumulation): same tolerances met, errors bounded normwise (relative to

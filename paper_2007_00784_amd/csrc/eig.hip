@@ -26,6 +26,8 @@
 #include <chrono>
 #include <cstdio>
 #include <cstdlib>
+#include <cstdio>
+#include <cstdlib>
 #include <cmath>
 #include <thread>
 #include <cstdlib>
@@ -1211,7 +1213,7 @@ size_t kfac_eig_ws_bytes_impl(int batch, const int *d) {
 int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,
                     float *const *lam, const kfac_eig_opts *opts, kfac_eig_info *info) {
     const int max_sweeps = (opts && opts->max_sweeps > 0) ? opts->max_sweeps : 30;
-    const float tol = (opts && opts->tol > 0.f) ? opts->tol : 1e-6f;
+    const float tol = (opts && opts->tol > 0.f) ? opts->tol : 2e-6f;
     std::vector<int> small;
     std::vector<GroupPlan> groups;
     make_plan(batch, d, small, groups);
@@ -1409,6 +1411,11 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
                 if (c && !r.conv[i]) r.sweeps_done[i] = r.sweep;
                 r.conv[i] = c;
                 all &= c;
+            }
+            if (getenv("KFAC_EIG_TRACE")) {
+                fprintf(stderr, "[kfac_eig] group nblk=%d sweep %d off/norm:", r.plan->nblk, r.sweep);
+                for (int i = 0; i < r.nm; ++i) fprintf(stderr, " %.2e", r.offrel[i]);
+                fprintf(stderr, "\n");
             }
             int rc;
             if (all || r.sweep >= max_sweeps) {
