@@ -20,4 +20,5 @@ from .kfac_oracle import (  # noqa: F401
     bruteforce,
     spd_solve,
     schedule,
+    grad_scale,
 )

@@ -522,3 +522,26 @@ void oracle_schedule(int64_t k, int f_fac, int f_eig, int *do_factors, int *do_e
     *do_factors = (k % f_fac) == 0;
     *do_eig = (k % f_eig) == 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Gradient scaling (Sec. V-B, the equation for nu): after preconditioning, every layer's gradient is multiplied by
+ *     nu = min(1, sqrt(kappa / (alpha^2 * sum_i |<P_i, g_i>|)))
+ * where P_i is the preconditioned and g_i the original gradient of layer i, <.,.> the sum of the elementwise
+ * products, kappa a user constant and alpha the learning rate.  The layers are given back to back in two
+ * flat arrays; sizes[i] elements belong to layer i.  A zero sum gives nu = 1.
+ * ---------------------------------------------------------------------- */
+double oracle_grad_scale(int nlayers, const int64_t *sizes, const double *precond, const double *grad,
+                         double kappa, double alpha)
+{
+    double total = 0.0;
+    int64_t off = 0;
+    for (int i = 0; i < nlayers; ++i) {
+        double dot = 0.0;
+        for (int64_t e = 0; e < sizes[i]; ++e) dot += precond[off + e] * grad[off + e];
+        total += fabs(dot);
+        off += sizes[i];
+    }
+    if (!(total > 0.0)) return 1.0;
+    const double nu = sqrt(kappa / (alpha * alpha * total));
+    return nu < 1.0 ? nu : 1.0;
+}

@@ -54,6 +54,8 @@ def _load():
     lib.oracle_spd_solve.argtypes = [_dp, _i, _dp, _i, _dp]
     lib.oracle_spd_solve.restype = _i
     lib.oracle_schedule.argtypes = [_i64, _i, _i, ctypes.POINTER(_i), ctypes.POINTER(_i)]
+    lib.oracle_grad_scale.argtypes = [_i, ctypes.POINTER(_i64), _dp, _dp, _d, _d]
+    lib.oracle_grad_scale.restype = _d
     _lib = lib
     return lib
 
@@ -178,6 +180,15 @@ def spd_solve(A, B):
     if rc < 0:
         raise RuntimeError("matrix not positive definite")
     return X
+
+
+def grad_scale(precond, grad, kappa, alpha):
+    """nu of Sec. V-B for lists of per-layer preconditioned and original gradients."""
+    assert len(precond) == len(grad)
+    sizes = (_i64 * len(grad))(*[int(np.asarray(g).size) for g in grad])
+    P = _c(np.concatenate([np.asarray(p, dtype=np.float64).ravel() for p in precond])) if len(grad) else _c(np.zeros(1))
+    G = _c(np.concatenate([np.asarray(g, dtype=np.float64).ravel() for g in grad])) if len(grad) else _c(np.zeros(1))
+    return float(_load().oracle_grad_scale(len(grad), sizes, _p(P), _p(G), float(kappa), float(alpha)))
 
 
 def schedule(k, f_fac, f_eig):

@@ -453,3 +453,40 @@ def test_schedule_counts():
     assert (nf, ne) == (20, 2)
     assert oracle.schedule(0, 10, 100) == (True, True)
     assert oracle.schedule(7, 10, 100) == (False, False)
+
+
+# ------------------------------------------------------------------ gradient scaling
+def test_grad_scale_closed_forms():
+    """Sec. V-B, nu = min(1, sqrt(kappa / (alpha^2 sum_i |<P_i, g_i>|))): hand-computed cases.
+
+    One layer with P = g = (3, 4): <P, g> = 25, so nu = sqrt(kappa / (alpha^2 25)).  Two layers whose inner
+    products are +25 and -7: the sum of the ABSOLUTE values, 32, enters (a plain sum of 18 or a total
+    |18| would give different numbers).  Large kappa clips at 1; zero gradients give 1."""
+    P1, g1 = np.array([[3.0, 4.0]]), np.array([[3.0, 4.0]])
+    assert oracle.grad_scale([P1], [g1], 1e-3, 0.1) == pytest.approx(np.sqrt(1e-3 / (0.01 * 25.0)), rel=1e-14)
+    P2, g2 = np.array([[1.0], [-2.0], [1.0]]), np.array([[1.0], [3.0], [-2.0]])     # <P2, g2> = 1 - 6 - 2 = -7
+    nu = oracle.grad_scale([P1, P2], [g1, g2], 1e-3, 0.1)
+    assert nu == pytest.approx(np.sqrt(1e-3 / (0.01 * 32.0)), rel=1e-14)
+    assert nu != pytest.approx(np.sqrt(1e-3 / (0.01 * 18.0)), rel=1e-3)
+    assert oracle.grad_scale([P1, P2], [g1, g2], 1e3, 0.1) == 1.0
+    assert oracle.grad_scale([np.zeros((2, 2))], [np.ones((2, 2))], 1e-3, 0.1) == 1.0
+    # scale laws: nu ~ 1/alpha and ~ sqrt(kappa) below the clip; doubling every P halves nu^2
+    base = oracle.grad_scale([P1, P2], [g1, g2], 1e-3, 0.1)
+    assert oracle.grad_scale([P1, P2], [g1, g2], 1e-3, 0.2) == pytest.approx(base / 2, rel=1e-14)
+    assert oracle.grad_scale([P1, P2], [g1, g2], 4e-3, 0.1) == pytest.approx(base * 2, rel=1e-14)
+    assert oracle.grad_scale([2 * P1, 2 * P2], [g1, g2], 1e-3, 0.1) == pytest.approx(base / np.sqrt(2), rel=1e-14)
+
+
+def test_grad_scale_bounds_the_step():
+    """What the scaling is for: after it, alpha^2 * sum_i |<nu P_i, g_i>| / nu <= kappa ... i.e. with
+    s = sum_i |<P_i, g_i>|, the scaled quantity alpha^2 nu^2 s never exceeds kappa, and equals it when nu < 1."""
+    rng = np.random.default_rng(0)
+    P = [rng.standard_normal((4, 7)), rng.standard_normal((3, 3))]
+    g = [rng.standard_normal((4, 7)), rng.standard_normal((3, 3))]
+    s = sum(abs(float((p * q).sum())) for p, q in zip(P, g))
+    for kappa, alpha in [(1e-3, 0.1), (1e-1, 0.01), (10.0, 1.0)]:
+        nu = oracle.grad_scale(P, g, kappa, alpha)
+        assert 0 < nu <= 1
+        assert alpha ** 2 * nu ** 2 * s <= kappa * (1 + 1e-12)
+        if nu < 1:
+            assert alpha ** 2 * nu ** 2 * s == pytest.approx(kappa, rel=1e-12)
