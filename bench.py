@@ -26,6 +26,7 @@ BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
     "syrk": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
     "syrk_reduce": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "precond_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
+    "precond_scale": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "eig_small": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
     "eig_pivot_solve": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
     # K = 64 contraction per pass over W and Q: 16 flop/byte, below the fp32 ridge of 19.7

@@ -160,6 +160,16 @@ typedef struct {
 int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items /* host */);
 size_t kfac_precondition_workspace_bytes(int n, const kfac_precond_item *items /* host; only dA, dG are read */);
 
+/* The same, followed by the gradient scaling of Sec. V-B ("K-FAC Hyper-Parameters"): every preconditioned
+ * gradient P_l is multiplied by
+ *     nu = min(1, sqrt(kappa / (lr^2 * sum_l |<P_l, grad_l>|)))
+ * with grad_l the gradient as it was on entry and <.,.> the sum of elementwise products (for bf16 gradients
+ * of the values as stored).  The inner products are taken in the last GEMM's epilogue (per-tile partial sums,
+ * added in a fixed order: deterministic).  nu: DEVICE pointer to one float, written by the call (1 when the
+ * sum is zero); kappa > 0, lr > 0.  Same workspace as kfac_precondition_batched.  */
+int kfac_precondition_batched_scaled(kfac_ctx *ctx, int n, const kfac_precond_item *items /* host */, float kappa,
+                                     float lr, float *nu /* device, out */);
+
 /* Update-decoupled schedule (Sec. IV-C, Sec. V-C), host only: at iteration k refresh the factors
  * when k % f_fac == 0 and the eigendecompositions when k % f_eig == 0; precondition always.  */
 int kfac_schedule_due(int64_t k, int f_fac, int f_eig, int *do_factors, int *do_eig);

@@ -196,7 +196,8 @@ int kfac_profile_begin(kfac_ctx *ctx) {
 int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out, int max, int *n) {
     if (!ctx || !out || !n || max < 0) return KFAC_EINVAL;
     static const char *names[KC_COUNT] = {"unfold", "syrk", "syrk_reduce", "precond_gemm", "eig_small",
-                                          "eig_pivot_solve", "eig_apply", "eig_misc", "eig_post_gemm", "eig_copy", "eig_outer_gemm"};
+                                          "eig_pivot_solve", "eig_apply", "eig_misc", "eig_post_gemm", "eig_copy", "eig_outer_gemm",
+                                          "precond_scale"};
     ctx->prof_on = false;
     KFAC_HIP_CHECK(hipStreamSynchronize(ctx->stream));
     kfac_kernel_stat acc[KC_COUNT] = {};
@@ -233,7 +234,15 @@ int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *ite
     for (int i = 0; i < n; ++i)
         if (!valid_precond_item(items[i])) return KFAC_EINVAL;
     if (n == 0) return KFAC_OK;
-    return kfac_launch_precondition_batched(ctx, n, items);
+    return kfac_launch_precondition_batched(ctx, n, items, false, 0.f, 0.f, nullptr);
+}
+
+int kfac_precondition_batched_scaled(kfac_ctx *ctx, int n, const kfac_precond_item *items, float kappa, float lr, float *nu) {
+    if (!ctx || n < 1 || !items || !nu) return KFAC_EINVAL;
+    if (!(kappa > 0.f) || !std::isfinite(kappa) || !(lr > 0.f) || !std::isfinite(lr)) return KFAC_EINVAL;
+    for (int i = 0; i < n; ++i)
+        if (!valid_precond_item(items[i])) return KFAC_EINVAL;
+    return kfac_launch_precondition_batched(ctx, n, items, true, kappa, lr, nu);
 }
 
 size_t kfac_precondition_workspace_bytes(int n, const kfac_precond_item *items) {

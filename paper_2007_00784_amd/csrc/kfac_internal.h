@@ -9,7 +9,7 @@
 // Kernel classes for the optional per-kernel timing (kfac_profile_begin / kfac_profile_end).
 enum KfacKernelClass {
     KC_UNFOLD = 0, KC_SYRK, KC_SYRK_REDUCE, KC_PRECOND_GEMM, KC_EIG_SMALL, KC_EIG_SOLVE, KC_EIG_APPLY,
-    KC_EIG_MISC, KC_EIG_POST, KC_EIG_COPY, KC_EIG_OUTER, KC_COUNT
+    KC_EIG_MISC, KC_EIG_POST, KC_EIG_COPY, KC_EIG_OUTER, KC_PRECOND_SCALE, KC_COUNT
 };
 struct KfacProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
 
@@ -78,7 +78,8 @@ int kfac_launch_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layo
                                int append_ones, float scale, float decay, float *F);
 int kfac_launch_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,
                              const float *lamG, int dG, float damping, void *grad, int grad_dtype);
-int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items);
+int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items, bool scaled, float kappa, float lr,
+                                     float *nu);
 size_t kfac_precond_ws_bytes_impl(int n, const kfac_precond_item *items);
 size_t kfac_eig_ws_bytes_impl(int batch, const int *d);
 int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,

@@ -4,6 +4,10 @@
 //   V2 = (T QA) / (lamG lamA^T + damping)     (K = dA, divide fused into the epilogue)
 //   T  = QG V2                (K = dG)
 //   grad = T QA^T             (K = dA)
+// and optionally the gradient scaling of Sec. V-B on top: nu = min(1, sqrt(kappa / (lr^2 sum_l |<P_l, grad_l>|))),
+// P_l the preconditioned and grad_l the original gradient of layer l, every P_l multiplied by nu.  The inner
+// products cost no extra pass: the last stage overwrites grad element by element, so its epilogue reads the
+// old value just before it stores the new one.
 // Four dependent GEMM stages on the fp32 MFMA tile engine.  Each stage is ONE launch over the 128x128
 // output tiles of every layer in the batch (a device table maps a workgroup to its layer and tile,
 // longest contraction first), so small layers do not leave the machine idle and a 54-layer network
@@ -24,6 +28,7 @@ struct LayerDev {
     int dA, dG;
     float damping;
     int grad_bf16;
+    int tile_base;     // index of this layer's first tile in the per-tile inner-product array
 };
 struct TileRef { int layer, tile; };   // tile = ti * tiles_n + tj
 
@@ -45,7 +50,8 @@ __device__ inline void run_tile(OpA a, OpB b, int i0, int j0, int K, int M, int 
 }
 
 template <int STAGE>
-__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void precond_stage_kernel(const LayerDev *layers, const TileRef *tiles) {
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void precond_stage_kernel(const LayerDev *layers, const TileRef *tiles,
+                                                                                                       double *dots) {
     __shared__ TileSmem sm;
     const TileRef tr = tiles[blockIdx.x];
     const LayerDev L = layers[tr.layer];
@@ -85,12 +91,64 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
         // grad = T QA^T : A(m,k) = T[m][k], B(k,n) = QA[n][k] (k contiguous)
         OpStrided<float, true> t_mk{L.T, dA, 1, dG, dA, -1};
         OpStrided<float, true> qa_nk{L.QA, dA, 1, dA, dA, -1};
+        // dot: this thread's share of <new grad, old grad> (the values as stored, i.e. after bf16 rounding)
         void *grad = L.grad;
+        float dot = 0.f;
         if (L.grad_bf16)
-            run_tile(t_mk, qa_nk, i0, j0, dA, dG, dA, sm,
-                     [=](int r, int c, float v) { ((unsigned short *)grad)[(int64_t)r * dA + c] = f32_to_bf16_rne(v); });
+            run_tile(t_mk, qa_nk, i0, j0, dA, dG, dA, sm, [&](int r, int c, float v) {
+                unsigned short *p = (unsigned short *)grad + (int64_t)r * dA + c;
+                const unsigned short nv = f32_to_bf16_rne(v);
+                dot = fmaf(to_float(nv), to_float(*p), dot);
+                *p = nv;
+            });
         else
-            run_tile(t_mk, qa_nk, i0, j0, dA, dG, dA, sm, [=](int r, int c, float v) { ((float *)grad)[(int64_t)r * dA + c] = v; });
+            run_tile(t_mk, qa_nk, i0, j0, dA, dG, dA, sm, [&](int r, int c, float v) {
+                float *p = (float *)grad + (int64_t)r * dA + c;
+                dot = fmaf(v, *p, dot);
+                *p = v;
+            });
+        if (dots) {   // fixed-order sum over the workgroup, one double per tile
+            __shared__ double red[NTHREADS];
+            red[threadIdx.x] = (double)dot;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double t = 0.0;
+                for (int i = 0; i < NTHREADS; ++i) t += red[i];
+                dots[L.tile_base + tr.tile] = t;
+            }
+        }
+    }
+}
+
+// nu from the per-tile inner products (layer sums and the sum over layers in fixed order), one thread.
+__global__ void precond_nu_kernel(const LayerDev *layers, int n, const double *dots, float kappa, float lr, float *nu) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    double total = 0.0;
+    for (int l = 0; l < n; ++l) {
+        const int nt = ((layers[l].dG + BM - 1) / BM) * ((layers[l].dA + BM - 1) / BM);
+        double d = 0.0;
+        for (int t = 0; t < nt; ++t) d += dots[layers[l].tile_base + t];
+        total += fabs(d);
+    }
+    double v = 1.0;
+    if (total > 0.0) v = fmin(1.0, sqrt((double)kappa / ((double)lr * lr * total)));
+    *nu = (float)v;
+}
+
+// grad_l <- nu grad_l for every layer (blockIdx.y); nothing to do when nu = 1.
+__global__ __launch_bounds__(256) void precond_scale_kernel(const LayerDev *layers, const float *nu) {
+    const float v = *nu;
+    if (v == 1.f) return;
+    const LayerDev L = layers[blockIdx.y];
+    const int64_t count = (int64_t)L.dG * L.dA;
+    for (int64_t e = blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256) {
+        if (L.grad_bf16) {
+            unsigned short *p = (unsigned short *)L.grad + e;
+            *p = f32_to_bf16_rne(v * to_float(*p));
+        } else {
+            float *p = (float *)L.grad + e;
+            *p = v * *p;
+        }
     }
 }
 
@@ -102,7 +160,7 @@ size_t layout(int n, const kfac_precond_item *it, size_t &off_tiles, size_t &off
         tv += 2 * kfac_align_up((size_t)it[i].dG * it[i].dA, 64);
     }
     off_tiles = kfac_align_up((size_t)n * sizeof(LayerDev), 256);
-    off_tv = off_tiles + kfac_align_up(2 * ntiles * sizeof(TileRef), 256);
+    off_tv = off_tiles + kfac_align_up(2 * ntiles * sizeof(TileRef), 256) + kfac_align_up(ntiles * sizeof(double), 256);
     return off_tv + tv * sizeof(float);
 }
 
@@ -113,17 +171,20 @@ size_t kfac_precond_ws_bytes_impl(int n, const kfac_precond_item *items) {
     return layout(n, items, a, b, c);
 }
 
-int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items) {
+int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items, bool scaled, float kappa, float lr,
+                                     float *nu) {
     size_t off_tiles, off_tv, ntiles;
     const size_t need = layout(n, items, off_tiles, off_tv, ntiles);
     if (need > ctx->ws_bytes) return KFAC_EWORKSPACE;
     std::vector<LayerDev> dev(n);
     float *tv = (float *)(ctx->ws + off_tv);
     double flops = 0.0, bytes = 0.0;
+    int tile_base = 0;
     for (int i = 0; i < n; ++i) {
         const kfac_precond_item &p = items[i];
         const size_t e = kfac_align_up((size_t)p.dG * p.dA, 64);
-        dev[i] = LayerDev{p.QA, p.lamA, p.QG, p.lamG, p.grad, tv, tv + e, p.dA, p.dG, p.damping, p.grad_dtype == KFAC_BF16};
+        dev[i] = LayerDev{p.QA, p.lamA, p.QG, p.lamG, p.grad, tv, tv + e, p.dA, p.dG, p.damping, p.grad_dtype == KFAC_BF16, tile_base};
+        tile_base += ((p.dG + BM - 1) / BM) * ((p.dA + BM - 1) / BM);
         tv += 2 * e;
         flops += 4.0 * p.dA * p.dG * ((double)p.dA + p.dG);
         bytes += 4.0 * ((double)p.dA * p.dA + (double)p.dG * p.dG) * 2 + 4.0 * 8 * p.dA * p.dG;
@@ -140,25 +201,33 @@ int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_it
     std::stable_sort(byA.begin(), byA.end(), [&](const TileRef &a, const TileRef &b) { return items[a.layer].dA > items[b.layer].dA; });
     LayerDev *d_layers = (LayerDev *)ctx->ws;
     TileRef *d_byG = (TileRef *)(ctx->ws + off_tiles), *d_byA = d_byG + ntiles;
+    double *d_dots = scaled ? (double *)(ctx->ws + off_tiles + kfac_align_up(2 * ntiles * sizeof(TileRef), 256)) : nullptr;
     KFAC_HIP_CHECK(hipMemcpyAsync(d_layers, dev.data(), n * sizeof(LayerDev), hipMemcpyHostToDevice, ctx->stream));
     KFAC_HIP_CHECK(hipMemcpyAsync(d_byG, byG.data(), ntiles * sizeof(TileRef), hipMemcpyHostToDevice, ctx->stream));
     KFAC_HIP_CHECK(hipMemcpyAsync(d_byA, byA.data(), ntiles * sizeof(TileRef), hipMemcpyHostToDevice, ctx->stream));
     const dim3 grid((unsigned)ntiles), block(NTHREADS);
     {
         KfacProfScope prof(ctx, KC_PRECOND_GEMM, flops / 4, bytes / 4);
-        hipLaunchKernelGGL(precond_stage_kernel<0>, grid, block, 0, ctx->stream, d_layers, d_byG);
+        hipLaunchKernelGGL(precond_stage_kernel<0>, grid, block, 0, ctx->stream, d_layers, d_byG, (double *)nullptr);
     }
     {
         KfacProfScope prof(ctx, KC_PRECOND_GEMM, flops / 4, bytes / 4);
-        hipLaunchKernelGGL(precond_stage_kernel<1>, grid, block, 0, ctx->stream, d_layers, d_byA);
+        hipLaunchKernelGGL(precond_stage_kernel<1>, grid, block, 0, ctx->stream, d_layers, d_byA, (double *)nullptr);
     }
     {
         KfacProfScope prof(ctx, KC_PRECOND_GEMM, flops / 4, bytes / 4);
-        hipLaunchKernelGGL(precond_stage_kernel<2>, grid, block, 0, ctx->stream, d_layers, d_byG);
+        hipLaunchKernelGGL(precond_stage_kernel<2>, grid, block, 0, ctx->stream, d_layers, d_byG, (double *)nullptr);
     }
     {
         KfacProfScope prof(ctx, KC_PRECOND_GEMM, flops / 4, bytes / 4);
-        hipLaunchKernelGGL(precond_stage_kernel<3>, grid, block, 0, ctx->stream, d_layers, d_byA);
+        hipLaunchKernelGGL(precond_stage_kernel<3>, grid, block, 0, ctx->stream, d_layers, d_byA, d_dots);
+    }
+    if (scaled) {
+        double total = 0.0;
+        for (int i = 0; i < n; ++i) total += (double)items[i].dG * items[i].dA;
+        KfacProfScope prof(ctx, KC_PRECOND_SCALE, 0.0, 8.0 * total);   // read + write of every gradient (when nu < 1)
+        hipLaunchKernelGGL(precond_nu_kernel, dim3(1), dim3(64), 0, ctx->stream, d_layers, n, d_dots, kappa, lr, nu);
+        hipLaunchKernelGGL(precond_scale_kernel, dim3(64, n), dim3(256), 0, ctx->stream, d_layers, nu);
     }
     KFAC_HIP_CHECK(hipGetLastError());
     return KFAC_OK;
@@ -167,5 +236,5 @@ int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_it
 int kfac_launch_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,
                              const float *lamG, int dG, float damping, void *grad, int grad_dtype) {
     kfac_precond_item it{QA, lamA, dA, QG, lamG, dG, damping, grad, grad_dtype};
-    return kfac_launch_precondition_batched(ctx, 1, &it);
+    return kfac_launch_precondition_batched(ctx, 1, &it, false, 0.f, 0.f, nullptr);
 }

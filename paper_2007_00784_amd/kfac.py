@@ -19,7 +19,7 @@ EXPORTS = (
     "kfac_create", "kfac_destroy", "kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
     "kfac_unfold", "kfac_update_factors", "kfac_eig", "kfac_precondition", "kfac_schedule_due",
     "kfac_profile_begin", "kfac_profile_end", "kfac_precondition_batched", "kfac_precondition_workspace_bytes",
-    "kfac_update_factors_batched", "kfac_update_factors_workspace_bytes",
+    "kfac_update_factors_batched", "kfac_update_factors_workspace_bytes", "kfac_precondition_batched_scaled",
 )
 
 
@@ -86,6 +86,7 @@ def lib():
     L.kfac_precondition.argtypes = [vp, vp, vp, i, vp, vp, i, f, vp, i]
     L.kfac_schedule_due.argtypes = [i64, i, i, ip, ip]
     L.kfac_precondition_batched.argtypes = [vp, i, ctypes.POINTER(kfac_precond_item)]
+    L.kfac_precondition_batched_scaled.argtypes = [vp, i, ctypes.POINTER(kfac_precond_item), f, f, vp]
     L.kfac_precondition_workspace_bytes.argtypes = [i, ctypes.POINTER(kfac_precond_item)]
     L.kfac_precondition_workspace_bytes.restype = sz
     L.kfac_update_factors_batched.argtypes = [vp, i, ctypes.POINTER(kfac_factor_item)]
@@ -231,6 +232,14 @@ def kfac_precondition_batched(ctx, QA, lamA, QG, lamG, damping, grad):
     """Lists of per-layer device tensors; every grad[j] is preconditioned in place."""
     arr = _precond_items(QA, lamA, QG, lamG, damping, grad)
     _check(lib().kfac_precondition_batched(ctx, len(grad), arr), "kfac_precondition_batched")
+
+
+def kfac_precondition_batched_scaled(ctx, QA, lamA, QG, lamG, damping, grad, kappa, lr, nu):
+    """As kfac_precondition_batched, then every gradient is multiplied by the nu of Sec. V-B; nu: device tensor
+    of one float32, written by the call."""
+    arr = _precond_items(QA, lamA, QG, lamG, damping, grad)
+    _check(lib().kfac_precondition_batched_scaled(ctx, len(grad), arr, float(kappa), float(lr), _ptr(nu)),
+           "kfac_precondition_batched_scaled")
 
 
 def kfac_precondition_workspace_bytes(dims):

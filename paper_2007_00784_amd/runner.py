@@ -108,10 +108,16 @@ class KfacRunner:
         self.eig_info = K.kfac_eig(self.ctx, self.A + self.G, self.QA + self.QG, self.lamA + self.lamG, **kw)
         return self.eig_info
 
-    def precondition(self, damping=None):
+    def precondition(self, damping=None, kappa=None, lr=None):
+        """In-place preconditioning of a fresh copy of the gradients; with kappa and lr also the gradient
+        scaling nu (left in self.nu, a device tensor)."""
         gamma = self.wl.damping if damping is None else damping
         self.grad_flat.copy_(self.gradw_master_flat)
-        K.kfac_precondition_batched(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad)
+        if kappa is None:
+            K.kfac_precondition_batched(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad)
+        else:
+            self.nu = torch.zeros(1, dtype=torch.float32, device=self.dev)
+            K.kfac_precondition_batched_scaled(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad, kappa, lr, self.nu)
 
     # ---- algorithmic work of one step (flops, bytes) ----
     def work(self):

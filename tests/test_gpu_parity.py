@@ -246,6 +246,57 @@ def test_precondition_matches_oracle(ctx, dA, dG, bf16):
     assert relfro(got, ref) <= (TOL_BF16 if bf16 else TOL_F32)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_precondition_batched_with_gradient_scaling(ctx, bf16):
+    """Sec. V-B: the batched preconditioner followed by nu = min(1, sqrt(kappa / (lr^2 sum_l |<P_l, g_l>|))).
+    Three layers of different tile counts (one tile, ragged tiles, several tiles) in one call, against the oracle
+    end to end, against the oracle's nu on the library's own unscaled output, and with a kappa that does not clip."""
+    rng = np.random.default_rng(11)
+    dims = [(65, 16), (300, 130), (145, 257)]
+    QAs, lAs, QGs, lGs, grads, refs = [], [], [], [], [], []
+    gamma = None
+    for dA, dG in dims:
+        A = gram_factor(dA, 3 * dA, seed=dA).astype(np.float64)
+        G = oracle.gram(rng.standard_normal((3 * dG, dG)), 0, 1.0 / (3 * dG))
+        lamA, QA = oracle.eigh(A)
+        lamG, QG = oracle.eigh(G)
+        gamma = 1e-2
+        grad = (rng.standard_normal((dG, dA)) * 1e-2).astype(np.float32)
+        if bf16:
+            grad = S.bf16_bits_to_f32(S.to_bf16_bits(grad)).reshape(grad.shape)
+        refs.append(oracle.precondition(QA, lamA, QG, lamG, gamma, grad))
+        QAs.append(ctx.to_dev(QA.astype(np.float32))); lAs.append(ctx.to_dev(lamA.astype(np.float32)))
+        QGs.append(ctx.to_dev(QG.astype(np.float32))); lGs.append(ctx.to_dev(lamG.astype(np.float32)))
+        grads.append(grad)
+    tol = TOL_BF16 if bf16 else TOL_F32
+    # unscaled output of the library, for the same inputs
+    plain = [ctx.to_dev(g, bf16) for g in grads]
+    K.kfac_precondition_batched(ctx.h, QAs, lAs, QGs, lGs, gamma, plain)
+    torch.cuda.synchronize()
+    plain = [p.float().cpu().numpy().astype(np.float64) for p in plain]
+    lr = 0.1
+    s_sum = sum(abs(float((p * g).sum())) for p, g in zip(plain, grads))
+    for kappa, clipped in [(1e-3 * lr * lr * s_sum, True), (10.0 * lr * lr * s_sum, False)]:
+        gd = [ctx.to_dev(g, bf16) for g in grads]
+        nu_d = torch.full((1,), float("nan"), dtype=torch.float32, device=ctx.dev)
+        K.kfac_precondition_batched_scaled(ctx.h, QAs, lAs, QGs, lGs, gamma, gd, kappa, lr, nu_d)
+        torch.cuda.synchronize()
+        nu = float(nu_d.item())
+        nu_own = oracle.grad_scale(plain, grads, kappa, lr)          # oracle formula on the library's own P_l
+        nu_ref = oracle.grad_scale(refs, grads, kappa, lr)           # oracle end to end
+        assert (nu < 1.0) == clipped
+        assert abs(nu - nu_own) <= 2e-6 * nu_own
+        assert abs(nu - nu_ref) <= tol * nu_ref
+        if clipped:
+            assert nu == pytest.approx(np.sqrt(1e-3), rel=1e-5)
+        for j in range(len(dims)):
+            got = gd[j].float().cpu().numpy()
+            assert relfro(got, nu_ref * refs[j]) <= tol
+            assert relfro(got, nu * plain[j]) <= (4e-3 if bf16 else 1e-6)   # bf16: one more rounding of the product
+    with pytest.raises(K.KfacError):
+        K.kfac_precondition_batched_scaled(ctx.h, QAs, lAs, QGs, lGs, gamma, gd, 0.0, lr, nu_d)
+
+
 # ------------------------------------------------------------------ whole path, config 1
 def test_single_conv_layer_end_to_end(ctx):
     """3x3 conv 16->16 on 8x8, batch 32: three factor updates, eig, precondition, against the oracle and
