@@ -140,11 +140,15 @@ class Layer:
         return not (self.k == 1 and self.stride == 1 and self.pad == 0)
 
 
-def resnet50_layers():
-    """53 convs + FC of ResNet-50 on 224x224 inputs; stride of a down-sampling block on its 3x3."""
+BOTTLENECK_BLOCKS = {50: (3, 4, 6, 3), 101: (3, 4, 23, 3), 152: (3, 8, 36, 3)}
+
+
+def resnet50_layers(depth=50):
+    """Convs + FC of a bottleneck ResNet (depth 50: 53 convs; 101: 104; 152: 155) on 224x224 inputs; stride of
+    a down-sampling block on its 3x3."""
     L = [Layer("stem", 3, 64, 7, 2, 3, 224)]
     h, c_prev = 56, 64
-    for si, (width, blocks) in enumerate([(64, 3), (128, 4), (256, 6), (512, 3)]):
+    for si, (width, blocks) in enumerate(zip((64, 128, 256, 512), BOTTLENECK_BLOCKS[depth])):
         c_out = 4 * width
         for b in range(blocks):
             s = 2 if (b == 0 and si > 0) else 1
@@ -195,7 +199,7 @@ class Workload:
 
 
 def workload(name):
-    """The five benchmark configurations (shapes and distributions only)."""
+    """The five benchmark configurations and two deeper layer sets (shapes and distributions only)."""
     if name == "single_conv":
         return Workload(1, name, (Layer("conv", 16, 16, 3, 1, 1, 8),), 32, 1e-3, 1e-3)
     if name == "resnet32_cifar":
@@ -206,6 +210,11 @@ def workload(name):
         return Workload(4, name, (Layer("l4conv3", 512, 512, 3, 1, 1, 7),), 64, 1e-4, 1e-3, ill_conditioned=True)
     if name == "resnet50_bf16":
         return Workload(5, name, tuple(resnet50_layers()), 64, 1e-4, 1e-3, seed=1, bf16=True)
+    # the deeper models of the paper's scaling study (Sec. VI-C, Table V): same layer shapes, more of them
+    if name == "resnet101":
+        return Workload(6, name, tuple(resnet50_layers(101)), 32, 1e-4, 1e-3)
+    if name == "resnet152":
+        return Workload(7, name, tuple(resnet50_layers(152)), 32, 1e-4, 1e-3)
     raise KeyError(name)
 
 

@@ -308,3 +308,36 @@ def test_config5_bf16_schedule():
                 assert relfro(f64(run.grad[jj]), want) <= TOL_BF16, (k, l.name)
     assert counts == dict(f=3, e=1, p=21)
     run.close()
+
+
+@pytest.mark.timeout(900)
+def test_resnet101_step_properties():
+    """The deeper layer set of the paper's scaling study (Sec. VI-C, Table V: ResNet-101; 105 layers, 210
+    factors, one group of 23 factors of 2305 and 66 of 1024/1025): one whole step through properties -- every
+    factor symmetric with unit bias corner, every eigendecomposition converged, eigenpairs of one factor per
+    size class by residual and orthogonality, and the defining equation of the preconditioned gradient on
+    every seventh layer; one mid-network layer's factors against the oracle."""
+    wl = S.workload("resnet101")
+    run = KfacRunner(wl, n_updates=1)
+    run.update_factors(0, 0.0)
+    info = run.eig()
+    run.precondition()
+    torch.cuda.synchronize()
+    assert len(run.layers) == 105 and len(info) == 210
+    assert all(c for (_, _, c) in info), [x for x in info if not x[2]]
+    seen = set()
+    for i, l in enumerate(run.layers):
+        A = run.A[i]
+        assert torch.equal(A, A.T) and torch.equal(run.G[i], run.G[i].T)
+        assert abs(float(A[-1, -1]) - 1.0) < 1e-5
+        if i % 7 == 0:
+            assert precondition_equation_residual(run, i, wl.damping) <= TOL_F32, l.name
+        for F, lam, Q, d, tag in ((run.A[i], run.lamA[i], run.QA[i], l.d_a, "A"), (run.G[i], run.lamG[i], run.QG[i], l.d_g, "G")):
+            if d in seen or d > 2400:        # the 4609 class is covered by the ResNet-50 and config-4 tests
+                continue
+            seen.add(d)
+            eig_properties(F, lam, Q, "%s.%s" % (l.name, tag))
+    i = [k for k, l in enumerate(run.layers) if l.name == "s3b11.reduce"][0]
+    A, G = oracle_factors(run, i, 1)
+    assert relfro(f64(run.A[i]), A) <= TOL_F32 and relfro(f64(run.G[i]), G) <= TOL_F32
+    run.close()

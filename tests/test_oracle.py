@@ -490,3 +490,19 @@ def test_grad_scale_bounds_the_step():
         assert alpha ** 2 * nu ** 2 * s <= kappa * (1 + 1e-12)
         if nu < 1:
             assert alpha ** 2 * nu ** 2 * s == pytest.approx(kappa, rel=1e-12)
+
+
+# ------------------------------------------------------------------ layer tables
+def test_bottleneck_resnet_layer_tables():
+    """The synthetic layer sets against the published architectures: conv + FC weight counts of ResNet-50/101/152
+    (25.6 M / 44.5 M / 60.2 M parameters including ~0.05-0.15 M of batch-norm parameters, which carry no K-FAC
+    factors), the block counts of Sec. VI-C's models, and the factor dimensions BASELINE names."""
+    from paper_2007_00784_amd import synthetic as S
+    for name, nl, mparams in (("resnet50", 54, 25.5), ("resnet101", 105, 44.4), ("resnet152", 156, 60.0)):
+        L = S.workload(name).layers
+        assert len(L) == nl
+        weights = sum(l.c_in * l.c_out * l.k * l.k for l in L) + L[-1].c_out
+        assert abs(weights / 1e6 - mparams) < 0.1, (name, weights)
+        assert max(l.d_a for l in L) == 4609 and max(l.d_g for l in L) == 2048
+        assert L[0].d_a == 148 and L[-1].d_a == 2049 and L[-1].d_g == 1000
+        assert sum(1 for l in L if l.k == 3) == {54: 16, 105: 33, 156: 50}[nl]
