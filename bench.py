@@ -180,6 +180,19 @@ def main():
     sweeps = [s for (s, _, _) in info]
     nconv = sum(1 for (_, _, c) in info if c)
 
+    # what a training loop would do from its second decomposition on: start from the previous eigenvectors
+    # (two more steps, each folding another batch into the factors; not part of `value`)
+    warm_ms = []
+    for upd in (0, 1):
+        run.update_factors(upd, wl.decay)
+        e0, e1 = ev(), ev()
+        e0.record()
+        run.eig(raise_on_noconv=False, warm_start=True)
+        e1.record()
+        torch.cuda.synchronize()
+        warm_ms.append(e0.elapsed_time(e1))
+    warm_sweeps = max(s for (s, _, _) in run.eig_info)
+
     # one more, instrumented step: every kernel launch bracketed by hipEvents on the library's stream
     K.kfac_profile_begin(run.ctx)
     step()
@@ -212,6 +225,7 @@ def main():
         "precondition_frac_of_mfma_peak": round(w["precond_flops"] / (phases["precondition"] * 1e-3) / PEAK_MFMA_F32, 4),
         "eig_sum_d3_per_s": round(w["sum_d3"] / (phases["eig"] * 1e-3), 1),
         "eig_sweeps_max": max(sweeps), "eig_converged": "%d/%d" % (nconv, len(info)),
+        "eig_warm_start_ms": round(min(warm_ms), 3), "eig_warm_start_sweeps_max": warm_sweeps,
     }
     out = {
         "metric": "kfac_step_ms", "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1,

@@ -67,6 +67,11 @@ typedef struct {
                                 accumulation): same tolerances met, errors bounded normwise (relative to
                                 ||F||_F).  1: every product on the fp32 MFMA path: slower, keeps fp32's
                                 elementwise accuracy on strongly graded spectra.                   */
+    int warm_start;          /* 1: on entry every Q_i with d_i > 128 holds an orthonormal basis to start from
+                                (typically the eigenvectors of the previous decomposition of a slowly moving
+                                factor, Sec. V-B); the iteration then runs on Q_i^T F_i Q_i, which is close to
+                                diagonal, and needs fewer sweeps.  Costs 4 d^3 flops per factor up front; a basis
+                                that is not orthonormal to fp32 rounding gives wrong results.  0: start from I.   */
 } kfac_eig_opts;
 
 typedef struct {             /* host memory, filled when kfac_eig() returns       */

@@ -412,15 +412,29 @@ __device__ inline void sched_pair(const BlkGroup &g, int round, int j, int &p, i
 }
 struct BlkItem { const float *F; float *Q; float *lam; int n; int pad_; };
 
-__global__ void blk_init_kernel(BlkGroup g, const BlkItem *items) {
+// W <- F (zero padded), accumulator <- I, or with `warm` <- the basis the caller left in Q (identity on the padding).
+__global__ void blk_init_kernel(BlkGroup g, const BlkItem *items, int warm) {
     const int m = blockIdx.y;
     const BlkItem it = items[m];
     const int64_t np2 = (int64_t)g.npad * g.npad;
     float *W = g.W + m * np2, *Qw = g.Qw + m * np2;
     for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < np2; e += (int64_t)gridDim.x * blockDim.x) {
         const int i = (int)(e / g.npad), j = (int)(e - (int64_t)i * g.npad);
-        W[e] = (i < it.n && j < it.n) ? it.F[(int64_t)i * it.n + j] : 0.f;
-        Qw[e] = (i == j) ? 1.f : 0.f;
+        const bool in = i < it.n && j < it.n;
+        W[e] = in ? it.F[(int64_t)i * it.n + j] : 0.f;
+        Qw[e] = (warm && in) ? it.Q[(int64_t)i * it.n + j] : ((i == j) ? 1.f : 0.f);
+    }
+}
+
+// W <- (W + W^T) / 2 on the leading n x n part (a warm start's Q^T F Q is symmetric only up to rounding).
+__global__ __launch_bounds__(NT) void blk_symmetrise_kernel(float *W, int64_t ld, int n) {
+    const int64_t n2 = (int64_t)n * n;
+    for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < n2; e += (int64_t)gridDim.x * NT) {
+        const int i = (int)(e / n), j = (int)(e - (int64_t)i * n);
+        if (j >= i) continue;
+        const float v = 0.5f * (W[(int64_t)i * ld + j] + W[(int64_t)j * ld + i]);
+        W[(int64_t)i * ld + j] = v;
+        W[(int64_t)j * ld + i] = v;
     }
 }
 
@@ -1223,6 +1237,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     for (auto &gp : groups) pinned_need += 2 * gp.members.size() * sizeof(double);
     if (pinned_need > ctx->pinned_bytes) return KFAC_EWORKSPACE;
     const bool fp32_outer = opts && opts->fp32_only != 0;
+    const bool warm = opts && opts->warm_start != 0;
     const int inner_cap = 1;       // one Jacobi sweep over a pivot per visit: fewest total rotations
     const float inner_tol = 1e-7f;
     const size_t lds_solve = JacobiSmem::bytes(KP, PLD);
@@ -1379,9 +1394,37 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         KFAC_HIP_CHECK(hipMemcpyAsync(r.d_items, r.items.data(), nm * sizeof(BlkItem), hipMemcpyHostToDevice, r.st));
         {
             KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
-            hipLaunchKernelGGL(blk_init_kernel, dim3(r.fill_blocks, nm), dim3(NT), 0, r.st, g, r.d_items);
+            hipLaunchKernelGGL(blk_init_kernel, dim3(r.fill_blocks, nm), dim3(NT), 0, r.st, g, r.d_items, warm ? 1 : 0);
         }
         KFAC_HIP_CHECK(hipGetLastError());
+        if (warm) {
+            // W <- Q0^T F Q0 for the start basis Q0 now in the accumulator; the caller's Q buffer (to be overwritten
+            // anyway) holds the intermediate F Q0
+            using namespace kfac;
+            for (int i = 0; i < nm; ++i) {
+                const int n = r.items[i].n;
+                float *Wm = g.W + i * np2, *Qm = g.Qw + i * np2;
+                const int64_t ld = gp.npad;
+                const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
+                OpStrided<float, true> f_mk{r.items[i].F, n, 1, n, n, -1};
+                OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};                  // elem(c,k) = Q0[k][c]
+                {
+                    KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, r.st);
+                    hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(q_kn), EpiStore>), grid, block, 0, r.st,
+                                       f_mk, q_kn, EpiStore{r.items[i].Q, n}, n, n, n);
+                }
+                OpStrided<float, false> qt_mk{Qm, 1, ld, n, n, -1};                 // elem(r,k) = Q0[k][r]
+                OpStrided<float, false> t_kn{r.items[i].Q, 1, n, n, n, -1};         // elem(c,k) = (F Q0)[k][c]
+                {
+                    KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, r.st);
+                    hipLaunchKernelGGL((gemm_generic_kernel<decltype(qt_mk), decltype(t_kn), EpiStore>), grid, block, 0, r.st,
+                                       qt_mk, t_kn, EpiStore{Wm, ld}, n, n, n);
+                }
+                KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
+                hipLaunchKernelGGL(blk_symmetrise_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, r.st, Wm, ld, n);
+            }
+            KFAC_HIP_CHECK(hipGetLastError());
+        }
         int rc = enqueue_offnorm(ctx, r);
         if (rc) return rc;
         r.x3 = gp.two_level && !fp32_outer;

@@ -29,7 +29,8 @@ class kfac_conv_desc(ctypes.Structure):
 
 
 class kfac_eig_opts(ctypes.Structure):
-    _fields_ = [("max_sweeps", ctypes.c_int), ("tol", ctypes.c_float), ("fp32_only", ctypes.c_int)]
+    _fields_ = [("max_sweeps", ctypes.c_int), ("tol", ctypes.c_float), ("fp32_only", ctypes.c_int),
+                ("warm_start", ctypes.c_int)]
 
 
 class kfac_eig_info(ctypes.Structure):
@@ -193,7 +194,7 @@ def kfac_update_factors_workspace_bytes(items):
     return int(lib().kfac_update_factors_workspace_bytes(len(items), _factor_items(items)))
 
 
-def kfac_eig(ctx, F, Q, lam, max_sweeps=0, tol=0.0, raise_on_noconv=True, fp32_only=False):
+def kfac_eig(ctx, F, Q, lam, max_sweeps=0, tol=0.0, raise_on_noconv=True, fp32_only=False, warm_start=False):
     """F, Q, lam: lists of device tensors.  Returns a list of (sweeps, off_norm_rel, converged)."""
     n = len(F)
     vp = ctypes.c_void_p
@@ -201,7 +202,7 @@ def kfac_eig(ctx, F, Q, lam, max_sweeps=0, tol=0.0, raise_on_noconv=True, fp32_o
     Qa = (vp * n)(*[_ptr(t) for t in Q])
     La = (vp * n)(*[_ptr(t) for t in lam])
     dims = (ctypes.c_int * n)(*[int(t.shape[0]) for t in F])
-    opts = kfac_eig_opts(int(max_sweeps), float(tol), int(bool(fp32_only)))
+    opts = kfac_eig_opts(int(max_sweeps), float(tol), int(bool(fp32_only)), int(bool(warm_start)))
     info = (kfac_eig_info * n)()
     rc = lib().kfac_eig(ctx, n, Fa, dims, Qa, La, ctypes.byref(opts), info)
     _check(rc, "kfac_eig", allow=() if raise_on_noconv else (KFAC_ENOCONV,))

@@ -211,6 +211,36 @@ def test_eig_known_spectrum_and_diagonal(ctx):
     assert info[1][0] == 0
 
 
+def test_eig_warm_start(ctx):
+    """A slowly moving factor (running average with 5 % of a new batch, Sec. IV-B) decomposed again from the
+    previous eigenvectors: the same invariants hold, in fewer sweeps than from the identity; a flat-path
+    factor and a two-level one, plus a small one (which ignores the option) in the same batch.  Starting from
+    the exact eigenvectors of the same matrix converges at once."""
+    sizes = [(577, 1500), (2100, 3000), (65, 200)]
+    F0 = [gram_factor(n, r, seed=40 + i) for i, (n, r) in enumerate(sizes)]
+    F1 = [(0.95 * a.astype(np.float64) + 0.05 * gram_factor(n, r, seed=50 + i)).astype(np.float32)
+          for i, (a, (n, r)) in enumerate(zip(F0, sizes))]
+    Fd0 = [ctx.to_dev(f) for f in F0]
+    Fd1 = [ctx.to_dev(f) for f in F1]
+    Q = [torch.zeros_like(f) for f in Fd0]
+    lam = [torch.zeros(f.shape[0], dtype=torch.float32, device=ctx.dev) for f in Fd0]
+    info0 = K.kfac_eig(ctx.h, Fd0, Q, lam)
+    again = K.kfac_eig(ctx.h, Fd0, Q, lam, warm_start=True)          # Q holds the eigenvectors of the same matrices
+    torch.cuda.synchronize()
+    assert all(c for (_, _, c) in again) and again[0][0] <= 1 and again[1][0] <= 1, again
+    for i, F in enumerate(F0):
+        check_eigpairs(F, lam[i].cpu().numpy(), Q[i].cpu().numpy(), "warm-same[%d]" % i)
+    warm = K.kfac_eig(ctx.h, Fd1, Q, lam, warm_start=True)
+    torch.cuda.synchronize()
+    for i, F in enumerate(F1):
+        check_eigpairs(F, lam[i].cpu().numpy(), Q[i].cpu().numpy(), "warm[%d]" % i)
+    cold = K.kfac_eig(ctx.h, Fd1, Q, lam)
+    torch.cuda.synchronize()
+    print("sweeps cold", [x[0] for x in cold], "warm", [x[0] for x in warm], "first", [x[0] for x in info0])
+    assert all(c for (_, _, c) in warm) and all(c for (_, _, c) in cold)
+    assert warm[0][0] < cold[0][0] and warm[1][0] < cold[1][0]
+
+
 def test_eig_max_sweeps_reports_noconv(ctx):
     F = gram_factor(300, 500, seed=7)
     with pytest.raises(K.KfacError) as e:
