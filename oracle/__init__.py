@@ -21,4 +21,5 @@ from .kfac_oracle import (  # noqa: F401
     spd_solve,
     schedule,
     grad_scale,
+    precondition_inverse,
 )

@@ -545,3 +545,38 @@ double oracle_grad_scale(int nlayers, const int64_t *sizes, const double *precon
     const double nu = sqrt(kappa / (alpha * alpha * total));
     return nu < 1.0 ? nu : 1.0;
 }
+
+/* ------------------------------------------------------------------------
+ * The explicit-inverse method (Sec. II-C, Eq. (kfac-damped) and the update step below it): the damping
+ * is added to each Kronecker factor and the step is
+ *     out = (G + gamma I)^{-1} grad (A + gamma I)^{-1}
+ * Computed here with no eigendecomposition at all: two Cholesky solves.  grad, out: dG x dA row-major.
+ * Returns 0, or -1 if a damped factor is not positive definite.
+ * ---------------------------------------------------------------------- */
+int oracle_precondition_inverse(const double *G, int dG, const double *A, int dA, double gamma,
+                                const double *grad, double *out)
+{
+    int rc = -1;
+    double *Gd = (double *)malloc(sizeof(double) * (size_t)dG * dG);
+    double *Ad = (double *)malloc(sizeof(double) * (size_t)dA * dA);
+    double *Y = (double *)malloc(sizeof(double) * (size_t)dG * dA);    /* (G + gamma I)^{-1} grad          */
+    double *Yt = (double *)malloc(sizeof(double) * (size_t)dG * dA);   /* its transpose, dA x dG            */
+    double *Zt = (double *)malloc(sizeof(double) * (size_t)dG * dA);   /* (A + gamma I)^{-1} Y^T = out^T    */
+    if (Gd && Ad && Y && Yt && Zt) {
+        for (int64_t i = 0; i < (int64_t)dG * dG; ++i) Gd[i] = G[i];
+        for (int i = 0; i < dG; ++i) Gd[(int64_t)i * dG + i] += gamma;
+        for (int64_t i = 0; i < (int64_t)dA * dA; ++i) Ad[i] = A[i];
+        for (int i = 0; i < dA; ++i) Ad[(int64_t)i * dA + i] += gamma;
+        if (oracle_spd_solve(Gd, dG, grad, dA, Y) == 0) {
+            for (int i = 0; i < dG; ++i)
+                for (int j = 0; j < dA; ++j) Yt[(int64_t)j * dG + i] = Y[(int64_t)i * dA + j];
+            if (oracle_spd_solve(Ad, dA, Yt, dG, Zt) == 0) {      /* A symmetric: Y A^{-1} = (A^{-1} Y^T)^T */
+                for (int i = 0; i < dG; ++i)
+                    for (int j = 0; j < dA; ++j) out[(int64_t)i * dA + j] = Zt[(int64_t)j * dG + i];
+                rc = 0;
+            }
+        }
+    }
+    free(Gd); free(Ad); free(Y); free(Yt); free(Zt);
+    return rc;
+}

@@ -54,6 +54,7 @@ def _load():
     lib.oracle_spd_solve.argtypes = [_dp, _i, _dp, _i, _dp]
     lib.oracle_spd_solve.restype = _i
     lib.oracle_schedule.argtypes = [_i64, _i, _i, ctypes.POINTER(_i), ctypes.POINTER(_i)]
+    lib.oracle_precondition_inverse.argtypes = [_dp, _i, _dp, _i, _d, _dp, _dp]
     lib.oracle_grad_scale.argtypes = [_i, ctypes.POINTER(_i64), _dp, _dp, _d, _d]
     lib.oracle_grad_scale.restype = _d
     _lib = lib
@@ -180,6 +181,18 @@ def spd_solve(A, B):
     if rc < 0:
         raise RuntimeError("matrix not positive definite")
     return X
+
+
+def precondition_inverse(G, A, gamma, grad):
+    """(G + gamma I)^-1 grad (A + gamma I)^-1 by Cholesky solves (the explicit-inverse method of Sec. II-C)."""
+    G, A, grad = _c(G), _c(A), _c(grad)
+    dG, dA = G.shape[0], A.shape[0]
+    assert grad.shape == (dG, dA)
+    out = np.empty((dG, dA))
+    rc = _load().oracle_precondition_inverse(_p(G), dG, _p(A), dA, float(gamma), _p(grad), _p(out))
+    if rc < 0:
+        raise RuntimeError("damped factor not positive definite")
+    return out
 
 
 def grad_scale(precond, grad, kappa, alpha):

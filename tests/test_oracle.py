@@ -506,3 +506,36 @@ def test_bottleneck_resnet_layer_tables():
         assert max(l.d_a for l in L) == 4609 and max(l.d_g for l in L) == 2048
         assert L[0].d_a == 148 and L[-1].d_a == 2049 and L[-1].d_g == 1000
         assert sum(1 for l in L if l.k == 3) == {54: 16, 105: 33, 156: 50}[nl]
+
+
+# ------------------------------------------------------------------ explicit-inverse method
+def test_precondition_inverse_pins():
+    """Sec. II-C, Eq. (kfac-damped): out = (G + gamma I)^-1 grad (A + gamma I)^-1.
+
+    Diagonal factors give out_ij = grad_ij / ((g_i + gamma)(a_j + gamma)) by hand; dense factors against
+    numpy's inverse; the defining equation (G + gamma I) out (A + gamma I) = grad; and the relation to the
+    eigenbasis form with the FACTORED denominator (lam_G + gamma)(lam_A + gamma)^T, which differs from the
+    hot path's lam_G lam_A^T + gamma by the cross terms gamma (lam_G + lam_A) + gamma^2 - gamma."""
+    rng = np.random.default_rng(3)
+    g, a, gamma = np.array([1.0, 4.0]), np.array([2.0, 0.5, 3.0]), 0.25
+    grad = rng.standard_normal((2, 3))
+    out = oracle.precondition_inverse(np.diag(g), np.diag(a), gamma, grad)
+    assert np.allclose(out, grad / np.outer(g + gamma, a + gamma), rtol=1e-14)
+    dG, dA = 7, 11
+    X, Y = rng.standard_normal((30, dG)), rng.standard_normal((40, dA))
+    G, A = oracle.gram(X, 0, 1 / 30), oracle.gram(Y, 0, 1 / 40)
+    grad = rng.standard_normal((dG, dA))
+    out = oracle.precondition_inverse(G, A, gamma, grad)
+    ref = np.linalg.inv(G + gamma * np.eye(dG)) @ grad @ np.linalg.inv(A + gamma * np.eye(dA))
+    assert relfro(out, ref) < 1e-12
+    assert relfro((G + gamma * np.eye(dG)) @ out @ (A + gamma * np.eye(dA)), grad) < 1e-12
+    lamA, QA = oracle.eigh(A)
+    lamG, QG = oracle.eigh(G)
+    fact = QG @ ((QG.T @ grad @ QA) / np.outer(lamG + gamma, lamA + gamma)) @ QA.T
+    assert relfro(out, fact) < 1e-10
+    kron = oracle.precondition(QA, lamA, QG, lamG, gamma, grad)          # the hot path's exact Tikhonov damping
+    assert relfro(out, kron) > 1e-2                                        # a different method, not a rewrite
+    # rank-deficient factor: still defined for gamma > 0
+    Gr = oracle.gram(rng.standard_normal((3, dG)), 0, 1 / 3)
+    o2 = oracle.precondition_inverse(Gr, A, gamma, grad)
+    assert relfro((Gr + gamma * np.eye(dG)) @ o2 @ (A + gamma * np.eye(dA)), grad) < 1e-11
