@@ -161,6 +161,10 @@ typedef struct {
     float damping;
     void *grad;
     int grad_dtype;
+    int factored_damping;    /* 0: the step of Eqs. (v1), (v2), (kfac-eigen): divide by lamG lamA^T + damping (exact
+                                Tikhonov damping of the Kronecker product).  1: the explicit-inverse method of
+                                Sec. II-C, Eq. (kfac-damped): (G + damping I)^-1 grad (A + damping I)^-1, computed in
+                                the eigenbasis as a division by (lamG + damping)(lamA + damping)^T              */
 } kfac_precond_item;
 int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items /* host */);
 size_t kfac_precondition_workspace_bytes(int n, const kfac_precond_item *items /* host; only dA, dG are read */);

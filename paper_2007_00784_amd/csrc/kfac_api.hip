@@ -226,7 +226,7 @@ int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out, int max, int *n) {
 static bool valid_precond_item(const kfac_precond_item &p) {
     if (!p.QA || !p.lamA || !p.QG || !p.lamG || !p.grad) return false;
     if (p.dA < 1 || p.dG < 1 || p.dA > KFAC_MAX_D || p.dG > KFAC_MAX_D) return false;
-    return p.damping > 0.f && std::isfinite(p.damping) && valid_dtype(p.grad_dtype);
+    return p.damping > 0.f && std::isfinite(p.damping) && valid_dtype(p.grad_dtype) && (p.factored_damping == 0 || p.factored_damping == 1);
 }
 
 int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items) {

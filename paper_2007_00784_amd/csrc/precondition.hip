@@ -29,6 +29,7 @@ struct LayerDev {
     float damping;
     int grad_bf16;
     int tile_base;     // index of this layer's first tile in the per-tile inner-product array
+    int factored;      // denominator (lamG + damping)(lamA + damping) instead of lamG lamA + damping
 };
 struct TileRef { int layer, tile; };   // tile = ti * tiles_n + tj
 
@@ -77,9 +78,10 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
         float *V = L.V;
         const float *lamG = L.lamG, *lamA = L.lamA;
         const float damping = L.damping;
+        const bool factored = L.factored != 0;
         run_tile(t_mk, qa_kn, i0, j0, dA, dG, dA, sm, [=](int r, int c, float v) {
             const float lg = fmaxf(lamG[r], 0.f), la = fmaxf(lamA[c], 0.f);
-            V[(int64_t)r * dA + c] = v / (lg * la + damping);
+            V[(int64_t)r * dA + c] = v / (factored ? (lg + damping) * (la + damping) : lg * la + damping);
         });
     } else if (STAGE == 2) {
         // T = QG V : A(m,k) = QG[m][k] (k contiguous), B(k,n) = V[k][n]
@@ -183,7 +185,7 @@ int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_it
     for (int i = 0; i < n; ++i) {
         const kfac_precond_item &p = items[i];
         const size_t e = kfac_align_up((size_t)p.dG * p.dA, 64);
-        dev[i] = LayerDev{p.QA, p.lamA, p.QG, p.lamG, p.grad, tv, tv + e, p.dA, p.dG, p.damping, p.grad_dtype == KFAC_BF16, tile_base};
+        dev[i] = LayerDev{p.QA, p.lamA, p.QG, p.lamG, p.grad, tv, tv + e, p.dA, p.dG, p.damping, p.grad_dtype == KFAC_BF16, tile_base, p.factored_damping};
         tile_base += ((p.dG + BM - 1) / BM) * ((p.dA + BM - 1) / BM);
         tv += 2 * e;
         flops += 4.0 * p.dA * p.dG * ((double)p.dA + p.dG);
@@ -235,6 +237,6 @@ int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_it
 
 int kfac_launch_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,
                              const float *lamG, int dG, float damping, void *grad, int grad_dtype) {
-    kfac_precond_item it{QA, lamA, dA, QG, lamG, dG, damping, grad, grad_dtype};
+    kfac_precond_item it{QA, lamA, dA, QG, lamG, dG, damping, grad, grad_dtype, 0};
     return kfac_launch_precondition_batched(ctx, 1, &it, false, 0.f, 0.f, nullptr);
 }

@@ -45,7 +45,8 @@ class kfac_kernel_stat(ctypes.Structure):
 class kfac_precond_item(ctypes.Structure):
     _fields_ = [("QA", ctypes.c_void_p), ("lamA", ctypes.c_void_p), ("dA", ctypes.c_int),
                 ("QG", ctypes.c_void_p), ("lamG", ctypes.c_void_p), ("dG", ctypes.c_int),
-                ("damping", ctypes.c_float), ("grad", ctypes.c_void_p), ("grad_dtype", ctypes.c_int)]
+                ("damping", ctypes.c_float), ("grad", ctypes.c_void_p), ("grad_dtype", ctypes.c_int),
+                ("factored_damping", ctypes.c_int)]
 
 
 class kfac_factor_item(ctypes.Structure):
@@ -217,7 +218,7 @@ def kfac_precondition(ctx, QA, lamA, QG, lamG, damping, grad):
                                    _ptr(grad), _dtype_code(grad)), "kfac_precondition")
 
 
-def _precond_items(QA, lamA, QG, lamG, damping, grad):
+def _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping=False):
     n = len(grad)
     arr = (kfac_precond_item * n)()
     for j in range(n):
@@ -225,13 +226,14 @@ def _precond_items(QA, lamA, QG, lamG, damping, grad):
         if tuple(grad[j].shape) != (dG, dA):
             raise ValueError("grad[%d] must be [dG, dA]" % j)
         arr[j] = kfac_precond_item(_ptr(QA[j]), _ptr(lamA[j]), dA, _ptr(QG[j]), _ptr(lamG[j]), dG, float(damping),
-                                   _ptr(grad[j]), _dtype_code(grad[j]))
+                                   _ptr(grad[j]), _dtype_code(grad[j]), int(bool(factored_damping)))
     return arr
 
 
-def kfac_precondition_batched(ctx, QA, lamA, QG, lamG, damping, grad):
-    """Lists of per-layer device tensors; every grad[j] is preconditioned in place."""
-    arr = _precond_items(QA, lamA, QG, lamG, damping, grad)
+def kfac_precondition_batched(ctx, QA, lamA, QG, lamG, damping, grad, factored_damping=False):
+    """Lists of per-layer device tensors; every grad[j] is preconditioned in place.  factored_damping: the
+    explicit-inverse method (G + damping I)^-1 grad (A + damping I)^-1 instead of the eigenbasis step."""
+    arr = _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping)
     _check(lib().kfac_precondition_batched(ctx, len(grad), arr), "kfac_precondition_batched")
 
 

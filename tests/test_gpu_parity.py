@@ -327,6 +327,40 @@ def test_precondition_batched_with_gradient_scaling(ctx, bf16):
         K.kfac_precondition_batched_scaled(ctx.h, QAs, lAs, QGs, lGs, gamma, gd, 0.0, lr, nu_d)
 
 
+@pytest.mark.parametrize("dA,dG", [(145, 16), (300, 130), (577, 64)])
+def test_explicit_inverse_method_matches_cholesky_oracle(ctx, dA, dG):
+    """Sec. II-C, Eq. (kfac-damped): (G + gamma I)^-1 grad (A + gamma I)^-1.  The library forms it in the eigenbasis
+    of its own eigendecompositions (factored denominator); the oracle by two Cholesky solves with no
+    eigendecomposition at all, so this checks factors -> eig -> precondition against an independent route."""
+    rng = np.random.default_rng(dA)
+    # zero-mean unit-variance samples on both sides: spectra within [0.1, 3], so that one damping value means the same
+    # for both factors and the damped inverses are well conditioned (the sensitivity to the eigensolver's 1e-6 ||F||
+    # stays below the 1e-4 bar; ill-conditioned cases are exercised in test_gpu_configs.py)
+    X = rng.standard_normal((3 * dA, dA - 1)).astype(np.float32)
+    Gr = rng.standard_normal((4 * dG, dG)).astype(np.float32)
+    Ad = torch.zeros((dA, dA), dtype=torch.float32, device=ctx.dev)
+    Gd = torch.zeros((dG, dG), dtype=torch.float32, device=ctx.dev)
+    ctx.update_factors(ctx.to_dev(X), K.KFAC_LAYOUT_RD, X.shape[0], dA - 1, 1, 1, 1.0 / X.shape[0], 0.0, Ad)
+    ctx.update_factors(ctx.to_dev(Gr), K.KFAC_LAYOUT_RD, Gr.shape[0], dG, 1, 0, 1.0 / Gr.shape[0], 0.0, Gd)
+    Ld, Qd, info = ctx.eig([Ad, Gd])
+    assert all(c for (_, _, c) in info)
+    A = oracle.gram(X, 1, 1.0 / X.shape[0])
+    G = oracle.gram(Gr, 0, 1.0 / Gr.shape[0])
+    grad = (rng.standard_normal((dG, dA)) * 1e-2).astype(np.float32)
+    for gamma in (0.3, 1.0):
+        ref = oracle.precondition_inverse(G, A, gamma, grad)
+        gd = ctx.to_dev(grad)
+        K.kfac_precondition_batched(ctx.h, [Qd[0]], [Ld[0]], [Qd[1]], [Ld[1]], gamma, [gd], factored_damping=True)
+        torch.cuda.synchronize()
+        got = gd.cpu().numpy()
+        assert relfro(got, ref) <= TOL_F32, (gamma, relfro(got, ref))
+        # and it is not the hot path's damping
+        g2 = ctx.to_dev(grad)
+        K.kfac_precondition_batched(ctx.h, [Qd[0]], [Ld[0]], [Qd[1]], [Ld[1]], gamma, [g2])
+        torch.cuda.synchronize()
+        assert relfro(g2.cpu().numpy(), ref) > 1e-3
+
+
 # ------------------------------------------------------------------ whole path, config 1
 def test_single_conv_layer_end_to_end(ctx):
     """3x3 conv 16->16 on 8x8, batch 32: three factor updates, eig, precondition, against the oracle and
