@@ -201,7 +201,7 @@ void plan_single(int d, int64_t R, int &ntri, int &nsplit, int &kchunk) {
 // In a batch the other factors fill the machine, so a factor is cut into jobs of about JOB_SLABS slabs
 // each: long enough to amortise a job's fixed cost and its 64 KB partial, short enough that the longest
 // job is a small part of the launch.
-constexpr int JOB_SLABS = 256;
+constexpr int JOB_SLABS = 512;
 void plan_batched(int d, int64_t R, int &ntri, int &nsplit, int &kchunk) {
     const int ntile = (d + BM - 1) / BM;
     ntri = ntile * (ntile + 1) / 2;
