@@ -392,7 +392,7 @@ struct BlkGroup {
     float *W, *Qw, *J;
     int *idt;
     double *norms;   // [nmat][2] = off^2, diag^2
-    int nmat, nblk, npad, players, npairs, npp;   // npp: unused
+    int nmat, nblk, npad, players, npairs;
     int bipartite;   // 0: tournament over all blocks; 1: block j of the first half with a block of the second
     const int *done; // [factors]: 1 once a factor has met the tolerance; its workgroups return at once
     int per_factor;  // matrices of this group per factor (units of a two-level group; 1 otherwise)
@@ -963,7 +963,7 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
 
 // ---- host side ---------------------------------------------------------------------------------
 struct GroupPlan {
-    int nblk, npad, players, npairs, npp;
+    int nblk, npad, players, npairs;
     bool two_level;
     int nsuper, splayers, U;      // two-level: super-blocks, outer players (even), units per outer round
     std::vector<int> members;
@@ -1019,7 +1019,6 @@ void make_plan(int batch, const int *d, std::vector<int> &small, std::vector<Gro
             g.npad = npad;
             g.players = (nblk + 1) & ~1;
             g.npairs = g.players / 2;
-            g.npp = 0;
             g.nsuper = npad / SB;
             g.splayers = (g.nsuper + 1) & ~1;
             g.U = g.splayers / 2;
@@ -1315,13 +1314,12 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         r.nm = (int)gp.members.size();
         r.tol2 = (double)tol * tol;
         r.st = ctx->aux[stream_of[gi]];
-        if (getenv("KFAC_DEBUG")) fprintf(stderr, "[kfac] group %zu nblk=%d nm=%d two=%d -> stream %d (%p)\n", gi, gp.nblk, (int)gp.members.size(), (int)gp.two_level, stream_of[gi], (void *)r.st);
         r.ev = ctx->ev_group[gi];
         const size_t np2 = (size_t)gp.npad * gp.npad;
         const int nm = r.nm;
         char *p = wsp;
         BlkGroup &g = r.g;
-        g.nmat = nm; g.nblk = gp.nblk; g.npad = gp.npad; g.players = gp.players; g.npairs = gp.npairs; g.npp = gp.npp;
+        g.nmat = nm; g.nblk = gp.nblk; g.npad = gp.npad; g.players = gp.players; g.npairs = gp.npairs;
         g.bipartite = 0;
         g.W = (float *)p;
         g.Qw = g.W + nm * np2;
@@ -1341,11 +1339,9 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             sp.scale = (float *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(float), 256);
             g.J = Jin; g.idt = idtin;   // unused by the flat kernels for this group
             // inner group of a regular outer round: units of 4 + 4 small blocks, bipartite pairing
-            r.gi = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.U, 2 * SB / EB, LDI, 2 * SB / EB, SB / EB,
-                            0, 1, nullptr, 1};
+            r.gi = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.U, 2 * SB / EB, LDI, 2 * SB / EB, SB / EB, 1, nullptr, 1};
             // inner group of the diagonal phase: one super-block of 4 small blocks each, tournament pairing
-            r.gd = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.nsuper, SB / EB, SB, SB / EB, SB / EB / 2,
-                            0, 0, nullptr, 1};
+            r.gd = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.nsuper, SB / EB, SB, SB / EB, SB / EB / 2, 0, nullptr, 1};
         } else {
             p += kfac_align_up(nm * 2 * np2 * sizeof(float), 256);
             g.J = (float *)p; p += kfac_align_up((size_t)nm * gp.npairs * KP * KP * sizeof(float), 256);
@@ -1455,7 +1451,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
                 r.conv[i] = c;
                 all &= c;
             }
-            if (getenv("KFAC_EIG_TRACE")) {
+            if (getenv("KFAC_EIG_TRACE")) {   // debugging aid: the convergence history on stderr
                 fprintf(stderr, "[kfac_eig] group nblk=%d sweep %d off/norm:", r.plan->nblk, r.sweep);
                 for (int i = 0; i < r.nm; ++i) fprintf(stderr, " %.2e", r.offrel[i]);
                 fprintf(stderr, "\n");
