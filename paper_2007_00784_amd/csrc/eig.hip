@@ -852,14 +852,18 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
     // every other round (and negating the result) turns it upwards there, so it cancels over two rounds.
     const float sgn = (round & 1) ? -1.f : 1.f;
     float in_scale = X3_UNIT, out_scale = 1.f / (X3_UNIT * X3_UNIT);   // split engine: accumulator part
+    // Workgroup order: the two tiles that share an A operand (column halves b = 0, 1 of one unit) are 8 apart in
+    // the launch, i.e. they run at the same time on the same XCD (workgroups go round the 8 XCDs), so the second
+    // read of the operand is an L2 hit instead of a second trip to memory.  c counts the (operand, unit) pairs.
     const int bx = blockIdx.x + bx0;
     if (bx < nW) {
         if (X3) { in_scale = g.scale[2 * m]; out_scale = g.scale[2 * m + 1] * (1.f / X3_UNIT); }
-        const int idx = bx;
-        const int a = (idx >> 1) & 1;
-        b = idx & 1;
+        const int c = (bx >> 4) * 8 + (bx & 7);
+        if (c >= (U * (U - 1) / 2) * 2) return;
+        const int a = c & 1;
+        b = (bx >> 3) & 1;
         int i1;
-        tri_decode(idx >> 2, i1, J);
+        tri_decode(c >> 1, i1, J);
         int I0, I1;
         unit_blocks(g, round, i1 + 1, I0, I1);
         rowblk = a ? I1 : I0;
@@ -868,9 +872,11 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
         dst = g.T + m * np2;
     } else {
         const int idx = bx - nW;
-        rowblk = idx % nrb;
-        J = (idx / nrb) >> 1;
-        b = (idx / nrb) & 1;
+        const int c = (idx >> 4) * 8 + (idx & 7);
+        if (c >= nrb * U) return;
+        rowblk = c % nrb;
+        J = c / nrb;
+        b = (idx >> 3) & 1;
         src = Qin + m * np2;
         dst = Qout + m * np2;
     }
@@ -917,10 +923,13 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
     if (g.done[m]) return;
     const int64_t np2 = (int64_t)g.npad * g.npad;
     const int ld = g.npad;
+    // the two tiles that share the B operand (row halves a = 0, 1 of one unit) are 8 apart: see the column pass
     const int idx = blockIdx.x;
-    const int a = (idx >> 1) & 1, b = idx & 1;
+    const int c = (idx >> 4) * 8 + (idx & 7);
+    if (c >= (U * (U - 1) / 2) * 2) return;
+    const int a = (idx >> 3) & 1, b = c & 1;
     int i1, J;
-    tri_decode(idx >> 2, i1, J);
+    tri_decode(c >> 1, i1, J);
     const int I = i1 + 1;
     int I0, I1, J0, J1;
     unit_blocks(g, round, I, I0, I1);
@@ -1117,8 +1126,9 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
         const int count = r.nm * U * s;
         hipLaunchKernelGGL(sp_minus_identity_kernel, dim3((count + NT - 1) / NT), dim3(NT), 0, st, r.sp, s, U, count);
     }
-    const int nW = 4 * (U * (U - 1) / 2);
+    const int nW = ((2 * (U * (U - 1) / 2) + 7) / 8) * 16;      // padded to whole groups of 8 pairs x 2 halves
     const int nrb = gp.npad / SB;
+    const int nQ = ((nrb * U + 7) / 8) * 16;
     // algorithmic work of the two passes: every element of half the symmetric matrix and of the
     // accumulator gets two (one) dot products of the unit edge s
     // algorithmic bytes: the column pass reads Q and the lower half of W and writes as much (12 n^2 bytes), the
@@ -1131,10 +1141,10 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
     {
         KfacProfScope prof(ctx, KC_EIG_OUTER, 0.75 * fl, 12.0 * n2, st);
         if (r.x3)
-            hipLaunchKernelGGL(sp_pass_cols_kernel<true>, dim3(nW + nrb * U * 2, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s,
+            hipLaunchKernelGGL(sp_pass_cols_kernel<true>, dim3(nW + nQ, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s,
                                nW, nrb, (const float *)r.g.Qw, r.Qalt, 0);
         else
-            hipLaunchKernelGGL(sp_pass_cols_kernel<false>, dim3(nW + nrb * U * 2, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s,
+            hipLaunchKernelGGL(sp_pass_cols_kernel<false>, dim3(nW + nQ, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s,
                                nW, nrb, (const float *)r.g.Qw, r.Qalt, 0);
     }
     if (nW > 0) {
