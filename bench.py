@@ -24,6 +24,7 @@ PEAK_HBM = 8.0e12          # bytes/s
 BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
     "unfold": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "syrk": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
+    "syrk_bf16": ("mfma", PEAK_MFMA_F16, "TFLOP/s", "flops"),   # bf16 and fp16 share the dense matrix peak
     "syrk_reduce": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "precond_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
     "precond_scale": ("hbm", PEAK_HBM, "GB/s", "bytes"),

@@ -197,7 +197,7 @@ int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out, int max, int *n) {
     if (!ctx || !out || !n || max < 0) return KFAC_EINVAL;
     static const char *names[KC_COUNT] = {"unfold", "syrk", "syrk_reduce", "precond_gemm", "eig_small",
                                           "eig_pivot_solve", "eig_apply", "eig_misc", "eig_post_gemm", "eig_copy", "eig_outer_gemm",
-                                          "precond_scale"};
+                                          "precond_scale", "syrk_bf16"};
     ctx->prof_on = false;
     KFAC_HIP_CHECK(hipStreamSynchronize(ctx->stream));
     kfac_kernel_stat acc[KC_COUNT] = {};

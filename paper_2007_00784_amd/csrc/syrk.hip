@@ -12,6 +12,7 @@
 #include <vector>
 #include "kfac_internal.h"
 #include "mfma_gemm.h"
+#include "mfma_gemm_bf16.h"
 
 using namespace kfac;
 
@@ -28,6 +29,8 @@ struct SyrkArgs {     // one factor update of a batch
     int kchunk;       // K rows per split (multiple of BK)
     int K;            // total sample rows
     int T;            // [N][d][T] layout: positions per example
+    int gpe;          // bf16 engine: groups of eight positions per example, ceil(T / 8); kchunk counts groups
+    int Q;            // bf16 engine: groups in all, N * gpe
     int ntri;         // lower-triangular tiles
     float alpha;      // (1-decay)*scale
     float decay;
@@ -90,6 +93,28 @@ template <> __device__ inline OpStrided<unsigned short, false> make_op(const Syr
     return OpStrided<unsigned short, false>{(const unsigned short *)g.X, 1, g.d, g.d, 0, -1};
 }
 
+// Final sum of a tile (running average applied, mirrored) or this split's partial.
+__device__ inline void syrk_epilogue(const SyrkArgs &g, const SyrkJob &job, int ti, int tj, bool want_cs,
+                                     const floatx16 (&acc)[2][2], const float *cs) {
+    const bool diag = ti == tj;
+    if (g.nsplit == 1) {
+        for_each_acc(acc, [&](int r, int c, float v) {
+            const int gr = ti * BM + r, gc = tj * BM + c;
+            if (gr < g.d && gc < g.d && (!diag || gc <= gr))
+                ema_store(g.F, g.D, gr, gc, v, g.alpha, g.decay, gr != gc);
+        });
+        if (want_cs) {
+            const int gc = ti * BM + threadIdx.x;
+            if (threadIdx.x < BM && gc < g.d) ema_store(g.F, g.D, g.d, gc, cs[threadIdx.x], g.alpha, g.decay, true);
+            if (job.tri == 0 && threadIdx.x == 0) ema_store(g.F, g.D, g.d, g.d, (float)g.K, g.alpha, g.decay, false);
+        }
+    } else {
+        float *dst = g.partial + ((int64_t)job.split * g.ntri + job.tri) * PART;
+        for_each_acc(acc, [&](int r, int c, float v) { dst[r * BM + c] = v; });
+        if (want_cs && threadIdx.x < BM) dst[BM * BM + threadIdx.x] = cs[threadIdx.x];
+    }
+}
+
 // One launch serves every factor of a batch that shares an operand form: workgroup b takes jobs[b].
 template <class Op>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void syrk_kernel(const SyrkArgs *items, const SyrkJob *jobs) {
@@ -117,22 +142,45 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
     } else {
         gemm_tile<Op, Op, false>(a, b, ti * BM, tj * BM, kbeg, kend, sm, acc);
     }
-    if (g.nsplit == 1) {
-        for_each_acc(acc, [&](int r, int c, float v) {
-            const int gr = ti * BM + r, gc = tj * BM + c;
-            if (gr < g.d && gc < g.d && (!diag || gc <= gr))
-                ema_store(g.F, g.D, gr, gc, v, g.alpha, g.decay, gr != gc);
-        });
-        if (want_cs) {
-            const int gc = ti * BM + threadIdx.x;
-            if (threadIdx.x < BM && gc < g.d) ema_store(g.F, g.D, g.d, gc, cs[threadIdx.x], g.alpha, g.decay, true);
-            if (job.tri == 0 && threadIdx.x == 0) ema_store(g.F, g.D, g.d, g.d, (float)g.K, g.alpha, g.decay, false);
+    syrk_epilogue(g, job, ti, tj, want_cs, acc, cs);
+}
+
+// The same for bf16 samples in [N][d][T] layout with T >= 8, on the bf16 engine.  kchunk and Q count groups
+// of eight positions.  Dynamic LDS: B16Smem, then 128 floats of column sums.
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void syrk_b16_kernel(const SyrkArgs *items, const SyrkJob *jobs) {
+    extern __shared__ __align__(16) char smem[];
+    B16Smem &sm = *reinterpret_cast<B16Smem *>(smem);
+    float *cs = reinterpret_cast<float *>(smem + sizeof(B16Smem));
+    const SyrkJob job = jobs[blockIdx.x];
+    const SyrkArgs g = items[job.item];
+    int ti, tj;
+    tri_decode(job.tri, ti, tj);
+    const int q0 = job.split * g.kchunk;
+    const int q_end = min(g.Q, q0 + g.kchunk);
+    const bool diag = ti == tj;
+    const bool want_cs = diag && g.ones;
+    B16OpNDT a{(const unsigned short *)g.X, g.d, g.T, g.gpe, 0}, b = a;
+    floatx16 acc[2][2];
+    float csum[B16_RPT];
+#pragma unroll
+    for (int u = 0; u < B16_RPT; ++u) csum[u] = 0.f;
+    if (want_cs) gemm_tile_b16<true, true>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
+    else if (diag) gemm_tile_b16<true, false>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
+    else gemm_tile_b16<false, false>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
+    if (want_cs) {   // the K loop ended on a barrier, so the slab buffers are free: sum the eight threads of a row in order
+        const int tid = threadIdx.x;
+        float *scratch = reinterpret_cast<float *>(sm.a[0]);
+#pragma unroll
+        for (int u = 0; u < B16_RPT; ++u) scratch[((tid >> 3) + 32 * u) * 8 + (tid & 7)] = csum[u];
+        __syncthreads();
+        if (tid < BM) {
+            float t = 0.f;
+            for (int k = 0; k < 8; ++k) t += scratch[tid * 8 + k];
+            cs[tid] = t;
         }
-    } else {
-        float *dst = g.partial + ((int64_t)split * g.ntri + job.tri) * PART;
-        for_each_acc(acc, [&](int r, int c, float v) { dst[r * BM + c] = v; });
-        if (want_cs && threadIdx.x < BM) dst[BM * BM + threadIdx.x] = cs[threadIdx.x];
+        __syncthreads();
     }
+    syrk_epilogue(g, job, ti, tj, want_cs, acc, cs);
 }
 
 // Sum the split partials of each tile in split order, then apply the running average and mirror.
@@ -178,22 +226,24 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkArgs *items,
 
 // Choose the number of K splits of one factor launched alone.  Two workgroups share a compute unit
 // (register budget), so the machine has 512 slots; a launch takes ceil(workgroups / 512) rounds of (slabs
-// per split + a fixed per-workgroup cost of about 12 slabs for prologue, epilogue and partial traffic).
-void plan_single(int d, int64_t R, int &ntri, int &nsplit, int &kchunk) {
+// per split + a fixed per-workgroup cost, in slabs, for prologue, epilogue and partial traffic: about 12
+// slabs of the fp32 engine).  R counts contraction units (sample rows; groups on the bf16 engine) and `slab`
+// is the engine's slab in those units.
+void plan_single(int d, int64_t R, int slab, double fixed, int &ntri, int &nsplit, int &kchunk) {
     const int ntile = (d + BM - 1) / BM;
     ntri = ntile * (ntile + 1) / 2;
-    const int64_t slabs = (R + BK - 1) / BK;
+    const int64_t slabs = (R + slab - 1) / slab;
     int best = 1;
     double best_cost = 1e300;
     for (int ns = 1; ns <= 512; ++ns) {
-        if (ns > 1 && slabs / ns < 8) break;                 // keep >= 128 rows per split
+        if (ns > 1 && slabs / ns < 8) break;                 // keep >= 8 slabs per split
         const double rounds = std::ceil((double)ntri * ns / 512.0);
-        const double cost = rounds * ((double)((slabs + ns - 1) / ns) + 12.0);
+        const double cost = rounds * ((double)((slabs + ns - 1) / ns) + fixed);
         if (cost < best_cost * 0.999) { best_cost = cost; best = ns; }
     }
     nsplit = best;
     int64_t chunk = (R + nsplit - 1) / nsplit;
-    chunk = (chunk + BK - 1) / BK * BK;
+    chunk = (chunk + slab - 1) / slab * slab;
     kchunk = (int)chunk;
     nsplit = (int)((R + chunk - 1) / chunk);
 }
@@ -202,21 +252,38 @@ void plan_single(int d, int64_t R, int &ntri, int &nsplit, int &kchunk) {
 // each: long enough to amortise a job's fixed cost and its 64 KB partial, short enough that the longest
 // job is a small part of the launch.
 constexpr int JOB_SLABS = 512;
-void plan_batched(int d, int64_t R, int &ntri, int &nsplit, int &kchunk) {
+constexpr int JOB_SLABS_B16 = 256;   // bf16 engine: slabs of 64 sample rows
+void plan_batched(int d, int64_t R, int slab, int job_slabs, int &ntri, int &nsplit, int &kchunk) {
     const int ntile = (d + BM - 1) / BM;
     ntri = ntile * (ntile + 1) / 2;
-    const int64_t slabs = (R + BK - 1) / BK;
-    nsplit = (int)std::max<int64_t>(1, (slabs + JOB_SLABS / 2) / JOB_SLABS);
+    const int64_t slabs = (R + slab - 1) / slab;
+    nsplit = (int)std::max<int64_t>(1, (slabs + job_slabs / 2) / job_slabs);
     int64_t chunk = (R + nsplit - 1) / nsplit;
-    chunk = (chunk + BK - 1) / BK * BK;
+    chunk = (chunk + slab - 1) / slab * slab;
     kchunk = (int)chunk;
     nsplit = (int)((R + chunk - 1) / chunk);
 }
 
+// Operand forms, one launch each: 0: [N][d][T] fp32, 1: [N][d][T] bf16 with T < 8 (fp32 engine), 2: [R][d] fp32,
+// 3: [R][d] bf16, 4: [N][d][T] bf16 on the bf16 engine.
+constexpr int NFORM = 5;
+int form_of(const kfac_factor_item &it) {
+    const bool ndt = it.layout == KFAC_LAYOUT_NDT && it.T > 1;
+    if (it.dtype == KFAC_F32) return ndt ? 0 : 2;
+    if (!ndt) return 3;
+    return it.T >= 8 ? 4 : 1;
+}
+
 void plan_item(int n, const kfac_factor_item &it, int &ntri, int &nsplit, int &kchunk) {
+    if (form_of(it) == 4) {   // contraction units are groups of eight positions
+        const int64_t Q = (int64_t)it.N * ((it.T + 7) / 8);
+        if (n == 1) plan_single(it.d, Q, B16_GROUPS, 30.0, ntri, nsplit, kchunk);
+        else plan_batched(it.d, Q, B16_GROUPS, JOB_SLABS_B16, ntri, nsplit, kchunk);
+        return;
+    }
     const int64_t R = (int64_t)it.N * it.T;
-    if (n == 1) plan_single(it.d, R, ntri, nsplit, kchunk);
-    else plan_batched(it.d, R, ntri, nsplit, kchunk);
+    if (n == 1) plan_single(it.d, R, BK, 12.0, ntri, nsplit, kchunk);
+    else plan_batched(it.d, R, BK, JOB_SLABS, ntri, nsplit, kchunk);
 }
 
 // Workspace layout: SyrkArgs[n], the job table, the reducer's job table, then every factor's partials.
@@ -265,10 +332,9 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
     const size_t need = layout(n, items, off_jobs, off_rjobs, off_part, njobs, nrjobs);
     if (need > ctx->ws_bytes) return KFAC_EWORKSPACE;
     std::vector<SyrkArgs> args(n);
-    // jobs grouped by operand form (0: [N][d][T] fp32, 1: [N][d][T] bf16, 2: [R][d] fp32, 3: [R][d] bf16), inside
-    // a form the longest contraction first
-    std::vector<SyrkJob> jobs[4], rjobs;
-    double flops[4] = {0, 0, 0, 0}, bytes[4] = {0, 0, 0, 0}, rbytes = 0.0;
+    // jobs grouped by operand form, inside a form the longest contraction first
+    std::vector<SyrkJob> jobs[NFORM], rjobs;
+    double flops[NFORM] = {0, 0, 0, 0, 0}, bytes[NFORM] = {0, 0, 0, 0, 0}, rbytes = 0.0;
     float *part = (float *)(ctx->ws + off_part);
     for (int i = 0; i < n; ++i) {
         const kfac_factor_item &it = items[i];
@@ -281,12 +347,14 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
         g.ones = it.append_ones ? 1 : 0;
         g.K = (int)R;
         g.T = it.T;
+        g.gpe = (it.T + 7) / 8;
+        g.Q = it.N * g.gpe;
         g.alpha = (1.f - it.decay) * it.scale;
         g.decay = it.decay;
         g.F = it.F;
         g.partial = part;
         if (g.nsplit > 1) part += (size_t)g.nsplit * g.ntri * PART;
-        const int form = ((it.layout == KFAC_LAYOUT_NDT && it.T > 1) ? 0 : 2) + (it.dtype == KFAC_F32 ? 0 : 1);
+        const int form = form_of(it);
         for (int t = 0; t < g.ntri; ++t)
             for (int sp = 0; sp < g.nsplit; ++sp) jobs[form].push_back(SyrkJob{i, t, sp});
         if (g.nsplit > 1)
@@ -301,8 +369,8 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
     SyrkArgs *d_items = (SyrkArgs *)ctx->ws;
     SyrkJob *d_jobs = (SyrkJob *)(ctx->ws + off_jobs), *d_rjobs = (SyrkJob *)(ctx->ws + off_rjobs);
     KFAC_HIP_CHECK(hipMemcpyAsync(d_items, args.data(), n * sizeof(SyrkArgs), hipMemcpyHostToDevice, ctx->stream));
-    size_t at[4], pos = 0;
-    for (int f = 0; f < 4; ++f) {
+    size_t at[NFORM], pos = 0;
+    for (int f = 0; f < NFORM; ++f) {
         std::stable_sort(jobs[f].begin(), jobs[f].end(), [&](const SyrkJob &a, const SyrkJob &b) { return args[a.item].kchunk > args[b.item].kchunk; });
         at[f] = pos;
         if (!jobs[f].empty())
@@ -315,6 +383,13 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
     launch_class<OpNDT<unsigned short>>(ctx, d_items, d_jobs + at[1], jobs[1].size(), flops[1], bytes[1]);
     launch_class<OpStrided<float, false>>(ctx, d_items, d_jobs + at[2], jobs[2].size(), flops[2], bytes[2]);
     launch_class<OpStrided<unsigned short, false>>(ctx, d_items, d_jobs + at[3], jobs[3].size(), flops[3], bytes[3]);
+    if (!jobs[4].empty()) {
+        const int lds = (int)(sizeof(B16Smem) + BM * sizeof(float));
+        if (lds > ctx->max_lds) return KFAC_EHIP;
+        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)syrk_b16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        KfacProfScope prof(ctx, KC_SYRK_B16, flops[4], bytes[4]);
+        hipLaunchKernelGGL(syrk_b16_kernel, dim3((unsigned)jobs[4].size()), dim3(NTHREADS), lds, ctx->stream, d_items, d_jobs + at[4]);
+    }
     KFAC_HIP_CHECK(hipGetLastError());
     if (!rjobs.empty()) {
         KfacProfScope prof(ctx, KC_SYRK_REDUCE, 0.0, rbytes);

@@ -69,6 +69,9 @@ FACTOR_CASES = [
     ("NDT", 5, 300, 5, 1),         # T < K slab
     ("RD", 5000, 33, 1, 1),        # split-K on a single tile
     ("NDT", 64, 64, 784, 1),       # deep split-K
+    ("NDT", 9, 200, 9, 1),         # bf16 engine: every example ends in a group that overlaps the one before by 7
+    ("NDT", 4, 130, 8, 0),         # bf16 engine: exactly one group per example
+    ("NDT", 40, 257, 100, 1),      # bf16 engine: T = 12.5 groups, three tiles per side, contraction ends mid-slab
 ]
 
 
