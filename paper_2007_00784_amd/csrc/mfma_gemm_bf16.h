@@ -51,23 +51,26 @@ struct B16OpNDT {
             rowoff[u] = min(row, d - 1) * T;
         }
     }
-    __device__ void fetch(uint4 (&v)[B16_RPT]) const {
+    // Issue the loads of this thread's groups; `m` receives the element masks that apply() puts on them.  Kept
+    // apart so that nothing touches the loaded registers until the slab is moved to LDS, one step later.
+    __device__ void fetch(uint4 (&v)[B16_RPT], unsigned (&m)[4]) const {
         const bool valid = q < q_end;
         const int t0 = min(8 * gi, T - 8);
         const int sh = valid ? 8 * gi - t0 : 8;   // positions below sh belong to the previous group (or nothing is valid)
         const unsigned short *base = p + (valid ? (int64_t)n * d * T + t0 : (int64_t)0);
-        unsigned m[4];
 #pragma unroll
         for (int w = 0; w < 4; ++w) m[w] = (2 * w >= sh ? 0x0000ffffu : 0u) | (2 * w + 1 >= sh ? 0xffff0000u : 0u);
 #pragma unroll
+        for (int u = 0; u < B16_RPT; ++u) __builtin_memcpy(&v[u], base + rowoff[u], 16);
+    }
+    __device__ void apply(uint4 (&v)[B16_RPT], const unsigned (&m)[4]) const {
+#pragma unroll
         for (int u = 0; u < B16_RPT; ++u) {
-            uint4 x;
-            __builtin_memcpy(&x, base + rowoff[u], 16);
             const unsigned keep = ((rowmask >> u) & 1u) ? 0xffffffffu : 0u;
-            v[u].x = x.x & m[0] & keep;
-            v[u].y = x.y & m[1] & keep;
-            v[u].z = x.z & m[2] & keep;
-            v[u].w = x.w & m[3] & keep;
+            v[u].x &= m[0] & keep;
+            v[u].y &= m[1] & keep;
+            v[u].z &= m[2] & keep;
+            v[u].w &= m[3] & keep;
         }
     }
     __device__ void next() {
@@ -109,31 +112,46 @@ __device__ inline void gemm_tile_b16(B16OpNDT &A, B16OpNDT &B, int i0, int j0, i
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     const int nslab = (q_end - q0 + B16_GROUPS - 1) / B16_GROUPS;
     if (nslab <= 0) return;
-    uint4 ra[B16_RPT], rb[B16_RPT];
+    // Pipeline: slab s is multiplied out of LDS while slab s+1 waits in registers for its LDS buffer and the
+    // loads of slab s+2 are in flight: at the bf16 MFMA rate one slab of arithmetic is much shorter than a trip
+    // to L2, so a single slab of look-ahead leaves the matrix core idle most of the time.  Slabs past the end read
+    // as zero (q >= q_end), so the look-ahead needs no special case.
+    uint4 ra[2][B16_RPT], rb[2][B16_RPT];
+    unsigned ma[2][4], mb[2][4];
     A.q_end = q_end;
     B.q_end = q_end;
     A.start(tid, i0, q0);
-    A.fetch(ra);
+    A.fetch(ra[0], ma[0]);
     if (!DIAG) {
         B.start(tid, j0, q0);
-        B.fetch(rb);
+        B.fetch(rb[0], mb[0]);
     }
+    A.next();
+    A.fetch(ra[1], ma[1]);   // slab 1
+    if (!DIAG) {
+        B.next();
+        B.fetch(rb[1], mb[1]);
+    }
+    A.apply(ra[0], ma[0]);
+    if (!DIAG) B.apply(rb[0], mb[0]);
     if (COLSUM) {
 #pragma unroll
-        for (int u = 0; u < B16_RPT; ++u) csum[u] += b16_sum8(ra[u]);
+        for (int u = 0; u < B16_RPT; ++u) csum[u] += b16_sum8(ra[0][u]);
     }
-    B16OpNDT::store(sm.a[0], ra, tid);
-    if (!DIAG) B16OpNDT::store(sm.b[0], rb, tid);
+    B16OpNDT::store(sm.a[0], ra[0], tid);
+    if (!DIAG) B16OpNDT::store(sm.b[0], rb[0], tid);
     __syncthreads();
-    for (int s = 0; s < nslab; ++s) {
+    // one step: start the loads of slab s+2 into `f*` (free since slab s went to LDS), multiply slab s out of
+    // LDS buffer s & 1, then move slab s+1, whose loads have had two steps to land, from `s*` to the other buffer
+    auto step = [&](int s, int f, int o) {   // f = s & 1: register set to fetch into, o = 1 - f: set to move to LDS
         const int cur = s & 1;
-        const bool more = s + 1 < nslab;
-        if (more) {
+        uint4 (&fa_)[B16_RPT] = ra[f], (&fb_)[B16_RPT] = rb[f], (&sa_)[B16_RPT] = ra[o], (&sb_)[B16_RPT] = rb[o];
+        if (s + 2 < nslab) {
             A.next();
-            A.fetch(ra);
+            A.fetch(fa_, ma[f]);
             if (!DIAG) {
                 B.next();
-                B.fetch(rb);
+                B.fetch(fb_, mb[f]);
             }
         }
         const char *pa = sm.a[cur];
@@ -156,15 +174,21 @@ __device__ inline void gemm_tile_b16(B16OpNDT &A, B16OpNDT &B, int i0, int j0, i
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
-        if (more) {
+        if (s + 1 < nslab) {
+            A.apply(sa_, ma[o]);
+            if (!DIAG) B.apply(sb_, mb[o]);
             if (COLSUM) {
 #pragma unroll
-                for (int u = 0; u < B16_RPT; ++u) csum[u] += b16_sum8(ra[u]);
+                for (int u = 0; u < B16_RPT; ++u) csum[u] += b16_sum8(sa_[u]);
             }
-            B16OpNDT::store(sm.a[cur ^ 1], ra, tid);
-            if (!DIAG) B16OpNDT::store(sm.b[cur ^ 1], rb, tid);
+            B16OpNDT::store(sm.a[cur ^ 1], sa_, tid);
+            if (!DIAG) B16OpNDT::store(sm.b[cur ^ 1], sb_, tid);
         }
         __syncthreads();
+    };
+    for (int s = 0; s < nslab; s += 2) {
+        step(s, 0, 1);           // slab s+1 sits in set 1; slab s+2 is fetched into set 0
+        if (s + 1 < nslab) step(s + 1, 1, 0);
     }
 }
 

@@ -50,20 +50,65 @@ __global__ __launch_bounds__(256) void unfold_kernel(const E *__restrict__ x, E 
         tile[cc * plane + hr * a.Wp + wc] = v;
     }
     __syncthreads();
-    // ---- write: for each (cc, ky, kx) the run of rows_out*Wo outputs starting at (ho0, 0) ----
+    // ---- write ----
+    // For (cc, ky, kx) the outputs of this workgroup are the run of Tc = rows_out*Wo positions starting at
+    // (ho0, 0).  With full-height chunks (Tc == T) the runs of consecutive patch rows are adjacent, so the whole
+    // workgroup writes ONE contiguous run; otherwise one run per patch row.  A run is cut into 16-byte vectors
+    // aligned in global memory (the first and last may be partial and are stored element by element); the
+    // decode of a vector's first element costs a few divisions, the rest of the vector is reached by carries.
+    constexpr int VEC = 16 / (int)sizeof(E);
     const int Tc = rows_out * a.Wo;
     const int T = a.Ho * a.Wo;
     const int khw = a.kh * a.kw;
-    const int total = nch * khw * Tc;
+    const bool one_run = Tc == T;
+    const int nrun = one_run ? 1 : nch * khw;
+    const int L = one_run ? nch * khw * T : Tc;
     const float inv_Tc = 1.0f / (float)Tc;
-    for (int e = threadIdx.x; e < total; e += 256) {
-        int prow, t, cc, kk, ky, kx, hoo, wo;
-        fdivmod(e, Tc, inv_Tc, prow, t);
-        fdivmod(prow, khw, 1.0f / (float)khw, cc, kk);
-        fdivmod(kk, a.kw, a.inv_kw, ky, kx);
-        fdivmod(t, a.Wo, a.inv_Wo, hoo, wo);
-        const E v = tile[cc * plane + (hoo * a.sh + ky) * a.Wp + wo * a.sw + kx];
-        out[((int64_t)n * a.C * khw + (int64_t)(c0 + cc) * khw + kk) * T + (int64_t)ho0 * a.Wo + t] = v;
+    const float inv_khw = 1.0f / (float)khw;
+    E *const out0 = out + ((int64_t)n * a.C + c0) * khw * T + (int64_t)ho0 * a.Wo;   // run 0, element 0
+    for (int run = 0; run < nrun; ++run) {
+        E *const dst = out0 + (int64_t)run * T;
+        const int g0 = (int)((reinterpret_cast<uintptr_t>(dst) / sizeof(E)) % VEC);   // elements past a 16-byte boundary
+        const int nvec = (L + g0 + VEC - 1) / VEC;
+        for (int v = threadIdx.x; v < nvec; v += 256) {
+            const int j0 = v * VEC - g0;             // first element of the vector inside the run (may be < 0)
+            const int jb = max(j0, 0), je = min(j0 + VEC, L);
+            int prow, t, cc, kk, ky, kx, hoo, wo;
+            if (one_run) fdivmod(jb, Tc, inv_Tc, prow, t);
+            else { prow = run; t = jb; }
+            fdivmod(prow, khw, inv_khw, cc, kk);
+            fdivmod(kk, a.kw, a.inv_kw, ky, kx);
+            fdivmod(t, a.Wo, a.inv_Wo, hoo, wo);
+            E vals[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                const int j = j0 + i;
+                E x = 0;
+                if (j >= jb && j < je) {
+                    x = tile[cc * plane + (hoo * a.sh + ky) * a.Wp + wo * a.sw + kx];
+                    if (++wo == a.Wo) {
+                        wo = 0;
+                        if (++hoo == rows_out) {     // only reached inside the single run: next patch row
+                            hoo = 0;
+                            if (++kx == a.kw) {
+                                kx = 0;
+                                if (++ky == a.kh) { ky = 0; ++cc; }
+                            }
+                        }
+                    }
+                }
+                vals[i] = x;
+            }
+            if (jb == j0 && je == j0 + VEC) {
+                uint4 q;
+                __builtin_memcpy(&q, vals, 16);
+                *reinterpret_cast<uint4 *>(dst + j0) = q;
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i)
+                    if (j0 + i >= jb && j0 + i < je) dst[j0 + i] = vals[i];
+            }
+        }
     }
 }
 
