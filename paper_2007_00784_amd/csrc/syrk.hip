@@ -12,7 +12,7 @@
 #include <vector>
 #include "kfac_internal.h"
 #include "mfma_gemm.h"
-#include "mfma_gemm_bf16.h"
+#include "mfma_gemm_grouped.h"
 
 using namespace kfac;
 
@@ -29,8 +29,8 @@ struct SyrkArgs {     // one factor update of a batch
     int kchunk;       // K rows per split (multiple of BK)
     int K;            // total sample rows
     int T;            // [N][d][T] layout: positions per example
-    int gpe;          // bf16 engine: groups of eight positions per example, ceil(T / 8); kchunk counts groups
-    int Q;            // bf16 engine: groups in all, N * gpe
+    int gpe;          // grouped engine: groups of 16 bytes of positions per example, ceil(T / EPG); kchunk counts groups
+    int Q;            // grouped engine: groups in all, N * gpe
     int ntri;         // lower-triangular tiles
     float alpha;      // (1-decay)*scale
     float decay;
@@ -145,12 +145,13 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
     syrk_epilogue(g, job, ti, tj, want_cs, acc, cs);
 }
 
-// The same for bf16 samples in [N][d][T] layout with T >= 8, on the bf16 engine.  kchunk and Q count groups
-// of eight positions.  Dynamic LDS: B16Smem, then 128 floats of column sums.
-__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void syrk_b16_kernel(const SyrkArgs *items, const SyrkJob *jobs) {
+// The same for samples in [N][d][T] layout with T >= EPG (4 fp32, 8 bf16), on the grouped-load engine.  kchunk
+// and Q count groups of EPG positions.  Dynamic LDS: GrpSmem, then 128 floats of column sums.
+template <typename E>
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void syrk_grouped_kernel(const SyrkArgs *items, const SyrkJob *jobs) {
     extern __shared__ __align__(16) char smem[];
-    B16Smem &sm = *reinterpret_cast<B16Smem *>(smem);
-    float *cs = reinterpret_cast<float *>(smem + sizeof(B16Smem));
+    GrpSmem &sm = *reinterpret_cast<GrpSmem *>(smem);
+    float *cs = reinterpret_cast<float *>(smem + sizeof(GrpSmem));
     const SyrkJob job = jobs[blockIdx.x];
     const SyrkArgs g = items[job.item];
     int ti, tj;
@@ -159,19 +160,19 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
     const int q_end = min(g.Q, q0 + g.kchunk);
     const bool diag = ti == tj;
     const bool want_cs = diag && g.ones;
-    B16OpNDT a{(const unsigned short *)g.X, g.d, g.T, g.gpe, 0}, b = a;
+    GrpOpNDT<E> a{(const E *)g.X, g.d, g.T, g.gpe, 0}, b = a;
     floatx16 acc[2][2];
-    float csum[B16_RPT];
+    float csum[GRP_RPT];
 #pragma unroll
-    for (int u = 0; u < B16_RPT; ++u) csum[u] = 0.f;
-    if (want_cs) gemm_tile_b16<true, true>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
-    else if (diag) gemm_tile_b16<true, false>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
-    else gemm_tile_b16<false, false>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
+    for (int u = 0; u < GRP_RPT; ++u) csum[u] = 0.f;
+    if (want_cs) gemm_tile_grouped<E, true, true>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
+    else if (diag) gemm_tile_grouped<E, true, false>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
+    else gemm_tile_grouped<E, false, false>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
     if (want_cs) {   // the K loop ended on a barrier, so the slab buffers are free: sum the eight threads of a row in order
         const int tid = threadIdx.x;
         float *scratch = reinterpret_cast<float *>(sm.a[0]);
 #pragma unroll
-        for (int u = 0; u < B16_RPT; ++u) scratch[((tid >> 3) + 32 * u) * 8 + (tid & 7)] = csum[u];
+        for (int u = 0; u < GRP_RPT; ++u) scratch[((tid >> 3) + 32 * u) * 8 + (tid & 7)] = csum[u];
         __syncthreads();
         if (tid < BM) {
             float t = 0.f;
@@ -252,7 +253,8 @@ void plan_single(int d, int64_t R, int slab, double fixed, int &ntri, int &nspli
 // each: long enough to amortise a job's fixed cost and its 64 KB partial, short enough that the longest
 // job is a small part of the launch.
 constexpr int JOB_SLABS = 512;
-constexpr int JOB_SLABS_B16 = 256;   // bf16 engine: slabs of 64 sample rows
+constexpr int JOB_SLABS_GRP_F32 = 256;   // grouped engine, fp32: slabs of 32 sample rows
+constexpr int JOB_SLABS_GRP_B16 = 256;   // grouped engine, bf16: slabs of 64 sample rows
 void plan_batched(int d, int64_t R, int slab, int job_slabs, int &ntri, int &nsplit, int &kchunk) {
     const int ntile = (d + BM - 1) / BM;
     ntri = ntile * (ntile + 1) / 2;
@@ -264,21 +266,22 @@ void plan_batched(int d, int64_t R, int slab, int job_slabs, int &ntri, int &nsp
     nsplit = (int)((R + chunk - 1) / chunk);
 }
 
-// Operand forms, one launch each: 0: [N][d][T] fp32, 1: [N][d][T] bf16 with T < 8 (fp32 engine), 2: [R][d] fp32,
-// 3: [R][d] bf16, 4: [N][d][T] bf16 on the bf16 engine.
-constexpr int NFORM = 5;
+// Operand forms, one launch each.  0: [N][d][T] fp32 with T < 4, 1: [N][d][T] bf16 with T < 8, 2: [R][d] fp32,
+// 3: [R][d] bf16 (all on the element-wise fp32 engine); 4: [N][d][T] bf16, 5: [N][d][T] fp32 on the grouped engine.
+constexpr int NFORM = 6;
 int form_of(const kfac_factor_item &it) {
     const bool ndt = it.layout == KFAC_LAYOUT_NDT && it.T > 1;
-    if (it.dtype == KFAC_F32) return ndt ? 0 : 2;
-    if (!ndt) return 3;
-    return it.T >= 8 ? 4 : 1;
+    if (it.dtype == KFAC_F32) return !ndt ? 2 : (it.T >= 4 ? 5 : 0);
+    return !ndt ? 3 : (it.T >= 8 ? 4 : 1);
 }
 
 void plan_item(int n, const kfac_factor_item &it, int &ntri, int &nsplit, int &kchunk) {
-    if (form_of(it) == 4) {   // contraction units are groups of eight positions
-        const int64_t Q = (int64_t)it.N * ((it.T + 7) / 8);
-        if (n == 1) plan_single(it.d, Q, B16_GROUPS, 30.0, ntri, nsplit, kchunk);
-        else plan_batched(it.d, Q, B16_GROUPS, JOB_SLABS_B16, ntri, nsplit, kchunk);
+    const int form = form_of(it);
+    if (form >= 4) {   // contraction units are groups of 16 bytes
+        const int epg = form == 4 ? 8 : 4;
+        const int64_t Q = (int64_t)it.N * ((it.T + epg - 1) / epg);
+        if (n == 1) plan_single(it.d, Q, GRP_GROUPS, form == 4 ? 30.0 : 6.0, ntri, nsplit, kchunk);
+        else plan_batched(it.d, Q, GRP_GROUPS, form == 4 ? JOB_SLABS_GRP_B16 : JOB_SLABS_GRP_F32, ntri, nsplit, kchunk);
         return;
     }
     const int64_t R = (int64_t)it.N * it.T;
@@ -334,7 +337,7 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
     std::vector<SyrkArgs> args(n);
     // jobs grouped by operand form, inside a form the longest contraction first
     std::vector<SyrkJob> jobs[NFORM], rjobs;
-    double flops[NFORM] = {0, 0, 0, 0, 0}, bytes[NFORM] = {0, 0, 0, 0, 0}, rbytes = 0.0;
+    double flops[NFORM] = {}, bytes[NFORM] = {}, rbytes = 0.0;
     float *part = (float *)(ctx->ws + off_part);
     for (int i = 0; i < n; ++i) {
         const kfac_factor_item &it = items[i];
@@ -347,7 +350,8 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
         g.ones = it.append_ones ? 1 : 0;
         g.K = (int)R;
         g.T = it.T;
-        g.gpe = (it.T + 7) / 8;
+        const int epg = it.dtype == KFAC_F32 ? 4 : 8;
+        g.gpe = (it.T + epg - 1) / epg;
         g.Q = it.N * g.gpe;
         g.alpha = (1.f - it.decay) * it.scale;
         g.decay = it.decay;
@@ -383,12 +387,17 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
     launch_class<OpNDT<unsigned short>>(ctx, d_items, d_jobs + at[1], jobs[1].size(), flops[1], bytes[1]);
     launch_class<OpStrided<float, false>>(ctx, d_items, d_jobs + at[2], jobs[2].size(), flops[2], bytes[2]);
     launch_class<OpStrided<unsigned short, false>>(ctx, d_items, d_jobs + at[3], jobs[3].size(), flops[3], bytes[3]);
+    const int lds = (int)(sizeof(GrpSmem) + BM * sizeof(float));
+    if ((!jobs[4].empty() || !jobs[5].empty()) && lds > ctx->max_lds) return KFAC_EHIP;
+    if (!jobs[5].empty()) {
+        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)syrk_grouped_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        KfacProfScope prof(ctx, KC_SYRK, flops[5], bytes[5]);
+        hipLaunchKernelGGL(syrk_grouped_kernel<float>, dim3((unsigned)jobs[5].size()), dim3(NTHREADS), lds, ctx->stream, d_items, d_jobs + at[5]);
+    }
     if (!jobs[4].empty()) {
-        const int lds = (int)(sizeof(B16Smem) + BM * sizeof(float));
-        if (lds > ctx->max_lds) return KFAC_EHIP;
-        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)syrk_b16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)syrk_grouped_kernel<unsigned short>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         KfacProfScope prof(ctx, KC_SYRK_B16, flops[4], bytes[4]);
-        hipLaunchKernelGGL(syrk_b16_kernel, dim3((unsigned)jobs[4].size()), dim3(NTHREADS), lds, ctx->stream, d_items, d_jobs + at[4]);
+        hipLaunchKernelGGL(syrk_grouped_kernel<unsigned short>, dim3((unsigned)jobs[4].size()), dim3(NTHREADS), lds, ctx->stream, d_items, d_jobs + at[4]);
     }
     KFAC_HIP_CHECK(hipGetLastError());
     if (!rjobs.empty()) {
