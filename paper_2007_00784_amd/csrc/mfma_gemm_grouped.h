@@ -3,14 +3,15 @@
 // as the generic fp32 engine, but every operand access is 16 bytes wide from HBM to the matrix core.
 //
 // The contraction runs over "groups" of EPG = 16 / sizeof(E) consecutive positions of one example (4 fp32, 8 bf16),
-// q = n * gpe + gi with gpe = ceil(T / EPG); group gi covers positions EPG gi .. EPG gi + EPG - 1.  A thread moves a
-// group with one 16-byte load and one 16-byte LDS store, and a lane's MFMA operands of a group are one 16-byte LDS
-// read: a quarter (fp32) or an eighth (bf16) of the memory instructions of the element-wise engine, which is what
-// separated that engine (102-117 TFLOP/s fp32 on a probe) from what its LDS reads and MFMAs alone sustain (142).
+// q = n * gpe + gi with gpe = ceil(T / EPG); group gi covers positions EPG gi .. EPG gi + EPG - 1.  A group travels
+// from global memory straight into LDS (one 16-byte direct load per lane) and a lane's MFMA operands of a group
+// are one 16-byte LDS read: no staging registers, no LDS store instructions and a quarter (fp32) or an eighth
+// (bf16) of the LDS reads of the element-wise engine.
 // Rows are not 16-byte aligned when T is odd, so the loads are unaligned ones (global memory allows that).  The
 // last group of an example, when T is not a multiple of EPG, is loaded from position T - EPG instead and the
-// positions that the previous group already covered are masked to zero: no load ever leaves its row, and since
-// both operands of a product use the same grouping the sum over positions is unchanged.  Requires T >= EPG.
+// positions that the previous group already covered are cleared in LDS once the load has landed: no load ever
+// leaves its row, and since both operands of a product use the same grouping the sum over positions is
+// unchanged.  Requires T >= EPG.
 //
 // bf16 operands stay bf16 all the way (v_mfma_f32_32x32x16_bf16: exact products, fp32 accumulation, 16 times the
 // fp32 MFMA rate); at that rate the tile is bound by operand delivery through LDS, not by the matrix core.
@@ -24,15 +25,23 @@ namespace kfac {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int GRP_GROUPS = 8;                  // groups per K slab
-constexpr int GRP_ROWB = 16 * GRP_GROUPS + 16; // LDS bytes per operand row: 128 B of data, 16 B pad
-                                               // (144 B = 36 banks: sixteen 16-byte accesses at this pitch
-                                               // hit distinct banks)
+constexpr int GRP_ROWB = 16 * GRP_GROUPS;      // LDS bytes per operand row: 128 B, no padding; the group slots of a
+                                               // row are permuted instead (physical slot = group ^ ((row >> 1) & 7)),
+                                               // which keeps both the 16-byte fragment reads and the landing
+                                               // loads free of bank conflicts
 constexpr int GRP_RPT = BM * GRP_GROUPS / NTHREADS;   // (row, group) pairs per thread per slab = 4
 
 struct GrpSmem {
     __attribute__((aligned(16))) char a[2][BM * GRP_ROWB];
     __attribute__((aligned(16))) char b[2][BM * GRP_ROWB];
 };
+
+// Source of the groups that lie outside an operand (rows >= d, groups past the end of the contraction).
+static __device__ __attribute__((aligned(16))) unsigned grp_zero16[4];
+
+// s_waitcnt vmcnt(0) with the other counters unconstrained (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4, lgkmcnt 11:8): all of this wave's loads, including those that land in LDS, have completed.
+__device__ inline void grp_wait_loads() { __builtin_amdgcn_s_waitcnt((0x7 << 4) | (0xF << 8)); }
 
 template <typename E> struct GrpTraits;
 template <> struct GrpTraits<float> {
@@ -61,7 +70,12 @@ template <> struct GrpTraits<unsigned short> {   // bf16 bits
     }
 };
 
-// Thread mapping: group slot gs = tid & 7, rows (tid >> 3) + 32 u, u = 0..3.
+// Thread mapping: physical slot tid & 7 of rows (tid >> 3) + 32 u, u = 0..3, i.e. group (tid & 7) ^ ((tid >> 4) & 7)
+// (the permutation term is the same for the four rows).  A slab is moved by global_load_lds_dwordx4: every lane
+// names its own 16 bytes of global memory and the wave's 64 groups land in 1 KB of consecutive LDS (lane l at
+// 16 l, i.e. eight whole rows), with no trip through registers and no LDS store instructions -- staging through
+// registers was what bound this engine (a probe of the bf16 loop: 450 TFLOP/s with register staging even without
+// any global loads, 700 with direct loads).
 template <typename E>
 struct GrpOpNDT {
     static constexpr int EPG = GrpTraits<E>::EPG;
@@ -73,7 +87,7 @@ struct GrpOpNDT {
     unsigned rowmask;     // per u: row inside the operand
     int q, n, gi;
     __device__ void start(int tid, int i0, int q0) {
-        q = q0 + (tid & 7);
+        q = q0 + ((tid & 7) ^ ((tid >> 4) & 7));
         n = q / gpe;
         gi = q - n * gpe;
         rowmask = 0;
@@ -84,44 +98,53 @@ struct GrpOpNDT {
             rowoff[u] = min(row, d - 1) * T;
         }
     }
-    // Issue the loads of this thread's groups; `m` receives the element masks that apply() puts on them.  Kept
-    // apart so that nothing touches the loaded registers until the slab is moved to LDS, one or two steps later.
-    __device__ void fetch(uint4 (&v)[GRP_RPT], unsigned (&m)[4]) const {
+    // Start the loads of this thread's groups of the current slab into `slab` (this operand's 16 KB buffer).
+    // Returns how many leading positions of the landed groups belong to the previous group of the example
+    // (the last, overlapping group when T is not a multiple of EPG) and must be cleared by patch().
+    __device__ int issue(char *slab, int tid) const {
         const bool valid = q < q_end;
         const int t0 = min(EPG * gi, T - EPG);
-        const int sh = valid ? EPG * gi - t0 : EPG;   // positions below sh belong to the previous group (or nothing is valid)
         const E *base = p + (valid ? (int64_t)n * d * T + t0 : (int64_t)0);
-        GrpTraits<E>::masks(sh, m);
-#pragma unroll
-        for (int u = 0; u < GRP_RPT; ++u) __builtin_memcpy(&v[u], base + rowoff[u], 16);
-    }
-    __device__ void apply(uint4 (&v)[GRP_RPT], const unsigned (&m)[4]) const {
+        const int wave = tid >> 6;
 #pragma unroll
         for (int u = 0; u < GRP_RPT; ++u) {
-            const unsigned keep = ((rowmask >> u) & 1u) ? 0xffffffffu : 0u;
-            v[u].x &= m[0] & keep;
-            v[u].y &= m[1] & keep;
-            v[u].z &= m[2] & keep;
-            v[u].w &= m[3] & keep;
+            const bool ok = valid && ((rowmask >> u) & 1u);
+            const void *src = ok ? (const void *)(base + rowoff[u]) : (const void *)grp_zero16;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(slab + (8 * wave + 32 * u) * GRP_ROWB), 16, 0, 0);
         }
+        return valid ? EPG * gi - t0 : 0;
+    }
+    // After the loads have landed: clear the first `sh` positions of this thread's groups.
+    __device__ void patch(char *slab, int tid, int sh) const {
+        if (sh == 0) return;
+        unsigned m[4];
+        GrpTraits<E>::masks(sh, m);
+#pragma unroll
+        for (int u = 0; u < GRP_RPT; ++u) {
+            uint4 *x = reinterpret_cast<uint4 *>(slab + ((tid >> 3) + 32 * u) * GRP_ROWB + (tid & 7) * 16);
+            uint4 v = *x;
+            v.x &= m[0]; v.y &= m[1]; v.z &= m[2]; v.w &= m[3];
+            *x = v;
+        }
+    }
+    // Sum of the elements of this thread's landed (and patched) group of row u.
+    __device__ static float landed_sum(const char *slab, int tid, int u) {
+        return GrpTraits<E>::sum(*reinterpret_cast<const uint4 *>(slab + ((tid >> 3) + 32 * u) * GRP_ROWB + (tid & 7) * 16));
     }
     __device__ void next() {
         q += GRP_GROUPS;
         gi += GRP_GROUPS;
         while (gi >= gpe) { gi -= gpe; ++n; }
     }
-    __device__ static void store(char *slab, const uint4 (&v)[GRP_RPT], int tid) {
-#pragma unroll
-        for (int u = 0; u < GRP_RPT; ++u)
-            *reinterpret_cast<uint4 *>(slab + ((tid >> 3) + 32 * u) * GRP_ROWB + (tid & 7) * 16) = v[u];
-    }
 };
 
 // One slab of MFMAs from fragments: lane (c, g) holds group 2 ks + g of row (column) c in k-step ks.  Any
 // assignment of contraction indices to MFMA k-lanes works as long as both operands share it.
+template <int KS0, int KS1>
 __device__ inline void grp_mfma(const uint4 (&fa)[4][2], const uint4 (&fb)[4][2], floatx16 (&acc)[2][2], float) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = KS0; ks < KS1; ++ks) {
         const unsigned a[2][4] = {{fa[ks][0].x, fa[ks][0].y, fa[ks][0].z, fa[ks][0].w}, {fa[ks][1].x, fa[ks][1].y, fa[ks][1].z, fa[ks][1].w}};
         const unsigned b[2][4] = {{fb[ks][0].x, fb[ks][0].y, fb[ks][0].z, fb[ks][0].w}, {fb[ks][1].x, fb[ks][1].y, fb[ks][1].z, fb[ks][1].w}};
 #pragma unroll
@@ -133,9 +156,10 @@ __device__ inline void grp_mfma(const uint4 (&fa)[4][2], const uint4 (&fb)[4][2]
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[i][e]), __uint_as_float(b[j][e]), acc[i][j], 0, 0, 0);
     }
 }
+template <int KS0, int KS1>
 __device__ inline void grp_mfma(const uint4 (&fa)[4][2], const uint4 (&fb)[4][2], floatx16 (&acc)[2][2], unsigned short) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
+    for (int ks = KS0; ks < KS1; ++ks)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -166,47 +190,27 @@ __device__ inline void gemm_tile_grouped(GrpOpNDT<E> &A, GrpOpNDT<E> &B, int i0,
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     const int nslab = (q_end - q0 + GRP_GROUPS - 1) / GRP_GROUPS;
     if (nslab <= 0) return;
-    // Pipeline: slab s is multiplied out of LDS while slab s+1 waits in registers for its LDS buffer and the
-    // loads of slab s+2 are in flight: at the bf16 MFMA rate one slab of arithmetic is much shorter than a trip
-    // to L2, so a single slab of look-ahead leaves the matrix core idle most of the time.  Slabs past the end read
-    // as zero (q >= q_end), so the look-ahead needs no special case.
-    uint4 ra[2][GRP_RPT], rb[2][GRP_RPT];
-    unsigned ma[2][4], mb[2][4];
+    // Two LDS buffers.  Step s: wait for this wave's loads of slab s, clear overlapping positions, barrier (slab s is
+    // complete and nobody reads slab s-1 any more), start the loads of slab s+1 into the buffer slab s-1 used, then
+    // multiply slab s.  The loads fly during the MFMAs of the slab before; the second workgroup on the compute unit
+    // covers what is left of their latency.
     A.q_end = q_end;
     B.q_end = q_end;
     A.start(tid, i0, q0);
-    A.fetch(ra[0], ma[0]);
-    if (!DIAG) {
-        B.start(tid, j0, q0);
-        B.fetch(rb[0], mb[0]);
-    }
-    A.next();
-    A.fetch(ra[1], ma[1]);   // slab 1
-    if (!DIAG) {
-        B.next();
-        B.fetch(rb[1], mb[1]);
-    }
-    A.apply(ra[0], ma[0]);
-    if (!DIAG) B.apply(rb[0], mb[0]);
-    if (COLSUM) {
-#pragma unroll
-        for (int u = 0; u < GRP_RPT; ++u) csum[u] += GrpTraits<E>::sum(ra[0][u]);
-    }
-    GrpOpNDT<E>::store(sm.a[0], ra[0], tid);
-    if (!DIAG) GrpOpNDT<E>::store(sm.b[0], rb[0], tid);
-    __syncthreads();
-    // one step: start the loads of slab s+2 into set f (free since slab s went to LDS), multiply slab s out of
-    // LDS buffer s & 1, then move slab s+1, whose loads have had two steps to land, from set o to the other buffer
-    auto step = [&](int s, int f, int o) {
+    if (!DIAG) B.start(tid, j0, q0);
+    int sha = A.issue(sm.a[0], tid), shb = 0;
+    if (!DIAG) shb = B.issue(sm.b[0], tid);
+    const int swz = (lc >> 1) & 7;   // (row >> 1) & 7 of this lane's fragment rows (they differ by multiples of 32)
+    for (int s = 0; s < nslab; ++s) {
         const int cur = s & 1;
-        if (s + 2 < nslab) {
-            A.next();
-            A.fetch(ra[f], ma[f]);
-            if (!DIAG) {
-                B.next();
-                B.fetch(rb[f], mb[f]);
-            }
+        grp_wait_loads();
+        A.patch(sm.a[cur], tid, sha);
+        if (!DIAG) B.patch(sm.b[cur], tid, shb);
+        if (COLSUM) {
+#pragma unroll
+            for (int u = 0; u < GRP_RPT; ++u) csum[u] += GrpOpNDT<E>::landed_sum(sm.a[cur], tid, u);
         }
+        __syncthreads();
         const char *pa = sm.a[cur];
         const char *pb = DIAG ? sm.a[cur] : sm.b[cur];
         uint4 fa[4][2], fb[4][2];
@@ -214,27 +218,24 @@ __device__ inline void gemm_tile_grouped(GrpOpNDT<E> &A, GrpOpNDT<E> &B, int i0,
         for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                fa[ks][i] = *reinterpret_cast<const uint4 *>(pa + (wm + 32 * i + lc) * GRP_ROWB + (2 * ks + lk) * 16);
-                fb[ks][i] = *reinterpret_cast<const uint4 *>(pb + (wn + 32 * i + lc) * GRP_ROWB + (2 * ks + lk) * 16);
+                fa[ks][i] = *reinterpret_cast<const uint4 *>(pa + (wm + 32 * i + lc) * GRP_ROWB + (((2 * ks + lk) ^ swz) * 16));
+                fb[ks][i] = *reinterpret_cast<const uint4 *>(pb + (wn + 32 * i + lc) * GRP_ROWB + (((2 * ks + lk) ^ swz) * 16));
             }
         __builtin_amdgcn_sched_barrier(0);
-        grp_mfma(fa, fb, acc, E());
-        if (s + 1 < nslab) {
-            A.apply(ra[o], ma[o]);
-            if (!DIAG) B.apply(rb[o], mb[o]);
-            if (COLSUM) {
-#pragma unroll
-                for (int u = 0; u < GRP_RPT; ++u) csum[u] += GrpTraits<E>::sum(ra[o][u]);
+        grp_mfma<0, 1>(fa, fb, acc, E());
+        __builtin_amdgcn_sched_barrier(0);
+        if (s + 1 < nslab) {   // address arithmetic and load issue in the shadow of the MFMAs just queued
+            A.next();
+            sha = A.issue(sm.a[cur ^ 1], tid);
+            if (!DIAG) {
+                B.next();
+                shb = B.issue(sm.b[cur ^ 1], tid);
             }
-            GrpOpNDT<E>::store(sm.a[cur ^ 1], ra[o], tid);
-            if (!DIAG) GrpOpNDT<E>::store(sm.b[cur ^ 1], rb[o], tid);
         }
-        __syncthreads();
-    };
-    for (int s = 0; s < nslab; s += 2) {
-        step(s, 0, 1);           // slab s+1 sits in set 1; slab s+2 is fetched into set 0
-        if (s + 1 < nslab) step(s + 1, 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        grp_mfma<1, 4>(fa, fb, acc, E());
     }
+    __syncthreads();   // callers reuse the slab buffers
 }
 
 }  // namespace kfac
