@@ -28,6 +28,8 @@ BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
     "syrk_reduce": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "precond_gemm": ("mfma", PEAK_MFMA_F32, "TFLOP/s", "flops"),
     "precond_scale": ("hbm", PEAK_HBM, "GB/s", "bytes"),
+    # three fp16 matrix products per algorithmic fp32 product: the issued rate against the fp16 peak
+    "precond_gemm_split": ("mfma", PEAK_MFMA_F16 / 3.0, "TFLOP/s", "flops"),
     "eig_small": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
     "eig_pivot_solve": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
     # K = 64 contraction per pass over W and Q: 16 flop/byte, below the fp32 ridge of 19.7

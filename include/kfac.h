@@ -165,6 +165,12 @@ typedef struct {
                                 Tikhonov damping of the Kronecker product).  1: the explicit-inverse method of
                                 Sec. II-C, Eq. (kfac-damped): (G + damping I)^-1 grad (A + damping I)^-1, computed in
                                 the eigenbasis as a division by (lamG + damping)(lamA + damping)^T              */
+    int split_f16;           /* 0: the four GEMMs run on the fp32 matrix instructions.  1: every fp32 operand element
+                                is split into two fp16 halves (22 significand bits) and a product is three fp16
+                                matrix instructions with fp32 accumulation: about twice as fast, relative Frobenius
+                                error of the result about 1e-6 instead of 1e-7 (entries more than 2^25 below the
+                                largest of their matrix are not resolved).  Meant for bf16 gradients, whose own
+                                rounding is 4e-3, and for callers who accept the normwise bound             */
 } kfac_precond_item;
 int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items /* host */);
 size_t kfac_precondition_workspace_bytes(int n, const kfac_precond_item *items /* host; only dA, dG are read */);

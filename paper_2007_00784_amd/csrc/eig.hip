@@ -895,6 +895,8 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
         out_scale *= sgn;
         if (J1 >= 0) A.set_segment(SB, (int64_t)(J1 - J0 - 1) * SB);
         X3Op<false> B{V + b * SB, s, X3_UNIT, 0, 0};      // V holds V - I here: X V = X + X (V - I)
+        A.start(threadIdx.x);
+        B.start(threadIdx.x);
         gemm_tile_x3(A, B, K, sm, acc);
         // all loads of the input tile are issued before the first store (the two may alias for the compiler)
         const float *in = src + (int64_t)rowblk * SB * ld + cb * SB;
@@ -947,6 +949,8 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
         X3Op<false> A{V + a * SB, s, sgn * X3_UNIT, 0, 0};                              // elem(m,k) = (V - I)[k][m]
         X3Op<false> B{T + (int64_t)I0 * SB * ld + cb * SB, ld, g.scale[2 * m], 0, 0};   // elem(n,k) = T[k][n]
         if (I1 >= 0) B.set_segment(SB, (int64_t)(I1 - I0 - 1) * SB * ld);
+        A.start(threadIdx.x);
+        B.start(threadIdx.x);
         gemm_tile_x3(A, B, K, sm, acc);
         out_scale = sgn * g.scale[2 * m + 1] * (1.f / X3_UNIT);
     } else {

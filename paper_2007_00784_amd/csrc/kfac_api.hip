@@ -197,7 +197,7 @@ int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out, int max, int *n) {
     if (!ctx || !out || !n || max < 0) return KFAC_EINVAL;
     static const char *names[KC_COUNT] = {"unfold", "syrk", "syrk_reduce", "precond_gemm", "eig_small",
                                           "eig_pivot_solve", "eig_apply", "eig_misc", "eig_post_gemm", "eig_copy", "eig_outer_gemm",
-                                          "precond_scale", "syrk_bf16"};
+                                          "precond_scale", "syrk_bf16", "precond_gemm_split"};
     ctx->prof_on = false;
     KFAC_HIP_CHECK(hipStreamSynchronize(ctx->stream));
     kfac_kernel_stat acc[KC_COUNT] = {};
@@ -226,7 +226,8 @@ int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out, int max, int *n) {
 static bool valid_precond_item(const kfac_precond_item &p) {
     if (!p.QA || !p.lamA || !p.QG || !p.lamG || !p.grad) return false;
     if (p.dA < 1 || p.dG < 1 || p.dA > KFAC_MAX_D || p.dG > KFAC_MAX_D) return false;
-    return p.damping > 0.f && std::isfinite(p.damping) && valid_dtype(p.grad_dtype) && (p.factored_damping == 0 || p.factored_damping == 1);
+    return p.damping > 0.f && std::isfinite(p.damping) && valid_dtype(p.grad_dtype) && (p.factored_damping == 0 || p.factored_damping == 1) &&
+           (p.split_f16 == 0 || p.split_f16 == 1);
 }
 
 int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items) {

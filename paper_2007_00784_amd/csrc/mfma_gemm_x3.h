@@ -10,8 +10,9 @@
 // For a near-identity transform V a caller does best to compute X (V - I) here and to add X itself in
 // fp32: the split engine's error then scales with |V - I|.
 //
-// Restrictions (the eigensolver's outer passes meet them by construction): full 128-row operand tiles,
-// K a multiple of 16, 16-byte aligned k-contiguous operands.
+// Two loaders: X3Op for whole, aligned tiles (the eigensolver's outer passes meet its restrictions by
+// construction: full 128-row operand tiles, K a multiple of 16, 16-byte aligned k-contiguous operands) and
+// X3OpG for operands of any extent and alignment (the preconditioner's GEMM chain).
 #pragma once
 #include "mfma_gemm.h"
 
@@ -80,8 +81,80 @@ struct X3Op {
     }
 };
 
+// General operand for the same engine: any extent and alignment, fp32 or bf16 elements.  elem(i,k) = p[i*ld + k]
+// (KFAST) or p[k*ld + i], zero for i >= I or k >= K (i counted from the operand's first row; the tile's first row
+// i0 is given to start()).  Whole in-range runs of eight k are fetched with two unaligned 16-byte loads (one for
+// bf16); the ragged last slab and rows past the edge go element by element.
+template <typename E, bool KFAST_>
+struct X3OpG {
+    static constexpr bool KFAST = KFAST_;
+    const E *p;
+    int64_t ld;
+    float scale;
+    int I, K;
+    // thread state
+    const E *pb;       // KFAST: first element of this thread's row; else p + this thread's i
+    int row, kg, k;    // k: first of this thread's eight contraction indices in the current slab
+    bool row_ok;
+    __device__ void start(int tid, int i0) {
+        row = KFAST ? tid >> 1 : tid & 127;
+        kg = KFAST ? tid & 1 : tid >> 7;
+        k = 8 * kg;
+        row_ok = i0 + row < I;
+        const int i = row_ok ? i0 + row : 0;
+        pb = KFAST ? p + (int64_t)i * ld : p + i;
+    }
+    __device__ void fetch(float (&r)[8]) const {
+        if (KFAST) {
+            if (row_ok && k + 8 <= K) {
+                if (sizeof(E) == 4) {
+                    uint4 x, y;
+                    __builtin_memcpy(&x, pb + k, 16);
+                    __builtin_memcpy(&y, pb + k + 4, 16);
+                    r[0] = __uint_as_float(x.x); r[1] = __uint_as_float(x.y); r[2] = __uint_as_float(x.z); r[3] = __uint_as_float(x.w);
+                    r[4] = __uint_as_float(y.x); r[5] = __uint_as_float(y.y); r[6] = __uint_as_float(y.z); r[7] = __uint_as_float(y.w);
+                } else {
+                    uint4 x;
+                    __builtin_memcpy(&x, pb + k, 16);
+                    const unsigned w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) { r[2 * t] = __uint_as_float(w[t] << 16); r[2 * t + 1] = __uint_as_float(w[t] & 0xffff0000u); }
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    const bool ok = row_ok && k + s < K;
+                    const float v = to_float(pb[ok ? k + s : 0]);
+                    r[s] = ok ? v : 0.f;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const bool ok = row_ok && k + s < K;
+                const float v = to_float(pb[ok ? (int64_t)(k + s) * ld : (int64_t)0]);
+                r[s] = ok ? v : 0.f;
+            }
+        }
+    }
+    __device__ void next() { k += BK; }
+    __device__ void store(char *slab, const float (&r)[8]) const {
+        half8 hi, lo;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const float v = r[s] * scale;
+            const _Float16 h = (_Float16)v;
+            hi[s] = h;
+            lo[s] = (_Float16)(v - (float)h);
+        }
+        *reinterpret_cast<half8 *>(slab + row * X3_ROWB + kg * 16) = hi;
+        *reinterpret_cast<half8 *>(slab + row * X3_ROWB + 32 + kg * 16) = lo;
+    }
+};
+
 // acc = (scaleA A) (scaleB B)^T-style product over K (operands as elem(i,k)); same accumulator layout as
 // gemm_tile, so for_each_acc applies.
+// The caller has already called start() on both loaders.
 template <class OpA, class OpB>
 __device__ inline void gemm_tile_x3(OpA &A, OpB &B, int K, X3Smem &sm, floatx16 (&acc)[2][2]) {
     const int tid = threadIdx.x;
@@ -94,11 +167,9 @@ __device__ inline void gemm_tile_x3(OpA &A, OpB &B, int K, X3Smem &sm, floatx16 
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    const int nslab = K / BK;
+    const int nslab = (K + BK - 1) / BK;   // loaders without an extent of their own are given whole slabs
     if (nslab <= 0) return;
     float ra[8], rb[8];
-    A.start(tid);
-    B.start(tid);
     A.fetch(ra);
     B.fetch(rb);
     A.store(sm.a[0], ra);

@@ -46,7 +46,7 @@ class kfac_precond_item(ctypes.Structure):
     _fields_ = [("QA", ctypes.c_void_p), ("lamA", ctypes.c_void_p), ("dA", ctypes.c_int),
                 ("QG", ctypes.c_void_p), ("lamG", ctypes.c_void_p), ("dG", ctypes.c_int),
                 ("damping", ctypes.c_float), ("grad", ctypes.c_void_p), ("grad_dtype", ctypes.c_int),
-                ("factored_damping", ctypes.c_int)]
+                ("factored_damping", ctypes.c_int), ("split_f16", ctypes.c_int)]
 
 
 class kfac_factor_item(ctypes.Structure):
@@ -218,7 +218,7 @@ def kfac_precondition(ctx, QA, lamA, QG, lamG, damping, grad):
                                    _ptr(grad), _dtype_code(grad)), "kfac_precondition")
 
 
-def _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping=False):
+def _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping=False, split_f16=False):
     n = len(grad)
     arr = (kfac_precond_item * n)()
     for j in range(n):
@@ -226,21 +226,22 @@ def _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping=False):
         if tuple(grad[j].shape) != (dG, dA):
             raise ValueError("grad[%d] must be [dG, dA]" % j)
         arr[j] = kfac_precond_item(_ptr(QA[j]), _ptr(lamA[j]), dA, _ptr(QG[j]), _ptr(lamG[j]), dG, float(damping),
-                                   _ptr(grad[j]), _dtype_code(grad[j]), int(bool(factored_damping)))
+                                   _ptr(grad[j]), _dtype_code(grad[j]), int(bool(factored_damping)), int(bool(split_f16)))
     return arr
 
 
-def kfac_precondition_batched(ctx, QA, lamA, QG, lamG, damping, grad, factored_damping=False):
+def kfac_precondition_batched(ctx, QA, lamA, QG, lamG, damping, grad, factored_damping=False, split_f16=False):
     """Lists of per-layer device tensors; every grad[j] is preconditioned in place.  factored_damping: the
-    explicit-inverse method (G + damping I)^-1 grad (A + damping I)^-1 instead of the eigenbasis step."""
-    arr = _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping)
+    explicit-inverse method (G + damping I)^-1 grad (A + damping I)^-1 instead of the eigenbasis step.
+    split_f16: run the GEMM chain on the split-fp16 engine."""
+    arr = _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping, split_f16)
     _check(lib().kfac_precondition_batched(ctx, len(grad), arr), "kfac_precondition_batched")
 
 
-def kfac_precondition_batched_scaled(ctx, QA, lamA, QG, lamG, damping, grad, kappa, lr, nu):
+def kfac_precondition_batched_scaled(ctx, QA, lamA, QG, lamG, damping, grad, kappa, lr, nu, split_f16=False):
     """As kfac_precondition_batched, then every gradient is multiplied by the nu of Sec. V-B; nu: device tensor
     of one float32, written by the call."""
-    arr = _precond_items(QA, lamA, QG, lamG, damping, grad)
+    arr = _precond_items(QA, lamA, QG, lamG, damping, grad, split_f16=split_f16)
     _check(lib().kfac_precondition_batched_scaled(ctx, len(grad), arr, float(kappa), float(lr), _ptr(nu)),
            "kfac_precondition_batched_scaled")
 

@@ -108,16 +108,18 @@ class KfacRunner:
         self.eig_info = K.kfac_eig(self.ctx, self.A + self.G, self.QA + self.QG, self.lamA + self.lamG, **kw)
         return self.eig_info
 
-    def precondition(self, damping=None, kappa=None, lr=None):
+    def precondition(self, damping=None, kappa=None, lr=None, split_f16=None):
         """In-place preconditioning of a fresh copy of the gradients; with kappa and lr also the gradient
-        scaling nu (left in self.nu, a device tensor)."""
+        scaling nu (left in self.nu, a device tensor).  split_f16 defaults to the workload's gradient type:
+        bf16 gradients (rounding 4e-3) go through the split-fp16 GEMM chain (error 1e-6), fp32 ones through fp32."""
         gamma = self.wl.damping if damping is None else damping
+        split = self.wl.bf16 if split_f16 is None else split_f16
         self.grad_flat.copy_(self.gradw_master_flat)
         if kappa is None:
-            K.kfac_precondition_batched(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad)
+            K.kfac_precondition_batched(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad, split_f16=split)
         else:
             self.nu = torch.zeros(1, dtype=torch.float32, device=self.dev)
-            K.kfac_precondition_batched_scaled(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad, kappa, lr, self.nu)
+            K.kfac_precondition_batched_scaled(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad, kappa, lr, self.nu, split_f16=split)
 
     # ---- algorithmic work of one step (flops, bytes) ----
     def work(self):

@@ -279,8 +279,39 @@ def test_precondition_matches_oracle(ctx, dA, dG, bf16):
     assert relfro(got, ref) <= (TOL_BF16 if bf16 else TOL_F32)
 
 
+@pytest.mark.parametrize("dA,dG", PRECOND_CASES + [(1000, 300), (4, 1)])
 @pytest.mark.parametrize("bf16", [False, True])
-def test_precondition_batched_with_gradient_scaling(ctx, bf16):
+def test_precondition_split_f16_matches_oracle(ctx, dA, dG, bf16):
+    """The same step with the GEMM chain on the split-fp16 engine (operands of any extent and alignment, per-layer
+    power-of-two scales from the gradient's and V2's Frobenius norms), to the same bar as the fp32 chain; a
+    gradient scaled far outside fp16's range (1e-9, 1e+6) must come out the same, and a zero gradient stays zero."""
+    rng = np.random.default_rng(8)
+    A = gram_factor(dA, 3 * dA, seed=dA).astype(np.float64)
+    G = oracle.gram(rng.standard_normal((3 * dG, dG)) * 1e-2, 0, 1.0 / (3 * dG))
+    lamA, QA = oracle.eigh(A)
+    lamG, QG = oracle.eigh(G)
+    gamma = 1e-3 * lamA.mean() * lamG.mean()
+    dev = [ctx.to_dev(QA.astype(np.float32)), ctx.to_dev(lamA.astype(np.float32)),
+           ctx.to_dev(QG.astype(np.float32)), ctx.to_dev(lamG.astype(np.float32))]
+    for mag in (1e-2, 1e-9, 1e6, 0.0):
+        grad = (rng.standard_normal((dG, dA)) * mag).astype(np.float32)
+        if bf16:
+            grad = S.bf16_bits_to_f32(S.to_bf16_bits(grad)).reshape(grad.shape)
+        ref = oracle.precondition(QA, lamA, QG, lamG, gamma, grad)
+        gd = ctx.to_dev(grad, bf16)
+        K.kfac_precondition_batched(ctx.h, [dev[0]], [dev[1]], [dev[2]], [dev[3]], gamma, [gd], split_f16=True)
+        torch.cuda.synchronize()
+        got = gd.float().cpu().numpy()
+        assert np.isfinite(got).all()
+        if mag == 0.0:
+            assert not got.any()
+        else:
+            assert relfro(got, ref) <= (TOL_BF16 if bf16 else TOL_F32), (mag, relfro(got, ref))
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("split", [False, True])
+def test_precondition_batched_with_gradient_scaling(ctx, bf16, split):
     """Sec. V-B: the batched preconditioner followed by nu = min(1, sqrt(kappa / (lr^2 sum_l |<P_l, g_l>|))).
     Three layers of different tile counts (one tile, ragged tiles, several tiles) in one call, against the oracle
     end to end, against the oracle's nu on the library's own unscaled output, and with a kappa that does not clip."""
@@ -304,7 +335,7 @@ def test_precondition_batched_with_gradient_scaling(ctx, bf16):
     tol = TOL_BF16 if bf16 else TOL_F32
     # unscaled output of the library, for the same inputs
     plain = [ctx.to_dev(g, bf16) for g in grads]
-    K.kfac_precondition_batched(ctx.h, QAs, lAs, QGs, lGs, gamma, plain)
+    K.kfac_precondition_batched(ctx.h, QAs, lAs, QGs, lGs, gamma, plain, split_f16=split)
     torch.cuda.synchronize()
     plain = [p.float().cpu().numpy().astype(np.float64) for p in plain]
     lr = 0.1
@@ -312,7 +343,7 @@ def test_precondition_batched_with_gradient_scaling(ctx, bf16):
     for kappa, clipped in [(1e-3 * lr * lr * s_sum, True), (10.0 * lr * lr * s_sum, False)]:
         gd = [ctx.to_dev(g, bf16) for g in grads]
         nu_d = torch.full((1,), float("nan"), dtype=torch.float32, device=ctx.dev)
-        K.kfac_precondition_batched_scaled(ctx.h, QAs, lAs, QGs, lGs, gamma, gd, kappa, lr, nu_d)
+        K.kfac_precondition_batched_scaled(ctx.h, QAs, lAs, QGs, lGs, gamma, gd, kappa, lr, nu_d, split_f16=split)
         torch.cuda.synchronize()
         nu = float(nu_d.item())
         nu_own = oracle.grad_scale(plain, grads, kappa, lr)          # oracle formula on the library's own P_l
