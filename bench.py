@@ -126,6 +126,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the measurements that are not part of `value` (warm start, decoupled schedule, split-fp16 "
+                         "preconditioner): for short profiler runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every GPU box here has one GPU); "
@@ -186,7 +189,7 @@ def main():
     # what a training loop would do from its second decomposition on: start from the previous eigenvectors
     # (two more steps, each folding another batch into the factors; not part of `value`)
     warm_ms = []
-    for upd in (0, 1):
+    for upd in (() if args.no_extras else (0, 1)):
         run.update_factors(upd, wl.decay)
         e0, e1 = ev(), ev()
         e0.record()
@@ -195,13 +198,15 @@ def main():
         torch.cuda.synchronize()
         warm_ms.append(e0.elapsed_time(e1))
     warm_sweeps = max(s for (s, _, _) in run.eig_info)
+    if args.no_extras:
+        warm_ms, warm_sweeps = [0.0], None
 
     # the update-decoupled schedule (factors every 10 iterations, eigendecompositions every 100, preconditioning
     # every iteration) over 200 iterations, amortised; not part of `value`
     torch.cuda.synchronize()
     ts = time.perf_counter()
     n_fac = 0
-    for k in range(200):
+    for k in range(0 if args.no_extras else 200):
         do_f, do_e = K.kfac_schedule_due(k, 10, 100)
         if do_f:
             run.update_factors(n_fac % 2, wl.decay)
@@ -211,6 +216,17 @@ def main():
         run.precondition()
     torch.cuda.synchronize()
     sched_ms = (time.perf_counter() - ts) * 1e3 / 200
+
+    # the preconditioner with its GEMM chain on the split-fp16 engine (an option of the call; the default above is
+    # what the workload's gradient type selects: fp32 chain for fp32 gradients), five calls, best
+    split_ms = []
+    for _ in range(1 if args.no_extras else 5):
+        e0, e1 = ev(), ev()
+        e0.record()
+        run.precondition(split_f16=True)
+        e1.record()
+        torch.cuda.synchronize()
+        split_ms.append(e0.elapsed_time(e1))
 
     # one more, instrumented step: every kernel launch bracketed by hipEvents on the library's stream
     K.kfac_profile_begin(run.ctx)
@@ -237,15 +253,18 @@ def main():
     roofline = {k: roofline[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic",
                                          "launches", "avg_ms", "total_ms", "algorithmic_bytes_per_launch", "algorithmic_tflops") if k in roofline}
     w = run.work()
+    peak_syrk = PEAK_MFMA_F16 if wl.bf16 else PEAK_MFMA_F32     # bf16 samples run on the bf16 matrix instructions
     derived = {
         "syrk_tflops": round(w["syrk_flops"] / (phases["factors"] * 1e-3) / 1e12, 2),
-        "syrk_frac_of_mfma_peak": round(w["syrk_flops"] / (phases["factors"] * 1e-3) / PEAK_MFMA_F32, 4),
+        "syrk_frac_of_mfma_peak": round(w["syrk_flops"] / (phases["factors"] * 1e-3) / peak_syrk, 4),
         "precondition_tflops": round(w["precond_flops"] / (phases["precondition"] * 1e-3) / 1e12, 2),
         "precondition_frac_of_mfma_peak": round(w["precond_flops"] / (phases["precondition"] * 1e-3) / PEAK_MFMA_F32, 4),
         "eig_sum_d3_per_s": round(w["sum_d3"] / (phases["eig"] * 1e-3), 1),
         "eig_sweeps_max": max(sweeps), "eig_converged": "%d/%d" % (nconv, len(info)),
-        "eig_warm_start_ms": round(min(warm_ms), 3), "eig_warm_start_sweeps_max": warm_sweeps,
-        "decoupled_schedule_ms_per_iteration": round(sched_ms, 3),
+        "eig_warm_start_ms": None if args.no_extras else round(min(warm_ms), 3), "eig_warm_start_sweeps_max": warm_sweeps,
+        "decoupled_schedule_ms_per_iteration": None if args.no_extras else round(sched_ms, 3),
+        "precondition_split_f16_ms": round(min(split_ms), 3),
+        "precondition_split_f16_tflops": round(w["precond_flops"] / (min(split_ms) * 1e-3) / 1e12, 2),
     }
     out = {
         "metric": "kfac_step_ms", "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1,
