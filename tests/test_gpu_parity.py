@@ -72,6 +72,10 @@ FACTOR_CASES = [
     ("NDT", 9, 200, 9, 1),         # bf16 engine: every example ends in a group that overlaps the one before by 7
     ("NDT", 4, 130, 8, 0),         # bf16 engine: exactly one group per example
     ("NDT", 40, 257, 100, 1),      # bf16 engine: T = 12.5 groups, three tiles per side, contraction ends mid-slab
+    ("NDT", 6, 70, 4, 1),          # grouped engine, fp32: one group per example (bf16: element-wise engine, T < 8)
+    ("NDT", 6, 70, 7, 1),          # grouped engine, fp32: second group overlaps the first by one position
+    ("NDT", 3, 20, 15, 0),         # grouped engine: bf16 second group overlaps by one, fp32 fourth by one
+    ("NDT", 600, 129, 49, 1),      # T = 49 with split-K: several jobs per tile, column sums across splits, ragged tile
 ]
 
 
