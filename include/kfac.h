@@ -103,6 +103,17 @@ const char *kfac_strerror(int code);
  *   patches : [N][C*kh*kw][Ho*Wo] (KFAC_LAYOUT_NDT), same dtype, no bias row.  */
 int kfac_unfold(kfac_ctx *ctx, const kfac_conv_desc *desc, const void *x, void *patches);
 
+/* The same for n layers in one launch per element type (a network's late layers are a few microseconds of work
+ * each, which separate launches cannot fill the machine with):
+ *   descs   : HOST array of n descriptors
+ *   x       : HOST array of n device pointers, x[i] as for kfac_unfold() with descs[i]
+ *   patches : HOST array of n device pointers, distinct, patches[i] as for kfac_unfold()
+ * Uses kfac_unfold_workspace_bytes(n) bytes at the start of the context's workspace (a table that the launch
+ * reads; later calls on the same stream may overwrite it).  KFAC_EINVAL for any invalid layer: nothing is launched. */
+int kfac_unfold_batched(kfac_ctx *ctx, int n, const kfac_conv_desc *descs /* host */, const void *const *x /* host */,
+                        void *const *patches /* host */);
+size_t kfac_unfold_workspace_bytes(int n);
+
 /* Kronecker factor of a mini-batch folded into its running average (Sec. II-C: A = a a^T, G = g g^T
  * over the samples; Sec. IV-B: running average with parameter xi):
  *   F <- decay * F + (1 - decay) * scale * Xt^T Xt,   Xt = [X | 1] if append_ones else X

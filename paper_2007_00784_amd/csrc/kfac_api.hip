@@ -117,17 +117,33 @@ size_t kfac_workspace_bytes(int max_d, int max_batch_factors, int64_t max_R) {
     return kfac_align_up(need, 256);
 }
 
+static bool valid_conv_desc(const kfac_conv_desc &d) {
+    if (d.N < 1 || d.C < 1 || d.H < 1 || d.W < 1 || d.kh < 1 || d.kw < 1) return false;
+    if (d.stride_h < 1 || d.stride_w < 1 || d.pad_h < 0 || d.pad_w < 0) return false;
+    if (d.pad_h >= d.kh || d.pad_w >= d.kw) return false;  // every window must touch the image
+    if (d.H + 2 * d.pad_h < d.kh || d.W + 2 * d.pad_w < d.kw) return false;
+    if (!valid_dtype(d.dtype)) return false;
+    return (int64_t)d.C * d.kh * d.kw <= KFAC_MAX_D;
+}
+
 int kfac_unfold(kfac_ctx *ctx, const kfac_conv_desc *desc, const void *x, void *patches) {
     if (!ctx || !desc || !x || !patches || x == patches) return KFAC_EINVAL;
-    const kfac_conv_desc &d = *desc;
-    if (d.N < 1 || d.C < 1 || d.H < 1 || d.W < 1 || d.kh < 1 || d.kw < 1) return KFAC_EINVAL;
-    if (d.stride_h < 1 || d.stride_w < 1 || d.pad_h < 0 || d.pad_w < 0) return KFAC_EINVAL;
-    if (d.pad_h >= d.kh || d.pad_w >= d.kw) return KFAC_EINVAL;  // every window must touch the image
-    if (d.H + 2 * d.pad_h < d.kh || d.W + 2 * d.pad_w < d.kw) return KFAC_EINVAL;
-    if (!valid_dtype(d.dtype)) return KFAC_EINVAL;
-    if ((int64_t)d.C * d.kh * d.kw > KFAC_MAX_D) return KFAC_EINVAL;
+    if (!valid_conv_desc(*desc)) return KFAC_EINVAL;
     return kfac_launch_unfold(ctx, desc, x, patches);
 }
+
+int kfac_unfold_batched(kfac_ctx *ctx, int n, const kfac_conv_desc *descs, const void *const *x, void *const *patches) {
+    if (!ctx || n < 0 || (n > 0 && (!descs || !x || !patches))) return KFAC_EINVAL;
+    for (int i = 0; i < n; ++i) {
+        if (!x[i] || !patches[i] || x[i] == patches[i] || !valid_conv_desc(descs[i])) return KFAC_EINVAL;
+        for (int j = 0; j < i; ++j)
+            if (patches[j] == patches[i]) return KFAC_EINVAL;
+    }
+    if (n == 0) return KFAC_OK;
+    return kfac_launch_unfold_batched(ctx, n, descs, x, patches);
+}
+
+size_t kfac_unfold_workspace_bytes(int n) { return n > 0 ? kfac_unfold_ws_bytes_impl(n) : 0; }
 
 static bool valid_factor_item(const kfac_factor_item &it, bool pointers) {
     if (pointers && (!it.X || !it.F || (const void *)it.F == it.X)) return false;

@@ -71,6 +71,8 @@ constexpr int KFAC_MAX_D = 8192;
 
 // ---- launchers implemented in the kernel files (all enqueue on ctx->stream) ----
 int kfac_launch_unfold(kfac_ctx *ctx, const kfac_conv_desc *d, const void *x, void *patches);
+int kfac_launch_unfold_batched(kfac_ctx *ctx, int n, const kfac_conv_desc *descs, const void *const *x, void *const *patches);
+size_t kfac_unfold_ws_bytes_impl(int n);
 size_t kfac_syrk_workspace_bytes(int D, int64_t R);
 size_t kfac_syrk_ws_bytes_impl(int n, const kfac_factor_item *items);
 int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_item *items);

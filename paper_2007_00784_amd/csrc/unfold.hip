@@ -4,6 +4,8 @@
 // fixed example and channel the kh*kw patch rows are adjacent in the output, so a workgroup's
 // output is one contiguous run (full-height chunks) or kh*kw runs of whole output rows, and both
 // the global reads (along W) and the global writes (along Ho*Wo) are coalesced.
+#include <algorithm>
+#include <vector>
 #include "kfac_internal.h"
 
 namespace {
@@ -28,11 +30,10 @@ __device__ inline void fdivmod(int e, int d, float inv_d, int &q, int &r) {
 }
 
 template <typename E>
-__global__ __launch_bounds__(256) void unfold_kernel(const E *__restrict__ x, E *__restrict__ out, UnfoldArgs a) {
-    __shared__ E tile[UNFOLD_LDS_ELEMS];
-    const int n = blockIdx.z;
-    const int c0 = blockIdx.y * a.cpb;
-    const int ho0 = blockIdx.x * a.rows_out;
+__device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out, const UnfoldArgs &a, int bx, int by, int bz, E *tile) {
+    const int n = bz;
+    const int c0 = by * a.cpb;
+    const int ho0 = bx * a.rows_out;
     const int nch = min(a.cpb, a.C - c0);
     const int rows_out = min(a.rows_out, a.Ho - ho0);
     const int rows_in = (rows_out - 1) * a.sh + a.kh;
@@ -112,17 +113,48 @@ __global__ __launch_bounds__(256) void unfold_kernel(const E *__restrict__ x, E 
     }
 }
 
+template <typename E>
+__global__ __launch_bounds__(256) void unfold_kernel(const E *__restrict__ x, E *__restrict__ out, UnfoldArgs a) {
+    __shared__ E tile[UNFOLD_LDS_ELEMS];
+    unfold_block<E>(x, out, a, blockIdx.x, blockIdx.y, blockIdx.z, tile);
+}
+
+// Several layers in one launch: workgroup b belongs to the layer l with first[l] <= b < first[l+1] and is
+// workgroup (bx, by, bz) of that layer's own grid (gx, gy, gz), bx fastest.
+struct UnfoldItem {
+    const void *x;
+    void *out;
+    UnfoldArgs a;
+    int gx, gy;
+    int first;     // index of the layer's first workgroup in the launch
+};
+template <typename E>
+__global__ __launch_bounds__(256) void unfold_batched_kernel(const UnfoldItem *items, int n) {
+    __shared__ E tile[UNFOLD_LDS_ELEMS];
+    const int b = blockIdx.x;
+    int lo = 0, hi = n - 1;                 // last layer whose first workgroup is <= b
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (items[mid].first <= b) lo = mid; else hi = mid - 1;
+    }
+    const UnfoldItem &it = items[lo];
+    const int r = b - it.first;
+    const int bx = r % it.gx, t = r / it.gx;
+    unfold_block<E>((const E *)it.x, (E *)it.out, it.a, bx, t % it.gy, t / it.gy, tile);
+}
+
 }  // namespace
 
-int kfac_launch_unfold(kfac_ctx *ctx, const kfac_conv_desc *d, const void *x, void *patches) {
-    UnfoldArgs a;
+namespace {
+// Tiling of one layer: fills `a` and the grid; false when the shape does not fit the kernel's limits.
+bool plan_unfold(const kfac_conv_desc *d, UnfoldArgs &a, dim3 &grid) {
     a.N = d->N; a.C = d->C; a.H = d->H; a.W = d->W; a.kh = d->kh; a.kw = d->kw;
     a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w;
     a.Ho = (d->H + 2 * d->pad_h - d->kh) / d->stride_h + 1;
     a.Wo = (d->W + 2 * d->pad_w - d->kw) / d->stride_w + 1;
     a.Wp = d->W + 2 * d->pad_w;
     const int rows_in_full = (a.Ho - 1) * a.sh + a.kh;
-    if ((int64_t)d->kh * a.Wp > UNFOLD_LDS_ELEMS) return KFAC_EINVAL;  // one output row must fit
+    if ((int64_t)d->kh * a.Wp > UNFOLD_LDS_ELEMS) return false;  // one output row must fit
     if ((int64_t)rows_in_full * a.Wp <= UNFOLD_LDS_ELEMS) {
         a.rows_out = a.Ho;
         int cpb = UNFOLD_LDS_ELEMS / (rows_in_full * a.Wp);
@@ -139,23 +171,78 @@ int kfac_launch_unfold(kfac_ctx *ctx, const kfac_conv_desc *d, const void *x, vo
     }
     a.rows_in = (a.rows_out - 1) * a.sh + a.kh;
     // the flattened per-workgroup counters must stay exactly representable in fp32
-    if ((int64_t)a.cpb * a.kh * a.kw * a.rows_out * a.Wo >= (1 << 24)) return KFAC_EINVAL;
+    if ((int64_t)a.cpb * a.kh * a.kw * a.rows_out * a.Wo >= (1 << 24)) return false;
     a.inv_Wp = 1.0f / (float)a.Wp;
     a.inv_Wo = 1.0f / (float)a.Wo;
     a.inv_kw = 1.0f / (float)a.kw;
     a.inv_kh = 1.0f / (float)a.kh;
     a.inv_rows_in = 0.f;
     a.inv_Tc = 0.f;
-    const dim3 grid((a.Ho + a.rows_out - 1) / a.rows_out, (d->C + a.cpb - 1) / a.cpb, d->N);
-    if (grid.y > 65535 || grid.z > 65535) return KFAC_EINVAL;
+    grid = dim3((a.Ho + a.rows_out - 1) / a.rows_out, (d->C + a.cpb - 1) / a.cpb, d->N);
+    return grid.y <= 65535 && grid.z <= 65535;
+}
+double unfold_bytes(const kfac_conv_desc *d, const UnfoldArgs &a) {
     const double esz = d->dtype == KFAC_F32 ? 4.0 : 2.0;
-    KfacProfScope prof(ctx, KC_UNFOLD, 0.0,
-                       esz * ((double)d->N * d->C * d->H * d->W + (double)d->N * d->C * d->kh * d->kw * a.Ho * a.Wo));
+    return esz * ((double)d->N * d->C * d->H * d->W + (double)d->N * d->C * d->kh * d->kw * a.Ho * a.Wo);
+}
+}  // namespace
+
+int kfac_launch_unfold(kfac_ctx *ctx, const kfac_conv_desc *d, const void *x, void *patches) {
+    UnfoldArgs a;
+    dim3 grid;
+    if (!plan_unfold(d, a, grid)) return KFAC_EINVAL;
+    KfacProfScope prof(ctx, KC_UNFOLD, 0.0, unfold_bytes(d, a));
     if (d->dtype == KFAC_F32)
         hipLaunchKernelGGL(unfold_kernel<float>, grid, dim3(256), 0, ctx->stream, (const float *)x, (float *)patches, a);
     else
         hipLaunchKernelGGL(unfold_kernel<unsigned short>, grid, dim3(256), 0, ctx->stream,
                            (const unsigned short *)x, (unsigned short *)patches, a);
+    KFAC_HIP_CHECK(hipGetLastError());
+    return KFAC_OK;
+}
+
+size_t kfac_unfold_ws_bytes_impl(int n) { return kfac_align_up((size_t)n * sizeof(UnfoldItem), 256); }
+
+// All layers of one element type in one launch (two launches for a mixed batch), largest layers first.
+int kfac_launch_unfold_batched(kfac_ctx *ctx, int n, const kfac_conv_desc *descs, const void *const *x, void *const *patches) {
+    if (kfac_unfold_ws_bytes_impl(n) > ctx->ws_bytes) return KFAC_EWORKSPACE;
+    std::vector<UnfoldItem> items[2];
+    double bytes[2] = {0.0, 0.0};
+    std::vector<int> order(n);
+    std::vector<int64_t> work(n);
+    for (int i = 0; i < n; ++i) {
+        order[i] = i;
+        work[i] = (int64_t)descs[i].N * descs[i].C * descs[i].kh * descs[i].kw * descs[i].H * descs[i].W;
+    }
+    std::stable_sort(order.begin(), order.end(), [&](int p, int q) { return work[p] > work[q]; });
+    int64_t total[2] = {0, 0};
+    for (int i : order) {
+        UnfoldItem it;
+        dim3 grid;
+        if (!plan_unfold(&descs[i], it.a, grid)) return KFAC_EINVAL;
+        const int f = descs[i].dtype == KFAC_F32 ? 0 : 1;
+        it.x = x[i];
+        it.out = patches[i];
+        it.gx = (int)grid.x;
+        it.gy = (int)grid.y;
+        if (total[f] + (int64_t)grid.x * grid.y * grid.z >= ((int64_t)1 << 31)) return KFAC_EINVAL;
+        it.first = (int)total[f];
+        total[f] += (int64_t)grid.x * grid.y * grid.z;
+        bytes[f] += unfold_bytes(&descs[i], it.a);
+        items[f].push_back(it);
+    }
+    UnfoldItem *d_items = (UnfoldItem *)ctx->ws;
+    size_t at = 0;
+    for (int f = 0; f < 2; ++f) {
+        if (items[f].empty()) continue;
+        KFAC_HIP_CHECK(hipMemcpyAsync(d_items + at, items[f].data(), items[f].size() * sizeof(UnfoldItem), hipMemcpyHostToDevice, ctx->stream));
+        KfacProfScope prof(ctx, KC_UNFOLD, 0.0, bytes[f]);
+        if (f == 0)
+            hipLaunchKernelGGL(unfold_batched_kernel<float>, dim3((unsigned)total[f]), dim3(256), 0, ctx->stream, d_items + at, (int)items[f].size());
+        else
+            hipLaunchKernelGGL(unfold_batched_kernel<unsigned short>, dim3((unsigned)total[f]), dim3(256), 0, ctx->stream, d_items + at, (int)items[f].size());
+        at += items[f].size();
+    }
     KFAC_HIP_CHECK(hipGetLastError());
     return KFAC_OK;
 }

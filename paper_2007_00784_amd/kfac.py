@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libkfac_hip.so")
 
 EXPORTS = (
     "kfac_create", "kfac_destroy", "kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
-    "kfac_unfold", "kfac_update_factors", "kfac_eig", "kfac_precondition", "kfac_schedule_due",
+    "kfac_unfold", "kfac_unfold_batched", "kfac_unfold_workspace_bytes", "kfac_update_factors", "kfac_eig", "kfac_precondition", "kfac_schedule_due",
     "kfac_profile_begin", "kfac_profile_end", "kfac_precondition_batched", "kfac_precondition_workspace_bytes",
     "kfac_update_factors_batched", "kfac_update_factors_workspace_bytes", "kfac_precondition_batched_scaled",
 )
@@ -82,6 +82,9 @@ def lib():
     L.kfac_strerror.argtypes = [i]
     L.kfac_strerror.restype = ctypes.c_char_p
     L.kfac_unfold.argtypes = [vp, ctypes.POINTER(kfac_conv_desc), vp, vp]
+    L.kfac_unfold_batched.argtypes = [vp, i, ctypes.POINTER(kfac_conv_desc), ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    L.kfac_unfold_workspace_bytes.argtypes = [i]
+    L.kfac_unfold_workspace_bytes.restype = sz
     L.kfac_update_factors.argtypes = [vp, vp, i, i, i, i, i, i, f, f, vp]
     L.kfac_eig.argtypes = [vp, i, ctypes.POINTER(vp), ip, ctypes.POINTER(vp), ctypes.POINTER(vp),
                            ctypes.POINTER(kfac_eig_opts), ctypes.POINTER(kfac_eig_info)]
@@ -98,7 +101,8 @@ def lib():
     L.kfac_profile_end.argtypes = [vp, ctypes.POINTER(kfac_kernel_stat), i, ip]
     for name in EXPORTS:
         if name not in ("kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
-                        "kfac_precondition_workspace_bytes", "kfac_update_factors_workspace_bytes"):
+                        "kfac_precondition_workspace_bytes", "kfac_update_factors_workspace_bytes",
+                        "kfac_unfold_workspace_bytes"):
             getattr(L, name).restype = i
     _lib = L
     return L
@@ -164,6 +168,24 @@ def kfac_unfold(ctx, x, kh, kw, stride, pad, patches):
     ph, pw = (pad, pad) if isinstance(pad, int) else pad
     d = kfac_conv_desc(N, C, H, W, kh, kw, sh, sw, ph, pw, _dtype_code(x))
     _check(lib().kfac_unfold(ctx, ctypes.byref(d), _ptr(x), _ptr(patches)), "kfac_unfold")
+
+
+def kfac_unfold_batched(ctx, xs, convs, patches):
+    """xs: list of [N,C,H,W] device tensors; convs: list of (kh, kw, stride, pad); patches: list of outputs."""
+    n = len(xs)
+    descs = (kfac_conv_desc * n)()
+    for j, (x, (kh, kw, stride, pad)) in enumerate(zip(xs, convs)):
+        N, C, H, W = x.shape
+        sh, sw = (stride, stride) if isinstance(stride, int) else stride
+        ph, pw = (pad, pad) if isinstance(pad, int) else pad
+        descs[j] = kfac_conv_desc(N, C, H, W, kh, kw, sh, sw, ph, pw, _dtype_code(x))
+    xp = (ctypes.c_void_p * n)(*[_ptr(x) for x in xs])
+    pp = (ctypes.c_void_p * n)(*[_ptr(p) for p in patches])
+    _check(lib().kfac_unfold_batched(ctx, n, descs, xp, pp), "kfac_unfold_batched")
+
+
+def kfac_unfold_workspace_bytes(n):
+    return int(lib().kfac_unfold_workspace_bytes(int(n)))
 
 
 def kfac_update_factors(ctx, X, layout, N, d, T, append_ones, scale, decay, F, dtype=None):

@@ -93,8 +93,14 @@ class KfacRunner:
         return items
 
     def update_factors(self, upd, decay, batched=True):
-        for i, l in enumerate(self.layers):
-            if l.needs_unfold:
+        idx = [i for i, l in enumerate(self.layers) if l.needs_unfold]
+        if batched and idx:
+            K.kfac_unfold_batched(self.ctx, [self.x[upd][i] for i in idx],
+                                  [(self.layers[i].k, self.layers[i].k, self.layers[i].stride, self.layers[i].pad) for i in idx],
+                                  [self.patches[i] for i in idx])
+        else:
+            for i in idx:
+                l = self.layers[i]
                 K.kfac_unfold(self.ctx, self.x[upd][i], l.k, l.k, l.stride, l.pad, self.patches[i])
         items = self._factor_items(upd, decay)
         if batched:

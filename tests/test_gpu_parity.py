@@ -79,6 +79,32 @@ FACTOR_CASES = [
 ]
 
 
+def test_unfold_batched_bit_exact(ctx):
+    """Every unfold case, fp32 and bf16 mixed, in one batched call (one launch per element type; a workgroup finds
+    its layer by binary search over the layers' first workgroup indices), bit-exact against the oracle; an empty
+    batch is a no-op and two layers writing the same output are rejected."""
+    rng = np.random.default_rng(3)
+    K.kfac_unfold_batched(ctx.h, [], [], [])
+    xs, convs, outs, refs = [], [], [], []
+    for (N, C, H, k, s, p) in UNFOLD_CASES:
+        for bf16 in (False, True):
+            x = rng.standard_normal((N, C, H, H)).astype(np.float32)
+            if bf16:
+                x = S.bf16_bits_to_f32(S.to_bf16_bits(x)).reshape(x.shape)
+            Ho = (H + 2 * p - k) // s + 1
+            xd = ctx.to_dev(x, bf16)
+            xs.append(xd); convs.append((k, k, s, p))
+            outs.append(torch.full((N, C * k * k, Ho * Ho), float("nan"), dtype=xd.dtype, device=ctx.dev))
+            refs.append(oracle.unfold(x, k, k, s, s, p, p))
+    assert K.kfac_unfold_workspace_bytes(len(xs)) <= ctx.ws.numel()
+    K.kfac_unfold_batched(ctx.h, xs, convs, outs)
+    torch.cuda.synchronize()
+    for o, ref in zip(outs, refs):
+        assert np.array_equal(ndt_to_rows(o.float().cpu().numpy()), ref)
+    with pytest.raises(K.KfacError):
+        K.kfac_unfold_batched(ctx.h, xs[:2], convs[:2], [outs[0], outs[0]])
+
+
 @pytest.mark.parametrize("case", FACTOR_CASES)
 @pytest.mark.parametrize("bf16", [False, True])
 def test_update_factors_matches_oracle(ctx, case, bf16):
