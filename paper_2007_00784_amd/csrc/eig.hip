@@ -1444,6 +1444,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         }
     }
     // state per group: waiting for norms (post == 0) or for its post-processing (post == 1)
+    const auto t_start = std::chrono::steady_clock::now();
     std::vector<char> post(runs.size(), 0);
     size_t remaining = runs.size();
     while (remaining > 0) {
@@ -1455,7 +1456,14 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             if (q == hipErrorNotReady) continue;
             if (q != hipSuccess) return KFAC_EHIP;
             progressed = true;
-            if (post[gi]) { r.done = true; --remaining; continue; }
+            if (post[gi]) {
+                r.done = true;
+                --remaining;
+                if (getenv("KFAC_EIG_TRACE"))
+                    fprintf(stderr, "[kfac_eig] group nblk=%d (%d factors, stream %d) finished at %.1f ms\n", r.plan->nblk, r.nm,
+                            (int)stream_of[gi], std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count());
+                continue;
+            }
             bool all = true;
             for (int i = 0; i < r.nm; ++i) {
                 const double o2 = r.h_norms[2 * i], n2 = o2 + r.h_norms[2 * i + 1];
