@@ -121,6 +121,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
     __shared__ TileSmem sm;
     __shared__ float cs[BM];
     const SyrkJob job = jobs[blockIdx.x];
+    if (job.item < 0) return;   // padding of the launch order
     const SyrkArgs g = items[job.item];
     int ti, tj;
     tri_decode(job.tri, ti, tj);
@@ -153,6 +154,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
     GrpSmem &sm = *reinterpret_cast<GrpSmem *>(smem);
     float *cs = reinterpret_cast<float *>(smem + sizeof(GrpSmem));
     const SyrkJob job = jobs[blockIdx.x];
+    if (job.item < 0) return;   // padding of the launch order
     const SyrkArgs g = items[job.item];
     int ti, tj;
     tri_decode(job.tri, ti, tj);
@@ -252,6 +254,7 @@ void plan_single(int d, int64_t R, int slab, double fixed, int &ntri, int &nspli
 // In a batch the other factors fill the machine, so a factor is cut into jobs of about JOB_SLABS slabs
 // each: long enough to amortise a job's fixed cost and its 64 KB partial, short enough that the longest
 // job is a small part of the launch.
+constexpr int XCD_PAD = 8 * 16;   // no-op jobs that the XCD-aware launch order may add to one operand form
 constexpr int JOB_SLABS = 512;
 constexpr int JOB_SLABS_GRP_F32 = 256;   // grouped engine, fp32: slabs of 32 sample rows
 constexpr int JOB_SLABS_GRP_B16 = 256;   // grouped engine, bf16: slabs of 64 sample rows
@@ -303,9 +306,55 @@ size_t layout(int n, const kfac_factor_item *items, size_t &off_jobs, size_t &of
         }
     }
     off_jobs = kfac_align_up((size_t)n * sizeof(SyrkArgs), 256);
-    off_rjobs = off_jobs + kfac_align_up(njobs * sizeof(SyrkJob), 256);
+    off_rjobs = off_jobs + kfac_align_up((njobs + NFORM * XCD_PAD) * sizeof(SyrkJob), 256);   // + padding of the XCD order
     off_part = off_rjobs + kfac_align_up(nrjobs * sizeof(SyrkJob), 256);
     return off_part + part * sizeof(float);
+}
+
+// Launch order of one operand form.  Workgroups go round the 8 XCDs (workgroup b runs on XCD b % 8), each with its
+// own L2.  Tiles that share operand panels -- the tiles of one 4 x 4 block of tiles of one K range of one factor:
+// 16 tiles, 8 panels -- are therefore placed 8 apart, one after the other on the same XCD, where they run at the
+// same time and fetch each panel from memory once instead of once per tile.  Blocks are dealt to the XCD whose list
+// is shortest; lists are padded to equal length with no-op jobs (item -1) so that the positions stay aligned.
+constexpr int XCDS = 8, SUPER = 4;
+void xcd_order(std::vector<SyrkJob> &jobs) {
+    if (jobs.size() < 2 * XCDS) return;
+    std::vector<SyrkJob> lists[XCDS];
+    auto tile_of = [](int tri, int &ti, int &tj) {
+        int t = (int)((std::sqrt(8.0 * tri + 1.0) - 1.0) * 0.5);
+        while ((t + 1) * (t + 2) / 2 <= tri) ++t;
+        while (t * (t + 1) / 2 > tri) --t;
+        ti = t;
+        tj = tri - t * (t + 1) / 2;
+    };
+    size_t i = 0;
+    while (i < jobs.size()) {
+        // the jobs of one (factor, K range) are contiguous; cut them into blocks of SUPER x SUPER tiles
+        size_t e = i;
+        while (e < jobs.size() && jobs[e].item == jobs[i].item && jobs[e].split == jobs[i].split) ++e;
+        std::vector<std::pair<int, SyrkJob>> keyed;
+        keyed.reserve(e - i);
+        for (size_t k = i; k < e; ++k) {
+            int ti, tj;
+            tile_of(jobs[k].tri, ti, tj);
+            keyed.push_back({(ti / SUPER) * 4096 + tj / SUPER, jobs[k]});
+        }
+        std::stable_sort(keyed.begin(), keyed.end(), [](const std::pair<int, SyrkJob> &a, const std::pair<int, SyrkJob> &b) { return a.first < b.first; });
+        size_t k = 0;
+        while (k < keyed.size()) {
+            size_t ke = k;
+            while (ke < keyed.size() && keyed[ke].first == keyed[k].first) ++ke;
+            int best = 0;
+            for (int x = 1; x < XCDS; ++x) if (lists[x].size() < lists[best].size()) best = x;
+            for (; k < ke; ++k) lists[best].push_back(keyed[k].second);
+        }
+        i = e;
+    }
+    size_t len = 0;
+    for (auto &l : lists) len = std::max(len, l.size());
+    jobs.assign(len * XCDS, SyrkJob{-1, 0, 0});
+    for (int x = 0; x < XCDS; ++x)
+        for (size_t k = 0; k < lists[x].size(); ++k) jobs[k * XCDS + x] = lists[x][k];
 }
 
 template <class Op>
@@ -359,8 +408,10 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
         g.partial = part;
         if (g.nsplit > 1) part += (size_t)g.nsplit * g.ntri * PART;
         const int form = form_of(it);
-        for (int t = 0; t < g.ntri; ++t)
-            for (int sp = 0; sp < g.nsplit; ++sp) jobs[form].push_back(SyrkJob{i, t, sp});
+        // all tiles of one K range next to one another: they run at the same time and share their operand panels
+        // in L2 and the Infinity Cache instead of each fetching them from memory
+        for (int sp = 0; sp < g.nsplit; ++sp)
+            for (int t = 0; t < g.ntri; ++t) jobs[form].push_back(SyrkJob{i, t, sp});
         if (g.nsplit > 1)
             for (int t = 0; t < g.ntri; ++t) rjobs.push_back(SyrkJob{i, t, 0});
         // useful flops of the symmetric update R*D*(D+1); bytes: the samples once, F read (if averaged) and written
@@ -376,6 +427,7 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
     size_t at[NFORM], pos = 0;
     for (int f = 0; f < NFORM; ++f) {
         std::stable_sort(jobs[f].begin(), jobs[f].end(), [&](const SyrkJob &a, const SyrkJob &b) { return args[a.item].kchunk > args[b.item].kchunk; });
+        xcd_order(jobs[f]);
         at[f] = pos;
         if (!jobs[f].empty())
             KFAC_HIP_CHECK(hipMemcpyAsync(d_jobs + pos, jobs[f].data(), jobs[f].size() * sizeof(SyrkJob), hipMemcpyHostToDevice, ctx->stream));
