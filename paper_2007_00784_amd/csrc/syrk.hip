@@ -1,8 +1,10 @@
 // Kronecker-factor update: F <- decay*F + (1-decay)*scale * Xt^T Xt  (Sec. II-C factors, Sec. IV-B
-// running average).  The Gram matrix is a symmetric rank-R update on the fp32 MFMA engine: only the
+// running average).  The Gram matrix is a symmetric rank-R update on the matrix cores: only the
 // lower-triangular 128x128 tiles of X^T X are computed and mirrored, the contraction over the sample
 // rows is split across workgroups when there are few tiles, and the running average is applied where
-// the final sum is formed (the SYRK epilogue, or the fixed-order split reducer).
+// the final sum is formed (the SYRK epilogue, or the fixed-order split reducer).  Samples in [N][d][T]
+// layout (every conv factor) run on the grouped-load engine -- fp32 MFMAs for fp32 samples, bf16 MFMAs
+// for bf16 ones -- the rest ([R][d] layout, T below one 16-byte group) on the element-wise fp32 engine.
 //
 // The appended ones column is not materialised and costs no MFMA tile: its row of the factor is the
 // vector of column sums of X, which every diagonal tile accumulates for its own 128 columns from the
