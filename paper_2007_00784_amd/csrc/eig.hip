@@ -1474,7 +1474,8 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
                 all &= c;
             }
             if (getenv("KFAC_EIG_TRACE")) {   // debugging aid: the convergence history on stderr
-                fprintf(stderr, "[kfac_eig] group nblk=%d sweep %d off/norm:", r.plan->nblk, r.sweep);
+                fprintf(stderr, "[kfac_eig] %.1f ms group nblk=%d sweep %d off/norm:",
+                        std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count(), r.plan->nblk, r.sweep);
                 for (int i = 0; i < r.nm; ++i) fprintf(stderr, " %.2e", r.offrel[i]);
                 fprintf(stderr, "\n");
             }
