@@ -238,4 +238,89 @@ __device__ inline void gemm_tile_grouped(GrpOpNDT<E> &A, GrpOpNDT<E> &B, int i0,
     __syncthreads();   // callers reuse the slab buffers
 }
 
+// The single (diagonal) tile of a factor with at most 64 rows.  A 128 x 128 tile would spend three quarters of its
+// MFMAs on rows and columns that do not exist; here all four waves compute the same 64 x 64 block, each over a
+// quarter of every slab (k-step `wave`), and the four partial sums are added through LDS at the end.  On return
+// wave 0 holds the block in the usual accumulator layout and the other waves hold zeros.
+template <typename E, bool COLSUM>
+__device__ inline void gemm_tile_grouped_small(GrpOpNDT<E> &A, int q0, int q_end, GrpSmem &sm, floatx16 (&acc)[2][2], float *csum) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int lk = lane >> 5, lc = lane & 31;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const int nslab = (q_end - q0 + GRP_GROUPS - 1) / GRP_GROUPS;
+    if (nslab <= 0) return;
+    A.q_end = q_end;
+    A.start(tid, 0, q0);
+    int sha = A.issue(sm.a[0], tid);
+    const int swz = (lc >> 1) & 7;
+    for (int s = 0; s < nslab; ++s) {
+        const int cur = s & 1;
+        grp_wait_loads();
+        A.patch(sm.a[cur], tid, sha);
+        if (COLSUM) {
+#pragma unroll
+            for (int u = 0; u < GRP_RPT; ++u) csum[u] += GrpOpNDT<E>::landed_sum(sm.a[cur], tid, u);
+        }
+        __syncthreads();
+        uint4 f[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            f[i] = *reinterpret_cast<const uint4 *>(sm.a[cur] + (32 * i + lc) * GRP_ROWB + (((2 * wave + lk) ^ swz) * 16));
+        __builtin_amdgcn_sched_barrier(0);
+        if (s + 1 < nslab) {
+            A.next();
+            sha = A.issue(sm.a[cur ^ 1], tid);
+        }
+        if (sizeof(E) == 4) {
+            const unsigned a[2][4] = {{f[0].x, f[0].y, f[0].z, f[0].w}, {f[1].x, f[1].y, f[1].z, f[1].w}};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[i][e]), __uint_as_float(a[j][e]), acc[i][j], 0, 0, 0);
+        } else {
+            bf16x8 x[2];
+            __builtin_memcpy(&x[0], &f[0], 16);
+            __builtin_memcpy(&x[1], &f[1], 16);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[i], x[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+    float *scratch = reinterpret_cast<float *>(&sm);   // 3 waves x 64 values x 64 lanes = 48 KB of the 64 KB
+    if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    scratch[(((wave - 1) * 64) + (i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+                    acc[i][j][r] = 0.f;
+                }
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += scratch[((w * 64) + (i * 2 + j) * 16 + r) * 64 + lane];
+    }
+    __syncthreads();   // callers reuse the slab buffers
+}
+
 }  // namespace kfac

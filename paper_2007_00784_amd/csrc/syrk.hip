@@ -169,7 +169,10 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
     float csum[GRP_RPT];
 #pragma unroll
     for (int u = 0; u < GRP_RPT; ++u) csum[u] = 0.f;
-    if (want_cs) gemm_tile_grouped<E, true, true>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
+    if (g.d <= 64) {   // one tile, a quarter of it in use: contraction split over the waves instead
+        if (want_cs) gemm_tile_grouped_small<E, true>(a, q0, q_end, sm, acc, csum);
+        else gemm_tile_grouped_small<E, false>(a, q0, q_end, sm, acc, csum);
+    } else if (want_cs) gemm_tile_grouped<E, true, true>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
     else if (diag) gemm_tile_grouped<E, true, false>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
     else gemm_tile_grouped<E, false, false>(a, b, ti * BM, tj * BM, q0, q_end, sm, acc, csum);
     if (want_cs) {   // the K loop ended on a barrier, so the slab buffers are free: sum the eight threads of a row in order
