@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkfac_hip.so")
 SOURCES = ["kfac_api.hip", "unfold.hip", "syrk.hip", "precondition.hip", "eig.hip"]
 FLAGS = os.environ.get("KFAC_EXTRA_FLAGS", "").split() + [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-munsafe-fp-atomics",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 VALU forms are disabled for all device code of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",

@@ -354,6 +354,14 @@ __global__ __launch_bounds__(NT) void eig_small_kernel(const SmallItem *items, E
     }
     __syncthreads();
     const JacobiResult res = jacobi_lds<0>(sm.S, sm.V, k, ld, max_sweeps, tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
+    if (!(res.nrm2 < INFINITY)) {
+        // non-finite input: nothing was rotated (every comparison with a NaN fails); say so in every output element
+        const float nan = __uint_as_float(0x7fc00000u);
+        for (int i = tid; i < n; i += NT) it.lam[i] = nan;
+        for (int e = tid; e < n * n; e += NT) it.Q[e] = nan;
+        if (tid == 0) stats[blockIdx.x] = EigStat{(float)res.sweeps, nan, 0.f, 0.f};
+        return;
+    }
     for (int i = tid; i < k; i += NT) sm.diag[i] = sm.S[i * ld + i];
     __syncthreads();
     if (res.rotations > 0) polish_lds_valu(sm.V, sm.S, k, ld);
@@ -438,12 +446,12 @@ __global__ __launch_bounds__(NT) void blk_symmetrise_kernel(float *W, int64_t ld
     }
 }
 
-__global__ void blk_zero_f64_kernel(double *p, int count) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) p[i] = 0.0;
-}
+// Squared Frobenius norms of the off-diagonal and of the diagonal part of every matrix of a group, in two
+// steps whose summation order is fixed (the eigenvalues' stopping decision is then the same run to run):
+// workgroup (b, m) leaves its share in part[m][b][2], one workgroup per matrix adds the shares in order.
+constexpr int NORM_PARTS_MAX = 512;
 
-__global__ __launch_bounds__(NT) void blk_offnorm_kernel(BlkGroup g) {
+__global__ __launch_bounds__(NT) void blk_offnorm_kernel(BlkGroup g, double *part) {
     __shared__ float red[8];
     const int m = blockIdx.y;
     const int64_t np2 = (int64_t)g.npad * g.npad;
@@ -457,17 +465,34 @@ __global__ __launch_bounds__(NT) void blk_offnorm_kernel(BlkGroup g) {
     o2 = block_sum(o2, red);
     d2 = block_sum(d2, red);
     if (threadIdx.x == 0) {
-        atomicAdd(&g.norms[2 * m], (double)o2);
-        atomicAdd(&g.norms[2 * m + 1], (double)d2);
+        double *dst = part + ((int64_t)m * gridDim.x + blockIdx.x) * 2;
+        dst[0] = (double)o2;
+        dst[1] = (double)d2;
     }
 }
 
-// done[m] = the factor met the tolerance (same test, on the same sums, as the host's).
-__global__ void blk_flag_kernel(const double *norms, int *done, int nmat, double tol2) {
-    const int m = blockIdx.x * blockDim.x + threadIdx.x;
-    if (m >= nmat) return;
-    const double o2 = norms[2 * m], n2 = o2 + norms[2 * m + 1];
-    done[m] = (o2 <= tol2 * n2) ? 1 : 0;
+// norms[m] = (off^2, diag^2) from the nparts shares of matrix m; done[m] = 1 when the factor has met the
+// tolerance (the host applies the same test to the same sums) or its norms are not finite (nothing more
+// can be done for it: its workgroups return at once from then on).
+__global__ __launch_bounds__(NT) void blk_norm_reduce_kernel(const double *part, int nparts, double *norms, int *done, double tol2) {
+    __shared__ double so[NT], sd[NT];
+    const int m = blockIdx.x, t = threadIdx.x;
+    const double *src = part + (int64_t)m * nparts * 2;
+    double o = 0.0, d = 0.0;
+    for (int i = t; i < nparts; i += NT) { o += src[2 * i]; d += src[2 * i + 1]; }
+    so[t] = o;
+    sd[t] = d;
+    __syncthreads();
+    for (int w = NT / 2; w > 0; w >>= 1) {
+        if (t < w) { so[t] += so[t + w]; sd[t] += sd[t + w]; }
+        __syncthreads();
+    }
+    if (t == 0) {
+        const double o2 = so[0], n2 = so[0] + sd[0];
+        norms[2 * m] = o2;
+        norms[2 * m + 1] = sd[0];
+        done[m] = !(o2 > tol2 * n2) ? 1 : 0;
+    }
 }
 
 // Row/column index in the padded matrix of element a (0..KP-1) of the pair (p, q); -1 if the block is
@@ -689,16 +714,25 @@ struct EpiNewtonSchulz {
     __device__ void operator()(int r, int c, float v) const { Y[(int64_t)r * ld + c] = (r == c ? 1.5f : 0.f) - 0.5f * v; }
 };
 
-// Rayleigh quotients lam[i] = q_i^T (F q_i) from Q [n][ldq] and Z = F Q [n][ldz]; rows split over blockIdx.y.
+// Rayleigh quotients lam[i] = q_i^T (F q_i) from Q [n][ldq] and Z = F Q [n][ldz]: the rows are split over
+// blockIdx.y, whose shares land in part[y][i] and are added in order by the kernel below.
+constexpr int RAY_PARTS = 32;
 __global__ __launch_bounds__(NT) void blk_rayleigh_kernel(const float *Q, int64_t ldq, const float *Z, int64_t ldz,
-                                                          int n, double *lam64) {
+                                                          int n, double *part) {
     const int i = blockIdx.x * NT + threadIdx.x;
     if (i >= n) return;
     const int rows_per = (n + gridDim.y - 1) / gridDim.y;
     const int r0 = blockIdx.y * rows_per, r1 = min(n, r0 + rows_per);
     double s = 0.0;
     for (int r = r0; r < r1; ++r) s += (double)Q[(int64_t)r * ldq + i] * (double)Z[(int64_t)r * ldz + i];
-    atomicAdd(&lam64[i], s);
+    part[(int64_t)blockIdx.y * n + i] = s;
+}
+__global__ __launch_bounds__(NT) void blk_rayleigh_sum_kernel(const double *part, int n, double *lam64) {
+    const int i = blockIdx.x * NT + threadIdx.x;
+    if (i >= n) return;
+    double s = 0.0;
+    for (int y = 0; y < RAY_PARTS; ++y) s += part[(int64_t)y * n + i];
+    lam64[i] = s;
 }
 
 // perm[rank] = index of the rank-th smallest eigenvalue (ties by index); lam[rank] = that eigenvalue.
@@ -706,13 +740,19 @@ __global__ __launch_bounds__(NT) void blk_rank_kernel(const double *lam64, int n
     const int i = blockIdx.x * NT + threadIdx.x;
     if (i >= n) return;
     const float li = (float)lam64[i];
+    const bool nan_i = li != li;
     int rank = 0;
-    for (int j = 0; j < n; ++j) {
+    for (int j = 0; j < n; ++j) {       // NaNs order after every number, among themselves by index: always a permutation
         const float lj = (float)lam64[j];
-        rank += (lj < li) || (lj == li && j < i);
+        const bool nan_j = lj != lj;
+        rank += nan_i ? (!nan_j || j < i) : (!nan_j && ((lj < li) || (lj == li && j < i)));
     }
     perm[rank] = i;
     lam_out[rank] = li;
+}
+
+__global__ __launch_bounds__(NT) void blk_fill_kernel(float *dst, int64_t count, float v) {
+    for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < count; e += (int64_t)gridDim.x * NT) dst[e] = v;
 }
 
 __global__ __launch_bounds__(NT) void blk_copy_kernel(const float *src, float *dst, int64_t count) {
@@ -995,9 +1035,10 @@ struct GroupPlan {
             b += kfac_align_up(nm * (size_t)npairs * sizeof(int), 256);                            // idt
         }
         b += kfac_align_up(nm * 2 * sizeof(double), 256);                            // norms
+        b += kfac_align_up(nm * 2 * NORM_PARTS_MAX * sizeof(double), 256);           // their per-workgroup shares
         b += kfac_align_up(nm * sizeof(int), 256);                                   // done flags
         b += kfac_align_up(nm * (size_t)npad * sizeof(int), 256);                    // perm
-        b += kfac_align_up(nm * (size_t)npad * sizeof(double), 256);                 // Rayleigh quotients
+        b += kfac_align_up(nm * (size_t)npad * (RAY_PARTS + 1) * sizeof(double), 256);   // Rayleigh quotients and their shares
         b += kfac_align_up(nm * sizeof(BlkItem), 256);                               // items
         return b;
     }
@@ -1060,6 +1101,8 @@ struct GroupRun {
     BlkItem *d_items;
     int *perm;
     double *lam64;
+    double *normpart;     // [nm][norm_blocks][2]
+    int norm_blocks;
     double *h_norms;      // pinned, 2 per factor
     int nm, ntiles_w, nrb, ntiles, nmax, fill_blocks;
     double apply_flops, solve_flops;
@@ -1069,6 +1112,7 @@ struct GroupRun {
     int *d_done;          // device flags, one per factor
     double tol2;
     std::vector<char> conv;
+    std::vector<char> bad;        // norms not finite: the factor is given up (outputs filled with NaN)
     std::vector<int> sweeps_done;
     std::vector<float> offrel;
 };
@@ -1076,9 +1120,9 @@ struct GroupRun {
 int enqueue_offnorm(kfac_ctx *ctx, GroupRun &r) {
     {
         KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
-        hipLaunchKernelGGL(blk_zero_f64_kernel, dim3(1), dim3(256), 0, r.st, r.g.norms, 2 * r.nm);
-        hipLaunchKernelGGL(blk_offnorm_kernel, dim3(std::min(r.fill_blocks, 512), r.nm), dim3(NT), 0, r.st, r.g);
-        hipLaunchKernelGGL(blk_flag_kernel, dim3((r.nm + 63) / 64), dim3(64), 0, r.st, (const double *)r.g.norms, r.d_done, r.nm, r.tol2);
+        hipLaunchKernelGGL(blk_offnorm_kernel, dim3(r.norm_blocks, r.nm), dim3(NT), 0, r.st, r.g, r.normpart);
+        hipLaunchKernelGGL(blk_norm_reduce_kernel, dim3(r.nm), dim3(NT), 0, r.st, (const double *)r.normpart, r.norm_blocks, r.g.norms,
+                           r.d_done, r.tol2);
     }
     KFAC_HIP_CHECK(hipGetLastError());
     KFAC_HIP_CHECK(hipMemcpyAsync(r.h_norms, r.g.norms, 2 * r.nm * sizeof(double), hipMemcpyDeviceToHost, r.st));
@@ -1178,9 +1222,14 @@ int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
     const GroupPlan &gp = *r.plan;
     const size_t np2 = (size_t)gp.npad * gp.npad;
     hipStream_t st = r.st;
-    hipLaunchKernelGGL(blk_zero_f64_kernel, dim3((r.nm * gp.npad + 255) / 256), dim3(256), 0, st, r.lam64, r.nm * gp.npad);
     for (int i = 0; i < r.nm; ++i) {
         const int n = r.items[i].n;
+        if (r.bad[i]) {   // non-finite input: non-finite output
+            const float nan = std::nanf("");
+            hipLaunchKernelGGL(blk_fill_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, r.items[i].Q, (int64_t)n * n, nan);
+            hipLaunchKernelGGL(blk_fill_kernel, dim3(1), dim3(NT), 0, st, r.items[i].lam, (int64_t)n, nan);
+            continue;
+        }
         float *Wm = r.g.W + i * np2, *Qm = r.g.Qw + i * np2;
         const int64_t ld = gp.npad;
         const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
@@ -1204,11 +1253,12 @@ int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
             hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(qo_kn), EpiStore>), grid, block, 0, st,
                                f_mk, qo_kn, EpiStore{Qm, ld}, n, n, n);
         }
-        double *l64 = r.lam64 + (size_t)i * gp.npad;
+        double *l64 = r.lam64 + (size_t)i * gp.npad * (RAY_PARTS + 1), *lpart = l64 + gp.npad;
         int *pm = r.perm + (size_t)i * gp.npad;
         {
             KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
-            hipLaunchKernelGGL(blk_rayleigh_kernel, dim3((n + NT - 1) / NT, 32), dim3(NT), 0, st, r.items[i].Q, (int64_t)n, Qm, ld, n, l64);
+            hipLaunchKernelGGL(blk_rayleigh_kernel, dim3((n + NT - 1) / NT, RAY_PARTS), dim3(NT), 0, st, r.items[i].Q, (int64_t)n, Qm, ld, n, lpart);
+            hipLaunchKernelGGL(blk_rayleigh_sum_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, (const double *)lpart, n, l64);
             hipLaunchKernelGGL(blk_rank_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, l64, n, pm, r.items[i].lam);
         }
         {
@@ -1237,18 +1287,12 @@ size_t kfac_eig_ws_bytes_impl(int batch, const int *d) {
     return need;
 }
 
-int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,
-                    float *const *lam, const kfac_eig_opts *opts, kfac_eig_info *info) {
+// Everything between the fork onto the internal streams and the join back: may return early with an error, the
+// caller joins in every case.
+static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q, float *const *lam,
+                   const kfac_eig_opts *opts, kfac_eig_info *info, std::vector<int> &small, std::vector<GroupPlan> &groups) {
     const int max_sweeps = (opts && opts->max_sweeps > 0) ? opts->max_sweeps : 30;
     const float tol = (opts && opts->tol > 0.f) ? opts->tol : 2e-6f;
-    std::vector<int> small;
-    std::vector<GroupPlan> groups;
-    make_plan(batch, d, small, groups);
-    if (kfac_eig_ws_bytes_impl(batch, d) > ctx->ws_bytes) return KFAC_EWORKSPACE;
-    if (groups.size() > (size_t)KFAC_MAX_GROUPS) return KFAC_EINVAL;
-    size_t pinned_need = 0;
-    for (auto &gp : groups) pinned_need += 2 * gp.members.size() * sizeof(double);
-    if (pinned_need > ctx->pinned_bytes) return KFAC_EWORKSPACE;
     const bool fp32_outer = opts && opts->fp32_only != 0;
     const bool warm = opts && opts->warm_start != 0;
     const int inner_cap = 1;       // one Jacobi sweep over a pivot per visit: fewest total rotations
@@ -1260,19 +1304,18 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     }
     bool all_conv = true;
 
-    // the internal streams start after everything already queued on the caller's stream
-    KFAC_HIP_CHECK(hipEventRecord(ctx->ev_fork, ctx->stream));
-    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) KFAC_HIP_CHECK(hipStreamWaitEvent(ctx->aux[i], ctx->ev_fork, 0));
-
     char *wsp = ctx->ws;
+    // host tables and the statistics that come back live in the context's pinned memory (after the norms), so
+    // that no copy waits for the stream it is queued on
+    char *ptab = (char *)ctx->pinned + KFAC_PINNED_NORMS;
     // ---- small factors: one launch, on the last internal stream ----
-    std::vector<SmallItem> sitems;
-    std::vector<EigStat> sstats;
+    SmallItem *sitems = nullptr;
+    EigStat *sstats = nullptr;
     hipStream_t st_small = ctx->aux[KFAC_NUM_AUX_STREAMS - 1];
     if (!small.empty()) {
         const size_t ns = small.size();
-        sitems.resize(ns);
-        sstats.resize(ns);
+        sitems = (SmallItem *)ptab; ptab += kfac_align_up(ns * sizeof(SmallItem), 64);
+        sstats = (EigStat *)ptab; ptab += kfac_align_up(ns * sizeof(EigStat), 64);
         int kmax = 2;
         for (size_t i = 0; i < ns; ++i) {
             sitems[i] = SmallItem{F[small[i]], Q[small[i]], lam[small[i]], d[small[i]], 0};
@@ -1281,7 +1324,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         SmallItem *d_items = (SmallItem *)wsp;
         EigStat *d_stats = (EigStat *)(wsp + kfac_align_up(ns * sizeof(SmallItem), 256));
         wsp += small_bytes(ns);
-        KFAC_HIP_CHECK(hipMemcpyAsync(d_items, sitems.data(), ns * sizeof(SmallItem), hipMemcpyHostToDevice, st_small));
+        KFAC_HIP_CHECK(hipMemcpyAsync(d_items, sitems, ns * sizeof(SmallItem), hipMemcpyHostToDevice, st_small));
         const size_t lds = JacobiSmem::bytes(kmax, kmax + 1);
         if ((int)lds > ctx->max_lds) return KFAC_EHIP;
         KFAC_HIP_CHECK(hipFuncSetAttribute((const void *)eig_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -1290,7 +1333,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             hipLaunchKernelGGL(eig_small_kernel, dim3((unsigned)ns), dim3(NT), lds, st_small, d_items, d_stats, max_sweeps, tol);
         }
         KFAC_HIP_CHECK(hipGetLastError());
-        KFAC_HIP_CHECK(hipMemcpyAsync(sstats.data(), d_stats, ns * sizeof(EigStat), hipMemcpyDeviceToHost, st_small));
+        KFAC_HIP_CHECK(hipMemcpyAsync(sstats, d_stats, ns * sizeof(EigStat), hipMemcpyDeviceToHost, st_small));
     }
 
     // ---- blocked groups: set up, then drive them sweep by sweep as their norms arrive ----
@@ -1362,6 +1405,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
             g.idt = (int *)p; p += kfac_align_up((size_t)nm * gp.npairs * sizeof(int), 256);
         }
         g.norms = (double *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(double), 256);
+        r.normpart = (double *)p; p += kfac_align_up((size_t)nm * 2 * NORM_PARTS_MAX * sizeof(double), 256);
         int *done = (int *)p; p += kfac_align_up((size_t)nm * sizeof(int), 256);
         g.done = done;
         g.per_factor = 1;
@@ -1373,7 +1417,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         }
         KFAC_HIP_CHECK(hipMemsetAsync(done, 0, (size_t)nm * sizeof(int), r.st));
         r.perm = (int *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(int), 256);
-        r.lam64 = (double *)p; p += kfac_align_up((size_t)nm * gp.npad * sizeof(double), 256);
+        r.lam64 = (double *)p; p += kfac_align_up((size_t)nm * gp.npad * (RAY_PARTS + 1) * sizeof(double), 256);
         r.d_items = (BlkItem *)p;
         wsp += gp.bytes();
         r.h_norms = pinned;
@@ -1396,12 +1440,16 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         r.nrb = (r.nmax + KP - 1) / KP;
         r.ntiles = r.ntiles_w + r.nrb * gp.npairs;
         r.fill_blocks = (int)std::min<size_t>((np2 + NT - 1) / NT, 4096);
+        r.norm_blocks = std::min(r.fill_blocks, NORM_PARTS_MAX);
         r.sweep = 0;
         r.done = false;
         r.conv.assign(nm, 0);
+        r.bad.assign(nm, 0);
         r.sweeps_done.assign(nm, 0);
         r.offrel.assign(nm, 0.f);
-        KFAC_HIP_CHECK(hipMemcpyAsync(r.d_items, r.items.data(), nm * sizeof(BlkItem), hipMemcpyHostToDevice, r.st));
+        BlkItem *h_items = (BlkItem *)ptab; ptab += kfac_align_up(nm * sizeof(BlkItem), 64);
+        std::copy(r.items.begin(), r.items.end(), h_items);
+        KFAC_HIP_CHECK(hipMemcpyAsync(r.d_items, h_items, nm * sizeof(BlkItem), hipMemcpyHostToDevice, r.st));
         {
             KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
             hipLaunchKernelGGL(blk_init_kernel, dim3(r.fill_blocks, nm), dim3(NT), 0, r.st, g, r.d_items, warm ? 1 : 0);
@@ -1471,7 +1519,8 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
                 const bool c = o2 <= (double)tol * tol * n2;   // false for NaN
                 if (c && !r.conv[i]) r.sweeps_done[i] = r.sweep;
                 r.conv[i] = c;
-                all &= c;
+                r.bad[i] = !std::isfinite(n2);
+                all &= c || r.bad[i];
             }
             if (getenv("KFAC_EIG_TRACE")) {   // debugging aid: the convergence history on stderr
                 fprintf(stderr, "[kfac_eig] %.1f ms group nblk=%d sweep %d off/norm:",
@@ -1495,12 +1544,8 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         // that finishes its sweep earlier waiting for the host.)
         if (!progressed) std::this_thread::sleep_for(std::chrono::microseconds(20));
     }
-    // join: the caller's stream continues after all internal streams
-    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) {
-        KFAC_HIP_CHECK(hipEventRecord(ctx->ev_join[i], ctx->aux[i]));
-        KFAC_HIP_CHECK(hipStreamWaitEvent(ctx->stream, ctx->ev_join[i], 0));
-    }
-    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) KFAC_HIP_CHECK(hipStreamSynchronize(ctx->aux[i]));
+    // the statistics of the small factors are read below
+    KFAC_HIP_CHECK(hipStreamSynchronize(st_small));
 
     for (size_t i = 0; i < small.size(); ++i) {
         const bool conv = sstats[i].converged > 0.5f;
@@ -1518,4 +1563,33 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
         }
     }
     return all_conv ? KFAC_OK : KFAC_ENOCONV;
+}
+
+int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,
+                    float *const *lam, const kfac_eig_opts *opts, kfac_eig_info *info) {
+    std::vector<int> small;
+    std::vector<GroupPlan> groups;
+    make_plan(batch, d, small, groups);
+    if (kfac_eig_ws_bytes_impl(batch, d) > ctx->ws_bytes) return KFAC_EWORKSPACE;
+    if (groups.size() > (size_t)KFAC_MAX_GROUPS) return KFAC_EINVAL;
+    size_t norms_need = 0, tables_need = kfac_align_up(small.size() * sizeof(SmallItem), 64) + kfac_align_up(small.size() * sizeof(EigStat), 64);
+    for (auto &gp : groups) {
+        norms_need += 2 * gp.members.size() * sizeof(double);
+        tables_need += kfac_align_up(gp.members.size() * sizeof(BlkItem), 64);
+    }
+    if (norms_need > KFAC_PINNED_NORMS || tables_need > KFAC_PINNED_TABLES) return KFAC_EINVAL;   // more than 4096 factors
+    // the internal streams start after everything already queued on the caller's stream ...
+    KFAC_HIP_CHECK(hipEventRecord(ctx->ev_fork, ctx->stream));
+    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) KFAC_HIP_CHECK(hipStreamWaitEvent(ctx->aux[i], ctx->ev_fork, 0));
+    const int rc = eig_run(ctx, batch, F, d, Q, lam, opts, info, small, groups);
+    // ... and the caller's stream continues after all of them.  On an error, too: whatever was queued before it is
+    // waited for here, so no kernel of this call is in flight, and no pointer of the caller in use, after the return.
+    int jrc = KFAC_OK;
+    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) {
+        if (hipEventRecord(ctx->ev_join[i], ctx->aux[i]) != hipSuccess) jrc = KFAC_EHIP;
+        else if (hipStreamWaitEvent(ctx->stream, ctx->ev_join[i], 0) != hipSuccess) jrc = KFAC_EHIP;
+    }
+    for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i)
+        if (hipStreamSynchronize(ctx->aux[i]) != hipSuccess) jrc = KFAC_EHIP;
+    return (rc != KFAC_OK && rc != KFAC_ENOCONV) ? rc : (jrc != KFAC_OK ? jrc : rc);
 }

@@ -2,6 +2,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstring>
 #include <new>
 #include <string_view>
 #include <vector>
@@ -19,10 +20,44 @@ bool is_device_ptr(const void *p) {
         (void)hipGetLastError();
         return false;
     }
-    return a.type == hipMemoryTypeDevice || a.type == hipMemoryTypeManaged;
+    return a.type == hipMemoryTypeDevice;   // plain device memory only: no managed or host-mapped workspace
 }
 
 }  // namespace
+
+int kfac_upload(kfac_ctx *c, void *dst_dev, const void *src_host, size_t bytes) {
+    if (bytes == 0) return KFAC_OK;
+    const size_t half = c->stage_bytes / 2, need = kfac_align_up(bytes, 64);
+    if (need > half) {
+        KFAC_HIP_CHECK(hipMemcpyAsync(dst_dev, src_host, bytes, hipMemcpyHostToDevice, c->stream));
+        return KFAC_OK;
+    }
+    if (c->stage_off + need > half) {
+        // this half is full: mark where its last copy sits in the stream, move to the other half and wait until
+        // the copies issued from that one (a whole half ago) are through
+        KFAC_HIP_CHECK(hipEventRecord(c->stage_ev[c->stage_half], c->stream));
+        c->stage_used[c->stage_half] = true;
+        c->stage_half ^= 1;
+        c->stage_off = 0;
+        if (c->stage_used[c->stage_half]) KFAC_HIP_CHECK(hipEventSynchronize(c->stage_ev[c->stage_half]));
+    }
+    char *slot = c->stage + (size_t)c->stage_half * half + c->stage_off;
+    memcpy(slot, src_host, bytes);
+    c->stage_off += need;
+    KFAC_HIP_CHECK(hipMemcpyAsync(dst_dev, slot, bytes, hipMemcpyHostToDevice, c->stream));
+    return KFAC_OK;
+}
+
+bool kfac_valid_factor_item(const kfac_factor_item &it, bool pointers) {
+    if (pointers && (!it.X || !it.F || (const void *)it.F == it.X)) return false;
+    if (!valid_dtype(it.dtype) || (it.layout != KFAC_LAYOUT_RD && it.layout != KFAC_LAYOUT_NDT)) return false;
+    if (it.N < 1 || it.d < 1 || it.T < 1 || (it.append_ones != 0 && it.append_ones != 1)) return false;
+    if (it.d + it.append_ones > KFAC_MAX_D) return false;
+    if ((int64_t)it.N * it.T >= (int64_t)1 << 30) return false;
+    if ((int64_t)it.d * it.T >= (int64_t)1 << 31) return false;   // 32-bit offsets inside one example's slab
+    if (pointers && (!(it.decay >= 0.f && it.decay <= 1.f) || !std::isfinite(it.scale))) return false;
+    return true;
+}
 
 extern "C" {
 
@@ -56,12 +91,20 @@ int kfac_create(kfac_ctx **out, int device, void *hip_stream, void *workspace_de
     c->ws = (char *)workspace_dev;
     c->ws_bytes = workspace_bytes;
     c->pinned = nullptr;
-    c->pinned_bytes = 1 << 16;
+    c->pinned_bytes = KFAC_PINNED_NORMS + KFAC_PINNED_TABLES;
+    c->stage = nullptr;
+    c->stage_bytes = KFAC_STAGE_BYTES;
+    c->stage_off = 0;
+    c->stage_half = 0;
+    c->stage_used[0] = c->stage_used[1] = false;
     bool ok = hipHostMalloc((void **)&c->pinned, c->pinned_bytes, hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipHostMalloc((void **)&c->stage, c->stage_bytes, hipHostMallocDefault) == hipSuccess;
     int made_streams = 0, made_events = 0;
-    hipEvent_t *evs[2 + KFAC_NUM_AUX_STREAMS + KFAC_MAX_GROUPS];
+    hipEvent_t *evs[4 + KFAC_NUM_AUX_STREAMS + KFAC_MAX_GROUPS];
     int ne = 0;
     evs[ne++] = &c->ev_fork;
+    evs[ne++] = &c->stage_ev[0];
+    evs[ne++] = &c->stage_ev[1];
     for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) evs[ne++] = &c->ev_join[i];
     for (int i = 0; i < KFAC_MAX_GROUPS; ++i) evs[ne++] = &c->ev_group[i];
     for (; ok && made_streams < KFAC_NUM_AUX_STREAMS; ++made_streams)
@@ -72,6 +115,7 @@ int kfac_create(kfac_ctx **out, int device, void *hip_stream, void *workspace_de
         for (int i = 0; i < made_events; ++i) (void)hipEventDestroy(*evs[i]);
         for (int i = 0; i < made_streams; ++i) (void)hipStreamDestroy(c->aux[i]);
         if (c->pinned) (void)hipHostFree(c->pinned);
+        if (c->stage) (void)hipHostFree(c->stage);
         delete c;
         return KFAC_EHIP;
     }
@@ -88,10 +132,13 @@ int kfac_destroy(kfac_ctx *ctx) {
     for (auto &r : ctx->prof) { (void)hipEventDestroy(r.t0); (void)hipEventDestroy(r.t1); }
     for (auto e : ctx->ev_pool) (void)hipEventDestroy(e);
     (void)hipEventDestroy(ctx->ev_fork);
+    (void)hipEventDestroy(ctx->stage_ev[0]);
+    (void)hipEventDestroy(ctx->stage_ev[1]);
     for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) (void)hipEventDestroy(ctx->ev_join[i]);
     for (int i = 0; i < KFAC_MAX_GROUPS; ++i) (void)hipEventDestroy(ctx->ev_group[i]);
     for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) (void)hipStreamDestroy(ctx->aux[i]);
     (void)hipHostFree(ctx->pinned);
+    (void)hipHostFree(ctx->stage);
     delete ctx;
     return KFAC_OK;
 }
@@ -105,10 +152,12 @@ size_t kfac_eig_workspace_bytes(int batch, const int *d) {
 
 size_t kfac_workspace_bytes(int max_d, int max_batch_factors, int64_t max_R) {
     if (max_d < 1 || max_d > KFAC_MAX_D || max_batch_factors < 1 || max_R < 1) return 0;
-    // SYRK split partials: at most 512 + one tile per lower-triangular tile, 64 KB each
-    const size_t nt = (max_d + KFAC_TILE) / KFAC_TILE + 1;
-    size_t need = (2048 + 2 * nt * (nt + 1) / 2) * (size_t)(KFAC_TILE * KFAC_TILE + KFAC_TILE) * sizeof(float);
-    need = std::max(need, kfac_syrk_workspace_bytes(max_d, max_R)) + (size_t)(1 << 20);   // + job tables
+    // SYRK split partials of a factor updated alone, whatever its operand form: at most
+    // max(KFAC_SYRK_MAX_SINGLE_PARTIALS, tiles) partial tiles of 128 x 128 + 128 floats, plus the job tables
+    const size_t nt = (max_d + KFAC_TILE - 1) / KFAC_TILE, ntri = nt * (nt + 1) / 2;
+    size_t need = std::max<size_t>(KFAC_SYRK_MAX_SINGLE_PARTIALS, ntri) * (size_t)(KFAC_TILE * KFAC_TILE + KFAC_TILE) * sizeof(float) +
+                  (size_t)(1 << 20);
+    (void)max_R;
     // precondition: two dG x dA temporaries
     need = std::max(need, 2 * kfac_align_up((size_t)max_d * max_d, 64) * sizeof(float) + (size_t)(1 << 20));
     // eig: every factor of the batch at the largest size, advanced together
@@ -145,29 +194,18 @@ int kfac_unfold_batched(kfac_ctx *ctx, int n, const kfac_conv_desc *descs, const
 
 size_t kfac_unfold_workspace_bytes(int n) { return n > 0 ? kfac_unfold_ws_bytes_impl(n) : 0; }
 
-static bool valid_factor_item(const kfac_factor_item &it, bool pointers) {
-    if (pointers && (!it.X || !it.F || (const void *)it.F == it.X)) return false;
-    if (!valid_dtype(it.dtype) || (it.layout != KFAC_LAYOUT_RD && it.layout != KFAC_LAYOUT_NDT)) return false;
-    if (it.N < 1 || it.d < 1 || it.T < 1 || (it.append_ones != 0 && it.append_ones != 1)) return false;
-    if (it.d + it.append_ones > KFAC_MAX_D) return false;
-    if ((int64_t)it.N * it.T >= (int64_t)1 << 30) return false;
-    if ((int64_t)it.d * it.T >= (int64_t)1 << 31) return false;   // 32-bit offsets inside one example's slab
-    if (pointers && (!(it.decay >= 0.f && it.decay <= 1.f) || !std::isfinite(it.scale))) return false;
-    return true;
-}
-
 int kfac_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layout, int N, int d, int T,
                         int append_ones, float scale, float decay, float *F) {
     if (!ctx) return KFAC_EINVAL;
     const kfac_factor_item it{X, dtype, layout, N, d, T, append_ones, scale, decay, F};
-    if (!valid_factor_item(it, true)) return KFAC_EINVAL;
+    if (!kfac_valid_factor_item(it, true)) return KFAC_EINVAL;
     return kfac_launch_update_factors_batched(ctx, 1, &it);
 }
 
 int kfac_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_item *items) {
     if (!ctx || n < 0 || (n > 0 && !items)) return KFAC_EINVAL;
     for (int i = 0; i < n; ++i) {
-        if (!valid_factor_item(items[i], true)) return KFAC_EINVAL;
+        if (!kfac_valid_factor_item(items[i], true)) return KFAC_EINVAL;
         for (int j = 0; j < i; ++j)
             if (items[j].F == items[i].F) return KFAC_EINVAL;
     }
@@ -178,7 +216,7 @@ int kfac_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_item *it
 size_t kfac_update_factors_workspace_bytes(int n, const kfac_factor_item *items) {
     if (n <= 0 || !items) return 0;
     for (int i = 0; i < n; ++i)
-        if (!valid_factor_item(items[i], false)) return 0;
+        if (!kfac_valid_factor_item(items[i], false)) return 0;
     return kfac_syrk_ws_bytes_impl(n, items);
 }
 

@@ -21,8 +21,15 @@ struct kfac_ctx {
     hipStream_t stream;
     hipStream_t aux[KFAC_NUM_AUX_STREAMS];
     hipEvent_t ev_fork, ev_join[KFAC_NUM_AUX_STREAMS], ev_group[KFAC_MAX_GROUPS];
-    double *pinned;      // pinned host scratch: the eigensolver's convergence read-back
+    double *pinned;      // pinned host scratch of the eigensolver: convergence read-back, then its tables and statistics
     size_t pinned_bytes;
+    // pinned staging ring for the host tables that the batched calls upload on ctx->stream (two halves; a half is
+    // reused only after the copies issued from it have completed)
+    char *stage;
+    size_t stage_bytes, stage_off;
+    int stage_half;
+    hipEvent_t stage_ev[2];
+    bool stage_used[2];
     char *ws;            // caller-owned device workspace
     size_t ws_bytes;
     int max_lds;         // bytes of LDS one workgroup may use on this device
@@ -61,13 +68,31 @@ struct KfacProfScope {
         if (_e != hipSuccess) return KFAC_EHIP;   \
     } while (0)
 
+#define KFAC_CHECK(expr)                          \
+    do {                                          \
+        const int _rc = (expr);                   \
+        if (_rc != KFAC_OK) return _rc;           \
+    } while (0)
+
 static inline size_t kfac_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+constexpr size_t KFAC_PINNED_NORMS = (size_t)1 << 16;    // the eigensolver's norms: 2 doubles per factor, 4096 factors
+constexpr size_t KFAC_PINNED_TABLES = (size_t)1 << 18;   // the eigensolver's item tables and small-factor statistics
+constexpr size_t KFAC_STAGE_BYTES = (size_t)4 << 20;     // staging ring of the batched calls
+
+// Copy a host table to device memory on ctx->stream through the pinned staging ring: the host buffer may be
+// freed as soon as this returns, and the call does not wait for work already queued on the stream (a copy from
+// pageable memory would).  Tables larger than half the ring go through the runtime's own staging instead.
+int kfac_upload(kfac_ctx *ctx, void *dst_dev, const void *src_host, size_t bytes);
 
 // Tiling constants shared between host-side sizing and kernels.
 constexpr int KFAC_TILE = 128;       // GEMM / SYRK output tile edge
 constexpr int KFAC_EIG_SMALL = 128;  // factors up to this size are solved inside one workgroup's LDS
 constexpr int KFAC_EIG_B = 32;       // block size of the blocked Jacobi path (sub-problems are 2B x 2B)
 constexpr int KFAC_MAX_D = 8192;
+// A factor updated alone splits its contraction into at most this many partial tiles (or one per tile, if it has
+// more tiles than that): what kfac_workspace_bytes() sizes the workspace of a single update for.
+constexpr int KFAC_SYRK_MAX_SINGLE_PARTIALS = 1536;
 
 // ---- launchers implemented in the kernel files (all enqueue on ctx->stream) ----
 int kfac_launch_unfold(kfac_ctx *ctx, const kfac_conv_desc *d, const void *x, void *patches);
@@ -76,6 +101,10 @@ size_t kfac_unfold_ws_bytes_impl(int n);
 size_t kfac_syrk_workspace_bytes(int D, int64_t R);
 size_t kfac_syrk_ws_bytes_impl(int n, const kfac_factor_item *items);
 int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_item *items);
+// the same with the scratch (tables, split partials) in `ws` instead of the context's workspace
+int kfac_launch_update_factors_ws(kfac_ctx *ctx, int n, const kfac_factor_item *items, char *ws, size_t ws_bytes);
+bool kfac_valid_factor_item(const kfac_factor_item &it, bool pointers);
+
 int kfac_launch_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layout, int N, int d, int T,
                                int append_ones, float scale, float decay, float *F);
 int kfac_launch_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,

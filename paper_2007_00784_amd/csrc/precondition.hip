@@ -359,9 +359,9 @@ int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_it
     LayerDev *d_layers = (LayerDev *)ctx->ws;
     TileRef *d_byG = (TileRef *)(ctx->ws + off_tiles), *d_byA = d_byG + ntiles;
     double *d_dots = scaled ? (double *)(ctx->ws + off_dots) : nullptr;
-    KFAC_HIP_CHECK(hipMemcpyAsync(d_layers, dev.data(), n * sizeof(LayerDev), hipMemcpyHostToDevice, ctx->stream));
-    KFAC_HIP_CHECK(hipMemcpyAsync(d_byG, byG.data(), ntiles * sizeof(TileRef), hipMemcpyHostToDevice, ctx->stream));
-    KFAC_HIP_CHECK(hipMemcpyAsync(d_byA, byA.data(), ntiles * sizeof(TileRef), hipMemcpyHostToDevice, ctx->stream));
+    KFAC_CHECK(kfac_upload(ctx, d_layers, dev.data(), n * sizeof(LayerDev)));
+    KFAC_CHECK(kfac_upload(ctx, d_byG, byG.data(), ntiles * sizeof(TileRef)));
+    KFAC_CHECK(kfac_upload(ctx, d_byA, byA.data(), ntiles * sizeof(TileRef)));
     const dim3 grid((unsigned)ntiles), block(NTHREADS);
     if (any_split) {
         KfacProfScope prof(ctx, KC_PRECOND_SCALE, 0.0, bytes / 16);   // one read of every gradient

@@ -245,6 +245,7 @@ void plan_single(int d, int64_t R, int slab, double fixed, int &ntri, int &nspli
     double best_cost = 1e300;
     for (int ns = 1; ns <= 512; ++ns) {
         if (ns > 1 && slabs / ns < 8) break;                 // keep >= 8 slabs per split
+        if (ns > 1 && (int64_t)ntri * ns > KFAC_SYRK_MAX_SINGLE_PARTIALS) break;   // bounds the workspace of a lone factor
         const double rounds = std::ceil((double)ntri * ns / 512.0);
         const double cost = rounds * ((double)((slabs + ns - 1) / ns) + fixed);
         if (cost < best_cost * 0.999) { best_cost = cost; best = ns; }
@@ -385,14 +386,18 @@ size_t kfac_syrk_workspace_bytes(int D, int64_t R) {
 }
 
 int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_item *items) {
+    return kfac_launch_update_factors_ws(ctx, n, items, ctx->ws, ctx->ws_bytes);
+}
+
+int kfac_launch_update_factors_ws(kfac_ctx *ctx, int n, const kfac_factor_item *items, char *ws, size_t ws_bytes) {
     size_t off_jobs, off_rjobs, off_part, njobs, nrjobs;
     const size_t need = layout(n, items, off_jobs, off_rjobs, off_part, njobs, nrjobs);
-    if (need > ctx->ws_bytes) return KFAC_EWORKSPACE;
+    if (need > ws_bytes) return KFAC_EWORKSPACE;
     std::vector<SyrkArgs> args(n);
     // jobs grouped by operand form, inside a form the longest contraction first
     std::vector<SyrkJob> jobs[NFORM], rjobs;
     double flops[NFORM] = {}, bytes[NFORM] = {}, rbytes = 0.0;
-    float *part = (float *)(ctx->ws + off_part);
+    float *part = (float *)(ws + off_part);
     for (int i = 0; i < n; ++i) {
         const kfac_factor_item &it = items[i];
         SyrkArgs &g = args[i];
@@ -426,20 +431,20 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
         bytes[form] += esz * (double)R * it.d + (g.nsplit == 1 ? fbytes : 0.0);
         if (g.nsplit > 1) rbytes += fbytes;
     }
-    SyrkArgs *d_items = (SyrkArgs *)ctx->ws;
-    SyrkJob *d_jobs = (SyrkJob *)(ctx->ws + off_jobs), *d_rjobs = (SyrkJob *)(ctx->ws + off_rjobs);
-    KFAC_HIP_CHECK(hipMemcpyAsync(d_items, args.data(), n * sizeof(SyrkArgs), hipMemcpyHostToDevice, ctx->stream));
+    SyrkArgs *d_items = (SyrkArgs *)ws;
+    SyrkJob *d_jobs = (SyrkJob *)(ws + off_jobs), *d_rjobs = (SyrkJob *)(ws + off_rjobs);
+    KFAC_CHECK(kfac_upload(ctx, d_items, args.data(), n * sizeof(SyrkArgs)));
     size_t at[NFORM], pos = 0;
     for (int f = 0; f < NFORM; ++f) {
         std::stable_sort(jobs[f].begin(), jobs[f].end(), [&](const SyrkJob &a, const SyrkJob &b) { return args[a.item].kchunk > args[b.item].kchunk; });
         xcd_order(jobs[f]);
         at[f] = pos;
         if (!jobs[f].empty())
-            KFAC_HIP_CHECK(hipMemcpyAsync(d_jobs + pos, jobs[f].data(), jobs[f].size() * sizeof(SyrkJob), hipMemcpyHostToDevice, ctx->stream));
+            KFAC_CHECK(kfac_upload(ctx, d_jobs + pos, jobs[f].data(), jobs[f].size() * sizeof(SyrkJob)));
         pos += jobs[f].size();
     }
     if (!rjobs.empty())
-        KFAC_HIP_CHECK(hipMemcpyAsync(d_rjobs, rjobs.data(), rjobs.size() * sizeof(SyrkJob), hipMemcpyHostToDevice, ctx->stream));
+        KFAC_CHECK(kfac_upload(ctx, d_rjobs, rjobs.data(), rjobs.size() * sizeof(SyrkJob)));
     launch_class<OpNDT<float>>(ctx, d_items, d_jobs + at[0], jobs[0].size(), flops[0], bytes[0]);
     launch_class<OpNDT<unsigned short>>(ctx, d_items, d_jobs + at[1], jobs[1].size(), flops[1], bytes[1]);
     launch_class<OpStrided<float, false>>(ctx, d_items, d_jobs + at[2], jobs[2].size(), flops[2], bytes[2]);

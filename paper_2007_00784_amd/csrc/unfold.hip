@@ -235,7 +235,7 @@ int kfac_launch_unfold_batched(kfac_ctx *ctx, int n, const kfac_conv_desc *descs
     size_t at = 0;
     for (int f = 0; f < 2; ++f) {
         if (items[f].empty()) continue;
-        KFAC_HIP_CHECK(hipMemcpyAsync(d_items + at, items[f].data(), items[f].size() * sizeof(UnfoldItem), hipMemcpyHostToDevice, ctx->stream));
+        KFAC_CHECK(kfac_upload(ctx, d_items + at, items[f].data(), items[f].size() * sizeof(UnfoldItem)));
         KfacProfScope prof(ctx, KC_UNFOLD, 0.0, bytes[f]);
         if (f == 0)
             hipLaunchKernelGGL(unfold_batched_kernel<float>, dim3((unsigned)total[f]), dim3(256), 0, ctx->stream, d_items + at, (int)items[f].size());

@@ -48,3 +48,19 @@ def test_host_functions():
     assert K.kfac_eig_workspace_bytes([577, 64, 577, 16]) <= a
     assert K.kfac_eig_workspace_bytes([0]) == 0
     assert K.kfac_workspace_bytes(100000, 1, 1) == 0
+
+
+def test_workspace_query_covers_every_operand_form():
+    """kfac_workspace_bytes(max_d, 1, max_R) suffices for one factor update of that size whatever the layout and
+    element type of its samples (the split plans differ between the operand forms)."""
+    for d in (64, 257, 1153, 4609):
+        for R in (1568, 25088, 401408):
+            cap = K.kfac_workspace_bytes(d, 1, R)
+            assert cap > 0
+            for dtype in (K.KFAC_F32, K.KFAC_BF16):
+                for T in (1, 4, 5, 8, 9, 49, 196, R):
+                    N = max(1, R // T)
+                    for layout in (K.KFAC_LAYOUT_RD, K.KFAC_LAYOUT_NDT):
+                        it = dict(X=None, dtype=dtype, layout=layout, N=N, d=d - 1, T=T, append_ones=1, scale=1.0, decay=0.0, F=None)
+                        need = K.kfac_update_factors_workspace_bytes([it])
+                        assert 0 < need <= cap, (d, R, dtype, T, layout, need, cap)

@@ -284,6 +284,49 @@ def test_eig_max_sweeps_reports_noconv(ctx):
     assert np.isfinite(Qd[0].cpu().numpy()).all()
 
 
+def test_eig_many_factors_of_one_size(ctx):
+    """200 factors of one blocked size class advance as one group: every one of them gets its own norms,
+    flags and eigenpairs (the group's bookkeeping is sized by its member count, not by a fixed launch)."""
+    n, count = 160, 200
+    mats = [gram_factor(n, 200 + 3 * i, seed=1000 + i, ones=(i % 2 == 0)) for i in range(count)]
+    Ld, Qd, info = ctx.eig(mats)
+    assert all(c for (_, _, c) in info), [i for i, x in enumerate(info) if not x[2]]
+    for i in list(range(0, count, 7)) + [127, 128, 129, count - 1]:
+        check_eigpairs(mats[i], Ld[i].cpu().numpy(), Qd[i].cpu().numpy(), "many[%d]" % i)
+    for i in range(count):      # the cheap invariants on every member: trace and orthonormal first/last columns
+        lam, Q = Ld[i].cpu().numpy().astype(np.float64), Qd[i].cpu().numpy().astype(np.float64)
+        assert abs(lam.sum() - np.trace(mats[i].astype(np.float64))) <= 1e-5 * abs(lam).max() * n, i
+        assert abs(np.linalg.norm(Q[:, 0]) - 1) < 1e-4 and abs(np.linalg.norm(Q[:, -1]) - 1) < 1e-4, i
+
+
+def test_eig_is_reproducible(ctx):
+    """Same input, same bits: the norms that decide convergence and the Rayleigh quotients are summed in a
+    fixed order (small, flat and two-level path)."""
+    mats = [gram_factor(n, r, seed=70 + i) for i, (n, r) in enumerate([(100, 300), (577, 900), (2100, 2500)])]
+    L1, Q1, i1 = ctx.eig(mats)
+    L2, Q2, i2 = ctx.eig(mats)
+    assert i1 == i2
+    for a, b in zip(L1 + Q1, L2 + Q2):
+        assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("n", [40, 300, 2100])
+def test_eig_non_finite_input(ctx, n):
+    """A NaN in the factor: KFAC_ENOCONV, and every element of that factor's outputs is non-finite, while a
+    healthy factor of the same call is decomposed as usual."""
+    bad = gram_factor(n, 2 * n, seed=3)
+    bad[n // 2, n // 3] = np.nan
+    bad[n // 3, n // 2] = np.nan
+    good = gram_factor(n, 2 * n, seed=4)
+    with pytest.raises(K.KfacError) as e:
+        ctx.eig([bad, good])
+    assert e.value.code == K.KFAC_ENOCONV
+    Ld, Qd, info = ctx.eig([bad, good], raise_on_noconv=False)
+    assert not info[0][2] and info[1][2], info
+    assert not np.isfinite(Ld[0].cpu().numpy()).any() and not np.isfinite(Qd[0].cpu().numpy()).any()
+    check_eigpairs(good, Ld[1].cpu().numpy(), Qd[1].cpu().numpy(), "beside NaN")
+
+
 # ------------------------------------------------------------------ precondition
 PRECOND_CASES = [(10, 4), (145, 16), (65, 10), (289, 32), (577, 64), (130, 257)]
 

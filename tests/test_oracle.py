@@ -300,6 +300,18 @@ def test_eigh_dispatch_threshold_agrees():
         assert np.abs(l1 - l2).max() < 1e-12 * l1.max() and np.abs(l3 - l2).max() < 1e-12 * l1.max()
 
 
+def test_eigh_tridiag_midsize_vs_lapack():
+    """The Householder + implicit-QR routine at a size well above the Jacobi threshold, on a rank-deficient
+    ReLU-activation Gram matrix (the kind it certifies at d = 4609), against LAPACK: runs in seconds."""
+    n = 600
+    X = np.maximum(rng(12).standard_normal((n // 3, n)), 0)
+    F = X.T @ X / X.shape[0]
+    lam, Q = oracle.eigh_tridiag(F)
+    check_eig(F, lam, Q)
+    assert np.abs(lam - np.linalg.eigvalsh(F)).max() <= 1e-13 * lam.max()
+    assert (lam > 1e-10 * lam.max()).sum() == n // 3
+
+
 @pytest.mark.slow
 def test_eigh_large_vs_lapack():
     n = 1500
