@@ -39,7 +39,8 @@ enum {
     KFAC_EINVAL = -1,     /* NULL / out-of-range / unsupported argument            */
     KFAC_ENOCONV = -2,    /* eigensolver reached max_sweeps; outputs still written */
     KFAC_EHIP = -3,       /* a HIP runtime call failed                             */
-    KFAC_EWORKSPACE = -4  /* the context's workspace is too small for this call    */
+    KFAC_EWORKSPACE = -4, /* the context's workspace is too small for this call    */
+    KFAC_ESCRATCH = -5    /* the input needs more than the library's static scratch */
 };
 
 typedef enum { KFAC_F32 = 0, KFAC_BF16 = 1 } kfac_dtype;
@@ -139,6 +140,19 @@ typedef struct {
 } kfac_factor_item;
 int kfac_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_item *items /* host */);
 size_t kfac_update_factors_workspace_bytes(int n, const kfac_factor_item *items /* host; X, F not read */);
+
+/* kfac_update_factors() for callers that cannot allocate device memory or provide a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments, result and kernels are those
+ * of kfac_update_factors() (bit-identical output); the job tables and split partials live in a static device
+ * array of the library (kfac_static_scratch_bytes() = 48 MiB, held by every device the library runs on until the
+ * process ends) instead of the context's workspace, and the call allocates nothing, on the device or in pinned
+ * memory.  A factor whose split plan needs more than that returns KFAC_ESCRATCH and launches nothing (the plan
+ * of a lone factor keeps at most 1536 partial tiles of 64.5 KB; 48 MiB hold 761 of them -- every plan that fills
+ * the machine once).  All calls on a device share the array: two calls that overlap on one device (different
+ * contexts or streams) race; calls on one stream are ordered and safe.  */
+int kfac_update_factors_static(kfac_ctx *ctx, const void *X, int dtype, int layout, int N, int d, int T,
+                               int append_ones, float scale, float decay, float *F);
+size_t kfac_static_scratch_bytes(void);
 
 /* Symmetric eigendecompositions F_i = Q_i diag(lam_i) Q_i^T (Sec. IV-A, Algorithm 1 step 2) of a
  * batch of factors by (block) Jacobi iteration; lam ascending, eigenvectors in the columns of Q.

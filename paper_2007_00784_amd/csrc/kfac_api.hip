@@ -68,6 +68,7 @@ const char *kfac_strerror(int code) {
         case KFAC_ENOCONV: return "eigensolver did not reach the tolerance within max_sweeps";
         case KFAC_EHIP: return "HIP runtime failure";
         case KFAC_EWORKSPACE: return "workspace too small";
+        case KFAC_ESCRATCH: return "input needs more scratch than the library's static device buffer holds";
         default: return "unknown status";
     }
 }
@@ -80,6 +81,7 @@ int kfac_create(kfac_ctx **out, int device, void *hip_stream, void *workspace_de
     if (device < 0 || device >= ndev) return KFAC_EINVAL;
     if (workspace_bytes > 0 && (!workspace_dev || ((uintptr_t)workspace_dev & 255))) return KFAC_EINVAL;
     KFAC_HIP_CHECK(hipSetDevice(device));
+    KFAC_CHECK(kfac_static_scratch_init(device));   // device address of the library's static scratch on this device
     hipDeviceProp_t prop;
     KFAC_HIP_CHECK(hipGetDeviceProperties(&prop, device));
     if (std::string_view(prop.gcnArchName).substr(0, 6) != "gfx950") return KFAC_EINVAL;  // built for gfx950 only

@@ -93,6 +93,7 @@ constexpr int KFAC_MAX_D = 8192;
 // A factor updated alone splits its contraction into at most this many partial tiles (or one per tile, if it has
 // more tiles than that): what kfac_workspace_bytes() sizes the workspace of a single update for.
 constexpr int KFAC_SYRK_MAX_SINGLE_PARTIALS = 1536;
+constexpr size_t KFAC_STATIC_SCRATCH_BYTES = (size_t)48 << 20;   // the library's static device scratch (per device)
 
 // ---- launchers implemented in the kernel files (all enqueue on ctx->stream) ----
 int kfac_launch_unfold(kfac_ctx *ctx, const kfac_conv_desc *d, const void *x, void *patches);
@@ -104,7 +105,8 @@ int kfac_launch_update_factors_batched(kfac_ctx *ctx, int n, const kfac_factor_i
 // the same with the scratch (tables, split partials) in `ws` instead of the context's workspace
 int kfac_launch_update_factors_ws(kfac_ctx *ctx, int n, const kfac_factor_item *items, char *ws, size_t ws_bytes);
 bool kfac_valid_factor_item(const kfac_factor_item &it, bool pointers);
-
+// Looks up, once per device and with that device current, the device address of the library's static scratch array.
+int kfac_static_scratch_init(int device);
 int kfac_launch_update_factors(kfac_ctx *ctx, const void *X, int dtype, int layout, int N, int d, int T,
                                int append_ones, float scale, float decay, float *F);
 int kfac_launch_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA, const float *QG,

@@ -8,7 +8,7 @@ paper_2007_00784_amd.build`` or ``__graft_entry__.build()``); there is no fallba
 import ctypes
 import os
 
-KFAC_OK, KFAC_EINVAL, KFAC_ENOCONV, KFAC_EHIP, KFAC_EWORKSPACE = 0, -1, -2, -3, -4
+KFAC_OK, KFAC_EINVAL, KFAC_ENOCONV, KFAC_EHIP, KFAC_EWORKSPACE, KFAC_ESCRATCH = 0, -1, -2, -3, -4, -5
 KFAC_F32, KFAC_BF16 = 0, 1
 KFAC_LAYOUT_RD, KFAC_LAYOUT_NDT = 0, 1
 
@@ -20,6 +20,7 @@ EXPORTS = (
     "kfac_unfold", "kfac_unfold_batched", "kfac_unfold_workspace_bytes", "kfac_update_factors", "kfac_eig", "kfac_precondition", "kfac_schedule_due",
     "kfac_profile_begin", "kfac_profile_end", "kfac_precondition_batched", "kfac_precondition_workspace_bytes",
     "kfac_update_factors_batched", "kfac_update_factors_workspace_bytes", "kfac_precondition_batched_scaled",
+    "kfac_update_factors_static", "kfac_static_scratch_bytes",
 )
 
 
@@ -86,6 +87,9 @@ def lib():
     L.kfac_unfold_workspace_bytes.argtypes = [i]
     L.kfac_unfold_workspace_bytes.restype = sz
     L.kfac_update_factors.argtypes = [vp, vp, i, i, i, i, i, i, f, f, vp]
+    L.kfac_update_factors_static.argtypes = [vp, vp, i, i, i, i, i, i, f, f, vp]
+    L.kfac_static_scratch_bytes.argtypes = []
+    L.kfac_static_scratch_bytes.restype = sz
     L.kfac_eig.argtypes = [vp, i, ctypes.POINTER(vp), ip, ctypes.POINTER(vp), ctypes.POINTER(vp),
                            ctypes.POINTER(kfac_eig_opts), ctypes.POINTER(kfac_eig_info)]
     L.kfac_precondition.argtypes = [vp, vp, vp, i, vp, vp, i, f, vp, i]
@@ -102,7 +106,7 @@ def lib():
     for name in EXPORTS:
         if name not in ("kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
                         "kfac_precondition_workspace_bytes", "kfac_update_factors_workspace_bytes",
-                        "kfac_unfold_workspace_bytes"):
+                        "kfac_unfold_workspace_bytes", "kfac_static_scratch_bytes"):
             getattr(L, name).restype = i
     _lib = L
     return L
@@ -192,6 +196,17 @@ def kfac_update_factors(ctx, X, layout, N, d, T, append_ones, scale, decay, F, d
     code = _dtype_code(X) if dtype is None else dtype
     _check(lib().kfac_update_factors(ctx, _ptr(X), code, int(layout), int(N), int(d), int(T), int(append_ones),
                                      float(scale), float(decay), _ptr(F)), "kfac_update_factors")
+
+
+def kfac_update_factors_static(ctx, X, layout, N, d, T, append_ones, scale, decay, F, dtype=None):
+    """kfac_update_factors with its scratch in the library's static device array (allocates nothing)."""
+    code = _dtype_code(X) if dtype is None else dtype
+    _check(lib().kfac_update_factors_static(ctx, _ptr(X), code, int(layout), int(N), int(d), int(T), int(append_ones),
+                                            float(scale), float(decay), _ptr(F)), "kfac_update_factors_static")
+
+
+def kfac_static_scratch_bytes():
+    return int(lib().kfac_static_scratch_bytes())
 
 
 def _factor_items(items):
