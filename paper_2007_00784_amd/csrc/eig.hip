@@ -27,8 +27,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstdio>
-#include <cstdlib>
 #include <cmath>
+#include <deque>
 #include <thread>
 #include <cstdlib>
 #include <type_traits>
@@ -1096,19 +1096,23 @@ struct GroupRun {
     BlkGroup gi, gd;      // two-level: inner groups of the regular rounds and of the diagonal phase
     float *Qalt;          // two-level: the other accumulator buffer
     hipStream_t st;
-    hipEvent_t ev;
+    hipEvent_t ev[KFAC_EIG_SLOTS];   // one per report slot; slot 0 also marks the end of the post-processing
+    struct Report { int slot, sweeps; bool final_ok; };   // norms after `sweeps` sweeps; final_ok: taken after the refresh
+    std::deque<Report> reports;      // enqueued, not yet read by the host (oldest first)
+    int next_slot;
     std::vector<BlkItem> items;
     BlkItem *d_items;
     int *perm;
     double *lam64;
     double *normpart;     // [nm][norm_blocks][2]
     int norm_blocks;
-    double *h_norms;      // pinned, 2 per factor
+    double *h_norms;      // pinned, KFAC_EIG_SLOTS x 2 per factor
     int nm, ntiles_w, nrb, ntiles, nmax, fill_blocks;
     double apply_flops, solve_flops;
     int sweep;
     bool done;
     bool x3;              // two-level: outer passes on the split-fp16 engine
+    bool refreshed;       // x3: W has been recomputed as Q^T F Q in fp32 (or never left fp32)
     int *d_done;          // device flags, one per factor
     double tol2;
     std::vector<char> conv;
@@ -1125,8 +1129,11 @@ int enqueue_offnorm(kfac_ctx *ctx, GroupRun &r) {
                            r.d_done, r.tol2);
     }
     KFAC_HIP_CHECK(hipGetLastError());
-    KFAC_HIP_CHECK(hipMemcpyAsync(r.h_norms, r.g.norms, 2 * r.nm * sizeof(double), hipMemcpyDeviceToHost, r.st));
-    KFAC_HIP_CHECK(hipEventRecord(r.ev, r.st));
+    const int slot = r.next_slot;
+    r.next_slot = (slot + 1) % KFAC_EIG_SLOTS;
+    KFAC_HIP_CHECK(hipMemcpyAsync(r.h_norms + (size_t)slot * 2 * r.nm, r.g.norms, 2 * r.nm * sizeof(double), hipMemcpyDeviceToHost, r.st));
+    KFAC_HIP_CHECK(hipEventRecord(r.ev[slot], r.st));
+    r.reports.push_back(GroupRun::Report{slot, r.sweep, r.refreshed || r.sweep == 0});
     return KFAC_OK;
 }
 
@@ -1214,6 +1221,60 @@ int enqueue_sweep_two_level(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int in
     return KFAC_OK;
 }
 
+// Refresh of a group whose passes run on the split engine.  Those passes carry 22 significand bits and an error
+// bounded relative to ||F||, so after several sweeps the working matrix W has drifted a little from Q^T F Q for
+// the accumulator Q that goes with it.  Once the off-norm is small the drift is removed: Q is re-orthogonalised
+// (one Newton-Schulz step) and W is recomputed from the caller's F as Q^T F Q, both on the fp32 engine.  From
+// then on the iteration is a Jacobi iteration started from a good basis -- what came before only chose that
+// basis -- and its remaining rounds are small corrections, which the split passes add to fp32 operands
+// (X + X (V - I)) with an error far below fp32 rounding.  Every factor of the group takes part, converged or not.
+int enqueue_refresh(kfac_ctx *ctx, GroupRun &r) {
+    using namespace kfac;
+    const GroupPlan &gp = *r.plan;
+    const size_t np2 = (size_t)gp.npad * gp.npad;
+    hipStream_t st = r.st;
+    for (int i = 0; i < r.nm; ++i) {
+        if (r.bad[i]) continue;
+        const int n = r.items[i].n;
+        float *Wm = r.g.W + i * np2, *Qm = r.g.Qw + i * np2, *Q1 = r.Qalt + i * np2, *Tm = r.sp.T + i * np2;
+        const int64_t ld = gp.npad;
+        const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
+        OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};          // elem(i,k) = Q[k][i]
+        {   // W (free from here on) <- Y = (3I - Q^T Q)/2
+            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz>), grid, block, 0, st,
+                               q_kn, q_kn, EpiNewtonSchulz{Wm, ld}, n, n, n);
+        }
+        OpStrided<float, true> q_mk{Qm, ld, 1, n, n, -1};           // elem(i,k) = Q[i][k]
+        OpStrided<float, false> y_kn{Wm, 1, ld, n, n, -1};
+        {   // Q1 = Q Y in the other accumulator buffer (its padding already holds the identity)
+            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_mk), decltype(y_kn), EpiStore>), grid, block, 0, st,
+                               q_mk, y_kn, EpiStore{Q1, ld}, n, n, n);
+        }
+        OpStrided<float, true> f_mk{r.items[i].F, n, 1, n, n, -1};
+        OpStrided<float, false> q1_kn{Q1, 1, ld, n, n, -1};         // elem(c,k) = Q1[k][c]
+        {   // T = F Q1
+            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+            hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(q1_kn), EpiStore>), grid, block, 0, st,
+                               f_mk, q1_kn, EpiStore{Tm, ld}, n, n, n);
+        }
+        OpStrided<float, false> q1t_mk{Q1, 1, ld, n, n, -1};        // elem(r,k) = Q1[k][r]
+        OpStrided<float, false> t_kn{Tm, 1, ld, n, n, -1};          // elem(c,k) = T[k][c]
+        {   // W = Q1^T T, made exactly symmetric
+            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q1t_mk), decltype(t_kn), EpiStore>), grid, block, 0, st,
+                               q1t_mk, t_kn, EpiStore{Wm, ld}, n, n, n);
+        }
+        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+        hipLaunchKernelGGL(blk_symmetrise_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, Wm, ld, n);
+    }
+    std::swap(r.g.Qw, r.Qalt);
+    r.refreshed = true;
+    KFAC_HIP_CHECK(hipGetLastError());
+    return KFAC_OK;
+}
+
 // Post-processing per factor: one Newton-Schulz step restores the orthogonality that thousands of fp32
 // transforms have eroded, Rayleigh quotients against the caller's F give the eigenvalues, and the
 // columns are put in ascending order.  W is dead by now and serves as scratch.
@@ -1270,7 +1331,7 @@ int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
         hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, Wm, (int64_t)n, r.items[i].Q, n, pm);
     }
     KFAC_HIP_CHECK(hipGetLastError());
-    KFAC_HIP_CHECK(hipEventRecord(r.ev, st));
+    KFAC_HIP_CHECK(hipEventRecord(r.ev[0], st));
     return KFAC_OK;
 }
 
@@ -1295,6 +1356,7 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
     const float tol = (opts && opts->tol > 0.f) ? opts->tol : 2e-6f;
     const bool fp32_outer = opts && opts->fp32_only != 0;
     const bool warm = opts && opts->warm_start != 0;
+    const float refresh_at = 3e-4f;   // off(W)/||W|| at which a split-engine group recomputes W = Q^T F Q in fp32
     const int inner_cap = 1;       // one Jacobi sweep over a pivot per visit: fewest total rotations
     const float inner_tol = 1e-7f;
     const size_t lds_solve = JacobiSmem::bytes(KP, PLD);
@@ -1371,7 +1433,8 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
         r.nm = (int)gp.members.size();
         r.tol2 = (double)tol * tol;
         r.st = ctx->aux[stream_of[gi]];
-        r.ev = ctx->ev_group[gi];
+        for (int k = 0; k < KFAC_EIG_SLOTS; ++k) r.ev[k] = ctx->ev_group[KFAC_EIG_SLOTS * gi + k];
+        r.next_slot = 0;
         const size_t np2 = (size_t)gp.npad * gp.npad;
         const int nm = r.nm;
         char *p = wsp;
@@ -1421,7 +1484,7 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
         r.d_items = (BlkItem *)p;
         wsp += gp.bytes();
         r.h_norms = pinned;
-        pinned += 2 * nm;
+        pinned += (size_t)KFAC_EIG_SLOTS * 2 * nm;
         r.items.resize(nm);
         r.nmax = 0;
         r.apply_flops = 0.0;
@@ -1486,13 +1549,30 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
         int rc = enqueue_offnorm(ctx, r);
         if (rc) return rc;
         r.x3 = gp.two_level && !fp32_outer;
+        r.refreshed = !r.x3 || warm;   // a warm start begins from W = Q0^T F Q0 formed in fp32
         if (r.x3) {
             hipLaunchKernelGGL(sp_scale_kernel, dim3((nm + 63) / 64), dim3(64), 0, r.st, r.sp, (const double *)g.norms);
             KFAC_HIP_CHECK(hipGetLastError());
         }
     }
-    // state per group: waiting for norms (post == 0) or for its post-processing (post == 1)
+    // One sweep of a group = one chain of launches followed by a report (norms -> pinned memory, event).  The host
+    // keeps one sweep queued behind the one whose report it is waiting for, so a stream never idles while the host
+    // reads norms or enqueues another group's launches; the device-side flags make the workgroups of a factor
+    // that converged meanwhile return at once, so a sweep queued in vain costs only its empty launches.
+    // state per group: waiting for reports (post == 0) or for its post-processing (post == 1)
     const auto t_start = std::chrono::steady_clock::now();
+    const bool trace = getenv("KFAC_EIG_TRACE") != nullptr;
+    double host_enqueue_ms = 0.0;
+    auto now_ms = [&]() { return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count(); };
+    auto enqueue_sweep = [&](GroupRun &r) -> int {
+        int rc = r.plan->two_level ? enqueue_sweep_two_level(ctx, r, lds_solve, inner_cap, inner_tol)
+                                   : enqueue_sweep_flat(ctx, r, lds_solve, inner_cap, inner_tol);
+        ++r.sweep;
+        if (rc == KFAC_OK) rc = enqueue_offnorm(ctx, r);
+        return rc;
+    };
+    for (auto &r : runs)   // the first sweep goes out before its norms are known
+        if (r.sweep < max_sweeps) KFAC_CHECK(enqueue_sweep(r));
     std::vector<char> post(runs.size(), 0);
     size_t remaining = runs.size();
     while (remaining > 0) {
@@ -1500,50 +1580,66 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
         for (size_t gi = 0; gi < runs.size(); ++gi) {
             GroupRun &r = runs[gi];
             if (r.done) continue;
-            const hipError_t q = hipEventQuery(r.ev);
+            if (post[gi]) {
+                const hipError_t q = hipEventQuery(r.ev[0]);
+                if (q == hipErrorNotReady) continue;
+                if (q != hipSuccess) return KFAC_EHIP;
+                progressed = true;
+                r.done = true;
+                --remaining;
+                if (trace)
+                    fprintf(stderr, "[kfac_eig] group nblk=%d (%d factors, stream %d) finished at %.1f ms\n", r.plan->nblk, r.nm,
+                            (int)stream_of[gi], now_ms());
+                continue;
+            }
+            if (r.reports.empty()) return KFAC_EHIP;   // cannot happen: a group that is not finishing has a report queued
+            const GroupRun::Report R = r.reports.front();
+            const hipError_t q = hipEventQuery(r.ev[R.slot]);
             if (q == hipErrorNotReady) continue;
             if (q != hipSuccess) return KFAC_EHIP;
             progressed = true;
-            if (post[gi]) {
-                r.done = true;
-                --remaining;
-                if (getenv("KFAC_EIG_TRACE"))
-                    fprintf(stderr, "[kfac_eig] group nblk=%d (%d factors, stream %d) finished at %.1f ms\n", r.plan->nblk, r.nm,
-                            (int)stream_of[gi], std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count());
-                continue;
-            }
+            r.reports.pop_front();
+            const double *hn = r.h_norms + (size_t)R.slot * 2 * r.nm;
             bool all = true;
+            float worst = 0.f;
             for (int i = 0; i < r.nm; ++i) {
-                const double o2 = r.h_norms[2 * i], n2 = o2 + r.h_norms[2 * i + 1];
+                const double o2 = hn[2 * i], n2 = o2 + hn[2 * i + 1];
                 r.offrel[i] = n2 > 0 ? (float)std::sqrt(o2 / n2) : 0.f;
                 const bool c = o2 <= (double)tol * tol * n2;   // false for NaN
-                if (c && !r.conv[i]) r.sweeps_done[i] = r.sweep;
-                r.conv[i] = c;
                 r.bad[i] = !std::isfinite(n2);
                 all &= c || r.bad[i];
+                if (!r.bad[i]) worst = std::max(worst, r.offrel[i]);
+                if (R.final_ok) {   // no factor of a split-engine group counts as converged before the refresh
+                    if (c && !r.conv[i]) r.sweeps_done[i] = R.sweeps;
+                    r.conv[i] = c;
+                }
             }
-            if (getenv("KFAC_EIG_TRACE")) {   // debugging aid: the convergence history on stderr
-                fprintf(stderr, "[kfac_eig] %.1f ms group nblk=%d sweep %d off/norm:",
-                        std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count(), r.plan->nblk, r.sweep);
+            if (trace) {   // debugging aid: the convergence history on stderr
+                fprintf(stderr, "[kfac_eig] %.1f ms group nblk=%d sweep %d%s off/norm:", now_ms(), r.plan->nblk, R.sweeps, R.final_ok ? "" : " (before refresh)");
                 for (int i = 0; i < r.nm; ++i) fprintf(stderr, " %.2e", r.offrel[i]);
                 fprintf(stderr, "\n");
             }
-            int rc;
-            if (all || r.sweep >= max_sweeps) {
-                rc = enqueue_post(ctx, r);
+            const double t_enq = now_ms();
+            int rc = KFAC_OK;
+            if (R.final_ok && (all || R.sweeps >= max_sweeps)) {
+                rc = enqueue_post(ctx, r);     // after whatever is still queued, which no longer changes anything
                 post[gi] = 1;
+                r.reports.clear();
             } else {
-                rc = r.plan->two_level ? enqueue_sweep_two_level(ctx, r, lds_solve, inner_cap, inner_tol)
-                                       : enqueue_sweep_flat(ctx, r, lds_solve, inner_cap, inner_tol);
-                if (rc == KFAC_OK) rc = enqueue_offnorm(ctx, r);
-                ++r.sweep;
+                if (!r.refreshed && R.sweeps > 0 && (all || worst <= refresh_at || R.sweeps >= max_sweeps)) {
+                    rc = enqueue_refresh(ctx, r);
+                    if (rc == KFAC_OK) rc = enqueue_offnorm(ctx, r);
+                }
+                while (rc == KFAC_OK && r.reports.size() < 2 && r.sweep < max_sweeps) rc = enqueue_sweep(r);
             }
+            host_enqueue_ms += now_ms() - t_enq;
             if (rc) return rc;
         }
         // nothing ready: poll again shortly.  (Blocking on one group's event would leave every other group
         // that finishes its sweep earlier waiting for the host.)
         if (!progressed) std::this_thread::sleep_for(std::chrono::microseconds(20));
     }
+    if (trace) fprintf(stderr, "[kfac_eig] all groups done at %.1f ms; host time spent enqueueing %.1f ms\n", now_ms(), host_enqueue_ms);
     // the statistics of the small factors are read below
     KFAC_HIP_CHECK(hipStreamSynchronize(st_small));
 
@@ -1574,7 +1670,7 @@ int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *
     if (groups.size() > (size_t)KFAC_MAX_GROUPS) return KFAC_EINVAL;
     size_t norms_need = 0, tables_need = kfac_align_up(small.size() * sizeof(SmallItem), 64) + kfac_align_up(small.size() * sizeof(EigStat), 64);
     for (auto &gp : groups) {
-        norms_need += 2 * gp.members.size() * sizeof(double);
+        norms_need += (size_t)KFAC_EIG_SLOTS * 2 * gp.members.size() * sizeof(double);
         tables_need += kfac_align_up(gp.members.size() * sizeof(BlkItem), 64);
     }
     if (norms_need > KFAC_PINNED_NORMS || tables_need > KFAC_PINNED_TABLES) return KFAC_EINVAL;   // more than 4096 factors

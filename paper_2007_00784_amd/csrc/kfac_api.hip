@@ -102,13 +102,13 @@ int kfac_create(kfac_ctx **out, int device, void *hip_stream, void *workspace_de
     bool ok = hipHostMalloc((void **)&c->pinned, c->pinned_bytes, hipHostMallocDefault) == hipSuccess;
     ok = ok && hipHostMalloc((void **)&c->stage, c->stage_bytes, hipHostMallocDefault) == hipSuccess;
     int made_streams = 0, made_events = 0;
-    hipEvent_t *evs[4 + KFAC_NUM_AUX_STREAMS + KFAC_MAX_GROUPS];
+    hipEvent_t *evs[4 + KFAC_NUM_AUX_STREAMS + KFAC_EIG_SLOTS * KFAC_MAX_GROUPS];
     int ne = 0;
     evs[ne++] = &c->ev_fork;
     evs[ne++] = &c->stage_ev[0];
     evs[ne++] = &c->stage_ev[1];
     for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) evs[ne++] = &c->ev_join[i];
-    for (int i = 0; i < KFAC_MAX_GROUPS; ++i) evs[ne++] = &c->ev_group[i];
+    for (int i = 0; i < KFAC_EIG_SLOTS * KFAC_MAX_GROUPS; ++i) evs[ne++] = &c->ev_group[i];
     for (; ok && made_streams < KFAC_NUM_AUX_STREAMS; ++made_streams)
         ok = hipStreamCreateWithFlags(&c->aux[made_streams], hipStreamNonBlocking) == hipSuccess;
     for (; ok && made_events < ne; ++made_events)
@@ -137,7 +137,7 @@ int kfac_destroy(kfac_ctx *ctx) {
     (void)hipEventDestroy(ctx->stage_ev[0]);
     (void)hipEventDestroy(ctx->stage_ev[1]);
     for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) (void)hipEventDestroy(ctx->ev_join[i]);
-    for (int i = 0; i < KFAC_MAX_GROUPS; ++i) (void)hipEventDestroy(ctx->ev_group[i]);
+    for (int i = 0; i < KFAC_EIG_SLOTS * KFAC_MAX_GROUPS; ++i) (void)hipEventDestroy(ctx->ev_group[i]);
     for (int i = 0; i < KFAC_NUM_AUX_STREAMS; ++i) (void)hipStreamDestroy(ctx->aux[i]);
     (void)hipHostFree(ctx->pinned);
     (void)hipHostFree(ctx->stage);

@@ -15,12 +15,13 @@ struct KfacProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
 
 constexpr int KFAC_NUM_AUX_STREAMS = 4;   // internal streams of the eigensolver (default priority)
 constexpr int KFAC_MAX_GROUPS = 128;      // distinct block counts in one kfac_eig call (8192 / 64)
+constexpr int KFAC_EIG_SLOTS = 3;         // convergence reports a group may have in flight (events, pinned norms)
 
 struct kfac_ctx {
     int device;
     hipStream_t stream;
     hipStream_t aux[KFAC_NUM_AUX_STREAMS];
-    hipEvent_t ev_fork, ev_join[KFAC_NUM_AUX_STREAMS], ev_group[KFAC_MAX_GROUPS];
+    hipEvent_t ev_fork, ev_join[KFAC_NUM_AUX_STREAMS], ev_group[KFAC_EIG_SLOTS * KFAC_MAX_GROUPS];
     double *pinned;      // pinned host scratch of the eigensolver: convergence read-back, then its tables and statistics
     size_t pinned_bytes;
     // pinned staging ring for the host tables that the batched calls upload on ctx->stream (two halves; a half is
@@ -76,7 +77,7 @@ struct KfacProfScope {
 
 static inline size_t kfac_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-constexpr size_t KFAC_PINNED_NORMS = (size_t)1 << 16;    // the eigensolver's norms: 2 doubles per factor, 4096 factors
+constexpr size_t KFAC_PINNED_NORMS = (size_t)3 << 16;    // the eigensolver's norms: 2 doubles per factor and report slot, 4096 factors
 constexpr size_t KFAC_PINNED_TABLES = (size_t)1 << 18;   // the eigensolver's item tables and small-factor statistics
 constexpr size_t KFAC_STAGE_BYTES = (size_t)4 << 20;     // staging ring of the batched calls
 

@@ -209,7 +209,7 @@ def test_config3_resnet50_one_layer_against_oracle(resnet50_run):
     assert np.abs(f64(run.lamG[i]) - lamG).max() <= TOL_LAM * lamG.max()
     g0 = f64(run.gradw_master[i])
     assert relfro(f64(run.grad[i]), oracle.precondition(QA, lamA, QG, lamG, run.wl.damping, g0)) <= TOL_F32
-    check_scaled_damping(run, i, lamA, QA, lamG, QG, e2e_tol=3e-3)   # d_A = 2305: split-fp16 passes
+    check_scaled_damping(run, i, lamA, QA, lamG, QG, e2e_tol=1e-3)
 
 
 @pytest.mark.timeout(900)
@@ -240,7 +240,7 @@ def test_config4_largest_factor_ill_conditioned():
     g0 = f64(run.gradw_master[0])
     assert relfro(f64(run.grad[0]), oracle.precondition(QA, lamA, QG, lamG, wl.damping, g0)) <= TOL_F32
     assert precondition_equation_residual(run, 0, wl.damping) <= TOL_F32
-    check_scaled_damping(run, 0, lamA, QA, lamG, QG, e2e_tol=3e-3)
+    check_scaled_damping(run, 0, lamA, QA, lamG, QG, e2e_tol=1e-3)
     # the same factors with every eigensolver product in fp32
     info = run.eig(fp32_only=True)
     torch.cuda.synchronize()
