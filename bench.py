@@ -32,6 +32,8 @@ BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
     "precond_gemm_split": ("mfma", PEAK_MFMA_F16 / 3.0, "TFLOP/s", "flops"),
     "eig_small": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
     "eig_pivot_solve": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
+    # all inner rounds of an outer round in one launch: pivot sweeps in LDS (plain ALU) and 64-wide block updates
+    "eig_unit_rounds": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
     # K = 64 contraction per pass over W and Q: 16 flop/byte, below the fp32 ridge of 19.7
     "eig_apply": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "eig_misc": ("hbm", PEAK_HBM, "GB/s", "bytes"),
@@ -39,7 +41,8 @@ BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
     "eig_copy": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     # split-fp16 engine, three fp16 MFMA products per algorithmic fp32 product: 56 algorithmic flop/byte, i.e.
     # 168 issued fp16 flop/byte against an fp16 ridge of 312, so the HBM roof is the one that binds
-    "eig_outer_gemm": ("hbm", PEAK_HBM, "GB/s", "bytes"),
+    "eig_outer_cols": ("hbm", PEAK_HBM, "GB/s", "bytes"),
+    "eig_outer_rows": ("hbm", PEAK_HBM, "GB/s", "bytes"),
 }
 
 
@@ -57,25 +60,28 @@ def measured_traffic(kernel):
     return None
 
 
-SAMPLE_LAYERS = ("s3b1.conv3", "s4b1.reduce", "fc")   # d_A/d_G = 2305/256, 2049/512, 2049/1000
-
-
-def sample_layer_ids(wl):
-    ids = [i for i, l in enumerate(wl.layers) if l.name in SAMPLE_LAYERS]
-    return ids if ids else [0]
+def distinct_shape_layers(wl):
+    """First layer of every distinct shape of the set, with the number of layers of that shape."""
+    first, count = {}, {}
+    for i, l in enumerate(wl.layers):
+        key = (l.c_in, l.c_out, l.k, l.stride, l.pad, l.h_in, l.fc)
+        first.setdefault(key, i)
+        count[key] = count.get(key, 0) + 1
+    return [(first[k], count[k]) for k in first]
 
 
 def cpu_baseline(wl_name):
-    """The fp64 oracle, as it stands, timed on this host on a bounded sample of the workload: three
-    layers of the set, one K-FAC step each (unfold + both factors + both eigendecompositions +
-    preconditioning)."""
+    """The fp64 oracle, as it stands, timed on this host on the workload of `value`: one K-FAC step (unfold + both
+    factors + both eigendecompositions + preconditioning) of one layer of every distinct shape of the set, each
+    time multiplied by the number of layers of that shape (layers of one shape cost the oracle the same: its
+    loops and its eigensolver's operation count depend on the sizes only)."""
     import oracle
     from paper_2007_00784_amd import synthetic as S
     wl = S.workload(wl_name)
-    ids = sample_layer_ids(wl)
     ph = {"factors": 0.0, "eig": 0.0, "precondition": 0.0}
-    desc = []
-    for li in ids:
+    measured = 0.0
+    picks = distinct_shape_layers(wl)
+    for li, mult in picks:
         lay = wl.layers[li]
         t = S.layer_inputs(wl, li, update=0)
         R = wl.batch * lay.T
@@ -93,20 +99,25 @@ def cpu_baseline(wl_name):
         t2 = time.perf_counter()
         oracle.precondition(qa, la, qg, lg, wl.damping, t["gradw"])
         t3 = time.perf_counter()
-        ph["factors"] += (t1 - t0) * 1e3
-        ph["eig"] += (t2 - t1) * 1e3
-        ph["precondition"] += (t3 - t2) * 1e3
-        desc.append("%s (d_A=%d, d_G=%d, R=%d)" % (lay.name, lay.d_a, lay.d_g, R))
+        ph["factors"] += mult * (t1 - t0) * 1e3
+        ph["eig"] += mult * (t2 - t1) * 1e3
+        ph["precondition"] += mult * (t3 - t2) * 1e3
+        measured += (t3 - t0) * 1e3
+        print("[bench] oracle: %s x%d in %.1f s" % (lay.name, mult, t3 - t0), file=sys.stderr, flush=True)
     return {
         "value": round(sum(ph.values()), 1), "unit": "ms", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": "one K-FAC step of %d of the %d layers: %s" % (len(ids), len(wl.layers), ", ".join(desc)),
+        "sample": "one K-FAC step of the whole set (%d layers), composed: one layer of each of the %d distinct shapes "
+                  "timed once and multiplied by the number of layers of that shape; %.1f s of CPU work measured"
+                  % (len(wl.layers), len(picks), measured / 1e3),
         "phases_ms": {k: round(v, 1) for k, v in ph.items()},
+        "measured_ms": round(measured, 1),
     }
 
 
 def gpu_same_sample_ms(wl, torch, KfacRunner):
-    """The HIP path on exactly the layers the CPU baseline times (one step, after one warm-up step)."""
-    run = KfacRunner(wl, "cuda:0", n_updates=1, layers=sample_layer_ids(wl))
+    """The HIP path on exactly the layers the CPU baseline times, one of each distinct shape (one step, after one
+    warm-up step): compare with cpu_baseline.measured_ms."""
+    run = KfacRunner(wl, "cuda:0", n_updates=1, layers=[li for li, _ in distinct_shape_layers(wl)])
     for _ in range(2):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -117,6 +128,55 @@ def gpu_same_sample_ms(wl, torch, KfacRunner):
         ms = (time.perf_counter() - t0) * 1e3
     run.close()
     return round(ms, 3)
+
+
+def config_step_ms(name, torch, K, S, KfacRunner):
+    """Step time of one of the other benchmark configurations, after two warm-up steps: one factor update folded
+    into the running average + eigendecomposition of every factor + preconditioning of every gradient.  For the
+    bf16 configuration the update-decoupled schedule over 200 iterations instead (factors every 10 iterations,
+    eigendecompositions every 100 -- the second started from the eigenvectors of the first --, preconditioning
+    every iteration), amortised per iteration."""
+    wl = S.workload(name)
+    run = KfacRunner(wl, "cuda:0", n_updates=2)
+    run.update_factors(0, 0.0)
+    out = {}
+    if not wl.bf16:
+        ms = []
+        for it in range(5):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run.update_factors(1, wl.decay)
+            info = run.eig(raise_on_noconv=False)
+            run.precondition()
+            torch.cuda.synchronize()
+            ms.append((time.perf_counter() - t0) * 1e3)
+        out = {"step_ms": round(min(ms[2:]), 3), "layers": len(wl.layers), "batch": wl.batch,
+               "eig_converged": "%d/%d" % (sum(1 for (_, _, c) in info if c), len(info))}
+    else:
+        per_it = []
+        for rep in range(2):      # the first pass is the warm-up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            n_fac = n_eig = 0
+            t_eig = 0.0
+            for k in range(200):
+                do_f, do_e = K.kfac_schedule_due(k, 10, 100)
+                if do_f:
+                    run.update_factors(n_fac % 2, wl.decay)
+                    n_fac += 1
+                if do_e:
+                    te = time.perf_counter()
+                    info = run.eig(raise_on_noconv=False, warm_start=n_eig > 0)
+                    t_eig += time.perf_counter() - te
+                    n_eig += 1
+                run.precondition()
+            torch.cuda.synchronize()
+            per_it.append((time.perf_counter() - t0) * 1e3 / 200)
+        out = {"ms_per_iteration_200": round(per_it[-1], 3), "layers": len(wl.layers), "batch": wl.batch,
+               "eig_ms_total": round(t_eig * 1e3, 1), "factor_updates": n_fac, "eigendecompositions": n_eig,
+               "eig_converged": "%d/%d" % (sum(1 for (_, _, c) in info if c), len(info))}
+    run.close()
+    return out
 
 
 def main():
@@ -152,6 +212,7 @@ def main():
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
     def step(marks=None):
+        run.restore_gradients()      # the backward pass's part: fresh gradients (inside the step, outside the phases)
         if marks is not None:
             marks[0].record()
         run.update_factors(1, wl.decay)
@@ -160,7 +221,7 @@ def main():
         run.eig(raise_on_noconv=False)
         if marks is not None:
             marks[2].record()
-        run.precondition()
+        run.precondition(restore=False)
         if marks is not None:
             marks[3].record()
 
@@ -200,6 +261,21 @@ def main():
     warm_sweeps = max(s for (s, _, _) in run.eig_info)
     if args.no_extras:
         warm_ms, warm_sweeps = [0.0], None
+
+    # the eigendecomposition with every product on the fp32 matrix instructions (the default runs the rank-256 passes of
+    # factors with d >= 2048 on split-fp16 products until it recomputes W = Q^T F Q in fp32): not part of `value`
+    fp32_ms, fp32_sweeps = None, None
+    if not args.no_extras:
+        run.update_factors(1, wl.decay)
+        ts_ = []
+        for _ in range(2):
+            e0, e1 = ev(), ev()
+            e0.record()
+            run.eig(raise_on_noconv=False, fp32_only=True)
+            e1.record()
+            torch.cuda.synchronize()
+            ts_.append(e0.elapsed_time(e1))
+        fp32_ms, fp32_sweeps = round(min(ts_), 3), max(s for (s, _, _) in run.eig_info)
 
     # the update-decoupled schedule (factors every 10 iterations, eigendecompositions every 100, preconditioning
     # every iteration) over 200 iterations, amortised; not part of `value`
@@ -250,8 +326,12 @@ def main():
     roofline = dict(kernels[dom])
     roofline["kernel"] = dom
     roofline["traffic"] = measured_traffic(dom) if args.workload == "resnet50" else None
+    roofline["timing"] = ("hipEvents around every launch of the class on the stream it runs on, over one instrumented step "
+                          "with all groups in flight: a launch's bracket includes the time it waits for compute units "
+                          "behind kernels of the library's other internal streams")
     roofline = {k: roofline[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic",
-                                         "launches", "avg_ms", "total_ms", "algorithmic_bytes_per_launch", "algorithmic_tflops") if k in roofline}
+                                         "launches", "avg_ms", "total_ms", "algorithmic_bytes_per_launch", "algorithmic_tflops",
+                                         "timing") if k in roofline}
     w = run.work()
     peak_syrk = PEAK_MFMA_F16 if wl.bf16 else PEAK_MFMA_F32     # bf16 samples run on the bf16 matrix instructions
     derived = {
@@ -262,6 +342,7 @@ def main():
         "eig_sum_d3_per_s": round(w["sum_d3"] / (phases["eig"] * 1e-3), 1),
         "eig_sweeps_max": max(sweeps), "eig_converged": "%d/%d" % (nconv, len(info)),
         "eig_warm_start_ms": None if args.no_extras else round(min(warm_ms), 3), "eig_warm_start_sweeps_max": warm_sweeps,
+        "eig_fp32_only_ms": fp32_ms, "eig_fp32_only_sweeps_max": fp32_sweeps,
         "decoupled_schedule_ms_per_iteration": None if args.no_extras else round(sched_ms, 3),
         "precondition_split_f16_ms": round(min(split_ms), 3),
         "precondition_split_f16_tflops": round(w["precond_flops"] / (min(split_ms) * 1e-3) / 1e12, 2),
@@ -273,7 +354,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %d layers, batch %d, %s; factor update + eig of %d factors + precondition"
                                % (wl.name, len(wl.layers), wl.batch, "bf16 in / fp32 factors" if wl.bf16 else "fp32",
-                                  2 * len(wl.layers))},
+                                  2 * len(wl.layers)),
+                   "arithmetic": "factors, pivot solves, round applications, W = Q^T F Q, eigenvalues, preconditioner: fp32 "
+                                 "(fp32 MFMA); rank-256 update passes of the eigensolver for factors with d >= 2048: "
+                                 "split-fp16 MFMA (hi + lo halves, 3 products, fp32 accumulation), followed by a recomputation "
+                                 "of W = Q^T F Q in fp32; derived.eig_fp32_only_ms is the same step's eigensolve with "
+                                 "every product in fp32"},
         "phases_ms": {k: round(v, 3) for k, v in phases.items()},
         "step_ms_median": round(step_ms[len(step_ms) // 2], 3), "step_ms_min": round(step_ms[0], 3),
         "derived": derived,
@@ -281,6 +367,12 @@ def main():
         "kernels": kernels,
     }
     run.close()
+    if not args.no_extras and args.workload == "resnet50":
+        # the other four benchmark configurations, each after two warm-up steps
+        out["configs"] = {}
+        for name in ("single_conv", "resnet32_cifar", "largest_factor", "resnet50_bf16"):
+            out["configs"][name] = config_step_ms(name, torch, K, S, KfacRunner)
+            print("[bench] config %s: %s" % (name, out["configs"][name]), file=sys.stderr, flush=True)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
         out["cpu_baseline"]["gpu_same_sample_ms"] = gpu_same_sample_ms(wl, torch, KfacRunner)

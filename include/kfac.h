@@ -70,7 +70,7 @@ typedef struct {
                                 elementwise accuracy on strongly graded spectra.                   */
     int warm_start;          /* 1: on entry every Q_i with d_i > 128 holds an orthonormal basis to start from
                                 (typically the eigenvectors of the previous decomposition of a slowly moving
-                                factor, Sec. V-B); the iteration then runs on Q_i^T F_i Q_i, which is close to
+                                factor: the remark of Sec. V-C that the FIM becomes more stable as training progresses); the iteration then runs on Q_i^T F_i Q_i, which is close to
                                 diagonal, and needs fewer sweeps.  Costs 4 d^3 flops per factor up front; a basis
                                 that is not orthonormal to fp32 rounding gives wrong results.  0: start from I.   */
 } kfac_eig_opts;
@@ -200,7 +200,7 @@ typedef struct {
 int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items /* host */);
 size_t kfac_precondition_workspace_bytes(int n, const kfac_precond_item *items /* host; only dA, dG are read */);
 
-/* The same, followed by the gradient scaling of Sec. V-B ("K-FAC Hyper-Parameters"): every preconditioned
+/* The same, followed by the gradient scaling of Sec. V-C ("K-FAC Hyper-Parameters"): every preconditioned
  * gradient P_l is multiplied by
  *     nu = min(1, sqrt(kappa / (lr^2 * sum_l |<P_l, grad_l>|)))
  * with grad_l the gradient as it was on entry and <.,.> the sum of elementwise products (for bf16 gradients

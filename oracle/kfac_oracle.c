@@ -524,7 +524,7 @@ void oracle_schedule(int64_t k, int f_fac, int f_eig, int *do_factors, int *do_e
 }
 
 /* ------------------------------------------------------------------------
- * Gradient scaling (Sec. V-B, the equation for nu): after preconditioning, every layer's gradient is multiplied by
+ * Gradient scaling (Sec. V-C, "K-FAC Hyper-Parameters", the equation for nu): after preconditioning, every layer's gradient is multiplied by
  *     nu = min(1, sqrt(kappa / (alpha^2 * sum_i |<P_i, g_i>|)))
  * where P_i is the preconditioned and g_i the original gradient of layer i, <.,.> the sum of the elementwise
  * products, kappa a user constant and alpha the learning rate.  The layers are given back to back in two

@@ -196,7 +196,7 @@ def precondition_inverse(G, A, gamma, grad):
 
 
 def grad_scale(precond, grad, kappa, alpha):
-    """nu of Sec. V-B for lists of per-layer preconditioned and original gradients."""
+    """nu of Sec. V-C for lists of per-layer preconditioned and original gradients."""
     assert len(precond) == len(grad)
     sizes = (_i64 * len(grad))(*[int(np.asarray(g).size) for g in grad])
     P = _c(np.concatenate([np.asarray(p, dtype=np.float64).ravel() for p in precond])) if len(grad) else _c(np.zeros(1))

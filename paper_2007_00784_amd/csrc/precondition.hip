@@ -4,7 +4,7 @@
 //   V2 = (T QA) / (lamG lamA^T + damping)     (K = dA, divide fused into the epilogue)
 //   T  = QG V2                (K = dG)
 //   grad = T QA^T             (K = dA)
-// and optionally the gradient scaling of Sec. V-B on top: nu = min(1, sqrt(kappa / (lr^2 sum_l |<P_l, grad_l>|))),
+// and optionally the gradient scaling of Sec. V-C on top: nu = min(1, sqrt(kappa / (lr^2 sum_l |<P_l, grad_l>|))),
 // P_l the preconditioned and grad_l the original gradient of layer l, every P_l multiplied by nu.  The inner
 // products cost no extra pass: the last stage overwrites grad element by element, so its epilogue reads the
 // old value just before it stores the new one.

@@ -276,7 +276,7 @@ def kfac_precondition_batched(ctx, QA, lamA, QG, lamG, damping, grad, factored_d
 
 
 def kfac_precondition_batched_scaled(ctx, QA, lamA, QG, lamG, damping, grad, kappa, lr, nu, split_f16=False):
-    """As kfac_precondition_batched, then every gradient is multiplied by the nu of Sec. V-B; nu: device tensor
+    """As kfac_precondition_batched, then every gradient is multiplied by the nu of Sec. V-C; nu: device tensor
     of one float32, written by the call."""
     arr = _precond_items(QA, lamA, QG, lamG, damping, grad, split_f16=split_f16)
     _check(lib().kfac_precondition_batched_scaled(ctx, len(grad), arr, float(kappa), float(lr), _ptr(nu)),

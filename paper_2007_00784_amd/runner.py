@@ -114,13 +114,20 @@ class KfacRunner:
         self.eig_info = K.kfac_eig(self.ctx, self.A + self.G, self.QA + self.QG, self.lamA + self.lamG, **kw)
         return self.eig_info
 
-    def precondition(self, damping=None, kappa=None, lr=None, split_f16=None):
-        """In-place preconditioning of a fresh copy of the gradients; with kappa and lr also the gradient
-        scaling nu (left in self.nu, a device tensor).  split_f16 defaults to the workload's gradient type:
-        bf16 gradients (rounding 4e-3) go through the split-fp16 GEMM chain (error 1e-6), fp32 ones through fp32."""
+    def restore_gradients(self):
+        """Fresh gradients for the next in-place preconditioning (one device copy of the flat master buffer): what
+        the backward pass of a training iteration delivers."""
+        self.grad_flat.copy_(self.gradw_master_flat)
+
+    def precondition(self, damping=None, kappa=None, lr=None, split_f16=None, restore=True):
+        """In-place preconditioning of the gradients (restored from their masters first unless restore=False); with
+        kappa and lr also the gradient scaling nu (left in self.nu, a device tensor).  split_f16 defaults to the
+        workload's gradient type: bf16 gradients (rounding 4e-3) go through the split-fp16 GEMM chain (error 1e-6),
+        fp32 ones through fp32."""
         gamma = self.wl.damping if damping is None else damping
         split = self.wl.bf16 if split_f16 is None else split_f16
-        self.grad_flat.copy_(self.gradw_master_flat)
+        if restore:
+            self.restore_gradients()
         if kappa is None:
             K.kfac_precondition_batched(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad, split_f16=split)
         else:

@@ -215,6 +215,12 @@ def workload(name):
         return Workload(6, name, tuple(resnet50_layers(101)), 32, 1e-4, 1e-3)
     if name == "resnet152":
         return Workload(7, name, tuple(resnet50_layers(152)), 32, 1e-4, 1e-3)
+    # a stack of Linear layers only (the other layer kind the method handles, Sec. V): samples are [R][d] rows, no
+    # unfold anywhere, factors of rank <= batch
+    if name == "mlp":
+        widths = (2048, 2048, 2048, 1000)
+        layers = tuple(Layer("fc%d" % i, widths[i], widths[i + 1], 1, 1, 0, 1, fc=True) for i in range(len(widths) - 1))
+        return Workload(8, name, layers, 256, 1e-3, 1e-3)
     raise KeyError(name)
 
 

@@ -385,7 +385,7 @@ def test_precondition_split_f16_matches_oracle(ctx, dA, dG, bf16):
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("split", [False, True])
 def test_precondition_batched_with_gradient_scaling(ctx, bf16, split):
-    """Sec. V-B: the batched preconditioner followed by nu = min(1, sqrt(kappa / (lr^2 sum_l |<P_l, g_l>|))).
+    """Sec. V-C: the batched preconditioner followed by nu = min(1, sqrt(kappa / (lr^2 sum_l |<P_l, g_l>|))).
     Three layers of different tile counts (one tile, ragged tiles, several tiles) in one call, against the oracle
     end to end, against the oracle's nu on the library's own unscaled output, and with a kappa that does not clip."""
     rng = np.random.default_rng(11)

@@ -469,7 +469,7 @@ def test_schedule_counts():
 
 # ------------------------------------------------------------------ gradient scaling
 def test_grad_scale_closed_forms():
-    """Sec. V-B, nu = min(1, sqrt(kappa / (alpha^2 sum_i |<P_i, g_i>|))): hand-computed cases.
+    """Sec. V-C, nu = min(1, sqrt(kappa / (alpha^2 sum_i |<P_i, g_i>|))): hand-computed cases.
 
     One layer with P = g = (3, 4): <P, g> = 25, so nu = sqrt(kappa / (alpha^2 25)).  Two layers whose inner
     products are +25 and -7: the sum of the ABSOLUTE values, 32, enters (a plain sum of 18 or a total
