@@ -32,8 +32,6 @@ BOUNDS = {  # kernel class -> (bound, peak, unit, which work figure)
     "precond_gemm_split": ("mfma", PEAK_MFMA_F16 / 3.0, "TFLOP/s", "flops"),
     "eig_small": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
     "eig_pivot_solve": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
-    # all inner rounds of an outer round in one launch: pivot sweeps in LDS (plain ALU) and 64-wide block updates
-    "eig_unit_rounds": ("alu", PEAK_VALU_F32, "TFLOP/s", "flops"),
     # K = 64 contraction per pass over W and Q: 16 flop/byte, below the fp32 ridge of 19.7
     "eig_apply": ("hbm", PEAK_HBM, "GB/s", "bytes"),
     "eig_misc": ("hbm", PEAK_HBM, "GB/s", "bytes"),

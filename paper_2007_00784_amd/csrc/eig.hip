@@ -1203,7 +1203,7 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
                                nW, nrb, (const float *)r.g.Qw, r.Qalt, 0);
     }
     if (nW > 0) {
-        KfacProfScope prof(ctx, KC_EIG_OUTER, 0.25 * fl, 6.0 * n2, st);
+        KfacProfScope prof(ctx, KC_EIG_OUTER_ROWS, 0.25 * fl, 6.0 * n2, st);
         if (r.x3) hipLaunchKernelGGL(sp_pass_rows_kernel<true>, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
         else hipLaunchKernelGGL(sp_pass_rows_kernel<false>, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
     }

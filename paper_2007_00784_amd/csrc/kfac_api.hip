@@ -252,8 +252,8 @@ int kfac_profile_begin(kfac_ctx *ctx) {
 int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out, int max, int *n) {
     if (!ctx || !out || !n || max < 0) return KFAC_EINVAL;
     static const char *names[KC_COUNT] = {"unfold", "syrk", "syrk_reduce", "precond_gemm", "eig_small",
-                                          "eig_pivot_solve", "eig_apply", "eig_misc", "eig_post_gemm", "eig_copy", "eig_outer_gemm",
-                                          "precond_scale", "syrk_bf16", "precond_gemm_split"};
+                                          "eig_pivot_solve", "eig_apply", "eig_misc", "eig_post_gemm", "eig_copy", "eig_outer_cols",
+                                          "precond_scale", "syrk_bf16", "precond_gemm_split", "eig_outer_rows"};
     ctx->prof_on = false;
     KFAC_HIP_CHECK(hipStreamSynchronize(ctx->stream));
     kfac_kernel_stat acc[KC_COUNT] = {};

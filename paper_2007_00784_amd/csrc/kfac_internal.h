@@ -9,7 +9,7 @@
 // Kernel classes for the optional per-kernel timing (kfac_profile_begin / kfac_profile_end).
 enum KfacKernelClass {
     KC_UNFOLD = 0, KC_SYRK, KC_SYRK_REDUCE, KC_PRECOND_GEMM, KC_EIG_SMALL, KC_EIG_SOLVE, KC_EIG_APPLY,
-    KC_EIG_MISC, KC_EIG_POST, KC_EIG_COPY, KC_EIG_OUTER, KC_PRECOND_SCALE, KC_SYRK_B16, KC_PRECOND_GEMM_X3, KC_COUNT
+    KC_EIG_MISC, KC_EIG_POST, KC_EIG_COPY, KC_EIG_OUTER, KC_PRECOND_SCALE, KC_SYRK_B16, KC_PRECOND_GEMM_X3, KC_EIG_OUTER_ROWS, KC_COUNT
 };
 struct KfacProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
 
