@@ -404,8 +404,39 @@ struct BlkGroup {
     int bipartite;   // 0: tournament over all blocks; 1: block j of the first half with a block of the second
     const int *done; // [factors]: 1 once a factor has met the tolerance; its workgroups return at once
     int per_factor;  // matrices of this group per factor (units of a two-level group; 1 otherwise)
+    // Unit mode (the inner rounds of a two-level group): matrix m is unit m % per_factor of factor m / per_factor, W points
+    // to the factors' full matrices [factors][ldw][ldw] and the unit's small blocks are rotated in place there (block b
+    // of the unit is quarter b % 4 of super-block b0 (b < 4) or b1 of the outer round's pair), while Qw is the unit's own
+    // compact accumulator [nmat][npad][npad].
+    int unit_mode, ldw, outer_round, sp_players, sp_nsuper;
+    int qw_identity;        // the accumulator is taken to be the identity instead of being read (first inner round)
+    int qw_minus_identity;  // the identity is subtracted from the accumulator as it is written (last inner round)
 };
 __device__ inline bool blk_done(const BlkGroup &g, int m) { return g.done[m / g.per_factor] != 0; }
+
+// Where matrix m of a group lives: base pointer and leading dimension of the matrix its blocks are part of, and
+// (unit mode) the two super-blocks of the unit, -1 for an absent one.
+struct BlkWhere { float *W; int64_t ld; int b0, b1; };
+__device__ inline BlkWhere blk_where(const BlkGroup &g, int m) {
+    BlkWhere w;
+    if (!g.unit_mode) {
+        w.W = g.W + (int64_t)m * g.npad * g.npad;
+        w.ld = g.npad;
+        w.b0 = w.b1 = 0;
+        return w;
+    }
+    const int f = m / g.per_factor, u = m - f * g.per_factor;
+    w.W = g.W + (int64_t)f * g.ldw * g.ldw;
+    w.ld = g.ldw;
+    if (g.outer_round < 0) { w.b0 = u; w.b1 = -1; }      // diagonal phase: super-block u alone
+    else {
+        int p, q;
+        rr_pair(g.sp_players, g.outer_round, u, p, q);
+        w.b0 = p;
+        w.b1 = q < g.sp_nsuper ? q : -1;
+    }
+    return w;
+}
 
 // Pair j of round `round`: tournament over `players` blocks, or (bipartite) block j with block
 // half + (j + round) % half, which meets every cross pair of the two halves in `half` rounds.
@@ -501,6 +532,15 @@ __device__ inline int pair_index(int a, int p, int q, int nblk) {
     const int blk = a < EB ? p : q;
     return blk < nblk ? blk * EB + (a & (EB - 1)) : -1;
 }
+// The same inside the matrix the group's W points to: in unit mode small block b of the unit is quarter b % 4 of
+// super-block b0 (b < 4) or b1 (128-wide super-blocks of four small blocks).
+__device__ inline int blk_index(const BlkGroup &g, const BlkWhere &w, int a, int p, int q) {
+    if (!g.unit_mode) return pair_index(a, p, q, g.nblk);
+    const int blk = a < EB ? p : q;
+    if (blk >= g.nblk) return -1;
+    const int sb = blk < 4 ? w.b0 : w.b1;
+    return sb < 0 ? -1 : sb * (4 * EB) + (blk & 3) * EB + (a & (EB - 1));
+}
 
 // One sweep of the LDS Jacobi solver over the pivot sub-problem of every pair of this round; writes
 // the accumulated (and re-orthogonalised) transform J and whether it is the identity.
@@ -512,7 +552,8 @@ __global__ __launch_bounds__(SOLVE_NT) void blk_solve_kernel(BlkGroup g, int rou
     JacobiSmem sm(smem, KP, PLD);
     const int m = blockIdx.y, pj = blockIdx.x, tid = threadIdx.x;
     if (blk_done(g, m)) return;
-    const float *W = g.W + (int64_t)m * g.npad * g.npad;
+    const BlkWhere wh = blk_where(g, m);
+    const float *W = wh.W;
     int p, q;
     sched_pair(g, round, pj, p, q);
     constexpr int PER = KP * KP / SOLVE_NT;
@@ -521,10 +562,10 @@ __global__ __launch_bounds__(SOLVE_NT) void blk_solve_kernel(BlkGroup g, int rou
     for (int u = 0; u < PER; ++u) {
         const int e = tid + SOLVE_NT * u;
         const int a = e / KP, b = e % KP;
-        const int gi = pair_index(a, p, q, g.nblk), gj = pair_index(b, p, q, g.nblk);
+        const int gi = blk_index(g, wh, a, p, q), gj = blk_index(g, wh, b, p, q);
         // read the lower triangle only, so the sub-problem is exactly symmetric
         v[u] = 0.f;
-        if (gi >= 0 && gj >= 0) v[u] = (gi >= gj) ? W[(int64_t)gi * g.npad + gj] : W[(int64_t)gj * g.npad + gi];
+        if (gi >= 0 && gj >= 0) v[u] = (gi >= gj) ? W[(int64_t)gi * wh.ld + gj] : W[(int64_t)gj * wh.ld + gi];
     }
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
@@ -641,7 +682,8 @@ __global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, in
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32, lk = lane >> 5, lc = lane & 31;
     if ((int)blockIdx.x < nblocks_w) {
-        float *W = g.W + m * np2;
+        const BlkWhere wh = blk_where(g, m);
+        float *W = wh.W;
         int I, Jp;
         tri_decode(blockIdx.x, I, Jp);
         const bool idI = idt[I] != 0, idJ = idt[Jp] != 0;
@@ -649,14 +691,14 @@ __global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, in
         int pI, qI, pJ, qJ;
         sched_pair(g, round, I, pI, qI);
         sched_pair(g, round, Jp, pJ, qJ);
-        auto rowf = [&](int a) { return pair_index(a, pI, qI, nblk); };
-        auto colf = [&](int b) { return pair_index(b, pJ, qJ, nblk); };
+        auto rowf = [&](int a) { return blk_index(g, wh, a, pI, qI); };
+        auto colf = [&](int b) { return blk_index(g, wh, b, pJ, qJ); };
         // operands of both products in registers: bj[j] = J_J[2j + lk][wn + lc], aj[j] = J_I[2j + lk][wm + lc]
         float bj[KP / 2], aj[KP / 2];
         const float *Jc = Jall + (int64_t)Jp * (KP * KP) + wn + lc, *Jr = Jall + (int64_t)I * (KP * KP) + wm + lc;
 #pragma unroll
         for (int j = 0; j < KP / 2; ++j) bj[j] = Jc[(2 * j + lk) * KP];
-        block_load(Xs, W, g.npad, rowf, colf);
+        block_load(Xs, W, wh.ld, rowf, colf);
 #pragma unroll
         for (int j = 0; j < KP / 2; ++j) aj[j] = Jr[(2 * j + lk) * KP];
         __syncthreads();
@@ -680,13 +722,15 @@ __global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, in
             }
             __syncthreads();
         }
-        block_store<false>(Xs, W, g.npad, rowf, colf);
-        if (I != Jp) block_store<true>(Xs, W, g.npad, rowf, colf);
+        block_store<false>(Xs, W, wh.ld, rowf, colf);
+        if (I != Jp) block_store<true>(Xs, W, wh.ld, rowf, colf);
     } else {
         float *Qw = g.Qw + m * np2;
         const int t = blockIdx.x - nblocks_w;
         const int rb = t % nrb, Jp = t / nrb;
-        if (idt[Jp]) return;
+        // an identity transform leaves the accumulator as it is -- unless this launch also starts it or takes the
+        // identity off it, which every block has to see
+        if (idt[Jp] && !g.qw_identity && !g.qw_minus_identity) return;
         int pJ, qJ;
         sched_pair(g, round, Jp, pJ, qJ);
         const int row0 = rb * KP, npad = g.npad;
@@ -696,12 +740,26 @@ __global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, in
         const float *Jc = Jall + (int64_t)Jp * (KP * KP) + wn + lc;
 #pragma unroll
         for (int j = 0; j < KP / 2; ++j) bj[j] = Jc[(2 * j + lk) * KP];
-        block_load(Xs, Qw, g.npad, rowf, colf);
+        if (g.qw_identity) {
+            for (int e = threadIdx.x; e < KP * KP; e += NT) {
+                const int a = e >> 6, b = e & 63;
+                Xs[a * BLD + b] = (row0 + a == colf(b)) ? 1.f : 0.f;
+            }
+        } else {
+            block_load(Xs, Qw, g.npad, rowf, colf);
+        }
         __syncthreads();
         const floatx16 t2 = block_gemm<true>(Xs, bj, wm, wn, lk, lc);
         __syncthreads();
         acc_to_block(t2, Xs, wm, wn, lk, lc);
         __syncthreads();
+        if (g.qw_minus_identity) {
+            for (int e = threadIdx.x; e < KP * KP; e += NT) {
+                const int a = e >> 6, b = e & 63;
+                if (row0 + a == colf(b)) Xs[a * BLD + b] -= 1.f;
+            }
+            __syncthreads();
+        }
         block_store<false>(Xs, Qw, g.npad, rowf, colf);
     }
 }
@@ -782,12 +840,13 @@ __global__ __launch_bounds__(NT) void blk_gather_kernel(const float *Qin, int64_
 // blocks is still visited exactly once per sweep.
 // ------------------------------------------------------------------------------------------------
 constexpr int SB = 128;                 // super-block width
-constexpr int LDI = 2 * SB;             // edge of a gathered super-pair
+constexpr int LDI = 2 * SB;             // edge of a super-pair (unit)
+static_assert(SB == 4 * EB, "a super-block is four small blocks (blk_index)");
 constexpr int TWO_LEVEL_MIN = 2048;     // factors at least this large take the two-level path
 
 struct SpGroup {
     float *W, *T;          // [nmat][npad][npad]: rotated matrix, column-pass result
-    float *Wi, *Vi;        // gathered units and their accumulated transforms: [nmat*U][s][s]
+    float *Vi;             // accumulated transforms of the units: [nmat*U][s][s]
     float *scale;          // [nmat][2]: power of two that brings ||W||_F into [2^12, 2^13), and its inverse
     const int *done;       // [nmat]: as in BlkGroup
     int nmat, npad, nsuper, players;
@@ -822,54 +881,6 @@ __device__ inline void unit_blocks(const SpGroup &g, int round, int u, int &b0, 
     rr_pair(g.players, round, u, p, q);
     b0 = p;
     b1 = q < g.nsuper ? q : -1;
-}
-
-// Wi[unit] <- W[{b0,b1},{b0,b1}] (zero where a super-block is absent), Vi[unit] <- I.  s = unit edge.
-__global__ __launch_bounds__(NT) void sp_gather_kernel(SpGroup g, int round, int s) {
-    const int u = blockIdx.y, m = blockIdx.z, U = gridDim.y;
-    if (g.done[m]) return;
-    int b0, b1;
-    unit_blocks(g, round, u, b0, b1);
-    const float *W = g.W + (int64_t)m * g.npad * g.npad;
-    float *Wi = g.Wi + ((int64_t)m * U + u) * s * s;
-    float *Vi = g.Vi + ((int64_t)m * U + u) * s * s;
-    for (int e4 = blockIdx.x * NT + threadIdx.x; e4 < s * s / 4; e4 += gridDim.x * NT) {
-        const int a = (e4 * 4) / s, b = (e4 * 4) % s;
-        const int ba = a < SB ? b0 : b1, bb = b < SB ? b0 : b1;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ba >= 0 && bb >= 0)
-            v = *reinterpret_cast<const float4 *>(W + (int64_t)(ba * SB + (a & (SB - 1))) * g.npad + bb * SB + (b & (SB - 1)));
-        *reinterpret_cast<float4 *>(Wi + a * s + b) = v;
-        *reinterpret_cast<float4 *>(Vi + a * s + b) =
-            make_float4(a == b ? 1.f : 0.f, a == b + 1 ? 1.f : 0.f, a == b + 2 ? 1.f : 0.f, a == b + 3 ? 1.f : 0.f);
-    }
-}
-
-// W[{b0,b1},{b0,b1}] <- Wi[unit]: the unit's own blocks after its inner rounds.
-__global__ __launch_bounds__(NT) void sp_scatter_kernel(SpGroup g, int round, int s) {
-    const int u = blockIdx.y, m = blockIdx.z, U = gridDim.y;
-    if (g.done[m]) return;
-    int b0, b1;
-    unit_blocks(g, round, u, b0, b1);
-    float *W = g.W + (int64_t)m * g.npad * g.npad;
-    const float *Wi = g.Wi + ((int64_t)m * U + u) * s * s;
-    for (int e4 = blockIdx.x * NT + threadIdx.x; e4 < s * s / 4; e4 += gridDim.x * NT) {
-        const int a = (e4 * 4) / s, b = (e4 * 4) % s;
-        const int ba = a < SB ? b0 : b1, bb = b < SB ? b0 : b1;
-        if (ba >= 0 && bb >= 0)
-            *reinterpret_cast<float4 *>(W + (int64_t)(ba * SB + (a & (SB - 1))) * g.npad + bb * SB + (b & (SB - 1))) =
-                *reinterpret_cast<const float4 *>(Wi + a * s + b);
-    }
-}
-
-// Vi[unit] <- Vi[unit] - I for the split engine's passes, which compute X V as X + X (V - I) with only the
-// second term on the split engine: its error then scales with |V - I| and vanishes as the sweeps converge.
-__global__ __launch_bounds__(NT) void sp_minus_identity_kernel(SpGroup g, int s, int U, int count) {
-    const int e = blockIdx.x * NT + threadIdx.x;      // (unit, diagonal index)
-    if (e >= count) return;
-    const int u = e / s, a = e - u * s;
-    if (g.done[u / U]) return;
-    g.Vi[(int64_t)u * s * s + (int64_t)a * s + a] -= 1.f;
 }
 
 // Column pass.  W part: T[blk(I,a), blk(J,b)] = sum_c W[blk(I,a), blk(J,c)] V_J[c, b] for unit pairs I > J;
@@ -1026,7 +1037,7 @@ struct GroupPlan {
         size_t b = 0;
         b += kfac_align_up(nm * (two_level ? 4 : 2) * (size_t)npad * npad * sizeof(float), 256);   // W, Qw (+ T, Qw')
         if (two_level) {
-            b += kfac_align_up(nm * (size_t)U * 2 * LDI * LDI * sizeof(float), 256);              // Wi, Vi
+            b += kfac_align_up(nm * (size_t)U * LDI * LDI * sizeof(float), 256);                  // Vi
             b += kfac_align_up(inner_mats() * 4 * KP * KP * sizeof(float), 256);                   // inner J
             b += kfac_align_up(inner_mats() * 4 * sizeof(int), 256);                               // inner idt
             b += kfac_align_up(nm * 2 * sizeof(float), 256);                                       // scale
@@ -1158,7 +1169,7 @@ int enqueue_sweep_flat(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int inner_c
     return KFAC_OK;
 }
 
-// One phase of the two-level sweep: gather the units, run their inner rounds, apply their transforms.
+// One phase of the two-level sweep: the inner rounds of every unit, then the passes that apply the units' transforms.
 void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int inner_cap, float inner_tol) {
     const GroupPlan &gp = *r.plan;
     hipStream_t st = r.st;
@@ -1167,19 +1178,18 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
     const int s = diag ? SB : LDI;
     const BlkGroup &gin = diag ? r.gd : r.gi;
     const int inner_rounds = diag ? gin.players - 1 : gin.players / 2;
-    {
-        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
-        hipLaunchKernelGGL(sp_gather_kernel, dim3(s * s / 4 / NT, U, r.nm), dim3(NT), 0, st, r.sp, round, s);
-    }
+    // The unit's own blocks of W are rotated in place by the inner rounds (the passes below touch only blocks between
+    // different units); its transform is accumulated in the compact Vi, started from the identity by the first round
+    // and, for the split engine, left as V - I by the last.
     const int in_tw = gin.npairs * (gin.npairs + 1) / 2, in_nrb = s / KP, in_tiles = in_tw + in_nrb * gin.npairs;
     const double in_solve = (double)gin.nmat * gin.npairs * 9.0 * KP * KP * (KP / 2);
     const double in_apply = (double)gin.nmat * 8.0 * s * s * EB;
-    for (int ri = 0; ri < inner_rounds; ++ri)
-        enqueue_round(ctx, st, gin, ri, in_tiles, in_tw, in_nrb, lds_solve, inner_cap, inner_tol, in_solve, in_apply, 2.0 * in_apply / EB);
-    if (r.x3) {
-        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
-        const int count = r.nm * U * s;
-        hipLaunchKernelGGL(sp_minus_identity_kernel, dim3((count + NT - 1) / NT), dim3(NT), 0, st, r.sp, s, U, count);
+    for (int ri = 0; ri < inner_rounds; ++ri) {
+        BlkGroup gr = gin;
+        gr.outer_round = round;
+        gr.qw_identity = ri == 0;
+        gr.qw_minus_identity = r.x3 && ri == inner_rounds - 1;
+        enqueue_round(ctx, st, gr, ri, in_tiles, in_tw, in_nrb, lds_solve, inner_cap, inner_tol, in_solve, in_apply, 2.0 * in_apply / EB);
     }
     const int nW = ((2 * (U * (U - 1) / 2) + 7) / 8) * 16;      // padded to whole groups of 8 pairs x 2 halves
     const int nrb = gp.npad / SB;
@@ -1206,10 +1216,6 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
         KfacProfScope prof(ctx, KC_EIG_OUTER_ROWS, 0.25 * fl, 6.0 * n2, st);
         if (r.x3) hipLaunchKernelGGL(sp_pass_rows_kernel<true>, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
         else hipLaunchKernelGGL(sp_pass_rows_kernel<false>, dim3(nW, r.nm), dim3(kfac::NTHREADS), 0, st, r.sp, round, U, s);
-    }
-    {
-        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
-        hipLaunchKernelGGL(sp_scatter_kernel, dim3(s * s / 4 / NT, U, r.nm), dim3(NT), 0, st, r.sp, round, s);
     }
     std::swap(r.g.Qw, r.Qalt);
 }
@@ -1451,17 +1457,18 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
             r.Qalt = g.W + 3 * nm * np2;
             sp.nmat = nm; sp.npad = gp.npad; sp.nsuper = gp.nsuper; sp.players = gp.splayers;
             p += kfac_align_up(nm * 4 * np2 * sizeof(float), 256);
-            sp.Wi = (float *)p;
-            sp.Vi = sp.Wi + (size_t)nm * gp.U * LDI * LDI;
-            p += kfac_align_up((size_t)nm * gp.U * 2 * LDI * LDI * sizeof(float), 256);
+            sp.Vi = (float *)p;
+            p += kfac_align_up((size_t)nm * gp.U * LDI * LDI * sizeof(float), 256);
             float *Jin = (float *)p; p += kfac_align_up(gp.inner_mats() * 4 * KP * KP * sizeof(float), 256);
             int *idtin = (int *)p; p += kfac_align_up(gp.inner_mats() * 4 * sizeof(int), 256);
             sp.scale = (float *)p; p += kfac_align_up((size_t)nm * 2 * sizeof(float), 256);
             g.J = Jin; g.idt = idtin;   // unused by the flat kernels for this group
             // inner group of a regular outer round: units of 4 + 4 small blocks, bipartite pairing
-            r.gi = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.U, 2 * SB / EB, LDI, 2 * SB / EB, SB / EB, 1, nullptr, 1};
+            r.gi = BlkGroup{sp.W, sp.Vi, Jin, idtin, nullptr, nm * gp.U, 2 * SB / EB, LDI, 2 * SB / EB, SB / EB, 1, nullptr, 1,
+                            1, gp.npad, 0, gp.splayers, gp.nsuper, 0, 0};
             // inner group of the diagonal phase: one super-block of 4 small blocks each, tournament pairing
-            r.gd = BlkGroup{sp.Wi, sp.Vi, Jin, idtin, nullptr, nm * gp.nsuper, SB / EB, SB, SB / EB, SB / EB / 2, 0, nullptr, 1};
+            r.gd = BlkGroup{sp.W, sp.Vi, Jin, idtin, nullptr, nm * gp.nsuper, SB / EB, SB, SB / EB, SB / EB / 2, 0, nullptr, 1,
+                            1, gp.npad, -1, gp.splayers, gp.nsuper, 0, 0};
         } else {
             p += kfac_align_up(nm * 2 * np2 * sizeof(float), 256);
             g.J = (float *)p; p += kfac_align_up((size_t)nm * gp.npairs * KP * KP * sizeof(float), 256);
