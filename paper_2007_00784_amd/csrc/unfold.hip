@@ -11,6 +11,8 @@
 namespace {
 
 constexpr int UNFOLD_LDS_ELEMS = 8192;  // staged input elements per workgroup (32 KB as fp32)
+constexpr int UNFOLD_TILE_SLACK = 8;    // elements past the tile that a 16-byte read at its very end may touch
+constexpr int UNFOLD_MAX_PROWS = 2048;  // patch rows (channels of the workgroup x kh x kw) whose LDS offsets are tabulated
 
 struct UnfoldArgs {
     int N, C, H, W, kh, kw, sh, sw, ph, pw, Ho, Wo;
@@ -18,6 +20,12 @@ struct UnfoldArgs {
     int rows_out;  // output rows per workgroup
     int rows_in;   // staged input rows = (rows_out-1)*sh + kh
     int Wp;        // staged row width = W + 2*pw
+    int deint;     // 1 (column stride 2): even and odd staged columns are kept in separate half planes, so that the
+                   // columns one patch row needs (2*wo + kx: one parity) are contiguous in LDS
+    int Wq;        // LDS row pitch: Wp, or ceil(Wp / 2) when deinterleaved
+    int plane;     // LDS elements per staged channel: rows_in * Wp, or 2 * rows_in * Wq
+    int compact;   // 1 (1 x 1 kernel): only the pixels the windows touch are staged, as [rows_out][Wo] per channel, so the
+                   // output slab of a channel is one contiguous copy of its staged plane (Wq = Wo, plane = rows_out * Wo)
     float inv_Wp, inv_rows_in, inv_Tc, inv_Wo, inv_kw, inv_kh;
 };
 
@@ -30,7 +38,8 @@ __device__ inline void fdivmod(int e, int d, float inv_d, int &q, int &r) {
 }
 
 template <typename E>
-__device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out, const UnfoldArgs &a, int bx, int by, int bz, E *tile) {
+__device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out, const UnfoldArgs &a, int bx, int by, int bz, E *tile,
+                                    int *rowoff) {
     const int n = bz;
     const int c0 = by * a.cpb;
     const int ho0 = bx * a.rows_out;
@@ -38,25 +47,48 @@ __device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out
     const int rows_out = min(a.rows_out, a.Ho - ho0);
     const int rows_in = (rows_out - 1) * a.sh + a.kh;
     const int h_first = ho0 * a.sh - a.ph;
-    const int plane = a.rows_in * a.Wp;  // LDS pitch per channel
+    const int plane = a.plane;             // LDS pitch per channel
+    const int hplane = a.rows_in * a.Wq;   // deinterleaved: pitch between the even and the odd half plane
     // ---- stage: tile[cc][hr][wc] = x[n][c0+cc][h_first+hr][wc-pw] or 0 ----
-    const int stage_n = nch * rows_in * a.Wp;
-    for (int e = threadIdx.x; e < stage_n; e += 256) {
-        int row, wc, cc, hr;
-        fdivmod(e, a.Wp, a.inv_Wp, row, wc);
-        fdivmod(row, rows_in, 1.0f / (float)rows_in, cc, hr);
-        const int h = h_first + hr, w = wc - a.pw;
-        E v = 0;
-        if (h >= 0 && h < a.H && w >= 0 && w < a.W) v = x[(((int64_t)n * a.C + c0 + cc) * a.H + h) * a.W + w];
-        tile[cc * plane + hr * a.Wp + wc] = v;
+    // Eight elements per thread at a time: all eight addresses first, then the eight loads back to back, then the LDS
+    // stores -- so a thread waits for memory once per batch, not once per element.  (1 x 1 kernels: tile[cc][hoo][wo] =
+    // x[n][c0+cc][(ho0+hoo)*sh-ph][wo*sw-pw], only the pixels a window touches.)
+    const int srows = a.compact ? rows_out : rows_in, scols = a.compact ? a.Wo : a.Wp;   // staged rows and columns per channel
+    const int stage_n = nch * srows * scols;
+    const float inv_rows = 1.0f / (float)srows, inv_cols = a.compact ? a.inv_Wo : a.inv_Wp;
+    constexpr int SBATCH = 8;
+    for (int base = threadIdx.x; base < stage_n; base += 256 * SBATCH) {
+        E v[SBATCH];
+        int dst[SBATCH];
+        const E *src[SBATCH];
+#pragma unroll
+        for (int u = 0; u < SBATCH; ++u) {
+            const int e = min(base + 256 * u, stage_n - 1);
+            int row, wc, cc, hr;
+            fdivmod(e, scols, inv_cols, row, wc);
+            fdivmod(row, srows, inv_rows, cc, hr);
+            const int h = a.compact ? (ho0 + hr) * a.sh - a.ph : h_first + hr, w = a.compact ? wc * a.sw - a.pw : wc - a.pw;
+            const bool in = h >= 0 && h < a.H && w >= 0 && w < a.W;
+            src[u] = in ? x + ((((int64_t)n * a.C + c0 + cc) * a.H + h) * a.W + w) : nullptr;
+            dst[u] = a.deint ? cc * plane + (wc & 1) * hplane + hr * a.Wq + (wc >> 1) : cc * plane + hr * a.Wq + wc;
+            if (base + 256 * u >= stage_n) dst[u] = -1;
+        }
+#pragma unroll
+        for (int u = 0; u < SBATCH; ++u) v[u] = src[u] ? *src[u] : (E)0;
+#pragma unroll
+        for (int u = 0; u < SBATCH; ++u)
+            if (dst[u] >= 0) tile[dst[u]] = v[u];
     }
-    __syncthreads();
     // ---- write ----
     // For (cc, ky, kx) the outputs of this workgroup are the run of Tc = rows_out*Wo positions starting at
     // (ho0, 0).  With full-height chunks (Tc == T) the runs of consecutive patch rows are adjacent, so the whole
     // workgroup writes ONE contiguous run; otherwise one run per patch row.  A run is cut into 16-byte vectors
-    // aligned in global memory (the first and last may be partial and are stored element by element); the
-    // decode of a vector's first element costs a few divisions, the rest of the vector is reached by carries.
+    // aligned in global memory (the first and last may be partial and are stored element by element).
+    // The kernel is bound by its index arithmetic, not by memory, so a vector costs two divisions (position in the
+    // run -> patch row and output position -> output row and column) and one look-up of the patch row's LDS offset
+    // (tabulated once per workgroup).  Where consecutive output columns are consecutive in LDS (column stride 1, or 2
+    // with the parity-split staging) a vector inside one output row is one 16-byte LDS read, and one that runs over
+    // the end of a row into the next is two such reads merged; anything else goes element by element with carries.
     constexpr int VEC = 16 / (int)sizeof(E);
     const int Tc = rows_out * a.Wo;
     const int T = a.Ho * a.Wo;
@@ -66,6 +98,17 @@ __device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out
     const int L = one_run ? nch * khw * T : Tc;
     const float inv_Tc = 1.0f / (float)Tc;
     const float inv_khw = 1.0f / (float)khw;
+    for (int pr = threadIdx.x; pr <= nch * khw; pr += 256) {      // one entry past the end: read, never used
+        int cc, kk, ky, kx;
+        fdivmod(pr, khw, inv_khw, cc, kk);
+        fdivmod(kk, a.kw, a.inv_kw, ky, kx);
+        const int o = a.deint ? cc * plane + (kx & 1) * hplane + ky * a.Wq + (kx >> 1) : cc * plane + ky * a.Wq + kx;
+        rowoff[pr] = pr < nch * khw ? o : 0;
+    }
+    __syncthreads();
+    const int es = (a.deint || a.compact) ? 1 : a.sw;  // LDS step between consecutive output columns
+    const int rp = a.compact ? a.Wq : a.sh * a.Wq;     // ... and between consecutive output rows
+    const int row_step = rp - a.Wo * es;               // from the end of an output row to the start of the next
     E *const out0 = out + ((int64_t)n * a.C + c0) * khw * T + (int64_t)ho0 * a.Wo;   // run 0, element 0
     for (int run = 0; run < nrun; ++run) {
         E *const dst = out0 + (int64_t)run * T;
@@ -74,33 +117,54 @@ __device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out
         for (int v = threadIdx.x; v < nvec; v += 256) {
             const int j0 = v * VEC - g0;             // first element of the vector inside the run (may be < 0)
             const int jb = max(j0, 0), je = min(j0 + VEC, L);
-            int prow, t, cc, kk, ky, kx, hoo, wo;
+            int prow, t, hoo, wo;
             if (one_run) fdivmod(jb, Tc, inv_Tc, prow, t);
             else { prow = run; t = jb; }
-            fdivmod(prow, khw, inv_khw, cc, kk);
-            fdivmod(kk, a.kw, a.inv_kw, ky, kx);
             fdivmod(t, a.Wo, a.inv_Wo, hoo, wo);
+            int off = rowoff[prow] + hoo * rp + wo * es;     // LDS index of the vector's first element
+            const bool whole = jb == j0 && je == j0 + VEC;
+            if (whole && es == 1) {
+                const int c1 = a.Wo - wo;                     // elements left in this output row
+                if (c1 >= VEC) {
+                    uint4 q;
+                    __builtin_memcpy(&q, tile + off, 16);     // element aligned only: an unaligned LDS read
+                    *reinterpret_cast<uint4 *>(dst + j0) = q;
+                    continue;
+                }
+                // the rest of the vector comes from the start of the next output row (or of the next patch row)
+                const int off2 = (hoo + 1 == rows_out) ? rowoff[prow + 1] : off - wo + rp;
+                if (c1 + a.Wo >= VEC && off2 >= c1) {
+                    E va[VEC], vb[VEC];
+                    __builtin_memcpy(va, tile + off, 16);
+                    __builtin_memcpy(vb, tile + (off2 - c1), 16);
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) va[i] = i < c1 ? va[i] : vb[i];
+                    uint4 q;
+                    __builtin_memcpy(&q, va, 16);
+                    *reinterpret_cast<uint4 *>(dst + j0) = q;
+                    continue;
+                }
+            }
             E vals[VEC];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
                 const int j = j0 + i;
-                E x = 0;
+                E xv = 0;
                 if (j >= jb && j < je) {
-                    x = tile[cc * plane + (hoo * a.sh + ky) * a.Wp + wo * a.sw + kx];
+                    xv = tile[off];
+                    off += es;
                     if (++wo == a.Wo) {
                         wo = 0;
+                        off += row_step;
                         if (++hoo == rows_out) {     // only reached inside the single run: next patch row
                             hoo = 0;
-                            if (++kx == a.kw) {
-                                kx = 0;
-                                if (++ky == a.kh) { ky = 0; ++cc; }
-                            }
+                            off = rowoff[++prow];
                         }
                     }
                 }
-                vals[i] = x;
+                vals[i] = xv;
             }
-            if (jb == j0 && je == j0 + VEC) {
+            if (whole) {
                 uint4 q;
                 __builtin_memcpy(&q, vals, 16);
                 *reinterpret_cast<uint4 *>(dst + j0) = q;
@@ -115,8 +179,9 @@ __device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out
 
 template <typename E>
 __global__ __launch_bounds__(256) void unfold_kernel(const E *__restrict__ x, E *__restrict__ out, UnfoldArgs a) {
-    __shared__ E tile[UNFOLD_LDS_ELEMS];
-    unfold_block<E>(x, out, a, blockIdx.x, blockIdx.y, blockIdx.z, tile);
+    __shared__ __align__(16) E tile[UNFOLD_LDS_ELEMS + UNFOLD_TILE_SLACK];
+    __shared__ int rowoff[UNFOLD_MAX_PROWS + 1];
+    unfold_block<E>(x, out, a, blockIdx.x, blockIdx.y, blockIdx.z, tile, rowoff);
 }
 
 // Several layers in one launch: workgroup b belongs to the layer l with first[l] <= b < first[l+1] and is
@@ -130,46 +195,64 @@ struct UnfoldItem {
 };
 template <typename E>
 __global__ __launch_bounds__(256) void unfold_batched_kernel(const UnfoldItem *items, int n) {
-    __shared__ E tile[UNFOLD_LDS_ELEMS];
+    __shared__ __align__(16) E tile[UNFOLD_LDS_ELEMS + UNFOLD_TILE_SLACK];
+    __shared__ int rowoff[UNFOLD_MAX_PROWS + 1];
     const int b = blockIdx.x;
-    int lo = 0, hi = n - 1;                 // last layer whose first workgroup is <= b
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (items[mid].first <= b) lo = mid; else hi = mid - 1;
+    // last layer whose first workgroup is <= b: the first wave counts, 64 layers per step with one load each, the
+    // layers that start at or before b (their firsts ascend)
+    __shared__ int layer_of;
+    if (threadIdx.x < 64) {
+        int cnt = 0;
+        for (int base = 0; base < n; base += 64) {
+            const int l = base + (int)threadIdx.x;
+            const bool le = l < n && items[l].first <= b;
+            cnt += __popcll(__ballot(le));
+        }
+        if (threadIdx.x == 0) layer_of = cnt - 1;
     }
+    __syncthreads();
+    const int lo = layer_of;
     const UnfoldItem &it = items[lo];
     const int r = b - it.first;
     const int bx = r % it.gx, t = r / it.gx;
-    unfold_block<E>((const E *)it.x, (E *)it.out, it.a, bx, t % it.gy, t / it.gy, tile);
+    unfold_block<E>((const E *)it.x, (E *)it.out, it.a, bx, t % it.gy, t / it.gy, tile, rowoff);
 }
 
 }  // namespace
 
 namespace {
 // Tiling of one layer: fills `a` and the grid; false when the shape does not fit the kernel's limits.
-bool plan_unfold(const kfac_conv_desc *d, UnfoldArgs &a, dim3 &grid) {
+bool plan_unfold(const kfac_conv_desc *d, UnfoldArgs &a, dim3 &grid, bool batched = false) {
     a.N = d->N; a.C = d->C; a.H = d->H; a.W = d->W; a.kh = d->kh; a.kw = d->kw;
     a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w;
     a.Ho = (d->H + 2 * d->pad_h - d->kh) / d->stride_h + 1;
     a.Wo = (d->W + 2 * d->pad_w - d->kw) / d->stride_w + 1;
     a.Wp = d->W + 2 * d->pad_w;
-    const int rows_in_full = (a.Ho - 1) * a.sh + a.kh;
-    if ((int64_t)d->kh * a.Wp > UNFOLD_LDS_ELEMS) return false;  // one output row must fit
-    if ((int64_t)rows_in_full * a.Wp <= UNFOLD_LDS_ELEMS) {
+    a.compact = (a.kh == 1 && a.kw == 1) ? 1 : 0;
+    a.deint = (!a.compact && a.sw == 2) ? 1 : 0;
+    a.Wq = a.compact ? a.Wo : (a.deint ? (a.Wp + 1) / 2 : a.Wp);
+    const int row_elems = a.deint ? 2 * a.Wq : a.Wq;             // LDS elements per staged row
+    const int rows_in_full = a.compact ? a.Ho : (a.Ho - 1) * a.sh + a.kh;   // staged rows of a full-height chunk
+    if ((int64_t)d->kh * row_elems > UNFOLD_LDS_ELEMS) return false;  // one output row must fit
+    if ((int64_t)rows_in_full * row_elems <= UNFOLD_LDS_ELEMS) {
         a.rows_out = a.Ho;
-        int cpb = UNFOLD_LDS_ELEMS / (rows_in_full * a.Wp);
-        int64_t want_blocks = 2048;  // keep the grid large enough to fill 256 CUs several times over
+        int cpb = UNFOLD_LDS_ELEMS / (rows_in_full * row_elems);
+        // a layer launched alone keeps its grid large enough to fill 256 CUs several times over; in a batch the other
+        // layers fill the machine and fatter workgroups amortise their fixed costs
+        int64_t want_blocks = batched ? 32 : 2048;
         int64_t cap = ((int64_t)d->N * d->C + want_blocks - 1) / want_blocks;
         if (cap < 1) cap = 1;
         if (cpb > cap) cpb = (int)cap;
         if (cpb > d->C) cpb = d->C;
+        if (cpb > UNFOLD_MAX_PROWS / (d->kh * d->kw)) cpb = UNFOLD_MAX_PROWS / (d->kh * d->kw);   // the offset table holds them
         a.cpb = cpb < 1 ? 1 : cpb;
     } else {
         a.cpb = 1;
-        a.rows_out = (UNFOLD_LDS_ELEMS / a.Wp - a.kh) / a.sh + 1;
+        a.rows_out = a.compact ? UNFOLD_LDS_ELEMS / row_elems : (UNFOLD_LDS_ELEMS / row_elems - a.kh) / a.sh + 1;
         if (a.rows_out < 1) a.rows_out = 1;
     }
     a.rows_in = (a.rows_out - 1) * a.sh + a.kh;
+    a.plane = (a.compact ? a.rows_out : a.rows_in) * row_elems;
     // the flattened per-workgroup counters must stay exactly representable in fp32
     if ((int64_t)a.cpb * a.kh * a.kw * a.rows_out * a.Wo >= (1 << 24)) return false;
     a.inv_Wp = 1.0f / (float)a.Wp;
@@ -219,7 +302,7 @@ int kfac_launch_unfold_batched(kfac_ctx *ctx, int n, const kfac_conv_desc *descs
     for (int i : order) {
         UnfoldItem it;
         dim3 grid;
-        if (!plan_unfold(&descs[i], it.a, grid)) return KFAC_EINVAL;
+        if (!plan_unfold(&descs[i], it.a, grid, true)) return KFAC_EINVAL;
         const int f = descs[i].dtype == KFAC_F32 ? 0 : 1;
         it.x = x[i];
         it.out = patches[i];
