@@ -772,6 +772,37 @@ struct EpiNewtonSchulz {
     __device__ void operator()(int r, int c, float v) const { Y[(int64_t)r * ld + c] = (r == c ? 1.5f : 0.f) - 0.5f * v; }
 };
 
+// The same step on the split-fp16 engine, in delta form: D = (I - Q^T Q)/2 (entries of the size of the accumulated
+// rounding, 1e-6), then Q + Q D with the first term added in fp32 -- the split engine's 2^-22 then applies to a
+// correction that is itself 1e-6 of Q.  Operands are scaled by 2^14 (entries of Q and D are below 1).
+struct EpiNewtonSchulzDelta {
+    float *D;
+    int64_t ld;
+    __device__ void operator()(int r, int c, float v) const { D[(int64_t)r * ld + c] = (r == c ? 0.5f : 0.f) - 0.5f * v; }
+};
+struct EpiAddStore {
+    const float *X;
+    int64_t ldx;
+    float *C;
+    int64_t ldc;
+    __device__ void operator()(int r, int c, float v) const { C[(int64_t)r * ldc + c] = X[(int64_t)r * ldx + c] + v; }
+};
+template <class OpA, class OpB, class Epi>
+__global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void gemm_x3_kernel(OpA a, OpB b, Epi epi, int M, int N, int K,
+                                                                                                       float out_scale) {
+    using namespace kfac;
+    __shared__ X3Smem sm;
+    const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
+    floatx16 acc[2][2];
+    a.start(threadIdx.x, i0);
+    b.start(threadIdx.x, j0);
+    gemm_tile_x3(a, b, K, sm, acc);
+    for_each_acc(acc, [&](int r, int c, float v) {
+        const int gr = i0 + r, gc = j0 + c;
+        if (gr < M && gc < N) epi(gr, gc, v * out_scale);
+    });
+}
+
 // Rayleigh quotients lam[i] = q_i^T (F q_i) from Q [n][ldq] and Z = F Q [n][ldz]: the rows are split over
 // blockIdx.y, whose shares land in part[y][i] and are added in order by the kernel below.
 constexpr int RAY_PARTS = 32;
@@ -1227,6 +1258,40 @@ int enqueue_sweep_two_level(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int in
     return KFAC_OK;
 }
 
+// One Newton-Schulz step out = Q (3I - Q^T Q)/2 on the leading n x n part of Q (pitch ld); `scratch` (same pitch) is
+// overwritten.  On the fp32 engine, or (split: groups whose passes run there anyway) on the split-fp16 engine in delta form.
+void enqueue_newton_schulz(kfac_ctx *ctx, hipStream_t st, const float *Qm, int64_t ld, int n, float *scratch, float *out, int64_t ldout,
+                           bool split) {
+    using namespace kfac;
+    const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
+    if (split) {
+        constexpr float SC = 16384.f, OUT = 1.f / (SC * SC);
+        X3OpG<float, false> q_kn{Qm, ld, SC, n, n};               // elem(i,k) = Q[k][i]
+        {
+            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+            hipLaunchKernelGGL((gemm_x3_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulzDelta>), grid, block, 0, st, q_kn, q_kn,
+                               EpiNewtonSchulzDelta{scratch, ld}, n, n, n, OUT);
+        }
+        X3OpG<float, true> q_mk{Qm, ld, SC, n, n};                // elem(i,k) = Q[i][k]
+        X3OpG<float, false> d_kn{scratch, ld, SC, n, n};          // elem(j,k) = D[k][j]
+        KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+        hipLaunchKernelGGL((gemm_x3_kernel<decltype(q_mk), decltype(d_kn), EpiAddStore>), grid, block, 0, st, q_mk, d_kn,
+                           EpiAddStore{Qm, ld, out, ldout}, n, n, n, OUT);
+        return;
+    }
+    OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};          // elem(i,k) = Q[k][i]
+    {
+        KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+        hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz>), grid, block, 0, st,
+                           q_kn, q_kn, EpiNewtonSchulz{scratch, ld}, n, n, n);
+    }
+    OpStrided<float, true> q_mk{Qm, ld, 1, n, n, -1};           // elem(i,k) = Q[i][k]
+    OpStrided<float, false> y_kn{scratch, 1, ld, n, n, -1};
+    KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
+    hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_mk), decltype(y_kn), EpiStore>), grid, block, 0, st,
+                       q_mk, y_kn, EpiStore{out, ldout}, n, n, n);
+}
+
 // Refresh of a group whose passes run on the split engine.  Those passes carry 22 significand bits and an error
 // bounded relative to ||F||, so after several sweeps the working matrix W has drifted a little from Q^T F Q for
 // the accumulator Q that goes with it.  Once the off-norm is small the drift is removed: Q is re-orthogonalised
@@ -1245,19 +1310,9 @@ int enqueue_refresh(kfac_ctx *ctx, GroupRun &r) {
         float *Wm = r.g.W + i * np2, *Qm = r.g.Qw + i * np2, *Q1 = r.Qalt + i * np2, *Tm = r.sp.T + i * np2;
         const int64_t ld = gp.npad;
         const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
-        OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};          // elem(i,k) = Q[k][i]
-        {   // W (free from here on) <- Y = (3I - Q^T Q)/2
-            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz>), grid, block, 0, st,
-                               q_kn, q_kn, EpiNewtonSchulz{Wm, ld}, n, n, n);
-        }
-        OpStrided<float, true> q_mk{Qm, ld, 1, n, n, -1};           // elem(i,k) = Q[i][k]
-        OpStrided<float, false> y_kn{Wm, 1, ld, n, n, -1};
-        {   // Q1 = Q Y in the other accumulator buffer (its padding already holds the identity)
-            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_mk), decltype(y_kn), EpiStore>), grid, block, 0, st,
-                               q_mk, y_kn, EpiStore{Q1, ld}, n, n, n);
-        }
+        // Q1 = Q (3I - Q^T Q)/2 in the other accumulator buffer (its padding already holds the identity); W, free from
+        // here on, is the scratch
+        enqueue_newton_schulz(ctx, st, Qm, ld, n, Wm, Q1, ld, true);
         OpStrided<float, true> f_mk{r.items[i].F, n, 1, n, n, -1};
         OpStrided<float, false> q1_kn{Q1, 1, ld, n, n, -1};         // elem(c,k) = Q1[k][c]
         {   // T = F Q1
@@ -1300,19 +1355,7 @@ int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
         float *Wm = r.g.W + i * np2, *Qm = r.g.Qw + i * np2;
         const int64_t ld = gp.npad;
         const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
-        OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};          // elem(i,k) = Q[k][i]
-        {
-            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz>), grid, block, 0, st,
-                               q_kn, q_kn, EpiNewtonSchulz{Wm, ld}, n, n, n);
-        }
-        OpStrided<float, true> q_mk{Qm, ld, 1, n, n, -1};           // elem(i,k) = Q[i][k]
-        OpStrided<float, false> y_kn{Wm, 1, ld, n, n, -1};
-        {
-            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_mk), decltype(y_kn), EpiStore>), grid, block, 0, st,
-                               q_mk, y_kn, EpiStore{r.items[i].Q, n}, n, n, n);
-        }
+        enqueue_newton_schulz(ctx, st, Qm, ld, n, Wm, r.items[i].Q, n, r.x3);
         OpStrided<float, true> f_mk{r.items[i].F, n, 1, n, n, -1};
         OpStrided<float, false> qo_kn{r.items[i].Q, 1, n, n, n, -1};
         {

@@ -222,10 +222,16 @@ def _factor_items(items):
     return arr
 
 
+def factor_items(items):
+    """The marshalled item array of a batch of factor updates (see precond_items)."""
+    return _factor_items(items)
+
+
 def kfac_update_factors_batched(ctx, items):
-    """items: list of dicts(X, layout, N, d, T, append_ones, scale, decay, F[, dtype]); all updated in one call."""
-    arr = _factor_items(items)
-    _check(lib().kfac_update_factors_batched(ctx, len(items), arr), "kfac_update_factors_batched")
+    """items: list of dicts(X, layout, N, d, T, append_ones, scale, decay, F[, dtype]), or the array that
+    factor_items() made of such a list; all updated in one call."""
+    arr = _factor_items(items) if isinstance(items, list) else items
+    _check(lib().kfac_update_factors_batched(ctx, len(arr), arr), "kfac_update_factors_batched")
 
 
 def kfac_update_factors_workspace_bytes(items):
@@ -267,19 +273,27 @@ def _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping=False, sp
     return arr
 
 
-def kfac_precondition_batched(ctx, QA, lamA, QG, lamG, damping, grad, factored_damping=False, split_f16=False):
-    """Lists of per-layer device tensors; every grad[j] is preconditioned in place.  factored_damping: the
-    explicit-inverse method (G + damping I)^-1 grad (A + damping I)^-1 instead of the eigenbasis step.
-    split_f16: run the GEMM chain on the split-fp16 engine."""
-    arr = _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping, split_f16)
-    _check(lib().kfac_precondition_batched(ctx, len(grad), arr), "kfac_precondition_batched")
+def precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping=False, split_f16=False):
+    """The marshalled item array of a batch, for callers that precondition the same buffers every iteration and
+    want to marshal them once: pass it as `items=` to the batched calls below."""
+    return _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping, split_f16)
 
 
-def kfac_precondition_batched_scaled(ctx, QA, lamA, QG, lamG, damping, grad, kappa, lr, nu, split_f16=False):
+def kfac_precondition_batched(ctx, QA=None, lamA=None, QG=None, lamG=None, damping=None, grad=None, factored_damping=False,
+                              split_f16=False, items=None):
+    """Lists of per-layer device tensors (or a marshalled `items` array); every grad[j] is preconditioned in
+    place.  factored_damping: the explicit-inverse method (G + damping I)^-1 grad (A + damping I)^-1 instead
+    of the eigenbasis step.  split_f16: run the GEMM chain on the split-fp16 engine."""
+    arr = items if items is not None else _precond_items(QA, lamA, QG, lamG, damping, grad, factored_damping, split_f16)
+    _check(lib().kfac_precondition_batched(ctx, len(arr), arr), "kfac_precondition_batched")
+
+
+def kfac_precondition_batched_scaled(ctx, QA=None, lamA=None, QG=None, lamG=None, damping=None, grad=None, kappa=None, lr=None,
+                                     nu=None, split_f16=False, items=None):
     """As kfac_precondition_batched, then every gradient is multiplied by the nu of Sec. V-C; nu: device tensor
     of one float32, written by the call."""
-    arr = _precond_items(QA, lamA, QG, lamG, damping, grad, split_f16=split_f16)
-    _check(lib().kfac_precondition_batched_scaled(ctx, len(grad), arr, float(kappa), float(lr), _ptr(nu)),
+    arr = items if items is not None else _precond_items(QA, lamA, QG, lamG, damping, grad, split_f16=split_f16)
+    _check(lib().kfac_precondition_batched_scaled(ctx, len(arr), arr, float(kappa), float(lr), _ptr(nu)),
            "kfac_precondition_batched_scaled")
 
 

@@ -61,6 +61,7 @@ class KfacRunner:
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = K.kfac_create(self.dev.index or 0, self.stream.cuda_stream, self.ws)
         self.eig_info = None
+        self._marshalled = {}    # item arrays of the batched calls, marshalled once per distinct argument set
 
     def _up(self, a):
         t = torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
@@ -102,13 +103,15 @@ class KfacRunner:
             for i in idx:
                 l = self.layers[i]
                 K.kfac_unfold(self.ctx, self.x[upd][i], l.k, l.k, l.stride, l.pad, self.patches[i])
-        items = self._factor_items(upd, decay)
         if batched:
-            K.kfac_update_factors_batched(self.ctx, items)
-        else:
-            for it in items:
-                K.kfac_update_factors(self.ctx, it["X"], it["layout"], it["N"], it["d"], it["T"], it["append_ones"],
-                                      it["scale"], it["decay"], it["F"], dtype=it["dtype"])
+            key = ("factors", upd, float(decay))
+            if key not in self._marshalled:
+                self._marshalled[key] = K.factor_items(self._factor_items(upd, decay))
+            K.kfac_update_factors_batched(self.ctx, self._marshalled[key])
+            return
+        for it in self._factor_items(upd, decay):
+            K.kfac_update_factors(self.ctx, it["X"], it["layout"], it["N"], it["d"], it["T"], it["append_ones"],
+                                  it["scale"], it["decay"], it["F"], dtype=it["dtype"])
 
     def eig(self, **kw):
         self.eig_info = K.kfac_eig(self.ctx, self.A + self.G, self.QA + self.QG, self.lamA + self.lamG, **kw)
@@ -128,11 +131,14 @@ class KfacRunner:
         split = self.wl.bf16 if split_f16 is None else split_f16
         if restore:
             self.restore_gradients()
+        key = ("precond", float(gamma), bool(split))
+        if key not in self._marshalled:
+            self._marshalled[key] = K.precond_items(self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad, split_f16=split)
         if kappa is None:
-            K.kfac_precondition_batched(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad, split_f16=split)
+            K.kfac_precondition_batched(self.ctx, items=self._marshalled[key])
         else:
             self.nu = torch.zeros(1, dtype=torch.float32, device=self.dev)
-            K.kfac_precondition_batched_scaled(self.ctx, self.QA, self.lamA, self.QG, self.lamG, gamma, self.grad, kappa, lr, self.nu, split_f16=split)
+            K.kfac_precondition_batched_scaled(self.ctx, kappa=kappa, lr=lr, nu=self.nu, items=self._marshalled[key])
 
     # ---- algorithmic work of one step (flops, bytes) ----
     def work(self):
