@@ -324,9 +324,9 @@ def main():
     roofline = dict(kernels[dom])
     roofline["kernel"] = dom
     roofline["traffic"] = measured_traffic(dom) if args.workload == "resnet50" else None
-    roofline["timing"] = ("hipEvents around every launch of the class on the stream it runs on, over one instrumented step "
-                          "with all groups in flight: a launch's bracket includes the time it waits for compute units "
-                          "behind kernels of the library's other internal streams")
+    roofline["timing"] = ("hipEvents around every launch of the class, over one instrumented step in which the eigensolver's "
+                          "groups run one after another on one stream (the kernel's own duration, no waiting behind other "
+                          "streams); in the timed steps the groups overlap on four streams")
     roofline = {k: roofline[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic",
                                          "launches", "avg_ms", "total_ms", "algorithmic_bytes_per_launch", "algorithmic_tflops",
                                          "timing") if k in roofline}

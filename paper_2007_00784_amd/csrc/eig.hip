@@ -1422,7 +1422,7 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
     // ---- small factors: one launch, on the last internal stream ----
     SmallItem *sitems = nullptr;
     EigStat *sstats = nullptr;
-    hipStream_t st_small = ctx->aux[KFAC_NUM_AUX_STREAMS - 1];
+    hipStream_t st_small = ctx->aux[(ctx->prof_on || getenv("KFAC_EIG_SERIAL")) ? 0 : KFAC_NUM_AUX_STREAMS - 1];
     if (!small.empty()) {
         const size_t ns = small.size();
         sitems = (SmallItem *)ptab; ptab += kfac_align_up(ns * sizeof(SmallItem), 64);
@@ -1467,9 +1467,13 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
         std::sort(cost.begin(), cost.end(), [](const std::pair<double, size_t> &a, const std::pair<double, size_t> &b) { return a.first > b.first; });
         double load[KFAC_NUM_AUX_STREAMS] = {0};
         if (!small.empty()) load[KFAC_NUM_AUX_STREAMS - 1] += 0.5e-3;   // the small factors' one launch
+        // Measurement aid: while per-kernel timing is on (kfac_profile_begin) or KFAC_EIG_SERIAL is set, all groups share
+        // one stream, so an event bracket (or a profiler's kernel duration) is the kernel's own time and not also its
+        // wait behind the other groups' kernels.
+        const bool serial = ctx->prof_on || getenv("KFAC_EIG_SERIAL") != nullptr;
         for (auto &c : cost) {
             int best = 0;
-            for (int i = 1; i < KFAC_NUM_AUX_STREAMS; ++i) if (load[i] < load[best]) best = i;
+            for (int i = 1; i < KFAC_NUM_AUX_STREAMS && !serial; ++i) if (load[i] < load[best]) best = i;
             stream_of[c.second] = best;
             load[best] += c.first;
         }
