@@ -468,6 +468,39 @@ def test_explicit_inverse_method_matches_cholesky_oracle(ctx, dA, dG):
         assert relfro(g2.cpu().numpy(), ref) > 1e-3
 
 
+@pytest.mark.parametrize("dA,dG,rows", [(145, 16, 2048), (577, 64, 1500), (289, 32, 200)])
+def test_explicit_inverse_method_at_the_papers_damping(ctx, dA, dG, rows):
+    """The explicit-inverse method where it is hard: ReLU-activation A factors (one eigenvalue ~ 0.16 d_A over a bulk
+    of ~0.3; rank deficient in the last case), gradient factors of size 1e-6, damping 1e-3 (the paper's ImageNet
+    value, Sec. VI) -- against the oracle's two Cholesky solves.  The inverse of F + gamma I amplifies a perturbation
+    of F by cond(F + gamma I) = (lam_max + gamma) / (lam_min + gamma), and an fp32 eigendecomposition is a
+    perturbation of F of the order of fp32's unit roundoff, so the bound is
+    max(1e-4, 6e-8 * (cond_A + cond_G)), from the oracle's spectra (measured: 2e-9 .. 5e-9 times that sum)."""
+    rng = np.random.default_rng(1000 + dA)
+    X = np.maximum(rng.standard_normal((rows, dA - 1)), 0).astype(np.float32)
+    Gr = (rng.standard_normal((rows, dG)) * 1e-3).astype(np.float32)
+    Ad = torch.zeros((dA, dA), dtype=torch.float32, device=ctx.dev)
+    Gd = torch.zeros((dG, dG), dtype=torch.float32, device=ctx.dev)
+    ctx.update_factors(ctx.to_dev(X), K.KFAC_LAYOUT_RD, rows, dA - 1, 1, 1, 1.0 / rows, 0.0, Ad)
+    ctx.update_factors(ctx.to_dev(Gr), K.KFAC_LAYOUT_RD, rows, dG, 1, 0, 1.0 / rows, 0.0, Gd)
+    Ld, Qd, info = ctx.eig([Ad, Gd])
+    assert all(c for (_, _, c) in info)
+    A = oracle.gram(X, 1, 1.0 / rows)
+    G = oracle.gram(Gr, 0, 1.0 / rows)
+    gamma = 1e-3
+    la, lg = np.linalg.eigvalsh(A), np.linalg.eigvalsh(G)
+    cond = (la.max() + gamma) / (max(la.min(), 0.0) + gamma) + (lg.max() + gamma) / (max(lg.min(), 0.0) + gamma)
+    bound = max(TOL_F32, 6e-8 * cond)
+    grad = (rng.standard_normal((dG, dA)) * 1e-2).astype(np.float32)
+    ref = oracle.precondition_inverse(G, A, gamma, grad)
+    gd = ctx.to_dev(grad)
+    K.kfac_precondition_batched(ctx.h, [Qd[0]], [Ld[0]], [Qd[1]], [Ld[1]], gamma, [gd], factored_damping=True)
+    torch.cuda.synchronize()
+    err = relfro(gd.cpu().numpy(), ref)
+    print("explicit inverse dA=%d dG=%d rows=%d: cond %.1e, error %.2e (bound %.1e)" % (dA, dG, rows, cond, err, bound))
+    assert err <= bound
+
+
 # ------------------------------------------------------------------ whole path, config 1
 def test_single_conv_layer_end_to_end(ctx):
     """3x3 conv 16->16 on 8x8, batch 32: three factor updates, eig, precondition, against the oracle and
