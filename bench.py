@@ -187,7 +187,13 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements that are not part of `value` (warm start, decoupled schedule, split-fp16 "
                          "preconditioner): for short profiler runs")
+    ap.add_argument("--eig-serial", action="store_true",
+                    help="run the eigensolver's groups one after another on one stream, so that a profiler's kernel "
+                         "durations are the kernels' own (as in the instrumented step); `value` is then NOT the "
+                         "product's figure and the line says so in config.eig_serial")
     args = ap.parse_args()
+    if args.eig_serial:
+        os.environ["KFAC_EIG_SERIAL"] = "1"
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every GPU box here has one GPU); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -364,6 +370,8 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if args.eig_serial:
+        out["config"]["eig_serial"] = True      # profiling mode: the eigensolver's groups ran one after another
     run.close()
     if not args.no_extras and args.workload == "resnet50":
         # the other four benchmark configurations, each after two warm-up steps

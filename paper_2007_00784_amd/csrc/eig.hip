@@ -826,16 +826,24 @@ __global__ __launch_bounds__(NT) void blk_rayleigh_sum_kernel(const double *part
 
 // perm[rank] = index of the rank-th smallest eigenvalue (ties by index); lam[rank] = that eigenvalue.
 __global__ __launch_bounds__(NT) void blk_rank_kernel(const double *lam64, int n, int *perm, float *lam_out) {
+    __shared__ float chunk[NT];         // the values every thread compares against, a workgroup-load at a time
     const int i = blockIdx.x * NT + threadIdx.x;
-    if (i >= n) return;
-    const float li = (float)lam64[i];
+    const float li = i < n ? (float)lam64[i] : 0.f;
     const bool nan_i = li != li;
     int rank = 0;
-    for (int j = 0; j < n; ++j) {       // NaNs order after every number, among themselves by index: always a permutation
-        const float lj = (float)lam64[j];
-        const bool nan_j = lj != lj;
-        rank += nan_i ? (!nan_j || j < i) : (!nan_j && ((lj < li) || (lj == li && j < i)));
+    for (int j0 = 0; j0 < n; j0 += NT) {
+        __syncthreads();
+        chunk[threadIdx.x] = j0 + (int)threadIdx.x < n ? (float)lam64[j0 + threadIdx.x] : 0.f;
+        __syncthreads();
+        const int m = min(NT, n - j0);
+        for (int k = 0; k < m; ++k) {   // NaNs order after every number, among themselves by index: always a permutation
+            const float lj = chunk[k];
+            const int j = j0 + k;
+            const bool nan_j = lj != lj;
+            rank += nan_i ? (!nan_j || j < i) : (!nan_j && ((lj < li) || (lj == li && j < i)));
+        }
     }
+    if (i >= n) return;
     perm[rank] = i;
     lam_out[rank] = li;
 }
@@ -1453,6 +1461,10 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
     // streams longest chain first, each to the stream with the least work so far; the estimate per round is
     // a launch-latency floor plus the round's products at the rate those kernels reach.
     std::vector<int> stream_of(groups.size(), 0);
+    // Measurement aid: while per-kernel timing is on (kfac_profile_begin) or KFAC_EIG_SERIAL is set, all groups share
+    // one stream, so an event bracket (or a profiler's kernel duration) is the kernel's own time and not also its
+    // wait behind the other groups' kernels.
+    const bool serial = ctx->prof_on || getenv("KFAC_EIG_SERIAL") != nullptr;
     {
         std::vector<std::pair<double, size_t>> cost(groups.size());
         for (size_t gi = 0; gi < groups.size(); ++gi) {
@@ -1467,10 +1479,6 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
         std::sort(cost.begin(), cost.end(), [](const std::pair<double, size_t> &a, const std::pair<double, size_t> &b) { return a.first > b.first; });
         double load[KFAC_NUM_AUX_STREAMS] = {0};
         if (!small.empty()) load[KFAC_NUM_AUX_STREAMS - 1] += 0.5e-3;   // the small factors' one launch
-        // Measurement aid: while per-kernel timing is on (kfac_profile_begin) or KFAC_EIG_SERIAL is set, all groups share
-        // one stream, so an event bracket (or a profiler's kernel duration) is the kernel's own time and not also its
-        // wait behind the other groups' kernels.
-        const bool serial = ctx->prof_on || getenv("KFAC_EIG_SERIAL") != nullptr;
         for (auto &c : cost) {
             int best = 0;
             for (int i = 1; i < KFAC_NUM_AUX_STREAMS && !serial; ++i) if (load[i] < load[best]) best = i;
@@ -1623,6 +1631,9 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
                                    : enqueue_sweep_flat(ctx, r, lds_solve, inner_cap, inner_tol);
         ++r.sweep;
         if (rc == KFAC_OK) rc = enqueue_offnorm(ctx, r);
+        // measurement mode: all groups share one stream; keep its queue short (one group's sweep at a time), a
+        // profiler that wraps every dispatch in packets of its own has little room behind thousands of launches
+        if (rc == KFAC_OK && serial && hipStreamSynchronize(r.st) != hipSuccess) rc = KFAC_EHIP;
         return rc;
     };
     for (auto &r : runs)   // the first sweep goes out before its norms are known
