@@ -140,35 +140,45 @@ struct GrpOpNDT {
 };
 
 // One slab of MFMAs from fragments: lane (c, g) holds group 2 ks + g of row (column) c in k-step ks.  Any
-// assignment of contraction indices to MFMA k-lanes works as long as both operands share it.
+// assignment of contraction indices to MFMA k-lanes works as long as both operands share it.  `blocks` (uniform
+// over the wave) has bit 2 i + j set for the 32 x 32 accumulator blocks that anybody will read: blocks past the
+// edge of the operand and, in a diagonal tile, blocks strictly above the diagonal are left at zero and cost
+// no matrix-core time (a seventh of a ResNet-50 factor update's MFMAs otherwise).  `ksteps` has bit ks set for the
+// k-steps of the slab this wave multiplies (all four, except where two waves share a quadrant).
 template <int KS0, int KS1>
-__device__ inline void grp_mfma(const uint4 (&fa)[4][2], const uint4 (&fb)[4][2], floatx16 (&acc)[2][2], float) {
+__device__ inline void grp_mfma(const uint4 (&fa)[4][2], const uint4 (&fb)[4][2], floatx16 (&acc)[2][2], unsigned blocks, unsigned ksteps, float) {
 #pragma unroll
     for (int ks = KS0; ks < KS1; ++ks) {
-        const unsigned a[2][4] = {{fa[ks][0].x, fa[ks][0].y, fa[ks][0].z, fa[ks][0].w}, {fa[ks][1].x, fa[ks][1].y, fa[ks][1].z, fa[ks][1].w}};
-        const unsigned b[2][4] = {{fb[ks][0].x, fb[ks][0].y, fb[ks][0].z, fb[ks][0].w}, {fb[ks][1].x, fb[ks][1].y, fb[ks][1].z, fb[ks][1].w}};
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[i][e]), __uint_as_float(b[j][e]), acc[i][j], 0, 0, 0);
-    }
-}
-template <int KS0, int KS1>
-__device__ inline void grp_mfma(const uint4 (&fa)[4][2], const uint4 (&fb)[4][2], floatx16 (&acc)[2][2], unsigned short) {
-#pragma unroll
-    for (int ks = KS0; ks < KS1; ++ks)
+        if (!((ksteps >> ks) & 1u)) continue;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
+                if (!((blocks >> (2 * i + j)) & 1u)) continue;
+                const unsigned a[4] = {fa[ks][i].x, fa[ks][i].y, fa[ks][i].z, fa[ks][i].w};
+                const unsigned b[4] = {fb[ks][j].x, fb[ks][j].y, fb[ks][j].z, fb[ks][j].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[e]), __uint_as_float(b[e]), acc[i][j], 0, 0, 0);
+            }
+    }
+}
+template <int KS0, int KS1>
+__device__ inline void grp_mfma(const uint4 (&fa)[4][2], const uint4 (&fb)[4][2], floatx16 (&acc)[2][2], unsigned blocks, unsigned ksteps, unsigned short) {
+#pragma unroll
+    for (int ks = KS0; ks < KS1; ++ks) {
+        if (!((ksteps >> ks) & 1u)) continue;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if (!((blocks >> (2 * i + j)) & 1u)) continue;
                 bf16x8 x, y;
                 __builtin_memcpy(&x, &fa[ks][i], 16);
                 __builtin_memcpy(&y, &fb[ks][j], 16);
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[i][j], 0, 0, 0);
             }
+    }
 }
 
 // acc = A B^T over groups [q0, q_end) (both operands as elem(row, position)); DIAG: B is the same row block
@@ -180,7 +190,13 @@ __device__ inline void gemm_tile_grouped(GrpOpNDT<E> &A, GrpOpNDT<E> &B, int i0,
                                          floatx16 (&acc)[2][2], float *csum) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    // In a diagonal tile the quadrant above the diagonal (wave 1's) is never read, while the one below it is the
+    // only quadrant with four blocks to compute (the two on the diagonal have three).  Wave 1 therefore takes half
+    // of wave 2's work: both multiply the lower-left quadrant, each over two of a slab's four k-steps, and the two
+    // sums are added through LDS at the end.  No wave then has more than 12 of a slab's block-steps instead of 16.
+    const bool helper = DIAG && wave == 1;
+    const int wm = helper ? 64 : (wave >> 1) * 64, wn = helper ? 0 : (wave & 1) * 64;
+    const unsigned ksteps = __builtin_amdgcn_readfirstlane(!DIAG ? 0xFu : wave == 1 ? 0xCu : wave == 2 ? 0x3u : 0xFu);
     const int lk = lane >> 5, lc = lane & 31;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -201,6 +217,13 @@ __device__ inline void gemm_tile_grouped(GrpOpNDT<E> &A, GrpOpNDT<E> &B, int i0,
     int sha = A.issue(sm.a[0], tid), shb = 0;
     if (!DIAG) shb = B.issue(sm.b[0], tid);
     const int swz = (lc >> 1) & 7;   // (row >> 1) & 7 of this lane's fragment rows (they differ by multiples of 32)
+    unsigned blocks = 0;             // this wave's accumulator blocks that hold entries of the factor's lower triangle
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (i0 + wm + 32 * i < A.d && j0 + wn + 32 * j < A.d && (!DIAG || wn + 32 * j <= wm + 32 * i)) blocks |= 1u << (2 * i + j);
+    blocks = __builtin_amdgcn_readfirstlane(blocks);
     for (int s = 0; s < nslab; ++s) {
         const int cur = s & 1;
         grp_wait_loads();
@@ -222,7 +245,7 @@ __device__ inline void gemm_tile_grouped(GrpOpNDT<E> &A, GrpOpNDT<E> &B, int i0,
                 fb[ks][i] = *reinterpret_cast<const uint4 *>(pb + (wn + 32 * i + lc) * GRP_ROWB + (((2 * ks + lk) ^ swz) * 16));
             }
         __builtin_amdgcn_sched_barrier(0);
-        grp_mfma<0, 1>(fa, fb, acc, E());
+        grp_mfma<0, 1>(fa, fb, acc, blocks, ksteps, E());
         __builtin_amdgcn_sched_barrier(0);
         if (s + 1 < nslab) {   // address arithmetic and load issue in the shadow of the MFMAs just queued
             A.next();
@@ -233,9 +256,33 @@ __device__ inline void gemm_tile_grouped(GrpOpNDT<E> &A, GrpOpNDT<E> &B, int i0,
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        grp_mfma<1, 4>(fa, fb, acc, E());
+        grp_mfma<1, 4>(fa, fb, acc, blocks, ksteps, E());
     }
     __syncthreads();   // callers reuse the slab buffers
+    if (DIAG) {        // wave 2 += wave 1 (16 KB through LDS); wave 1 ends with the zeros of the quadrant it stands for
+        float *x = reinterpret_cast<float *>(&sm);
+        if (wave == 1) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        x[((i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+                        acc[i][j][r] = 0.f;
+                    }
+        }
+        __syncthreads();
+        if (wave == 2) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += x[((i * 2 + j) * 16 + r) * 64 + lane];
+        }
+        __syncthreads();
+    }
 }
 
 // The single (diagonal) tile of a factor with at most 64 rows.  A 128 x 128 tile would spend three quarters of its
