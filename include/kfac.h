@@ -101,7 +101,9 @@ const char *kfac_strerror(int code);
  * of every example as one sample): patches[n][(c*kh+ky)*kw+kx][ho*Wo+wo] = x[n][c][ho*sh-ph+ky][wo*sw-pw+kx],
  * zero outside the image; Ho = (H+2ph-kh)/sh+1, Wo likewise.
  *   x       : [N][C][H][W], dtype desc->dtype
- *   patches : [N][C*kh*kw][Ho*Wo] (KFAC_LAYOUT_NDT), same dtype, no bias row.  */
+ *   patches : [N][C*kh*kw][Ho*Wo] (KFAC_LAYOUT_NDT), same dtype, no bias row.
+ * Size limit: kh padded input rows must fit the 16 KB staging tile, kh*(W+2pw) <= 4096 elements (fp32) or
+ * 8192 (bf16); beyond that KFAC_EINVAL.  */
 int kfac_unfold(kfac_ctx *ctx, const kfac_conv_desc *desc, const void *x, void *patches);
 
 /* The same for n layers in one launch per element type (a network's late layers are a few microseconds of work

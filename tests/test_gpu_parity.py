@@ -41,6 +41,10 @@ UNFOLD_CASES = [
     (2, 130, 7, 3, 2, 1),      # many channels per workgroup, ragged channel tail
     (1, 3, 224, 7, 2, 3),      # stem geometry: chunked rows
     (2, 8, 56, 3, 1, 1),
+    (2, 5, 28, 3, 2, 1),       # stride 2 onto a 14 x 14 map: the tile holds the output
+    (1, 2, 14, 5, 2, 2),
+    (3, 20, 7, 3, 1, 1),       # 7 x 7 map, several channels per workgroup with a ragged tail
+    (2, 4, 56, 3, 2, 1),       # stride 2 onto 28 x 28: one channel per workgroup
 ]
 
 
