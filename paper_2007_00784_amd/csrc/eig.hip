@@ -787,12 +787,13 @@ struct EpiAddStore {
     int64_t ldc;
     __device__ void operator()(int r, int c, float v) const { C[(int64_t)r * ldc + c] = X[(int64_t)r * ldx + c] + v; }
 };
-template <class OpA, class OpB, class Epi>
+template <class OpA, class OpB, class Epi, bool SYM = false>   // SYM: as for gemm_generic_kernel
 __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void gemm_x3_kernel(OpA a, OpB b, Epi epi, int M, int N, int K,
                                                                                                        float out_scale) {
     using namespace kfac;
     __shared__ X3Smem sm;
     const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
+    if (SYM && j0 > i0) return;
     floatx16 acc[2][2];
     a.start(threadIdx.x, i0);
     b.start(threadIdx.x, j0);
@@ -801,6 +802,11 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
         const int gr = i0 + r, gc = j0 + c;
         if (gr < M && gc < N) epi(gr, gc, v * out_scale);
     });
+    if (SYM && j0 < i0)
+        for_each_acc_transposed(acc, reinterpret_cast<float *>(&sm), [&](int r, int c, float v) {
+            const int gr = j0 + r, gc = i0 + c;
+            if (gr < M && gc < N) epi(gr, gc, v * out_scale);
+        });
 }
 
 // Rayleigh quotients lam[i] = q_i^T (F q_i) from Q [n][ldq] and Z = F Q [n][ldz]: the rows are split over
@@ -857,14 +863,20 @@ __global__ __launch_bounds__(NT) void blk_copy_kernel(const float *src, float *d
 }
 
 // Qout[i][j] = Qin[i][perm[j]]
-__global__ __launch_bounds__(NT) void blk_gather_kernel(const float *Qin, int64_t ldin, float *Qout, int n, const int *perm) {
+__global__ __launch_bounds__(NT) void blk_gather_kernel(const float *Qin, int64_t ldin, float *Qout, int64_t ldout, int n, const int *perm) {
     const int64_t n2 = (int64_t)n * n;
     for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < n2; e += (int64_t)gridDim.x * NT) {
         const int i = (int)(e / n), j = (int)(e - (int64_t)i * n);
         int c = perm[j];
         c = c < 0 ? 0 : (c >= n ? n - 1 : c);  // ranks collide only when the input holds NaNs
-        Qout[e] = Qin[(int64_t)i * ldin + c];
+        Qout[(int64_t)i * ldout + j] = Qin[(int64_t)i * ldin + c];
     }
+}
+
+// out[i] = W[i][i]
+__global__ __launch_bounds__(NT) void blk_diag_kernel(const float *W, int64_t ld, int n, double *out) {
+    const int i = blockIdx.x * NT + threadIdx.x;
+    if (i < n) out[i] = (double)W[(int64_t)i * ld + i];
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1064,6 +1076,92 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
     store_acc_transposed(acc, reinterpret_cast<float *>(&sm), mir, ld);
 }
 
+// ---- ordering of the diagonal ------------------------------------------------------------------------
+// A symmetric permutation that puts the diagonal of W (the eigenvalue estimates) in ascending order, applied to W
+// and to the columns of the accumulator; all factors of a group in one launch each (blockIdx.y: factor).  A factor
+// that has met the tolerance is left alone.  `T` is n x n scratch per factor: the group's own (pitch npad) or, for
+// groups that have none, the caller's eigenvector buffer (pitch n), which nothing else uses before the very end.
+struct SortArgs {
+    float *W, *Qw, *T;
+    int64_t np2;
+    int npad;
+    const BlkItem *items;
+    const int *done;
+    double *lam64;        // [factor][lam_stride]
+    int64_t lam_stride;
+    int *perm;            // [factor][npad]
+};
+__device__ inline float *sort_scratch(const SortArgs &a, int m, int64_t &ld) {
+    if (a.T) { ld = a.npad; return a.T + m * a.np2; }
+    ld = a.items[m].n;
+    return a.items[m].Q;
+}
+__global__ __launch_bounds__(NT) void sort_diag_kernel(SortArgs a) {
+    const int m = blockIdx.y, i = blockIdx.x * NT + threadIdx.x;
+    if (a.done[m] || i >= a.items[m].n) return;
+    a.lam64[m * a.lam_stride + i] = (double)a.W[m * a.np2 + (int64_t)i * a.npad + i];
+}
+__global__ __launch_bounds__(NT) void sort_rank_kernel(SortArgs a) {
+    __shared__ float chunk[NT];
+    const int m = blockIdx.y;
+    if (a.done[m]) return;
+    const int n = a.items[m].n;
+    if ((int)(blockIdx.x * NT) >= n) return;
+    const double *lam64 = a.lam64 + m * a.lam_stride;
+    const int i = blockIdx.x * NT + threadIdx.x;
+    const float li = i < n ? (float)lam64[i] : 0.f;
+    const bool nan_i = li != li;
+    int rank = 0;
+    for (int j0 = 0; j0 < n; j0 += NT) {
+        __syncthreads();
+        chunk[threadIdx.x] = j0 + (int)threadIdx.x < n ? (float)lam64[j0 + threadIdx.x] : 0.f;
+        __syncthreads();
+        const int cnt = min(NT, n - j0);
+        for (int k = 0; k < cnt; ++k) {   // as in blk_rank_kernel: always a permutation
+            const float lj = chunk[k];
+            const int j = j0 + k;
+            const bool nan_j = lj != lj;
+            rank += nan_i ? (!nan_j || j < i) : (!nan_j && ((lj < li) || (lj == li && j < i)));
+        }
+    }
+    if (i < n) a.perm[(int64_t)m * a.npad + rank] = i;
+}
+// which = 0: scratch = P W P^T; which = 1: scratch[:, j] = Q[:, perm[j]]
+__global__ __launch_bounds__(NT) void sort_permute_kernel(SortArgs a, int which) {
+    const int m = blockIdx.y;
+    if (a.done[m]) return;
+    const int n = a.items[m].n;
+    const int *perm = a.perm + (int64_t)m * a.npad;
+    int64_t lds;
+    float *S = sort_scratch(a, m, lds);
+    const float *src = (which == 0 ? a.W : a.Qw) + m * a.np2;
+    const int64_t n2 = (int64_t)n * n;
+    for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < n2; e += (int64_t)gridDim.x * NT) {
+        const int i = (int)(e / n), j = (int)(e - (int64_t)i * n);
+        int c = perm[j];
+        c = c < 0 ? 0 : (c >= n ? n - 1 : c);
+        int r = i;
+        if (which == 0) {
+            r = perm[i];
+            r = r < 0 ? 0 : (r >= n ? n - 1 : r);
+        }
+        S[(int64_t)i * lds + j] = src[(int64_t)r * a.npad + c];
+    }
+}
+__global__ __launch_bounds__(NT) void sort_copyback_kernel(SortArgs a, int which) {
+    const int m = blockIdx.y;
+    if (a.done[m]) return;
+    const int n = a.items[m].n;
+    int64_t lds;
+    const float *S = sort_scratch(a, m, lds);
+    float *dst = (which == 0 ? a.W : a.Qw) + m * a.np2;
+    const int64_t n2 = (int64_t)n * n;
+    for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < n2; e += (int64_t)gridDim.x * NT) {
+        const int i = (int)(e / n), j = (int)(e - (int64_t)i * n);
+        dst[(int64_t)i * a.npad + j] = S[(int64_t)i * lds + j];
+    }
+}
+
 // ---- host side ---------------------------------------------------------------------------------
 struct GroupPlan {
     int nblk, npad, players, npairs;
@@ -1200,6 +1298,23 @@ void enqueue_round(kfac_ctx *ctx, hipStream_t st, const BlkGroup &g, int rd, int
     }
 }
 
+// Ascending order of the eigenvalue estimates along the diagonal (see SortArgs): six launches for the whole group.
+int enqueue_sort(kfac_ctx *ctx, GroupRun &r) {
+    const GroupPlan &gp = *r.plan;
+    SortArgs a{r.g.W, r.g.Qw, gp.two_level ? r.sp.T : nullptr, (int64_t)gp.npad * gp.npad, gp.npad, r.d_items, r.d_done,
+               r.lam64, (int64_t)gp.npad * (RAY_PARTS + 1), r.perm};
+    const dim3 gv((r.nmax + NT - 1) / NT, r.nm), gm(std::min(r.fill_blocks, 1024), r.nm);
+    KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
+    hipLaunchKernelGGL(sort_diag_kernel, gv, dim3(NT), 0, r.st, a);
+    hipLaunchKernelGGL(sort_rank_kernel, gv, dim3(NT), 0, r.st, a);
+    for (int which = 0; which < 2; ++which) {
+        hipLaunchKernelGGL(sort_permute_kernel, gm, dim3(NT), 0, r.st, a, which);
+        hipLaunchKernelGGL(sort_copyback_kernel, gm, dim3(NT), 0, r.st, a, which);
+    }
+    KFAC_HIP_CHECK(hipGetLastError());
+    return KFAC_OK;
+}
+
 int enqueue_sweep_flat(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int inner_cap, float inner_tol) {
     for (int rd = 0; rd < r.plan->players - 1; ++rd)
         enqueue_round(ctx, r.st, r.g, rd, r.ntiles, r.ntiles_w, r.nrb, lds_solve, inner_cap, inner_tol, r.solve_flops, r.apply_flops,
@@ -1266,6 +1381,13 @@ int enqueue_sweep_two_level(kfac_ctx *ctx, GroupRun &r, size_t lds_solve, int in
     return KFAC_OK;
 }
 
+// Flops a symmetric n x n product over a contraction of n is credited with when only the tiles on and below the
+// diagonal are computed.
+inline double sym_product_flops(int n) {
+    const double nt = (n + kfac::BM - 1) / kfac::BM;
+    return 2.0 * n * n * n * (nt + 1.0) / (2.0 * nt);
+}
+
 // One Newton-Schulz step out = Q (3I - Q^T Q)/2 on the leading n x n part of Q (pitch ld); `scratch` (same pitch) is
 // overwritten.  On the fp32 engine, or (split: groups whose passes run there anyway) on the split-fp16 engine in delta form.
 void enqueue_newton_schulz(kfac_ctx *ctx, hipStream_t st, const float *Qm, int64_t ld, int n, float *scratch, float *out, int64_t ldout,
@@ -1276,8 +1398,8 @@ void enqueue_newton_schulz(kfac_ctx *ctx, hipStream_t st, const float *Qm, int64
         constexpr float SC = 16384.f, OUT = 1.f / (SC * SC);
         X3OpG<float, false> q_kn{Qm, ld, SC, n, n};               // elem(i,k) = Q[k][i]
         {
-            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-            hipLaunchKernelGGL((gemm_x3_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulzDelta>), grid, block, 0, st, q_kn, q_kn,
+            KfacProfScope prof(ctx, KC_EIG_POST, sym_product_flops(n), 0.0, st);
+            hipLaunchKernelGGL((gemm_x3_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulzDelta, true>), grid, block, 0, st, q_kn, q_kn,
                                EpiNewtonSchulzDelta{scratch, ld}, n, n, n, OUT);
         }
         X3OpG<float, true> q_mk{Qm, ld, SC, n, n};                // elem(i,k) = Q[i][k]
@@ -1289,8 +1411,8 @@ void enqueue_newton_schulz(kfac_ctx *ctx, hipStream_t st, const float *Qm, int64
     }
     OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};          // elem(i,k) = Q[k][i]
     {
-        KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-        hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz>), grid, block, 0, st,
+        KfacProfScope prof(ctx, KC_EIG_POST, sym_product_flops(n), 0.0, st);
+        hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz, true>), grid, block, 0, st,
                            q_kn, q_kn, EpiNewtonSchulz{scratch, ld}, n, n, n);
     }
     OpStrided<float, true> q_mk{Qm, ld, 1, n, n, -1};           // elem(i,k) = Q[i][k]
@@ -1307,6 +1429,11 @@ void enqueue_newton_schulz(kfac_ctx *ctx, hipStream_t st, const float *Qm, int64
 // then on the iteration is a Jacobi iteration started from a good basis -- what came before only chose that
 // basis -- and its remaining rounds are small corrections, which the split passes add to fp32 operands
 // (X + X (V - I)) with an error far below fp32 rounding.  Every factor of the group takes part, converged or not.
+// The refresh also puts the columns in ascending order of their eigenvalue estimates (it costs one more pass over Q).
+// Cyclic Jacobi keeps its quadratic end phase in the presence of a multiple eigenvalue only if the diagonal entries
+// that converge to it are neighbours; the null space of a rank-deficient factor (1500 to 3000 wide for the largest
+// K-FAC factors of a small batch) is scattered over the diagonal otherwise, and the end phase was linear (off-norm
+// x 0.3 per sweep at d = 4609, two to three sweeps more than a full-rank factor of that size needs).
 int enqueue_refresh(kfac_ctx *ctx, GroupRun &r) {
     using namespace kfac;
     const GroupPlan &gp = *r.plan;
@@ -1315,12 +1442,25 @@ int enqueue_refresh(kfac_ctx *ctx, GroupRun &r) {
     for (int i = 0; i < r.nm; ++i) {
         if (r.bad[i]) continue;
         const int n = r.items[i].n;
-        float *Wm = r.g.W + i * np2, *Qm = r.g.Qw + i * np2, *Q1 = r.Qalt + i * np2, *Tm = r.sp.T + i * np2;
+        float *Wm = r.g.W + i * np2, *Qm = r.g.Qw + i * np2, *Qo = r.Qalt + i * np2, *Tm = r.sp.T + i * np2;
         const int64_t ld = gp.npad;
         const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
-        // Q1 = Q (3I - Q^T Q)/2 in the other accumulator buffer (its padding already holds the identity); W, free from
-        // here on, is the scratch
-        enqueue_newton_schulz(ctx, st, Qm, ld, n, Wm, Q1, ld, true);
+        // The diagonal of W, i.e. the eigenvalue estimates, before W becomes scratch: their ascending order is the order the
+        // columns take below.
+        double *l64 = r.lam64 + (size_t)i * gp.npad * (RAY_PARTS + 1);
+        int *pm = r.perm + (size_t)i * gp.npad;
+        {
+            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+            hipLaunchKernelGGL(blk_diag_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, (const float *)Wm, ld, n, l64);
+            hipLaunchKernelGGL(blk_rank_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, (const double *)l64, n, pm, r.items[i].lam);
+        }
+        // Q (3I - Q^T Q)/2 into the other accumulator buffer; W, free from here on, is the scratch
+        enqueue_newton_schulz(ctx, st, Qm, ld, n, Wm, Qo, ld, true);
+        {   // ... and back with the columns in ascending order of their eigenvalue estimates (the padding keeps its identity)
+            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+            hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, (const float *)Qo, ld, Qm, ld, n, pm);
+        }
+        float *Q1 = Qm;
         OpStrided<float, true> f_mk{r.items[i].F, n, 1, n, n, -1};
         OpStrided<float, false> q1_kn{Q1, 1, ld, n, n, -1};         // elem(c,k) = Q1[k][c]
         {   // T = F Q1
@@ -1331,14 +1471,13 @@ int enqueue_refresh(kfac_ctx *ctx, GroupRun &r) {
         OpStrided<float, false> q1t_mk{Q1, 1, ld, n, n, -1};        // elem(r,k) = Q1[k][r]
         OpStrided<float, false> t_kn{Tm, 1, ld, n, n, -1};          // elem(c,k) = T[k][c]
         {   // W = Q1^T T, made exactly symmetric
-            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q1t_mk), decltype(t_kn), EpiStore>), grid, block, 0, st,
+            KfacProfScope prof(ctx, KC_EIG_POST, sym_product_flops(n), 0.0, st);
+            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q1t_mk), decltype(t_kn), EpiStore, true>), grid, block, 0, st,
                                q1t_mk, t_kn, EpiStore{Wm, ld}, n, n, n);
         }
         KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
         hipLaunchKernelGGL(blk_symmetrise_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, Wm, ld, n);
     }
-    std::swap(r.g.Qw, r.Qalt);
     r.refreshed = true;
     KFAC_HIP_CHECK(hipGetLastError());
     return KFAC_OK;
@@ -1385,7 +1524,7 @@ int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
             hipLaunchKernelGGL(blk_copy_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, r.items[i].Q, Wm, (int64_t)n * n);
         }
         KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
-        hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, Wm, (int64_t)n, r.items[i].Q, n, pm);
+        hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, Wm, (int64_t)n, r.items[i].Q, (int64_t)n, n, pm);
     }
     KFAC_HIP_CHECK(hipGetLastError());
     KFAC_HIP_CHECK(hipEventRecord(r.ev[0], st));
@@ -1599,8 +1738,8 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
                 OpStrided<float, false> qt_mk{Qm, 1, ld, n, n, -1};                 // elem(r,k) = Q0[k][r]
                 OpStrided<float, false> t_kn{r.items[i].Q, 1, n, n, n, -1};         // elem(c,k) = (F Q0)[k][c]
                 {
-                    KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, r.st);
-                    hipLaunchKernelGGL((gemm_generic_kernel<decltype(qt_mk), decltype(t_kn), EpiStore>), grid, block, 0, r.st,
+                    KfacProfScope prof(ctx, KC_EIG_POST, sym_product_flops(n), 0.0, r.st);
+                    hipLaunchKernelGGL((gemm_generic_kernel<decltype(qt_mk), decltype(t_kn), EpiStore, true>), grid, block, 0, r.st,
                                        qt_mk, t_kn, EpiStore{Wm, ld}, n, n, n);
                 }
                 KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
@@ -1627,8 +1766,15 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
     double host_enqueue_ms = 0.0;
     auto now_ms = [&]() { return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count(); };
     auto enqueue_sweep = [&](GroupRun &r) -> int {
-        int rc = r.plan->two_level ? enqueue_sweep_two_level(ctx, r, lds_solve, inner_cap, inner_tol)
-                                   : enqueue_sweep_flat(ctx, r, lds_solve, inner_cap, inner_tol);
+        // The diagonal is put in order once the estimates are good enough to tell the clusters apart (after four sweeps:
+        // off-norm below 1e-2), and once more near the end -- for split-engine groups that is part of the refresh.  A
+        // sweep right after a reordering gains a little less than it would have, so more often does not pay (every
+        // sweep: two sweeps more; after two sweeps already: one more).
+        int rc = KFAC_OK;
+        if (r.sweep == 4 || (r.sweep == 7 && !r.x3)) rc = enqueue_sort(ctx, r);
+        if (rc != KFAC_OK) return rc;
+        rc = r.plan->two_level ? enqueue_sweep_two_level(ctx, r, lds_solve, inner_cap, inner_tol)
+                               : enqueue_sweep_flat(ctx, r, lds_solve, inner_cap, inner_tol);
         ++r.sweep;
         if (rc == KFAC_OK) rc = enqueue_offnorm(ctx, r);
         // measurement mode: all groups share one stream; keep its queue short (one group's sweep at a time), a

@@ -272,18 +272,51 @@ __device__ inline void store_acc_transposed(const floatx16 (&acc)[2][2], float *
         }
 }
 
+// f(c, r, acc(r, c)) for the whole tile, i.e. the transposed tile, visited so that a wave's lanes run along its rows
+// (coalesced if f stores).  Same LDS patches as store_acc_transposed; all threads of the workgroup must call it.
+template <class F>
+__device__ inline void for_each_acc_transposed(const floatx16 (&acc)[2][2], float *scratch, F f) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lk = lane >> 5, lc = lane & 31;
+    float *patch = scratch + wave * (32 * 33);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < 16; ++r) patch[lc * 33 + 8 * (r >> 2) + 4 * lk + (r & 3)] = acc[i][j][r];   // patch[col][row]
+            __syncthreads();
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                const int c = lk + 2 * t;
+                f(wn + 32 * j + c, wm + 32 * i + lc, patch[c * 33 + lc]);
+            }
+        }
+}
+
 // C = A * B over a rectangular grid of tiles (blockIdx.y: row tile, blockIdx.x: column tile); the
-// epilogue object is called as epi(row, col, value) for every in-range element.
-template <class OpA, class OpB, class Epi>
+// epilogue object is called as epi(row, col, value) for every in-range element.  SYM: the product is known to be
+// symmetric (M == N); tiles above the diagonal return at once and every tile below it also delivers its mirror
+// image, epi(col, row, value) -- half the matrix-core work, and the two halves agree to the last bit.
+template <class OpA, class OpB, class Epi, bool SYM = false>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void gemm_generic_kernel(OpA a, OpB b, Epi epi, int M, int N, int K) {
     __shared__ TileSmem sm;
     const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
+    if (SYM && j0 > i0) return;
     floatx16 acc[2][2];
     gemm_tile(a, b, i0, j0, 0, K, sm, acc);
     for_each_acc(acc, [&](int r, int c, float v) {
         const int gr = i0 + r, gc = j0 + c;
         if (gr < M && gc < N) epi(gr, gc, v);
     });
+    if (SYM && j0 < i0)
+        for_each_acc_transposed(acc, reinterpret_cast<float *>(&sm), [&](int r, int c, float v) {
+            const int gr = j0 + r, gc = i0 + c;
+            if (gr < M && gc < N) epi(gr, gc, v);
+        });
 }
 
 struct EpiStore {
