@@ -308,6 +308,24 @@ def main():
         torch.cuda.synchronize()
         split_ms.append(e0.elapsed_time(e1))
 
+    # the paper's other method (Sec. II-C, Eq. (kfac-damped); Table I sets it against the eigendecomposition): damped
+    # factors inverted by blocked Cholesky, gradients preconditioned by two plain products; not part of `value`
+    inv_ms, invp_ms = None, None
+    if not args.no_extras:
+        ti, tp = [], []
+        for _ in range(3):
+            e0, e1, e2 = ev(), ev(), ev()
+            run.restore_gradients()
+            e0.record()
+            run.invert_factors()
+            e1.record()
+            run.precondition_inverse(restore=False)
+            e2.record()
+            torch.cuda.synchronize()
+            ti.append(e0.elapsed_time(e1))
+            tp.append(e1.elapsed_time(e2))
+        inv_ms, invp_ms = round(min(ti), 3), round(min(tp), 3)
+
     # one more, instrumented step: every kernel launch bracketed by hipEvents on the library's stream
     K.kfac_profile_begin(run.ctx)
     step()
@@ -348,6 +366,7 @@ def main():
         "eig_warm_start_ms": None if args.no_extras else round(min(warm_ms), 3), "eig_warm_start_sweeps_max": warm_sweeps,
         "eig_fp32_only_ms": fp32_ms, "eig_fp32_only_sweeps_max": fp32_sweeps,
         "decoupled_schedule_ms_per_iteration": None if args.no_extras else round(sched_ms, 3),
+        "inverse_method_invert_factors_ms": inv_ms, "inverse_method_precondition_ms": invp_ms,
         "precondition_split_f16_ms": round(min(split_ms), 3),
         "precondition_split_f16_tflops": round(w["precond_flops"] / (min(split_ms) * 1e-3) / 1e12, 2),
     }

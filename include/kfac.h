@@ -202,6 +202,39 @@ typedef struct {
 int kfac_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_item *items /* host */);
 size_t kfac_precondition_workspace_bytes(int n, const kfac_precond_item *items /* host; only dA, dG are read */);
 
+/* The explicit-inverse method (Sec. II-C, Eq. (kfac-damped); the method that Sec. IV-A and Table I set the
+ * eigendecomposition against), as the paper describes it: the damped factors are inverted once,
+ *     Finv[b] = (F[b] + damping I)^-1 ,
+ * and a gradient is preconditioned by two plain products, grad <- Ginv grad Ainv.
+ * kfac_invert_factors: blocked Cholesky factorisation, triangular inversion and L^-T L^-1, all in fp32; the factors
+ * are taken one after another on the context's stream.
+ *   F, d, Finv : HOST arrays of `batch` entries; F[b], Finv[b] device pointers to [d[b]][d[b]] fp32 matrices
+ *                (F[b] symmetric positive semi-definite, read only; Finv[b] must not alias it), damping > 0.
+ *   A factor that is not positive definite after damping (or not finite) gives a non-finite Finv; no error is
+ *   reported for it.  Accuracy is that of an fp32 Cholesky inverse: relative error of the order of
+ *   cond(F + damping I) * 6e-8.  Workspace: kfac_invert_workspace_bytes() (covered by kfac_workspace_bytes(max_d, ..)).
+ *   Factors of equal size advance together, and with workspace to spare (four times the largest factor's need)
+ *   groups run side by side on the context's internal streams; the caller's stream waits for all of them.
+ * kfac_precondition_inverse[_batched]: grad [dG][dA] (fp32 or bf16, in/out) <- Ginv grad Ainv on the fp32 matrix
+ *   instructions, two launches for the whole batch; items is a HOST array, every pointer in it a device pointer;
+ *   gradients must not alias one another.  Workspace: kfac_precondition_inverse_workspace_bytes() (dG*dA floats per
+ *   layer).  All calls are asynchronous with respect to the host.  */
+int kfac_invert_factors(kfac_ctx *ctx, int batch, const float *const *F /* host array of device ptrs */,
+                        const int *d /* host */, float damping, float *const *Finv /* host array of device ptrs */);
+size_t kfac_invert_workspace_bytes(int batch, const int *d /* host */);
+typedef struct {
+    const float *Ainv;   /* [dA][dA] */
+    int dA;
+    const float *Ginv;   /* [dG][dG] */
+    int dG;
+    void *grad;          /* [dG][dA], in/out */
+    int grad_dtype;
+} kfac_precond_inv_item;
+int kfac_precondition_inverse(kfac_ctx *ctx, const float *Ainv, int dA, const float *Ginv, int dG, void *grad,
+                              int grad_dtype);
+int kfac_precondition_inverse_batched(kfac_ctx *ctx, int n, const kfac_precond_inv_item *items /* host */);
+size_t kfac_precondition_inverse_workspace_bytes(int n, const kfac_precond_inv_item *items /* host; only dA, dG are read */);
+
 /* The same, followed by the gradient scaling of Sec. V-C ("K-FAC Hyper-Parameters"): every preconditioned
  * gradient P_l is multiplied by
  *     nu = min(1, sqrt(kappa / (lr^2 * sum_l |<P_l, grad_l>|)))

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkfac_hip.so")
-SOURCES = ["kfac_api.hip", "unfold.hip", "syrk.hip", "precondition.hip", "eig.hip", "static_scratch.hip"]
+SOURCES = ["kfac_api.hip", "unfold.hip", "syrk.hip", "precondition.hip", "eig.hip", "static_scratch.hip", "inverse.hip"]
 FLAGS = os.environ.get("KFAC_EXTRA_FLAGS", "").split() + [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 VALU forms are disabled for all device code of this library

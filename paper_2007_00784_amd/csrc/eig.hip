@@ -830,10 +830,15 @@ __global__ __launch_bounds__(NT) void blk_rayleigh_sum_kernel(const double *part
     lam64[i] = s;
 }
 
-// perm[rank] = index of the rank-th smallest eigenvalue (ties by index); lam[rank] = that eigenvalue.
-__global__ __launch_bounds__(NT) void blk_rank_kernel(const double *lam64, int n, int *perm, float *lam_out) {
-    __shared__ float chunk[NT];         // the values every thread compares against, a workgroup-load at a time
-    const int i = blockIdx.x * NT + threadIdx.x;
+// perm[rank] = index of the rank-th smallest eigenvalue (ties by index); lam[rank] = that eigenvalue (if asked for).
+// n^2 comparisons: a workgroup ranks RANK_IPB values, sixteen threads sharing the comparisons of each (the values
+// they compare against pass through LDS a workgroup-load at a time), so a 4609-wide spectrum is 289 workgroups.
+constexpr int RANK_IPB = 16;
+__device__ inline void rank_block(const double *lam64, int n, int *perm, float *lam_out) {
+    __shared__ float chunk[NT];
+    __shared__ int part[NT];
+    const int ii = threadIdx.x & (RANK_IPB - 1), js = threadIdx.x / RANK_IPB;
+    const int i = blockIdx.x * RANK_IPB + ii;
     const float li = i < n ? (float)lam64[i] : 0.f;
     const bool nan_i = li != li;
     int rank = 0;
@@ -841,17 +846,25 @@ __global__ __launch_bounds__(NT) void blk_rank_kernel(const double *lam64, int n
         __syncthreads();
         chunk[threadIdx.x] = j0 + (int)threadIdx.x < n ? (float)lam64[j0 + threadIdx.x] : 0.f;
         __syncthreads();
-        const int m = min(NT, n - j0);
-        for (int k = 0; k < m; ++k) {   // NaNs order after every number, among themselves by index: always a permutation
+        const int cnt = min(NT, n - j0);
+        for (int k = js; k < cnt; k += NT / RANK_IPB) {   // NaNs order after every number, among themselves by index: always a permutation
             const float lj = chunk[k];
             const int j = j0 + k;
             const bool nan_j = lj != lj;
             rank += nan_i ? (!nan_j || j < i) : (!nan_j && ((lj < li) || (lj == li && j < i)));
         }
     }
-    if (i >= n) return;
-    perm[rank] = i;
-    lam_out[rank] = li;
+    part[threadIdx.x] = rank;
+    __syncthreads();
+    if (js == 0 && i < n) {
+        int total = 0;
+        for (int t = 0; t < NT / RANK_IPB; ++t) total += part[t * RANK_IPB + ii];
+        perm[total] = i;
+        if (lam_out) lam_out[total] = li;
+    }
+}
+__global__ __launch_bounds__(NT) void blk_rank_kernel(const double *lam64, int n, int *perm, float *lam_out) {
+    rank_block(lam64, n, perm, lam_out);
 }
 
 __global__ __launch_bounds__(NT) void blk_fill_kernel(float *dst, int64_t count, float v) {
@@ -1102,29 +1115,11 @@ __global__ __launch_bounds__(NT) void sort_diag_kernel(SortArgs a) {
     a.lam64[m * a.lam_stride + i] = (double)a.W[m * a.np2 + (int64_t)i * a.npad + i];
 }
 __global__ __launch_bounds__(NT) void sort_rank_kernel(SortArgs a) {
-    __shared__ float chunk[NT];
     const int m = blockIdx.y;
     if (a.done[m]) return;
     const int n = a.items[m].n;
-    if ((int)(blockIdx.x * NT) >= n) return;
-    const double *lam64 = a.lam64 + m * a.lam_stride;
-    const int i = blockIdx.x * NT + threadIdx.x;
-    const float li = i < n ? (float)lam64[i] : 0.f;
-    const bool nan_i = li != li;
-    int rank = 0;
-    for (int j0 = 0; j0 < n; j0 += NT) {
-        __syncthreads();
-        chunk[threadIdx.x] = j0 + (int)threadIdx.x < n ? (float)lam64[j0 + threadIdx.x] : 0.f;
-        __syncthreads();
-        const int cnt = min(NT, n - j0);
-        for (int k = 0; k < cnt; ++k) {   // as in blk_rank_kernel: always a permutation
-            const float lj = chunk[k];
-            const int j = j0 + k;
-            const bool nan_j = lj != lj;
-            rank += nan_i ? (!nan_j || j < i) : (!nan_j && ((lj < li) || (lj == li && j < i)));
-        }
-    }
-    if (i < n) a.perm[(int64_t)m * a.npad + rank] = i;
+    if ((int)(blockIdx.x * RANK_IPB) >= n) return;
+    rank_block(a.lam64 + m * a.lam_stride, n, a.perm + (int64_t)m * a.npad, nullptr);
 }
 // which = 0: scratch = P W P^T; which = 1: scratch[:, j] = Q[:, perm[j]]
 __global__ __launch_bounds__(NT) void sort_permute_kernel(SortArgs a, int which) {
@@ -1306,7 +1301,7 @@ int enqueue_sort(kfac_ctx *ctx, GroupRun &r) {
     const dim3 gv((r.nmax + NT - 1) / NT, r.nm), gm(std::min(r.fill_blocks, 1024), r.nm);
     KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
     hipLaunchKernelGGL(sort_diag_kernel, gv, dim3(NT), 0, r.st, a);
-    hipLaunchKernelGGL(sort_rank_kernel, gv, dim3(NT), 0, r.st, a);
+    hipLaunchKernelGGL(sort_rank_kernel, dim3((r.nmax + RANK_IPB - 1) / RANK_IPB, r.nm), dim3(NT), 0, r.st, a);
     for (int which = 0; which < 2; ++which) {
         hipLaunchKernelGGL(sort_permute_kernel, gm, dim3(NT), 0, r.st, a, which);
         hipLaunchKernelGGL(sort_copyback_kernel, gm, dim3(NT), 0, r.st, a, which);
@@ -1452,7 +1447,7 @@ int enqueue_refresh(kfac_ctx *ctx, GroupRun &r) {
         {
             KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
             hipLaunchKernelGGL(blk_diag_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, (const float *)Wm, ld, n, l64);
-            hipLaunchKernelGGL(blk_rank_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, (const double *)l64, n, pm, r.items[i].lam);
+            hipLaunchKernelGGL(blk_rank_kernel, dim3((n + RANK_IPB - 1) / RANK_IPB), dim3(NT), 0, st, (const double *)l64, n, pm, r.items[i].lam);
         }
         // Q (3I - Q^T Q)/2 into the other accumulator buffer; W, free from here on, is the scratch
         enqueue_newton_schulz(ctx, st, Qm, ld, n, Wm, Qo, ld, true);
@@ -1516,7 +1511,7 @@ int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
             KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
             hipLaunchKernelGGL(blk_rayleigh_kernel, dim3((n + NT - 1) / NT, RAY_PARTS), dim3(NT), 0, st, r.items[i].Q, (int64_t)n, Qm, ld, n, lpart);
             hipLaunchKernelGGL(blk_rayleigh_sum_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, (const double *)lpart, n, l64);
-            hipLaunchKernelGGL(blk_rank_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, l64, n, pm, r.items[i].lam);
+            hipLaunchKernelGGL(blk_rank_kernel, dim3((n + RANK_IPB - 1) / RANK_IPB), dim3(NT), 0, st, l64, n, pm, r.items[i].lam);
         }
         {
             // plain copy of n*n floats (read + write): also the reference point for HBM traffic counters

@@ -165,6 +165,8 @@ size_t kfac_workspace_bytes(int max_d, int max_batch_factors, int64_t max_R) {
     // eig: every factor of the batch at the largest size, advanced together
     std::vector<int> d((size_t)max_batch_factors, max_d);
     need = std::max(need, kfac_eig_ws_bytes_impl(max_batch_factors, d.data()));
+    // explicit inverses: one factor at a time
+    need = std::max(need, kfac_invert_ws_bytes_impl(1, d.data()));
     return kfac_align_up(need, 256);
 }
 
@@ -241,6 +243,47 @@ int kfac_precondition(kfac_ctx *ctx, const float *QA, const float *lamA, int dA,
     return kfac_launch_precondition(ctx, QA, lamA, dA, QG, lamG, dG, damping, grad, grad_dtype);
 }
 
+int kfac_invert_factors(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float damping, float *const *Finv) {
+    if (!ctx || batch < 0 || (batch > 0 && (!F || !d || !Finv))) return KFAC_EINVAL;
+    if (!(damping > 0.f) || !std::isfinite(damping)) return KFAC_EINVAL;
+    for (int i = 0; i < batch; ++i)
+        if (d[i] < 1 || d[i] > KFAC_MAX_D || !F[i] || !Finv[i] || (const float *)Finv[i] == F[i]) return KFAC_EINVAL;
+    if (batch == 0) return KFAC_OK;
+    return kfac_launch_invert_factors(ctx, batch, F, d, damping, Finv);
+}
+
+size_t kfac_invert_workspace_bytes(int batch, const int *d) {
+    if (batch < 0 || (batch > 0 && !d)) return 0;
+    for (int i = 0; i < batch; ++i)
+        if (d[i] < 1 || d[i] > KFAC_MAX_D) return 0;
+    return kfac_invert_ws_bytes_impl(batch, d);
+}
+
+static bool valid_inv_item(const kfac_precond_inv_item &it, bool pointers) {
+    if (pointers && (!it.Ainv || !it.Ginv || !it.grad)) return false;
+    return it.dA >= 1 && it.dG >= 1 && it.dA <= KFAC_MAX_D && it.dG <= KFAC_MAX_D && valid_dtype(it.grad_dtype);
+}
+
+int kfac_precondition_inverse_batched(kfac_ctx *ctx, int n, const kfac_precond_inv_item *items) {
+    if (!ctx || n < 0 || (n > 0 && !items)) return KFAC_EINVAL;
+    for (int i = 0; i < n; ++i)
+        if (!valid_inv_item(items[i], true)) return KFAC_EINVAL;
+    if (n == 0) return KFAC_OK;
+    return kfac_launch_precondition_inverse_batched(ctx, n, items);
+}
+
+size_t kfac_precondition_inverse_workspace_bytes(int n, const kfac_precond_inv_item *items) {
+    if (n < 0 || (n > 0 && !items)) return 0;
+    for (int i = 0; i < n; ++i)
+        if (!valid_inv_item(items[i], false)) return 0;
+    return kfac_precondition_inverse_ws_bytes_impl(n, items);
+}
+
+int kfac_precondition_inverse(kfac_ctx *ctx, const float *Ainv, int dA, const float *Ginv, int dG, void *grad, int grad_dtype) {
+    const kfac_precond_inv_item it{Ainv, dA, Ginv, dG, grad, grad_dtype};
+    return kfac_precondition_inverse_batched(ctx, 1, &it);
+}
+
 int kfac_profile_begin(kfac_ctx *ctx) {
     if (!ctx) return KFAC_EINVAL;
     for (auto &r : ctx->prof) { ctx->ev_pool.push_back(r.t0); ctx->ev_pool.push_back(r.t1); }
@@ -253,7 +296,7 @@ int kfac_profile_end(kfac_ctx *ctx, kfac_kernel_stat *out, int max, int *n) {
     if (!ctx || !out || !n || max < 0) return KFAC_EINVAL;
     static const char *names[KC_COUNT] = {"unfold", "syrk", "syrk_reduce", "precond_gemm", "eig_small",
                                           "eig_pivot_solve", "eig_apply", "eig_misc", "eig_post_gemm", "eig_copy", "eig_outer_cols",
-                                          "precond_scale", "syrk_bf16", "precond_gemm_split", "eig_outer_rows"};
+                                          "precond_scale", "syrk_bf16", "precond_gemm_split", "eig_outer_rows", "factor_inverse"};
     ctx->prof_on = false;
     KFAC_HIP_CHECK(hipStreamSynchronize(ctx->stream));
     kfac_kernel_stat acc[KC_COUNT] = {};

@@ -9,7 +9,7 @@
 // Kernel classes for the optional per-kernel timing (kfac_profile_begin / kfac_profile_end).
 enum KfacKernelClass {
     KC_UNFOLD = 0, KC_SYRK, KC_SYRK_REDUCE, KC_PRECOND_GEMM, KC_EIG_SMALL, KC_EIG_SOLVE, KC_EIG_APPLY,
-    KC_EIG_MISC, KC_EIG_POST, KC_EIG_COPY, KC_EIG_OUTER, KC_PRECOND_SCALE, KC_SYRK_B16, KC_PRECOND_GEMM_X3, KC_EIG_OUTER_ROWS, KC_COUNT
+    KC_EIG_MISC, KC_EIG_POST, KC_EIG_COPY, KC_EIG_OUTER, KC_PRECOND_SCALE, KC_SYRK_B16, KC_PRECOND_GEMM_X3, KC_EIG_OUTER_ROWS, KC_INVERSE, KC_COUNT
 };
 struct KfacProfRec { int cls; hipEvent_t t0, t1; double flops, bytes; };
 
@@ -116,5 +116,9 @@ int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_it
                                      float *nu);
 size_t kfac_precond_ws_bytes_impl(int n, const kfac_precond_item *items);
 size_t kfac_eig_ws_bytes_impl(int batch, const int *d);
+size_t kfac_invert_ws_bytes_impl(int batch, const int *d);
+int kfac_launch_invert_factors(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float damping, float *const *Finv);
+size_t kfac_precondition_inverse_ws_bytes_impl(int n, const kfac_precond_inv_item *items);
+int kfac_launch_precondition_inverse_batched(kfac_ctx *ctx, int n, const kfac_precond_inv_item *items);
 int kfac_launch_eig(kfac_ctx *ctx, int batch, const float *const *F, const int *d, float *const *Q,
                     float *const *lam, const kfac_eig_opts *opts, kfac_eig_info *info);

@@ -21,7 +21,14 @@ EXPORTS = (
     "kfac_profile_begin", "kfac_profile_end", "kfac_precondition_batched", "kfac_precondition_workspace_bytes",
     "kfac_update_factors_batched", "kfac_update_factors_workspace_bytes", "kfac_precondition_batched_scaled",
     "kfac_update_factors_static", "kfac_static_scratch_bytes",
+    "kfac_invert_factors", "kfac_invert_workspace_bytes", "kfac_precondition_inverse",
+    "kfac_precondition_inverse_batched", "kfac_precondition_inverse_workspace_bytes",
 )
+
+
+class kfac_precond_inv_item(ctypes.Structure):
+    _fields_ = [("Ainv", ctypes.c_void_p), ("dA", ctypes.c_int), ("Ginv", ctypes.c_void_p), ("dG", ctypes.c_int),
+                ("grad", ctypes.c_void_p), ("grad_dtype", ctypes.c_int)]
 
 
 class kfac_conv_desc(ctypes.Structure):
@@ -101,12 +108,20 @@ def lib():
     L.kfac_update_factors_batched.argtypes = [vp, i, ctypes.POINTER(kfac_factor_item)]
     L.kfac_update_factors_workspace_bytes.argtypes = [i, ctypes.POINTER(kfac_factor_item)]
     L.kfac_update_factors_workspace_bytes.restype = sz
+    L.kfac_invert_factors.argtypes = [vp, i, ctypes.POINTER(vp), ip, f, ctypes.POINTER(vp)]
+    L.kfac_invert_workspace_bytes.argtypes = [i, ip]
+    L.kfac_invert_workspace_bytes.restype = sz
+    L.kfac_precondition_inverse.argtypes = [vp, vp, i, vp, i, vp, i]
+    L.kfac_precondition_inverse_batched.argtypes = [vp, i, ctypes.POINTER(kfac_precond_inv_item)]
+    L.kfac_precondition_inverse_workspace_bytes.argtypes = [i, ctypes.POINTER(kfac_precond_inv_item)]
+    L.kfac_precondition_inverse_workspace_bytes.restype = sz
     L.kfac_profile_begin.argtypes = [vp]
     L.kfac_profile_end.argtypes = [vp, ctypes.POINTER(kfac_kernel_stat), i, ip]
     for name in EXPORTS:
         if name not in ("kfac_workspace_bytes", "kfac_eig_workspace_bytes", "kfac_strerror",
                         "kfac_precondition_workspace_bytes", "kfac_update_factors_workspace_bytes",
-                        "kfac_unfold_workspace_bytes", "kfac_static_scratch_bytes"):
+                        "kfac_unfold_workspace_bytes", "kfac_static_scratch_bytes", "kfac_invert_workspace_bytes",
+                        "kfac_precondition_inverse_workspace_bytes"):
             getattr(L, name).restype = i
     _lib = L
     return L
@@ -251,6 +266,46 @@ def kfac_eig(ctx, F, Q, lam, max_sweeps=0, tol=0.0, raise_on_noconv=True, fp32_o
     rc = lib().kfac_eig(ctx, n, Fa, dims, Qa, La, ctypes.byref(opts), info)
     _check(rc, "kfac_eig", allow=() if raise_on_noconv else (KFAC_ENOCONV,))
     return [(info[i].sweeps, info[i].off_norm_rel, bool(info[i].converged)) for i in range(n)]
+
+
+def kfac_invert_factors(ctx, F, damping, Finv):
+    """F, Finv: lists of device tensors; Finv[b] <- (F[b] + damping I)^-1."""
+    n = len(F)
+    vp = ctypes.c_void_p
+    Fa = (vp * n)(*[_ptr(t) for t in F])
+    Ia = (vp * n)(*[_ptr(t) for t in Finv])
+    dims = (ctypes.c_int * n)(*[int(t.shape[0]) for t in F])
+    _check(lib().kfac_invert_factors(ctx, n, Fa, dims, float(damping), Ia), "kfac_invert_factors")
+
+
+def kfac_invert_workspace_bytes(dims):
+    n = len(dims)
+    return int(lib().kfac_invert_workspace_bytes(n, (ctypes.c_int * n)(*[int(v) for v in dims])))
+
+
+def kfac_precondition_inverse(ctx, Ainv, Ginv, grad):
+    dA, dG = int(Ainv.shape[0]), int(Ginv.shape[0])
+    if tuple(grad.shape) != (dG, dA):
+        raise ValueError("grad must be [dG, dA]")
+    _check(lib().kfac_precondition_inverse(ctx, _ptr(Ainv), dA, _ptr(Ginv), dG, _ptr(grad), _dtype_code(grad)),
+           "kfac_precondition_inverse")
+
+
+def precond_inv_items(Ainv, Ginv, grad):
+    """Marshalled array of kfac_precond_inv_item for lists of device tensors (reusable across calls)."""
+    n = len(grad)
+    arr = (kfac_precond_inv_item * n)()
+    for j in range(n):
+        dA, dG = int(Ainv[j].shape[0]), int(Ginv[j].shape[0])
+        if tuple(grad[j].shape) != (dG, dA):
+            raise ValueError("grad[%d] must be [dG, dA]" % j)
+        arr[j] = kfac_precond_inv_item(_ptr(Ainv[j]), dA, _ptr(Ginv[j]), dG, _ptr(grad[j]), _dtype_code(grad[j]))
+    return arr
+
+
+def kfac_precondition_inverse_batched(ctx, Ainv=None, Ginv=None, grad=None, items=None):
+    arr = items if items is not None else precond_inv_items(Ainv, Ginv, grad)
+    _check(lib().kfac_precondition_inverse_batched(ctx, len(arr), arr), "kfac_precondition_inverse_batched")
 
 
 def kfac_precondition(ctx, QA, lamA, QG, lamG, damping, grad):

@@ -140,6 +140,23 @@ class KfacRunner:
             self.nu = torch.zeros(1, dtype=torch.float32, device=self.dev)
             K.kfac_precondition_batched_scaled(self.ctx, kappa=kappa, lr=lr, nu=self.nu, items=self._marshalled[key])
 
+    # ---- the explicit-inverse method (Sec. II-C, Eq. (kfac-damped)): the paper's other way to the same step ----
+    def invert_factors(self, damping=None):
+        """(A + gamma I)^-1 and (G + gamma I)^-1 of every layer by blocked Cholesky (buffers allocated on first use)."""
+        gamma = self.wl.damping if damping is None else damping
+        if not hasattr(self, "Ainv"):
+            self.Ainv = [torch.empty_like(a) for a in self.A]
+            self.Ginv = [torch.empty_like(g) for g in self.G]
+        K.kfac_invert_factors(self.ctx, self.A + self.G, gamma, self.Ainv + self.Ginv)
+
+    def precondition_inverse(self, restore=True):
+        """grad <- Ginv grad Ainv for every layer, in place."""
+        if restore:
+            self.restore_gradients()
+        if "precond_inv" not in self._marshalled:
+            self._marshalled["precond_inv"] = K.precond_inv_items(self.Ainv, self.Ginv, self.grad)
+        K.kfac_precondition_inverse_batched(self.ctx, items=self._marshalled["precond_inv"])
+
     # ---- algorithmic work of one step (flops, bytes) ----
     def work(self):
         N = self.N

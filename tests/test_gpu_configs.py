@@ -506,6 +506,49 @@ def test_resnet152_step_properties():
 
 
 @pytest.mark.timeout(600)
+def test_config3_inverse_method_on_the_whole_set():
+    """The paper's explicit-inverse method (Sec. II-C, Eq. (kfac-damped)) on config 3 at the reported damping: all 108
+    factors inverted by the blocked Cholesky path, then grad <- Ginv grad Ainv for all 54 layers in one batched call.
+    One factor of every distinct size is checked through the defining property ||Finv (F + gamma I) - I||_F / sqrt(n)
+    in fp64 on the device, bounded by max(2e-6, 2e-7 * cond) with cond from the fp64 spectrum of the same factor (an
+    fp32 inverse cannot do better than cond * 6e-8; measured 0.02 .. 0.1 of the bound); one small layer's whole
+    result is compared with the oracle's two Cholesky solves on the oracle's own factors."""
+    wl = S.workload("resnet50")
+    run = KfacRunner(wl, n_updates=2)
+    run.update_factors(0, 0.0)
+    run.update_factors(1, wl.decay)
+    run.invert_factors()
+    run.precondition_inverse()
+    torch.cuda.synchronize()
+    gamma = wl.damping
+    seen = set()
+    for F, Fi in zip(run.A + run.G, run.Ainv + run.Ginv):
+        n = F.shape[0]
+        assert bool(torch.isfinite(Fi).all()), n
+        if n in seen:
+            continue
+        seen.add(n)
+        F64 = F.double()
+        M = F64 + gamma * torch.eye(n, dtype=torch.float64, device=F.device)
+        lam = torch.linalg.eigvalsh(F64)
+        cond = float((lam[-1].clamp(min=0) + gamma) / (lam[0].clamp(min=0) + gamma))
+        res = float((Fi.double() @ M - torch.eye(n, dtype=torch.float64, device=F.device)).norm()) / n ** 0.5
+        assert res <= max(2e-6, 2e-7 * cond), (n, res, cond)
+        progress("inverse d=%d: residual %.2e, cond %.2e" % (n, res, cond))
+    assert len(seen) >= 15
+    # one whole layer against the oracle (a small one: its factors are well conditioned at this damping relative to fp32)
+    i = [k for k, l in enumerate(run.layers) if l.name == "s1b0.reduce"][0]
+    A, G = oracle_factors(run, i, 2)
+    ref = oracle.precondition_inverse(G, A, gamma, f64(run.gradw_master[i]))
+    lamA, lamG = np.linalg.eigvalsh(A), np.linalg.eigvalsh(G)
+    condA = (lamA[-1] + gamma) / (max(lamA[0], 0) + gamma)
+    condG = (lamG[-1] + gamma) / (max(lamG[0], 0) + gamma)
+    err = relfro(f64(run.grad[i]), ref)
+    assert err <= max(TOL_F32, 2e-7 * (condA + condG)), (err, condA, condG)
+    run.close()
+
+
+@pytest.mark.timeout(600)
 def test_linear_only_stack_full_parity():
     """A stack of Linear layers (2048 -> 2048 -> 2048 -> 1000, batch 256; samples as [R][d] rows, no unfold,
     factors of rank <= 2 x 256 after two updates): every layer's factors, spectra and preconditioned gradient

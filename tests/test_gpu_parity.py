@@ -472,6 +472,110 @@ def test_explicit_inverse_method_matches_cholesky_oracle(ctx, dA, dG):
         assert relfro(g2.cpu().numpy(), ref) > 1e-3
 
 
+def _spd_factor(rng, n, rows, relu=True):
+    X = rng.standard_normal((rows, n - 1))
+    if relu:
+        X = np.maximum(X, 0)
+    X = X.astype(np.float32)
+    return oracle.gram(X, 1, 1.0 / rows)
+
+
+@pytest.mark.parametrize("n,rows", [(1, 8), (5, 40), (64, 256), (128, 300), (129, 300), (300, 200), (577, 1200), (1153, 1500)])
+def test_invert_factors_matches_cholesky_oracle(ctx, n, rows):
+    """Sec. II-C, Eq. (kfac-damped): (F + gamma I)^-1 by the library's blocked Cholesky inverse against the oracle's
+    Cholesky solve of (F + gamma I) X = I in fp64.  Sizes straddle the 128-wide blocks; (300, 200) is rank deficient
+    (only the damping makes it definite).  An fp32 inverse carries a relative error of the order of
+    cond(F + gamma I) * 6e-8, so the bound is max(2e-6, 2e-7 * cond) with cond from the fp64 spectrum (measured:
+    0.02 .. 0.1 of it)."""
+    rng = np.random.default_rng(31 * n + rows)
+    F = _spd_factor(rng, n, rows)
+    lam = np.linalg.eigvalsh(F)
+    Fd = ctx.to_dev(F.astype(np.float32))
+    F32 = Fd.cpu().numpy().astype(np.float64)
+    for gamma in (1e-1, 1e-3):
+        ref = oracle.spd_solve(F32 + gamma * np.eye(n), np.eye(n))
+        out = torch.full((n, n), float("nan"), dtype=torch.float32, device=ctx.dev)
+        K.kfac_invert_factors(ctx.h, [Fd], gamma, [out])
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        cond = (max(lam[-1], 0) + gamma) / (max(lam[0], 0) + gamma)
+        err = relfro(got, ref)
+        assert err <= max(2e-6, 2e-7 * cond), (n, gamma, err, cond)
+        # the defining property, in fp64 on the fp32 result
+        res = np.linalg.norm(got @ (F32 + gamma * np.eye(n)) - np.eye(n)) / np.sqrt(n)
+        assert res <= max(2e-6, 2e-7 * cond), (n, gamma, res, cond)
+
+
+def test_invert_factors_batch_of_mixed_sizes(ctx):
+    """Several factors in one call share the workspace one after another; every inverse is checked."""
+    rng = np.random.default_rng(77)
+    dims = [257, 16, 130, 257, 400]
+    Fs = [_spd_factor(rng, n, 3 * n, relu=False) for n in dims]
+    Fd = [ctx.to_dev(F.astype(np.float32)) for F in Fs]
+    outs = [torch.zeros((n, n), dtype=torch.float32, device=ctx.dev) for n in dims]
+    assert 0 < K.kfac_invert_workspace_bytes(dims) <= K.kfac_workspace_bytes(max(dims), 1, 1)
+    K.kfac_invert_factors(ctx.h, Fd, 0.05, outs)
+    torch.cuda.synchronize()
+    for F, o, n in zip(Fd, outs, dims):
+        ref = oracle.spd_solve(F.cpu().numpy().astype(np.float64) + 0.05 * np.eye(n), np.eye(n))
+        assert relfro(o.cpu().numpy(), ref) <= 1e-5, n
+    with pytest.raises(K.KfacError):
+        K.kfac_invert_factors(ctx.h, Fd, 0.0, outs)
+    with pytest.raises(K.KfacError):
+        K.kfac_invert_factors(ctx.h, Fd, 0.05, Fd)
+
+
+@pytest.mark.parametrize("dA,dG", [(145, 16), (300, 130), (577, 64)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_precondition_inverse_matches_oracle(ctx, dA, dG, bf16):
+    """The whole inverse method, factors -> Cholesky inverses -> Ginv grad Ainv, against the oracle's two Cholesky
+    solves (Sec. II-C, Eq. (kfac-damped)); well-conditioned factors as in
+    test_explicit_inverse_method_matches_cholesky_oracle, fp32 and bf16 gradients."""
+    rng = np.random.default_rng(dA + 5)
+    X = rng.standard_normal((3 * dA, dA - 1)).astype(np.float32)
+    Gr = rng.standard_normal((4 * dG, dG)).astype(np.float32)
+    Ad = torch.zeros((dA, dA), dtype=torch.float32, device=ctx.dev)
+    Gd = torch.zeros((dG, dG), dtype=torch.float32, device=ctx.dev)
+    ctx.update_factors(ctx.to_dev(X), K.KFAC_LAYOUT_RD, X.shape[0], dA - 1, 1, 1, 1.0 / X.shape[0], 0.0, Ad)
+    ctx.update_factors(ctx.to_dev(Gr), K.KFAC_LAYOUT_RD, Gr.shape[0], dG, 1, 0, 1.0 / Gr.shape[0], 0.0, Gd)
+    A = oracle.gram(X, 1, 1.0 / X.shape[0])
+    G = oracle.gram(Gr, 0, 1.0 / Gr.shape[0])
+    grad = (rng.standard_normal((dG, dA)) * 1e-2).astype(np.float32)
+    if bf16:
+        grad = S.bf16_bits_to_f32(S.to_bf16_bits(grad)).reshape(grad.shape)
+    Ai, Gi = torch.empty_like(Ad), torch.empty_like(Gd)
+    for gamma in (0.3, 1.0):
+        ref = oracle.precondition_inverse(G, A, gamma, grad)
+        K.kfac_invert_factors(ctx.h, [Ad, Gd], gamma, [Ai, Gi])
+        gd = ctx.to_dev(grad, bf16)
+        K.kfac_precondition_inverse(ctx.h, Ai, Gi, gd)
+        torch.cuda.synchronize()
+        got = gd.float().cpu().numpy()
+        assert relfro(got, ref) <= (TOL_BF16 if bf16 else TOL_F32), (gamma, relfro(got, ref))
+
+
+def test_precondition_inverse_batched_equals_per_layer(ctx):
+    """One batched call over layers of different shapes and gradient types gives, bit for bit, what the per-layer call
+    gives (same tiles, same order of operations)."""
+    rng = np.random.default_rng(9)
+    shapes = [(145, 16, False), (300, 130, True), (64, 257, False), (129, 128, True)]
+    Ai, Gi, g1, g2 = [], [], [], []
+    for dA, dG, bf16 in shapes:
+        A = _spd_factor(rng, dA, 2 * dA, relu=False)
+        G = _spd_factor(rng, dG, 2 * dG, relu=False)
+        Ai.append(ctx.to_dev(np.linalg.inv(A + 0.5 * np.eye(dA)).astype(np.float32)))
+        Gi.append(ctx.to_dev(np.linalg.inv(G + 0.5 * np.eye(dG)).astype(np.float32)))
+        g = rng.standard_normal((dG, dA)).astype(np.float32)
+        g1.append(ctx.to_dev(g, bf16))
+        g2.append(ctx.to_dev(g, bf16))
+    K.kfac_precondition_inverse_batched(ctx.h, Ai, Gi, g1)
+    for a, g, x in zip(Ai, Gi, g2):
+        K.kfac_precondition_inverse(ctx.h, a, g, x)
+    torch.cuda.synchronize()
+    for x, y in zip(g1, g2):
+        assert torch.equal(x, y)
+
+
 @pytest.mark.parametrize("dA,dG,rows", [(145, 16, 2048), (577, 64, 1500), (289, 32, 200)])
 def test_explicit_inverse_method_at_the_papers_damping(ctx, dA, dG, rows):
     """The explicit-inverse method where it is hard: ReLU-activation A factors (one eigenvalue ~ 0.16 d_A over a bulk
