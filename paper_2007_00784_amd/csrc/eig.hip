@@ -671,7 +671,9 @@ __device__ inline void acc_to_block(const floatx16 &acc, float *Xs, int wm, int 
 }
 
 // grid.x: nblocks_w lower-triangular blocks of W, then nrb row slabs x npairs column pairs of the accumulator.
-__global__ __launch_bounds__(NT) void blk_apply_kernel(BlkGroup g, int round, int nblocks_w, int nrb) {
+// (waves_per_eu(4): with the register budget of four waves per SIMD the compiler keeps both transforms and the
+// staged block in flight; left to itself it aims at six, and the flat groups' rounds take 8 % longer)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void blk_apply_kernel(BlkGroup g, int round, int nblocks_w, int nrb) {
     __shared__ float Xs[KP * BLD];
     const int m = blockIdx.y;
     if (blk_done(g, m)) return;
