@@ -6,6 +6,14 @@
 #include <vector>
 #include "../../include/kfac.h"
 
+// A pointer that the compiler cannot trace back to a kernel argument (one read from a descriptor table in memory)
+// is generic to it, and a load through a generic pointer is a flat load: it counts on the vector-memory counter
+// and on the LDS counter, so every wait for an LDS read also waits for all the loads from memory still in flight,
+// which undoes a software pipeline that prefetches from memory while it multiplies out of LDS.  Every operand of
+// this library lives in device global memory; as_global() says so at the point of access.
+template <typename T> using global_ptr = T __attribute__((address_space(1))) *;
+template <typename T> __device__ inline global_ptr<T> as_global(T *p) { return (global_ptr<T>)p; }
+
 // Kernel classes for the optional per-kernel timing (kfac_profile_begin / kfac_profile_end).
 enum KfacKernelClass {
     KC_UNFOLD = 0, KC_SYRK, KC_SYRK_REDUCE, KC_PRECOND_GEMM, KC_EIG_SMALL, KC_EIG_SOLVE, KC_EIG_APPLY,

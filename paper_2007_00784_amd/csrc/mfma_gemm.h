@@ -11,6 +11,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "kfac_internal.h"
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -27,20 +28,45 @@ __device__ inline float to_float(unsigned short v) { return __uint_as_float(((un
 
 // ---- operand loaders ------------------------------------------------------------------------
 // Every loader defines:  KFAST  (thread mapping: consecutive threads walk k, else walk i)
-//                        start(tid, i0, k0), fetch(float r[EPT]), next()
+//                        Raw    (the element type as it sits in memory)
+//                        start(tid, i0, k0), fetch(Raw r[EPT]), value(r, s), next()
+// fetch() only issues the loads of a slab (from a clamped address where the element is outside the operand) and notes
+// which slots are inside; value() turns slot s of what was fetched into the operand element (zero outside, converted
+// to fp32).  Nothing may touch the loaded registers between the two: the engine calls value() after the MFMAs of the
+// slab before, so the loads stay in flight behind them.
 // Thread mapping, KFAST : kk = tid & 15,  ii = (tid >> 4) + 16*s
 //                 IFAST : ii = tid & 127, kk = (tid >> 7) + 2*s          (s = 0..7)
 
+// Buffer loads: the address is a descriptor in scalar registers (base, extent) plus a 32-bit byte offset per lane, and
+// the hardware returns zero for an offset outside the extent.  A load slot that is outside its operand is given
+// such an offset, so a slab's loads need no address arithmetic, no comparison and no select in vector registers
+// (in a probe of this engine's loop the vector instructions around the loads, not the loads, cost a fifth of the
+// MFMA rate).
+constexpr unsigned BUF_EXTENT = 0x7ffffff0u;   // bytes a descriptor covers from its base (offsets of real elements are far below)
+constexpr unsigned BUF_OUTSIDE = 0x7ffffff8u;  // an offset the range check rejects: the load returns zero
+__device__ inline __amdgpu_buffer_rsrc_t buffer_at(const void *base, unsigned extent = BUF_EXTENT) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, extent, 0x00020000);
+}
+__device__ inline void buffer_load(__amdgpu_buffer_rsrc_t rs, unsigned off, float &v) {
+    v = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
+}
+__device__ inline void buffer_load(__amdgpu_buffer_rsrc_t rs, unsigned off, unsigned short &v) {
+    v = __builtin_amdgcn_raw_buffer_load_b16(rs, off, 0, 0);
+}
+
 // elem(i,k) = p[i*si + k*sk] for i < I, k < K, else 0  (ones_i is unused and kept at -1).
-// Addressing: one base pointer that is uniform over the workgroup (it advances by a whole slab, so it
-// lives in scalar registers) plus an unsigned 32-bit offset per load slot that never changes.  Loads
-// are branch free: an out-of-range element reads the base and is replaced by a select, so a slab's
-// loads issue back to back and interleave with the MFMAs.
+// Addressing: a base pointer that is uniform over the workgroup (it advances by a whole slab, so it lives in
+// scalar registers) plus an unsigned 32-bit byte offset per load slot that never changes; the offset of a slot
+// whose row is outside the operand is BUF_OUTSIDE.  The end of the contraction, k >= K: where k is the slow index
+// in memory (IFAST; (i0 + i) si < sk is assumed, a row of the tile lies inside one leading dimension) the
+// descriptor's extent ends with row K - 1, where k is the fast one the thread's one k per slab is compared with K.
+// (127 si + 15 sk) * sizeof(E) must stay below 2^31: leading dimensions here are at most a few thousand.
 // A contraction index may run over two separate memory ranges: set_segment(k, delta) moves the base by
 // `delta` more elements when the slab starting at contraction index k is entered (k a multiple of BK).
 template <typename E, bool KFAST_>
 struct OpStrided {
     static constexpr bool KFAST = KFAST_;
+    using Raw = E;
     const E *p;
     int64_t si, sk;
     int I, K, ones_i;
@@ -48,34 +74,38 @@ struct OpStrided {
     int64_t seg_delta;
     // thread state
     const E *pb;          // tile base for the current slab (uniform)
-    unsigned off[EPT];    // slot offsets relative to pb
+    unsigned off[EPT];    // byte offsets of the slots relative to pb
     int k_t, k_slab;      // k of slot 0; first k of the current slab
-    unsigned in_mask;     // per slot: row index inside the operand
+    int64_t row0;         // i0 * si
     __device__ void set_segment(int k, int64_t delta) { seg_k = k; seg_delta = delta; }
     __device__ void start(int tid, int i0, int k0) {
         const int di = KFAST ? (tid >> 4) : (tid & 127);
         const int dk = KFAST ? (tid & 15) : (tid >> 7);
-        pb = p + (int64_t)i0 * si + (int64_t)k0 * sk;
+        row0 = (int64_t)i0 * si;
+        pb = p + row0 + (int64_t)k0 * sk;
         k_t = k0 + dk;
         k_slab = k0;
-        in_mask = 0;
 #pragma unroll
         for (int s = 0; s < EPT; ++s) {
             const int i = KFAST ? di + 16 * s : di;
             const int k = KFAST ? dk : dk + 2 * s;
-            off[s] = (unsigned)((int64_t)i * si + (int64_t)k * sk);
-            in_mask |= (i0 + i < I ? 1u : 0u) << s;
+            off[s] = i0 + i < I ? (unsigned)(((int64_t)i * si + (int64_t)k * sk) * (int64_t)sizeof(E)) : BUF_OUTSIDE;
         }
     }
-    __device__ void fetch(float (&r)[EPT]) const {
+    __device__ void fetch(E (&r)[EPT]) const {
+        if (KFAST) {
+            const __amdgpu_buffer_rsrc_t rs = buffer_at(pb);
+            const bool in = k_t < K;
 #pragma unroll
-        for (int s = 0; s < EPT; ++s) {
-            const int k = KFAST ? k_t : k_t + 2 * s;
-            const bool ld = (k < K) && ((in_mask >> s) & 1u);
-            const float v = to_float(pb[ld ? off[s] : 0u]);
-            r[s] = ld ? v : 0.f;
+            for (int s = 0; s < EPT; ++s) buffer_load(rs, in ? off[s] : BUF_OUTSIDE, r[s]);
+        } else {
+            const int64_t left = ((int64_t)(K - k_slab) * sk - row0) * (int64_t)sizeof(E);   // bytes from pb to the end of row K - 1
+            const __amdgpu_buffer_rsrc_t rs = buffer_at(pb, (unsigned)min(max(left, (int64_t)0), (int64_t)BUF_EXTENT));
+#pragma unroll
+            for (int s = 0; s < EPT; ++s) buffer_load(rs, off[s], r[s]);
         }
     }
+    __device__ float value(const E (&r)[EPT], int s) const { return to_float(r[s]); }
     __device__ void next() {
         k_t += BK;
         k_slab += BK;
@@ -96,6 +126,8 @@ struct OpNDT {
     int ioff[EPT];      // i*T per slot (d*T < 2^31 is checked on the host)
     int k_t, t_t;
     unsigned in_mask, ones_mask;
+    unsigned ok, one;   // per slot, for what was fetched last: inside the operand; on the ones row
+    using Raw = E;
     __device__ void start(int tid, int i0, int k0) {
         const int i_t = i0 + (tid >> 4);
         k_t = k0 + (tid & 15);
@@ -111,14 +143,15 @@ struct OpNDT {
             ones_mask |= (i == ones_i ? 1u : 0u) << s;
         }
     }
-    __device__ void fetch(float (&r)[EPT]) const {
+    __device__ void fetch(E (&r)[EPT]) {
         const bool kv = k_t < K;
+        ok = kv ? in_mask : 0u;
+        one = kv ? ones_mask : 0u;
 #pragma unroll
-        for (int s = 0; s < EPT; ++s) {
-            const bool ld = kv && ((in_mask >> s) & 1u);
-            const float v = to_float(p[ld ? base + ioff[s] : 0]);
-            r[s] = ld ? v : ((kv && ((ones_mask >> s) & 1u)) ? 1.f : 0.f);
-        }
+        for (int s = 0; s < EPT; ++s) r[s] = as_global(p)[((ok >> s) & 1u) ? base + ioff[s] : 0];
+    }
+    __device__ float value(const E (&r)[EPT], int s) const {
+        return ((ok >> s) & 1u) ? to_float(r[s]) : (((one >> s) & 1u) ? 1.f : 0.f);
     }
     __device__ void next() {
         k_t += BK;
@@ -128,12 +161,15 @@ struct OpNDT {
     }
 };
 
-template <bool KFAST>
-__device__ inline void store_slab(float (*dst)[LDT], const float (&r)[EPT], int tid) {
+// The slab fetched last through `op`, as operand elements, into its place in LDS; with COLSUM, csum[s] += element s.
+template <bool COLSUM, class Op>
+__device__ inline void store_slab(float (*dst)[LDT], const Op &op, const typename Op::Raw (&r)[EPT], int tid, float *csum) {
 #pragma unroll
     for (int s = 0; s < EPT; ++s) {
-        if (KFAST) dst[tid & 15][(tid >> 4) + 16 * s] = r[s];
-        else       dst[(tid >> 7) + 2 * s][tid & 127] = r[s];
+        const float v = op.value(r, s);
+        if (COLSUM) csum[s] += v;
+        if (Op::KFAST) dst[tid & 15][(tid >> 4) + 16 * s] = v;
+        else           dst[(tid >> 7) + 2 * s][tid & 127] = v;
     }
 }
 
@@ -163,17 +199,14 @@ __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int k
     }
     const int nslab = (kend - kbeg + BK - 1) / BK;
     if (nslab <= 0) return;
-    float ra[EPT], rb[EPT];
+    typename OpA::Raw ra[EPT];
+    typename OpB::Raw rb[EPT];
     A.start(tid, i0, kbeg);
     B.start(tid, j0, kbeg);
     A.fetch(ra);
     B.fetch(rb);
-    if (COLSUM) {
-#pragma unroll
-        for (int t = 0; t < EPT; ++t) csum[t] += ra[t];
-    }
-    store_slab<OpA::KFAST>(sm.a[0], ra, tid);
-    store_slab<OpB::KFAST>(sm.b[0], rb, tid);
+    store_slab<COLSUM>(sm.a[0], A, ra, tid, csum);
+    store_slab<false>(sm.b[0], B, rb, tid, nullptr);
     __syncthreads();
     for (int s = 0; s < nslab; ++s) {
         const int cur = s & 1;
@@ -202,13 +235,10 @@ __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int k
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b0[j], acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b1[j], acc[1][1], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);   // nothing that reads the fetched registers moves up in front of the MFMAs
         if (more) {
-            if (COLSUM) {   // here, not at the fetch: the loads stay in flight behind the MFMAs
-#pragma unroll
-                for (int t = 0; t < EPT; ++t) csum[t] += ra[t];
-            }
-            store_slab<OpA::KFAST>(sm.a[cur ^ 1], ra, tid);
-            store_slab<OpB::KFAST>(sm.b[cur ^ 1], rb, tid);
+            store_slab<COLSUM>(sm.a[cur ^ 1], A, ra, tid, csum);
+            store_slab<false>(sm.b[cur ^ 1], B, rb, tid, nullptr);
         }
         __syncthreads();
     }

@@ -39,21 +39,22 @@ struct X3Op {
     int seg_k;
     int64_t seg_delta;
     // thread state
-    const float *pb;
+    global_ptr<const float> pb;
     unsigned off;
     int k_slab, row, kg;
     __device__ void set_segment(int k, int64_t delta) { seg_k = k; seg_delta = delta; }
     __device__ void start(int tid) {
         row = KFAST ? tid >> 1 : tid & 127;
         kg = KFAST ? tid & 1 : tid >> 7;
-        pb = p;
+        pb = as_global(p);
         k_slab = 0;
         off = KFAST ? (unsigned)(row * ld + 8 * kg) : (unsigned)(8 * kg * ld + row);
     }
     __device__ void fetch(float (&r)[8]) const {
         if (KFAST) {
-            const float4 x = *reinterpret_cast<const float4 *>(pb + off);
-            const float4 y = *reinterpret_cast<const float4 *>(pb + off + 4);
+            typedef float floatx4 __attribute__((ext_vector_type(4)));
+            const floatx4 x = *(global_ptr<const floatx4>)(pb + off);
+            const floatx4 y = *(global_ptr<const floatx4>)(pb + off + 4);
             r[0] = x.x; r[1] = x.y; r[2] = x.z; r[3] = x.w;
             r[4] = y.x; r[5] = y.y; r[6] = y.z; r[7] = y.w;
         } else {
@@ -93,7 +94,7 @@ struct X3OpG {
     float scale;
     int I, K;
     // thread state
-    const E *pb;       // KFAST: first element of this thread's row; else p + this thread's i
+    global_ptr<const E> pb;   // KFAST: first element of this thread's row; else p + this thread's i
     int row, kg, k;    // k: first of this thread's eight contraction indices in the current slab
     bool row_ok;
     __device__ void start(int tid, int i0) {
@@ -102,7 +103,7 @@ struct X3OpG {
         k = 8 * kg;
         row_ok = i0 + row < I;
         const int i = row_ok ? i0 + row : 0;
-        pb = KFAST ? p + (int64_t)i * ld : p + i;
+        pb = KFAST ? as_global(p) + (int64_t)i * ld : as_global(p) + i;
     }
     __device__ void fetch(float (&r)[8]) const {
         if (KFAST) {

@@ -41,8 +41,13 @@ __device__ inline void fdivmod(int e, int d, float inv_d, int &q, int &r) {
 }
 
 template <typename E>
-__device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out, const UnfoldArgs &a, int bx, int by, int bz, E *tile,
+__device__ inline void unfold_block(const E *__restrict__ x_, E *__restrict__ out_, const UnfoldArgs &a, int bx, int by, int bz, E *tile,
                                     unsigned short *rowoff) {
+    // global loads and stores, not flat ones (the batched kernel reads its pointers from a table): a flat access
+    // counts on the LDS counter too, and every wait for an LDS read of the write phase would wait for the stores
+    typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+    const global_ptr<const E> x = as_global(x_);
+    const global_ptr<E> out = as_global(out_);
     const int n = bz;
     const int c0 = by * a.cpb;
     const int ho0 = bx * a.rows_out;
@@ -63,7 +68,7 @@ __device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out
     for (int base = threadIdx.x; base < stage_n; base += 256 * SBATCH) {
         E v[SBATCH];
         int dst[SBATCH];
-        const E *src[SBATCH];
+        global_ptr<const E> src[SBATCH];
 #pragma unroll
         for (int u = 0; u < SBATCH; ++u) {
             const int e = min(base + 256 * u, stage_n - 1);
@@ -112,10 +117,10 @@ __device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out
     const int es = (a.deint || a.compact) ? 1 : a.sw;  // LDS step between consecutive output columns
     const int rp = a.compact ? a.Wq : a.sh * a.Wq;     // ... and between consecutive output rows
     const int row_step = rp - a.Wo * es;               // from the end of an output row to the start of the next
-    E *const out0 = out + ((int64_t)n * a.C + c0) * khw * T + (int64_t)ho0 * a.Wo;   // run 0, element 0
+    const global_ptr<E> out0 = out + ((int64_t)n * a.C + c0) * khw * T + (int64_t)ho0 * a.Wo;   // run 0, element 0
     for (int run = 0; run < nrun; ++run) {
-        E *const dst = out0 + (int64_t)run * T;
-        const int g0 = (int)((reinterpret_cast<uintptr_t>(dst) / sizeof(E)) % VEC);   // elements past a 16-byte boundary
+        const global_ptr<E> dst = out0 + (int64_t)run * T;
+        const int g0 = (int)(((uintptr_t)dst / sizeof(E)) % VEC);   // elements past a 16-byte boundary
         const int nvec = (L + g0 + VEC - 1) / VEC;
         for (int v = threadIdx.x; v < nvec; v += 256) {
             const int j0 = v * VEC - g0;             // first element of the vector inside the run (may be < 0)
@@ -129,9 +134,9 @@ __device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out
             if (whole && es == 1) {
                 const int c1 = a.Wo - wo;                     // elements left in this output row
                 if (c1 >= VEC) {
-                    uint4 q;
+                    uintx4 q;
                     __builtin_memcpy(&q, tile + off, 16);     // element aligned only: an unaligned LDS read
-                    *reinterpret_cast<uint4 *>(dst + j0) = q;
+                    *(global_ptr<uintx4>)(dst + j0) = q;
                     continue;
                 }
                 // the rest of the vector comes from the start of the next output row (or of the next patch row)
@@ -142,9 +147,9 @@ __device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out
                     __builtin_memcpy(vb, tile + (off2 - c1), 16);
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) va[i] = i < c1 ? va[i] : vb[i];
-                    uint4 q;
+                    uintx4 q;
                     __builtin_memcpy(&q, va, 16);
-                    *reinterpret_cast<uint4 *>(dst + j0) = q;
+                    *(global_ptr<uintx4>)(dst + j0) = q;
                     continue;
                 }
             }
@@ -168,9 +173,9 @@ __device__ inline void unfold_block(const E *__restrict__ x, E *__restrict__ out
                 vals[i] = xv;
             }
             if (whole) {
-                uint4 q;
+                uintx4 q;
                 __builtin_memcpy(&q, vals, 16);
-                *reinterpret_cast<uint4 *>(dst + j0) = q;
+                *(global_ptr<uintx4>)(dst + j0) = q;
             } else {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i)
