@@ -39,27 +39,28 @@ struct X3Op {
     int seg_k;
     int64_t seg_delta;
     // thread state
-    global_ptr<const float> pb;
-    unsigned off;
+    const float *pb;      // uniform over the workgroup: the loads are buffer loads (scalar base, fixed offset per lane)
+    unsigned off;         // byte offset of this thread's first element of a slab
     int k_slab, row, kg;
     __device__ void set_segment(int k, int64_t delta) { seg_k = k; seg_delta = delta; }
     __device__ void start(int tid) {
         row = KFAST ? tid >> 1 : tid & 127;
         kg = KFAST ? tid & 1 : tid >> 7;
-        pb = as_global(p);
+        pb = p;
         k_slab = 0;
-        off = KFAST ? (unsigned)(row * ld + 8 * kg) : (unsigned)(8 * kg * ld + row);
+        off = 4u * (KFAST ? (unsigned)(row * ld + 8 * kg) : (unsigned)(8 * kg * ld + row));
     }
     __device__ void fetch(float (&r)[8]) const {
+        const __amdgpu_buffer_rsrc_t rs = buffer_at(pb);
         if (KFAST) {
-            typedef float floatx4 __attribute__((ext_vector_type(4)));
-            const floatx4 x = *(global_ptr<const floatx4>)(pb + off);
-            const floatx4 y = *(global_ptr<const floatx4>)(pb + off + 4);
-            r[0] = x.x; r[1] = x.y; r[2] = x.z; r[3] = x.w;
-            r[4] = y.x; r[5] = y.y; r[6] = y.z; r[7] = y.w;
+            typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+            const uintx4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+            const uintx4 y = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 16, 0, 0);
+            r[0] = __uint_as_float(x.x); r[1] = __uint_as_float(x.y); r[2] = __uint_as_float(x.z); r[3] = __uint_as_float(x.w);
+            r[4] = __uint_as_float(y.x); r[5] = __uint_as_float(y.y); r[6] = __uint_as_float(y.z); r[7] = __uint_as_float(y.w);
         } else {
 #pragma unroll
-            for (int s = 0; s < 8; ++s) r[s] = pb[off + (unsigned)(s * ld)];
+            for (int s = 0; s < 8; ++s) buffer_load(rs, off + 4u * (unsigned)(s * ld), r[s]);
         }
     }
     __device__ void next() {
@@ -72,10 +73,11 @@ struct X3Op {
         half8 hi, lo;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            const float v = r[s] * scale;
-            const _Float16 h = (_Float16)v;
+            // two mixed-precision FMAs per element: hi = rne(r * scale), lo = rne(r * scale - hi).  The scaling by a
+            // power of two and the difference are exact, so these are the values of the plain expressions.
+            const _Float16 h = (_Float16)__builtin_fmaf(r[s], scale, 0.f);
             hi[s] = h;
-            lo[s] = (_Float16)(v - (float)h);
+            lo[s] = (_Float16)__builtin_fmaf(r[s], scale, -(float)h);
         }
         *reinterpret_cast<half8 *>(slab + row * X3_ROWB + kg * 16) = hi;
         *reinterpret_cast<half8 *>(slab + row * X3_ROWB + 32 + kg * 16) = lo;
