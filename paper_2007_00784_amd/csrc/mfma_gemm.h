@@ -178,16 +178,62 @@ struct TileSmem {
     float b[2][BK][LDT];
 };
 
+// How the four waves share a tile.  A wave's accumulator acc[i][j] covers rows wm+32i.., columns wn+32j.. of the
+// tile and is computed only if bit 2i+j of `blocks` is set (the value is uniform over the wave).
+struct WaveMap {
+    int wm, wn;
+    unsigned blocks;
+};
+// Every wave a 64x64 quadrant, all four accumulators: the whole 128x128 tile.
+__device__ inline WaveMap wave_map_full() {
+    const int wave = threadIdx.x >> 6;
+    return WaveMap{(wave >> 1) * 64, (wave & 1) * 64, 0xFu};
+}
+// For a tile of which only the first mext rows and next columns are wanted (an edge tile of a ragged matrix):
+// 32x32 accumulator blocks wholly outside are not computed, and a tile that is at most 64 wide (tall) is cut into
+// four slices along the other side, so that all four waves - one per SIMD - share what is left.  An operand
+// dimension of 128 m + 1 (a factor with its bias column) costs a quarter of a tile's time for the last column
+// instead of a whole one.
+__device__ inline WaveMap wave_map_edge(int mext, int next) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    WaveMap m;
+    unsigned rows, cols;   // bit i: accumulator row block i wanted; bit j: column block j
+    if (next <= 64 || mext <= 64) {
+        const bool tall = next <= 64;                 // slices of 32 rows (tall) or of 32 columns
+        m.wm = tall ? 32 * wave : 0;
+        m.wn = tall ? 0 : 32 * wave;
+        const int se = tall ? mext : next, oe = tall ? next : mext;   // extent along / across the slices
+        const unsigned mine = 32 * wave < se ? 1u : 0u;
+        const unsigned other = oe > 32 ? 3u : 1u;
+        rows = tall ? mine : other;
+        cols = tall ? other : mine;
+    } else {
+        m.wm = (wave >> 1) * 64;
+        m.wn = (wave & 1) * 64;
+        rows = (m.wm < mext ? 1u : 0u) | (m.wm + 32 < mext ? 2u : 0u);
+        cols = (m.wn < next ? 1u : 0u) | (m.wn + 32 < next ? 2u : 0u);
+    }
+    m.blocks = 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (((rows >> i) & 1u) && ((cols >> j) & 1u)) m.blocks |= 1u << (2 * i + j);
+    return m;
+}
+
 // acc[i][j] accumulates rows wm+32i.., cols wn+32j.. of the tile; element r of a 32x32 accumulator
 // sits at row 8*(r/4) + 4*(lane/32) + r%4, column lane%32.
 // With COLSUM the thread also accumulates, per load slot, the sum over k of the A-operand elements it
 // fetches (csum[s]); summed over the threads that share a row index this is sum_k elem_A(i, k).
-template <class OpA, class OpB, bool COLSUM = false>
+template <class OpA, class OpB, bool COLSUM = false, bool EDGE = false>
 __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int kend, TileSmem &sm,
-                                 floatx16 (&acc)[2][2], float *csum = nullptr, bool zero_acc = true) {
+                                 floatx16 (&acc)[2][2], float *csum = nullptr, bool zero_acc = true,
+                                 const WaveMap map = wave_map_full()) {
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lane = tid & 63;
+    const int wm = map.wm, wn = map.wn;
+    const unsigned blocks = map.blocks;   // EDGE: the accumulators to compute; else all four
     const int lk = lane >> 5, lc = lane & 31;
     if (zero_acc) {   // false: keep accumulating into acc (a contraction given in several segments)
 #pragma unroll
@@ -220,20 +266,53 @@ __device__ inline void gemm_tile(OpA &A, OpB &B, int i0, int j0, int kbeg, int k
         // all MFMA operands of the slab are read from LDS up front (32 registers), so the LDS latency is
         // paid once per slab instead of once per k-step and the 32 MFMAs issue back to back
         float a0[BK / 2], a1[BK / 2], b0[BK / 2], b1[BK / 2];
+        if (!EDGE) {
 #pragma unroll
-        for (int j = 0; j < BK / 2; ++j) {
-            a0[j] = sm.a[cur][2 * j + lk][wm + lc];
-            a1[j] = sm.a[cur][2 * j + lk][wm + 32 + lc];
-            b0[j] = sm.b[cur][2 * j + lk][wn + lc];
-            b1[j] = sm.b[cur][2 * j + lk][wn + 32 + lc];
-        }
-        __builtin_amdgcn_sched_barrier(0);   // keep the reads above ahead of the MFMAs below
+            for (int j = 0; j < BK / 2; ++j) {
+                a0[j] = sm.a[cur][2 * j + lk][wm + lc];
+                a1[j] = sm.a[cur][2 * j + lk][wm + 32 + lc];
+                b0[j] = sm.b[cur][2 * j + lk][wn + lc];
+                b1[j] = sm.b[cur][2 * j + lk][wn + 32 + lc];
+            }
+            __builtin_amdgcn_sched_barrier(0);   // keep the reads above ahead of the MFMAs below
 #pragma unroll
-        for (int j = 0; j < BK / 2; ++j) {
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[j], b0[j], acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[j], b1[j], acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b0[j], acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b1[j], acc[1][1], 0, 0, 0);
+            for (int j = 0; j < BK / 2; ++j) {
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[j], b0[j], acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[j], b1[j], acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b0[j], acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b1[j], acc[1][1], 0, 0, 0);
+            }
+        } else if (blocks != 0u) {   // only the wanted blocks (the operands of a second block may lie outside the slab)
+#pragma unroll
+            for (int j = 0; j < BK / 2; ++j) {
+                a0[j] = sm.a[cur][2 * j + lk][wm + lc];
+                b0[j] = sm.b[cur][2 * j + lk][wn + lc];
+            }
+            if (blocks & 0xCu) {
+#pragma unroll
+                for (int j = 0; j < BK / 2; ++j) a1[j] = sm.a[cur][2 * j + lk][wm + 32 + lc];
+            }
+            if (blocks & 0xAu) {
+#pragma unroll
+                for (int j = 0; j < BK / 2; ++j) b1[j] = sm.b[cur][2 * j + lk][wn + 32 + lc];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (blocks & 1u) {
+#pragma unroll
+                for (int j = 0; j < BK / 2; ++j) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[j], b0[j], acc[0][0], 0, 0, 0);
+            }
+            if (blocks & 2u) {
+#pragma unroll
+                for (int j = 0; j < BK / 2; ++j) acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[j], b1[j], acc[0][1], 0, 0, 0);
+            }
+            if (blocks & 4u) {
+#pragma unroll
+                for (int j = 0; j < BK / 2; ++j) acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b0[j], acc[1][0], 0, 0, 0);
+            }
+            if (blocks & 8u) {
+#pragma unroll
+                for (int j = 0; j < BK / 2; ++j) acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[j], b1[j], acc[1][1], 0, 0, 0);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);   // nothing that reads the fetched registers moves up in front of the MFMAs
         if (more) {
@@ -258,6 +337,22 @@ __device__ inline void for_each_acc(const floatx16 (&acc)[2][2], F f) {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 f(wm + 32 * i + 8 * (r >> 2) + 4 * lk + (r & 3), wn + 32 * j + lc, acc[i][j][r]);
+}
+
+// The same for a tile computed under `map`: only the accumulators that were computed are visited.
+template <class F>
+__device__ inline void for_each_acc(const floatx16 (&acc)[2][2], const WaveMap map, F f) {
+    const int lane = threadIdx.x & 63;
+    const int lk = lane >> 5, lc = lane & 31;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (!((map.blocks >> (2 * i + j)) & 1u)) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                f(map.wm + 32 * i + 8 * (r >> 2) + 4 * lk + (r & 3), map.wn + 32 * j + lc, acc[i][j][r]);
+        }
 }
 
 // Fill every accumulator element of this thread: acc(row, col) = f(row_in_tile, col_in_tile).
