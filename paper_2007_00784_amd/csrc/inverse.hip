@@ -322,30 +322,28 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
     const InvLayer L = layers[l];
     const int t = blockIdx.x - L.tile0;
     const int i0 = (t / L.tn) * BM, j0 = (t % L.tn) * BM;
-    floatx16 acc[2][2];
     if (STAGE == 0) {
         OpStrided<float, false> b{L.Ainv, 1, L.dA, L.dA, L.dA, -1};            // elem(c,k) = Ainv[k][c]
+        float *T = L.T;
+        const int dA = L.dA;
+        auto epi = [=](int r, int c, float v) { T[(int64_t)r * dA + c] = v; };
         if (L.bf16) {
             OpStrided<unsigned short, true> a{(const unsigned short *)L.grad, L.dA, 1, L.dG, L.dA, -1};
-            gemm_tile(a, b, i0, j0, 0, L.dA, sm, acc);
+            gemm_tile_ragged(a, b, i0, j0, L.dA, L.dG, L.dA, sm, epi);
         } else {
             OpStrided<float, true> a{(const float *)L.grad, L.dA, 1, L.dG, L.dA, -1};
-            gemm_tile(a, b, i0, j0, 0, L.dA, sm, acc);
+            gemm_tile_ragged(a, b, i0, j0, L.dA, L.dG, L.dA, sm, epi);
         }
-        for_each_acc(acc, [&](int r, int c, float v) {
-            const int gr = i0 + r, gc = j0 + c;
-            if (gr < L.dG && gc < L.dA) L.T[(int64_t)gr * L.dA + gc] = v;
-        });
     } else {
         OpStrided<float, true> a{L.Ginv, L.dG, 1, L.dG, L.dG, -1};
         OpStrided<float, false> b{L.T, 1, L.dA, L.dA, L.dG, -1};               // elem(c,k) = T[k][c]
-        gemm_tile(a, b, i0, j0, 0, L.dG, sm, acc);
         if (L.bf16) {
-            EpiStoreBf16 e{(unsigned short *)L.grad, L.dA};
-            for_each_acc(acc, [&](int r, int c, float v) { if (i0 + r < L.dG && j0 + c < L.dA) e(i0 + r, j0 + c, v); });
+            const EpiStoreBf16 e{(unsigned short *)L.grad, L.dA};
+            gemm_tile_ragged(a, b, i0, j0, L.dG, L.dG, L.dA, sm, [=](int r, int c, float v) { e(r, c, v); });
         } else {
             float *g = (float *)L.grad;
-            for_each_acc(acc, [&](int r, int c, float v) { if (i0 + r < L.dG && j0 + c < L.dA) g[(int64_t)(i0 + r) * L.dA + j0 + c] = v; });
+            const int dA = L.dA;
+            gemm_tile_ragged(a, b, i0, j0, L.dG, L.dG, L.dA, sm, [=](int r, int c, float v) { g[(int64_t)r * dA + c] = v; });
         }
     }
 }

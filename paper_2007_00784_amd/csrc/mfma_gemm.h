@@ -422,6 +422,25 @@ __device__ inline void for_each_acc_transposed(const floatx16 (&acc)[2][2], floa
         }
 }
 
+// One tile of an M x N product with ragged edges: epi(row, col, value) for every element of the tile inside the
+// matrix.  A full tile runs under the full map; at an edge the waves share the blocks that hold something.
+template <class OpA, class OpB, class Epi>
+__device__ inline void gemm_tile_ragged(OpA &a, OpB &b, int i0, int j0, int K, int M, int N, TileSmem &sm, Epi epi) {
+    floatx16 acc[2][2];
+    const int mext = min(BM, M - i0), next = min(BM, N - j0);
+    if (mext == BM && next == BM) {
+        gemm_tile(a, b, i0, j0, 0, K, sm, acc);
+        for_each_acc(acc, [&](int r, int c, float v) { epi(i0 + r, j0 + c, v); });
+    } else {
+        const WaveMap map = wave_map_edge(mext, next);
+        gemm_tile<OpA, OpB, false, true>(a, b, i0, j0, 0, K, sm, acc, nullptr, true, map);
+        for_each_acc(acc, map, [&](int r, int c, float v) {
+            const int gr = i0 + r, gc = j0 + c;
+            if (gr < M && gc < N) epi(gr, gc, v);
+        });
+    }
+}
+
 // C = A * B over a rectangular grid of tiles (blockIdx.y: row tile, blockIdx.x: column tile); the
 // epilogue object is called as epi(row, col, value) for every in-range element.  SYM: the product is known to be
 // symmetric (M == N); tiles above the diagonal return at once and every tile below it also delivers its mirror
@@ -431,6 +450,10 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) v
     __shared__ TileSmem sm;
     const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
     if (SYM && j0 > i0) return;
+    if (!SYM) {
+        gemm_tile_ragged(a, b, i0, j0, K, M, N, sm, epi);
+        return;
+    }
     floatx16 acc[2][2];
     gemm_tile(a, b, i0, j0, 0, K, sm, acc);
     for_each_acc(acc, [&](int r, int c, float v) {

@@ -46,19 +46,7 @@ __device__ inline unsigned short f32_to_bf16_rne(float v) {
 
 template <class OpA, class OpB, class Epi>
 __device__ inline void run_tile(OpA a, OpB b, int i0, int j0, int K, int M, int N, TileSmem &sm, Epi epi) {
-    floatx16 acc[2][2];
-    const int mext = min(BM, M - i0), next = min(BM, N - j0);
-    if (mext == BM && next == BM) {
-        gemm_tile(a, b, i0, j0, 0, K, sm, acc);
-        for_each_acc(acc, [&](int r, int c, float v) { epi(i0 + r, j0 + c, v); });
-    } else {   // an edge tile: the waves share the blocks that hold something
-        const WaveMap map = wave_map_edge(mext, next);
-        gemm_tile<OpA, OpB, false, true>(a, b, i0, j0, 0, K, sm, acc, nullptr, true, map);
-        for_each_acc(acc, map, [&](int r, int c, float v) {
-            const int gr = i0 + r, gc = j0 + c;
-            if (gr < M && gc < N) epi(gr, gc, v);
-        });
-    }
+    gemm_tile_ragged(a, b, i0, j0, K, M, N, sm, epi);
 }
 
 template <int STAGE>
