@@ -205,6 +205,7 @@ __device__ inline void gemm_tile_x3(OpA &A, OpB &B, int K, X3Smem &sm, floatx16 
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[i], bl[j], acc[i][j], 0, 0, 0);
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[i], bh[j], acc[i][j], 0, 0, 0);
             }
+        __builtin_amdgcn_sched_barrier(0);
         if (more) {
             A.store(sm.a[cur ^ 1], ra);
             B.store(sm.b[cur ^ 1], rb);
