@@ -33,6 +33,8 @@ struct X3Smem {
 template <bool KFAST_>
 struct X3Op {
     static constexpr bool KFAST = KFAST_;
+    static constexpr bool HAS_BULK = false;   // its one fetch is already free of checks
+    __device__ void fetch_bulk(float (&r)[8]) const { fetch(r); }
     const float *p;
     int64_t ld;
     float scale;          // power of two applied before the split
@@ -86,17 +88,24 @@ struct X3Op {
 
 // General operand for the same engine: any extent and alignment, fp32 or bf16 elements.  elem(i,k) = p[i*ld + k]
 // (KFAST) or p[k*ld + i], zero for i >= I or k >= K (i counted from the operand's first row; the tile's first row
-// i0 is given to start()).  Whole in-range runs of eight k are fetched with two unaligned 16-byte loads (one for
-// bf16); the ragged last slab and rows past the edge go element by element.
+// i0 is given to start()).  Two ways to fetch a slab.  fetch_bulk(), for slabs that lie wholly below K: buffer loads
+// from a base in scalar registers that moves with the slab, at a byte offset per thread that never changes (a row
+// outside the operand has an offset the range check rejects, and reads zeros) -- no comparison, no select and no
+// address arithmetic in vector registers, which is what bound the products of this engine before (some 230 vector
+// instructions a slab beside its 12 MFMAs).  fetch(), for the ragged last slab: element by element, every index
+// checked.
 template <typename E, bool KFAST_>
 struct X3OpG {
     static constexpr bool KFAST = KFAST_;
+    static constexpr bool HAS_BULK = true;
     const E *p;
     int64_t ld;
     float scale;
     int I, K;
     // thread state
     global_ptr<const E> pb;   // KFAST: first element of this thread's row; else p + this thread's i
+    const E *ub;              // bulk: element (i0, first k of the current slab), uniform over the workgroup
+    unsigned boff;            // bulk: byte offset of this thread's first element from ub
     int row, kg, k;    // k: first of this thread's eight contraction indices in the current slab
     bool row_ok;
     __device__ void start(int tid, int i0) {
@@ -106,6 +115,33 @@ struct X3OpG {
         row_ok = i0 + row < I;
         const int i = row_ok ? i0 + row : 0;
         pb = KFAST ? as_global(p) + (int64_t)i * ld : as_global(p) + i;
+        ub = KFAST ? p + (int64_t)i0 * ld : p + i0;
+        const int64_t e = KFAST ? (int64_t)row * ld + 8 * kg : (int64_t)8 * kg * ld + row;
+        boff = row_ok ? (unsigned)(e * (int64_t)sizeof(E)) : BUF_OUTSIDE;
+    }
+    __device__ void fetch_bulk(float (&r)[8]) const {
+        typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+        const __amdgpu_buffer_rsrc_t rs = buffer_at(ub);
+        if (KFAST) {
+            if (sizeof(E) == 4) {
+                const uintx4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, boff, 0, 0);
+                const uintx4 y = __builtin_amdgcn_raw_buffer_load_b128(rs, boff + 16, 0, 0);
+                r[0] = __uint_as_float(x.x); r[1] = __uint_as_float(x.y); r[2] = __uint_as_float(x.z); r[3] = __uint_as_float(x.w);
+                r[4] = __uint_as_float(y.x); r[5] = __uint_as_float(y.y); r[6] = __uint_as_float(y.z); r[7] = __uint_as_float(y.w);
+            } else {
+                const uintx4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, boff, 0, 0);
+                const unsigned w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) { r[2 * t] = __uint_as_float(w[t] << 16); r[2 * t + 1] = __uint_as_float(w[t] & 0xffff0000u); }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                E v;
+                buffer_load(rs, boff + (unsigned)(s * ld) * (unsigned)sizeof(E), v);
+                r[s] = to_float(v);
+            }
+        }
     }
     __device__ void fetch(float (&r)[8]) const {
         if (KFAST) {
@@ -140,41 +176,38 @@ struct X3OpG {
             }
         }
     }
-    __device__ void next() { k += BK; }
+    __device__ void next() {
+        k += BK;
+        ub += KFAST ? (int64_t)BK : (int64_t)BK * ld;
+    }
     __device__ void store(char *slab, const float (&r)[8]) const {
         half8 hi, lo;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            const float v = r[s] * scale;
-            const _Float16 h = (_Float16)v;
+            const _Float16 h = (_Float16)__builtin_fmaf(r[s], scale, 0.f);   // as in X3Op::store
             hi[s] = h;
-            lo[s] = (_Float16)(v - (float)h);
+            lo[s] = (_Float16)__builtin_fmaf(r[s], scale, -(float)h);
         }
         *reinterpret_cast<half8 *>(slab + row * X3_ROWB + kg * 16) = hi;
         *reinterpret_cast<half8 *>(slab + row * X3_ROWB + 32 + kg * 16) = lo;
     }
 };
 
-// acc = (scaleA A) (scaleB B)^T-style product over K (operands as elem(i,k)); same accumulator layout as
-// gemm_tile, so for_each_acc applies.
-// The caller has already called start() on both loaders.
-template <class OpA, class OpB>
-__device__ inline void gemm_tile_x3(OpA &A, OpB &B, int K, X3Smem &sm, floatx16 (&acc)[2][2]) {
+// `nslab` slabs of the product, from the loaders' current position (with ADVANCE they first move on one slab);
+// BULK: the slabs lie wholly inside the contraction and are fetched with fetch_bulk().  Ends with a barrier, so
+// the slab buffers are free again.
+template <bool BULK, class OpA, class OpB>
+__device__ inline void x3_slabs(OpA &A, OpB &B, int nslab, bool advance, X3Smem &sm, floatx16 (&acc)[2][2]) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int lk = lane >> 5, lc = lane & 31;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    const int nslab = (K + BK - 1) / BK;   // loaders without an extent of their own are given whole slabs
-    if (nslab <= 0) return;
     float ra[8], rb[8];
-    A.fetch(ra);
-    B.fetch(rb);
+    if (advance) {
+        A.next();
+        B.next();
+    }
+    if (BULK) { A.fetch_bulk(ra); B.fetch_bulk(rb); } else { A.fetch(ra); B.fetch(rb); }
     A.store(sm.a[0], ra);
     B.store(sm.b[0], rb);
     __syncthreads();
@@ -184,8 +217,7 @@ __device__ inline void gemm_tile_x3(OpA &A, OpB &B, int K, X3Smem &sm, floatx16 
         if (more) {
             A.next();
             B.next();
-            A.fetch(ra);
-            B.fetch(rb);
+            if (BULK) { A.fetch_bulk(ra); B.fetch_bulk(rb); } else { A.fetch(ra); B.fetch(rb); }
         }
         // lane (c, g) of a 32x32x16 MFMA operand holds k = 8g .. 8g+7 of row (column) c
         half8 ah[2], al[2], bh[2], bl[2];
@@ -212,6 +244,26 @@ __device__ inline void gemm_tile_x3(OpA &A, OpB &B, int K, X3Smem &sm, floatx16 
         }
         __syncthreads();
     }
+}
+
+// acc = (scaleA A) (scaleB B)^T-style product over K (operands as elem(i,k)); same accumulator layout as
+// gemm_tile, so for_each_acc applies.  Loaders that have a bulk fetch run the whole slabs of the contraction on it
+// and the ragged last slab, if there is one, on the checked fetch, as a second short pipeline.
+// The caller has already called start() on both loaders.
+template <class OpA, class OpB>
+__device__ inline void gemm_tile_x3(OpA &A, OpB &B, int K, X3Smem &sm, floatx16 (&acc)[2][2]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const int nslab = (K + BK - 1) / BK;   // loaders without an extent of their own are given whole slabs
+    if (nslab <= 0) return;
+    constexpr bool TWO = OpA::HAS_BULK && OpB::HAS_BULK;
+    const int nbulk = TWO ? K / BK : 0;
+    if (TWO && nbulk > 0) x3_slabs<true>(A, B, nbulk, false, sm, acc);
+    if (nslab > nbulk) x3_slabs<false>(A, B, nslab - nbulk, nbulk > 0, sm, acc);
 }
 
 }  // namespace kfac
