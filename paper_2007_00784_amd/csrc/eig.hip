@@ -623,28 +623,33 @@ __device__ inline floatx16 block_gemm(const float *Xs, const float (&reg)[KP / 2
 
 // Block <-> global memory, four consecutive columns per access.  rowf(a) / colf(b) give the global row and
 // column of block row a / block column b (b a multiple of 4; the four columns are contiguous), or -1.
+// G is uniform over the workgroup (buffer accesses: a block row or column outside the matrix is given an offset the
+// range check rejects, which reads zeros and drops the store -- no branch around any access).
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 template <class RowF, class ColF>
 __device__ inline void block_load(float *Xs, const float *G, int64_t ld, RowF rowf, ColF colf) {
-    float4 v[KP * KP / 4 / NT];
+    const __amdgpu_buffer_rsrc_t rs = kfac::buffer_at(G);
+    uintx4 v[KP * KP / 4 / NT];
 #pragma unroll
     for (int u = 0; u < KP * KP / 4 / NT; ++u) {
         const int e4 = threadIdx.x + NT * u;
         const int a = e4 >> 4, b = (e4 & 15) * 4;
         const int gi = rowf(a), gj = colf(b);
-        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (gi >= 0 && gj >= 0) v[u] = *reinterpret_cast<const float4 *>(G + (int64_t)gi * ld + gj);
+        const unsigned off = (gi >= 0 && gj >= 0) ? (unsigned)(((int64_t)gi * ld + gj) * 4) : kfac::BUF_OUTSIDE;
+        v[u] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
     }
 #pragma unroll
     for (int u = 0; u < KP * KP / 4 / NT; ++u) {
         const int e4 = threadIdx.x + NT * u;
         float *dst = Xs + (e4 >> 4) * BLD + (e4 & 15) * 4;
-        dst[0] = v[u].x; dst[1] = v[u].y; dst[2] = v[u].z; dst[3] = v[u].w;
+        dst[0] = __uint_as_float(v[u].x); dst[1] = __uint_as_float(v[u].y); dst[2] = __uint_as_float(v[u].z); dst[3] = __uint_as_float(v[u].w);
     }
 }
 
 // TRANSPOSED: write Xs^T, i.e. global (colf(b), rowf(a..a+3)) <- Xs[a..a+3][b].
 template <bool TRANSPOSED, class RowF, class ColF>
 __device__ inline void block_store(const float *Xs, float *G, int64_t ld, RowF rowf, ColF colf) {
+    const __amdgpu_buffer_rsrc_t rs = kfac::buffer_at(G);
 #pragma unroll
     for (int u = 0; u < KP * KP / 4 / NT; ++u) {
         const int e4 = threadIdx.x + NT * u;
@@ -652,15 +657,16 @@ __device__ inline void block_store(const float *Xs, float *G, int64_t ld, RowF r
             const int a = e4 >> 4, b = (e4 & 15) * 4;
             const int gi = rowf(a), gj = colf(b);
             const float *src = Xs + a * BLD + b;
-            if (gi >= 0 && gj >= 0)
-                *reinterpret_cast<float4 *>(G + (int64_t)gi * ld + gj) = make_float4(src[0], src[1], src[2], src[3]);
+            const unsigned off = (gi >= 0 && gj >= 0) ? (unsigned)(((int64_t)gi * ld + gj) * 4) : kfac::BUF_OUTSIDE;
+            const uintx4 q = {__float_as_uint(src[0]), __float_as_uint(src[1]), __float_as_uint(src[2]), __float_as_uint(src[3])};
+            __builtin_amdgcn_raw_buffer_store_b128(q, rs, off, 0, 0);
         } else {
             const int b = e4 >> 4, a = (e4 & 15) * 4;
             const int gi = rowf(a), gj = colf(b);
             const float *src = Xs + a * BLD + b;
-            if (gi >= 0 && gj >= 0)
-                *reinterpret_cast<float4 *>(G + (int64_t)gj * ld + gi) =
-                    make_float4(src[0], src[BLD], src[2 * BLD], src[3 * BLD]);
+            const unsigned off = (gi >= 0 && gj >= 0) ? (unsigned)(((int64_t)gj * ld + gi) * 4) : kfac::BUF_OUTSIDE;
+            const uintx4 q = {__float_as_uint(src[0]), __float_as_uint(src[BLD]), __float_as_uint(src[2 * BLD]), __float_as_uint(src[3 * BLD])};
+            __builtin_amdgcn_raw_buffer_store_b128(q, rs, off, 0, 0);
         }
     }
 }
