@@ -87,7 +87,8 @@ struct RotEntry { int p, q; float c, s; };
 // each thread's column pair is loop invariant); KC == 0 takes k at run time.
 // CROSS: a sweep visits only the pairs (i, k/2 + j) between the two halves, in k/2 rounds (the pairs inside
 // each half are left to the caller's schedule).
-template <int KC, bool CROSS = false, int NTH = NT>
+// LAST_NORMS = false: the caller has no use for the norms after the last sweep (off2 and nrm2 are those before it).
+template <int KC, bool CROSS = false, int NTH = NT, bool LAST_NORMS = true>
 __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max_sweeps, float tol, float skip_rel,
                                    float *red, RotEntry *rot, int *rotflag) {
     const int tid = threadIdx.x;
@@ -96,6 +97,10 @@ __device__ JacobiResult jacobi_lds(float *S, float *V, int k_rt, int ld, int max
     JacobiResult res{0, 0.f, 0.f, 0};
     if (tid == 0) *rotflag = 0;
     for (int sweep = 0;; ++sweep) {
+        if (!LAST_NORMS && sweep > 0 && sweep >= max_sweeps) {
+            res.sweeps = sweep;
+            break;
+        }
         float o2 = 0.f, d2 = 0.f;
         for (int e = tid; e < k * k; e += NTH) {
             const int i = e / k, j = e - i * k;
@@ -579,8 +584,8 @@ __global__ __launch_bounds__(SOLVE_NT) void blk_solve_kernel(BlkGroup g, int rou
     // block plays, possibly against the phantom), a bipartite schedule leaves it to its caller.  Every
     // other visit rotates only the pairs between the two blocks.
     const JacobiResult res =
-        (g.bipartite || round > 0) ? jacobi_lds<KP, true, SOLVE_NT>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag)
-                                   : jacobi_lds<KP, false, SOLVE_NT>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
+        (g.bipartite || round > 0) ? jacobi_lds<KP, true, SOLVE_NT, false>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag)
+                                   : jacobi_lds<KP, false, SOLVE_NT, false>(sm.S, sm.V, KP, PLD, inner_sweeps, inner_tol, 1e-9f, sm.red, sm.rot, sm.rotflag);
     if (res.rotations > 0) polish_pivot_mfma(sm.V, sm.S);
     float *J = g.J + ((int64_t)m * g.npairs + pj) * (KP * KP);
     for (int e = tid; e < KP * KP; e += SOLVE_NT) J[e] = sm.V[(e / KP) * PLD + (e % KP)];
