@@ -314,7 +314,7 @@ def test_eig_is_reproducible(ctx):
         assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("n", [40, 300, 2100])
+@pytest.mark.parametrize("n", [40, 230, 300, 2100])
 def test_eig_non_finite_input(ctx, n):
     """A NaN in the factor: KFAC_ENOCONV, and every element of that factor's outputs is non-finite, while a
     healthy factor of the same call is decomposed as usual."""
@@ -332,7 +332,9 @@ def test_eig_non_finite_input(ctx, n):
 
 
 # ------------------------------------------------------------------ precondition
-PRECOND_CASES = [(10, 4), (145, 16), (65, 10), (289, 32), (577, 64), (130, 257)]
+# (230, 100) and (97, 200): edge tiles between 65 and 127 wide and tall (accumulator blocks masked under the full
+# wave map); the others: edge tiles at most 64 wide or tall (the waves share them in slices)
+PRECOND_CASES = [(10, 4), (145, 16), (65, 10), (289, 32), (577, 64), (130, 257), (230, 100), (97, 200)]
 
 
 @pytest.mark.parametrize("dA,dG", PRECOND_CASES)
