@@ -681,11 +681,15 @@ __device__ inline void acc_to_block(const floatx16 &acc, float *Xs, int wm, int 
     for (int r = 0; r < 16; ++r) Xs[(wm + 8 * (r >> 2) + 4 * lk + (r & 3)) * BLD + wn + lc] = acc[r];
 }
 
-// grid.x: nblocks_w lower-triangular blocks of W, then nrb row slabs x npairs column pairs of the accumulator.
+// grid.x: nblocks_w lower-triangular blocks of W, then ceil(nrb / 2) pairs of row slabs x npairs column pairs of the
+// accumulator.  A workgroup of the accumulator part takes TWO 64-row slabs of one column pair: the transform is read
+// once for both, both blocks travel to LDS together, and the barriers of the three phases are shared -- the launch of
+// a unit-mode round (54 units x 18 instead of 26 workgroups) then fits the machine in one go.
 // (waves_per_eu(4): with the register budget of four waves per SIMD the compiler keeps both transforms and the
 // staged block in flight; left to itself it aims at six, and the flat groups' rounds take 8 % longer)
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void blk_apply_kernel(BlkGroup g, int round, int nblocks_w, int nrb) {
-    __shared__ float Xs[KP * BLD];
+    __shared__ float Xs2[2][KP * BLD];
+    float *const Xs = Xs2[0];
     const int m = blockIdx.y;
     if (blk_done(g, m)) return;
     const int64_t np2 = (int64_t)g.npad * g.npad;
@@ -740,40 +744,61 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void bl
     } else {
         float *Qw = g.Qw + m * np2;
         const int t = blockIdx.x - nblocks_w;
-        const int rb = t % nrb, Jp = t / nrb;
+        const int nrb2 = (nrb + 1) >> 1;
+        const int rb2 = t % nrb2, Jp = t / nrb2;
         // an identity transform leaves the accumulator as it is -- unless this launch also starts it or takes the
         // identity off it, which every block has to see
         if (idt[Jp] && !g.qw_identity && !g.qw_minus_identity) return;
         int pJ, qJ;
         sched_pair(g, round, Jp, pJ, qJ);
-        const int row0 = rb * KP, npad = g.npad;
-        auto rowf = [&](int a) { return row0 + a < npad ? row0 + a : -1; };
+        const int npad = g.npad;
+        const int nslab = 2 * rb2 + 1 < nrb ? 2 : 1;   // uniform over the workgroup
         auto colf = [&](int b) { return pair_index(b, pJ, qJ, nblk); };
         float bj[KP / 2];
         const float *Jc = Jall + (int64_t)Jp * (KP * KP) + wn + lc;
 #pragma unroll
         for (int j = 0; j < KP / 2; ++j) bj[j] = Jc[(2 * j + lk) * KP];
-        if (g.qw_identity) {
-            for (int e = threadIdx.x; e < KP * KP; e += NT) {
-                const int a = e >> 6, b = e & 63;
-                Xs[a * BLD + b] = (row0 + a == colf(b)) ? 1.f : 0.f;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (h >= nslab) break;
+            const int row0 = (2 * rb2 + h) * KP;
+            auto rowf = [&](int a) { return row0 + a < npad ? row0 + a : -1; };
+            if (g.qw_identity) {
+                for (int e = threadIdx.x; e < KP * KP; e += NT) {
+                    const int a = e >> 6, b = e & 63;
+                    Xs2[h][a * BLD + b] = (row0 + a == colf(b)) ? 1.f : 0.f;
+                }
+            } else {
+                block_load(Xs2[h], Qw, g.npad, rowf, colf);
             }
-        } else {
-            block_load(Xs, Qw, g.npad, rowf, colf);
         }
         __syncthreads();
-        const floatx16 t2 = block_gemm<true>(Xs, bj, wm, wn, lk, lc);
+        floatx16 t2[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            if (h < nslab) t2[h] = block_gemm<true>(Xs2[h], bj, wm, wn, lk, lc);
         __syncthreads();
-        acc_to_block(t2, Xs, wm, wn, lk, lc);
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            if (h < nslab) acc_to_block(t2[h], Xs2[h], wm, wn, lk, lc);
         __syncthreads();
         if (g.qw_minus_identity) {
-            for (int e = threadIdx.x; e < KP * KP; e += NT) {
-                const int a = e >> 6, b = e & 63;
-                if (row0 + a == colf(b)) Xs[a * BLD + b] -= 1.f;
+            for (int h = 0; h < nslab; ++h) {
+                const int row0 = (2 * rb2 + h) * KP;
+                for (int e = threadIdx.x; e < KP * KP; e += NT) {
+                    const int a = e >> 6, b = e & 63;
+                    if (row0 + a == colf(b)) Xs2[h][a * BLD + b] -= 1.f;
+                }
             }
             __syncthreads();
         }
-        block_store<false>(Xs, Qw, g.npad, rowf, colf);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (h >= nslab) break;
+            const int row0 = (2 * rb2 + h) * KP;
+            auto rowf = [&](int a) { return row0 + a < npad ? row0 + a : -1; };
+            block_store<false>(Xs2[h], Qw, g.npad, rowf, colf);
+        }
     }
 }
 
@@ -1343,7 +1368,7 @@ void enqueue_phase(kfac_ctx *ctx, GroupRun &r, int round, size_t lds_solve, int 
     // The unit's own blocks of W are rotated in place by the inner rounds (the passes below touch only blocks between
     // different units); its transform is accumulated in the compact Vi, started from the identity by the first round
     // and, for the split engine, left as V - I by the last.
-    const int in_tw = gin.npairs * (gin.npairs + 1) / 2, in_nrb = s / KP, in_tiles = in_tw + in_nrb * gin.npairs;
+    const int in_tw = gin.npairs * (gin.npairs + 1) / 2, in_nrb = s / KP, in_tiles = in_tw + ((in_nrb + 1) / 2) * gin.npairs;
     const double in_solve = (double)gin.nmat * gin.npairs * 9.0 * KP * KP * (KP / 2);
     const double in_apply = (double)gin.nmat * 8.0 * s * s * EB;
     for (int ri = 0; ri < inner_rounds; ++ri) {
@@ -1710,7 +1735,7 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
         r.solve_flops = (double)nm * gp.npairs * 9.0 * KP * KP * (KP / 2);
         r.ntiles_w = gp.npairs * (gp.npairs + 1) / 2;
         r.nrb = (r.nmax + KP - 1) / KP;
-        r.ntiles = r.ntiles_w + r.nrb * gp.npairs;
+        r.ntiles = r.ntiles_w + ((r.nrb + 1) / 2) * gp.npairs;   // the accumulator part: two row slabs per workgroup
         r.fill_blocks = (int)std::min<size_t>((np2 + NT - 1) / NT, 4096);
         r.norm_blocks = std::min(r.fill_blocks, NORM_PARTS_MAX);
         r.sweep = 0;
