@@ -440,7 +440,7 @@ def test_precondition_batched_with_gradient_scaling(ctx, bf16, split):
         K.kfac_precondition_batched_scaled(ctx.h, QAs, lAs, QGs, lGs, gamma, gd, 0.0, lr, nu_d)
 
 
-@pytest.mark.parametrize("dA,dG", [(145, 16), (300, 130), (577, 64)])
+@pytest.mark.parametrize("dA,dG", [(145, 16), (300, 130), (577, 64), (230, 100)])
 def test_explicit_inverse_method_matches_cholesky_oracle(ctx, dA, dG):
     """Sec. II-C, Eq. (kfac-damped): (G + gamma I)^-1 grad (A + gamma I)^-1.  The library forms it in the eigenbasis
     of its own eigendecompositions (factored denominator); the oracle by two Cholesky solves with no
@@ -527,7 +527,7 @@ def test_invert_factors_batch_of_mixed_sizes(ctx):
         K.kfac_invert_factors(ctx.h, Fd, 0.05, Fd)
 
 
-@pytest.mark.parametrize("dA,dG", [(145, 16), (300, 130), (577, 64)])
+@pytest.mark.parametrize("dA,dG", [(145, 16), (300, 130), (577, 64), (230, 100)])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_precondition_inverse_matches_oracle(ctx, dA, dG, bf16):
     """The whole inverse method, factors -> Cholesky inverses -> Ginv grad Ainv, against the oracle's two Cholesky
