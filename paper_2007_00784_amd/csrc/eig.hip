@@ -847,6 +847,81 @@ __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(
         });
 }
 
+// ---- the same products for every factor of a group in one launch (blockIdx.z: factor) ----------------------------
+// The post-processing and refresh products of the mid-size factors are a few hundred tiles each, half a machine at
+// best; launched one factor after another they left it half empty (and the flat groups' 25-tile products nearly
+// idle).  An operand is one of the group's buffers (factor z at base + z * stride, the group's pitch) or one of the
+// caller's arrays of that factor (F or Q, pitch n), looked up in the group's item table.
+struct BatchOperand {
+    const float *base;
+    int64_t stride;
+    int kind;   // 0: group buffer, 1: the caller's F, 2: the caller's Q
+};
+__device__ inline float *batch_ptr(const BatchOperand &o, const BlkItem &it, int z, int64_t ldg, int64_t &ld) {
+    if (o.kind == 0) {
+        ld = ldg;
+        return const_cast<float *>(o.base) + z * o.stride;
+    }
+    ld = it.n;
+    return o.kind == 1 ? const_cast<float *>(it.F) : it.Q;
+}
+enum { EPI_STORE, EPI_NS, EPI_NS_DELTA, EPI_ADD_STORE };
+template <int EPI> struct EpiOf;
+template <> struct EpiOf<EPI_STORE> { using type = kfac::EpiStore; };
+template <> struct EpiOf<EPI_NS> { using type = EpiNewtonSchulz; };
+template <> struct EpiOf<EPI_NS_DELTA> { using type = EpiNewtonSchulzDelta; };
+template <> struct EpiOf<EPI_ADD_STORE> { using type = EpiAddStore; };
+template <int EPI>
+__device__ inline typename EpiOf<EPI>::type make_epi(float *c, int64_t ldc, const float *x, int64_t ldx) {
+    if constexpr (EPI == EPI_ADD_STORE) return EpiAddStore{x, ldx, c, ldc};
+    else return typename EpiOf<EPI>::type{c, ldc};
+}
+// C = A B (elem(i,k) operands; AK / BK: the contraction index is the fast one in memory) on the fp32 engine, or with X3
+// on the split-fp16 engine (operands scaled by sc, result by out_scale); SYM as for gemm_generic_kernel.
+template <bool AK, bool BK, int EPI, bool SYM, bool X3>
+__global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void gemm_batched_kernel(BatchOperand A, BatchOperand B, BatchOperand C,
+                                                                                                            BatchOperand X, const BlkItem *items,
+                                                                                                            int64_t ldg, float sc, float out_scale) {
+    using namespace kfac;
+    __shared__ typename std::conditional<X3, X3Smem, TileSmem>::type sm;
+    const int z = blockIdx.z;
+    const BlkItem it = items[z];
+    const int n = it.n;
+    const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
+    if (i0 >= n || j0 >= n || (SYM && j0 > i0)) return;
+    int64_t lda, ldb, ldc, ldx = 0;
+    const float *pa = batch_ptr(A, it, z, ldg, lda), *pb = batch_ptr(B, it, z, ldg, ldb);
+    float *pc = batch_ptr(C, it, z, ldg, ldc);
+    const float *px = EPI == EPI_ADD_STORE ? batch_ptr(X, it, z, ldg, ldx) : nullptr;
+    const auto epi = make_epi<EPI>(pc, ldc, px, ldx);
+    floatx16 acc[2][2];
+    if constexpr (X3) {
+        X3OpG<float, AK> a{pa, lda, sc, n, n};
+        X3OpG<float, BK> b{pb, ldb, sc, n, n};
+        a.start(threadIdx.x, i0);
+        b.start(threadIdx.x, j0);
+        gemm_tile_x3(a, b, n, sm, acc);
+    } else {
+        OpStrided<float, AK> a{pa, AK ? lda : 1, AK ? 1 : lda, n, n, -1};
+        OpStrided<float, BK> b{pb, BK ? ldb : 1, BK ? 1 : ldb, n, n, -1};
+        if (!SYM) {
+            gemm_tile_ragged(a, b, i0, j0, n, n, n, sm, epi);
+            return;
+        }
+        gemm_tile(a, b, i0, j0, 0, n, sm, acc);
+    }
+    const float os = X3 ? out_scale : 1.f;
+    for_each_acc(acc, [&](int r, int c, float v) {
+        const int gr = i0 + r, gc = j0 + c;
+        if (gr < n && gc < n) epi(gr, gc, v * os);
+    });
+    if (SYM && j0 < i0)
+        for_each_acc_transposed(acc, reinterpret_cast<float *>(&sm), [&](int r, int c, float v) {
+            const int gr = j0 + r, gc = i0 + c;
+            if (gr < n && gc < n) epi(gr, gc, v * os);
+        });
+}
+
 // Rayleigh quotients lam[i] = q_i^T (F q_i) from Q [n][ldq] and Z = F Q [n][ldz]: the rows are split over
 // blockIdx.y, whose shares land in part[y][i] and are added in order by the kernel below.
 constexpr int RAY_PARTS = 32;
@@ -1423,36 +1498,61 @@ inline double sym_product_flops(int n) {
 
 // One Newton-Schulz step out = Q (3I - Q^T Q)/2 on the leading n x n part of Q (pitch ld); `scratch` (same pitch) is
 // overwritten.  On the fp32 engine, or (split: groups whose passes run there anyway) on the split-fp16 engine in delta form.
-void enqueue_newton_schulz(kfac_ctx *ctx, hipStream_t st, const float *Qm, int64_t ld, int n, float *scratch, float *out, int64_t ldout,
-                           bool split) {
+void enqueue_newton_schulz(kfac_ctx *ctx, GroupRun &r, BatchOperand Qm, BatchOperand scratch, BatchOperand out, bool split) {
     using namespace kfac;
-    const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
+    const int64_t ld = r.plan->npad;
+    const int tiles = (r.nmax + BM - 1) / BM;
+    const dim3 grid(tiles, tiles, r.nm), block(NTHREADS);
+    double f_sym = 0.0, f_full = 0.0;
+    for (int i = 0; i < r.nm; ++i) {
+        const double n = r.items[i].n;
+        f_sym += sym_product_flops(r.items[i].n);
+        f_full += 2.0 * n * n * n;
+    }
+    const BatchOperand none{nullptr, 0, 0};
+    hipStream_t st = r.st;
     if (split) {
         constexpr float SC = 16384.f, OUT = 1.f / (SC * SC);
-        X3OpG<float, false> q_kn{Qm, ld, SC, n, n};               // elem(i,k) = Q[k][i]
-        {
-            KfacProfScope prof(ctx, KC_EIG_POST, sym_product_flops(n), 0.0, st);
-            hipLaunchKernelGGL((gemm_x3_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulzDelta, true>), grid, block, 0, st, q_kn, q_kn,
-                               EpiNewtonSchulzDelta{scratch, ld}, n, n, n, OUT);
+        {   // D = (I - Q^T Q) / 2
+            KfacProfScope prof(ctx, KC_EIG_POST, f_sym, 0.0, st);
+            hipLaunchKernelGGL((gemm_batched_kernel<false, false, EPI_NS_DELTA, true, true>), grid, block, 0, st, Qm, Qm, scratch, none,
+                               (const BlkItem *)r.d_items, ld, SC, OUT);
         }
-        X3OpG<float, true> q_mk{Qm, ld, SC, n, n};                // elem(i,k) = Q[i][k]
-        X3OpG<float, false> d_kn{scratch, ld, SC, n, n};          // elem(j,k) = D[k][j]
-        KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-        hipLaunchKernelGGL((gemm_x3_kernel<decltype(q_mk), decltype(d_kn), EpiAddStore>), grid, block, 0, st, q_mk, d_kn,
-                           EpiAddStore{Qm, ld, out, ldout}, n, n, n, OUT);
+        KfacProfScope prof(ctx, KC_EIG_POST, f_full, 0.0, st);   // Q + Q D
+        hipLaunchKernelGGL((gemm_batched_kernel<true, false, EPI_ADD_STORE, false, true>), grid, block, 0, st, Qm, scratch, out, Qm,
+                           (const BlkItem *)r.d_items, ld, SC, OUT);
         return;
     }
-    OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};          // elem(i,k) = Q[k][i]
-    {
-        KfacProfScope prof(ctx, KC_EIG_POST, sym_product_flops(n), 0.0, st);
-        hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_kn), decltype(q_kn), EpiNewtonSchulz, true>), grid, block, 0, st,
-                           q_kn, q_kn, EpiNewtonSchulz{scratch, ld}, n, n, n);
+    {   // Y = (3I - Q^T Q) / 2
+        KfacProfScope prof(ctx, KC_EIG_POST, f_sym, 0.0, st);
+        hipLaunchKernelGGL((gemm_batched_kernel<false, false, EPI_NS, true, false>), grid, block, 0, st, Qm, Qm, scratch, none,
+                           (const BlkItem *)r.d_items, ld, 1.f, 1.f);
     }
-    OpStrided<float, true> q_mk{Qm, ld, 1, n, n, -1};           // elem(i,k) = Q[i][k]
-    OpStrided<float, false> y_kn{scratch, 1, ld, n, n, -1};
-    KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-    hipLaunchKernelGGL((gemm_generic_kernel<decltype(q_mk), decltype(y_kn), EpiStore>), grid, block, 0, st,
-                       q_mk, y_kn, EpiStore{out, ldout}, n, n, n);
+    KfacProfScope prof(ctx, KC_EIG_POST, f_full, 0.0, st);       // Q Y
+    hipLaunchKernelGGL((gemm_batched_kernel<true, false, EPI_STORE, false, false>), grid, block, 0, st, Qm, scratch, out, none,
+                       (const BlkItem *)r.d_items, ld, 1.f, 1.f);
+}
+
+// C = A B (A with the contraction index fast, e.g. the caller's F; B with it slow) and C = A^T B made of lower tiles
+// and their mirror images, for every factor of the group, on the fp32 engine.
+void enqueue_product(kfac_ctx *ctx, GroupRun &r, BatchOperand A, BatchOperand B, BatchOperand C, bool sym) {
+    using namespace kfac;
+    const int64_t ld = r.plan->npad;
+    const int tiles = (r.nmax + BM - 1) / BM;
+    const dim3 grid(tiles, tiles, r.nm), block(NTHREADS);
+    double flops = 0.0;
+    for (int i = 0; i < r.nm; ++i) {
+        const double n = r.items[i].n;
+        flops += sym ? sym_product_flops(r.items[i].n) : 2.0 * n * n * n;
+    }
+    const BatchOperand none{nullptr, 0, 0};
+    KfacProfScope prof(ctx, KC_EIG_POST, flops, 0.0, r.st);
+    if (sym)
+        hipLaunchKernelGGL((gemm_batched_kernel<false, false, EPI_STORE, true, false>), grid, block, 0, r.st, A, B, C, none,
+                           (const BlkItem *)r.d_items, ld, 1.f, 1.f);
+    else
+        hipLaunchKernelGGL((gemm_batched_kernel<true, false, EPI_STORE, false, false>), grid, block, 0, r.st, A, B, C, none,
+                           (const BlkItem *)r.d_items, ld, 1.f, 1.f);
 }
 
 // Refresh of a group whose passes run on the split engine.  Those passes carry 22 significand bits and an error
@@ -1472,44 +1572,37 @@ int enqueue_refresh(kfac_ctx *ctx, GroupRun &r) {
     const GroupPlan &gp = *r.plan;
     const size_t np2 = (size_t)gp.npad * gp.npad;
     hipStream_t st = r.st;
+    const int64_t ld = gp.npad;
+    const BatchOperand bW{r.g.W, (int64_t)np2, 0}, bQ{r.g.Qw, (int64_t)np2, 0}, bQo{r.Qalt, (int64_t)np2, 0}, bT{r.sp.T, (int64_t)np2, 0};
+    const BatchOperand bF{nullptr, 0, 1};
+    // Every product below is one launch for the whole group (a factor with non-finite input rides along: its
+    // matrices are its own).
     for (int i = 0; i < r.nm; ++i) {
         if (r.bad[i]) continue;
         const int n = r.items[i].n;
-        float *Wm = r.g.W + i * np2, *Qm = r.g.Qw + i * np2, *Qo = r.Qalt + i * np2, *Tm = r.sp.T + i * np2;
-        const int64_t ld = gp.npad;
-        const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
+        const float *Wm = r.g.W + i * np2;
         // The diagonal of W, i.e. the eigenvalue estimates, before W becomes scratch: their ascending order is the order the
         // columns take below.
         double *l64 = r.lam64 + (size_t)i * gp.npad * (RAY_PARTS + 1);
         int *pm = r.perm + (size_t)i * gp.npad;
-        {
-            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
-            hipLaunchKernelGGL(blk_diag_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, (const float *)Wm, ld, n, l64);
-            hipLaunchKernelGGL(blk_rank_kernel, dim3((n + RANK_IPB - 1) / RANK_IPB), dim3(NT), 0, st, (const double *)l64, n, pm, r.items[i].lam);
-        }
-        // Q (3I - Q^T Q)/2 into the other accumulator buffer; W, free from here on, is the scratch
-        enqueue_newton_schulz(ctx, st, Qm, ld, n, Wm, Qo, ld, true);
-        {   // ... and back with the columns in ascending order of their eigenvalue estimates (the padding keeps its identity)
-            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
-            hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, (const float *)Qo, ld, Qm, ld, n, pm);
-        }
-        float *Q1 = Qm;
-        OpStrided<float, true> f_mk{r.items[i].F, n, 1, n, n, -1};
-        OpStrided<float, false> q1_kn{Q1, 1, ld, n, n, -1};         // elem(c,k) = Q1[k][c]
-        {   // T = F Q1
-            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-            hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(q1_kn), EpiStore>), grid, block, 0, st,
-                               f_mk, q1_kn, EpiStore{Tm, ld}, n, n, n);
-        }
-        OpStrided<float, false> q1t_mk{Q1, 1, ld, n, n, -1};        // elem(r,k) = Q1[k][r]
-        OpStrided<float, false> t_kn{Tm, 1, ld, n, n, -1};          // elem(c,k) = T[k][c]
-        {   // W = Q1^T T, made exactly symmetric
-            KfacProfScope prof(ctx, KC_EIG_POST, sym_product_flops(n), 0.0, st);
-            hipLaunchKernelGGL((gemm_generic_kernel<decltype(q1t_mk), decltype(t_kn), EpiStore, true>), grid, block, 0, st,
-                               q1t_mk, t_kn, EpiStore{Wm, ld}, n, n, n);
-        }
         KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
-        hipLaunchKernelGGL(blk_symmetrise_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, Wm, ld, n);
+        hipLaunchKernelGGL(blk_diag_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, st, Wm, ld, n, l64);
+        hipLaunchKernelGGL(blk_rank_kernel, dim3((n + RANK_IPB - 1) / RANK_IPB), dim3(NT), 0, st, (const double *)l64, n, pm, r.items[i].lam);
+    }
+    // Q (3I - Q^T Q)/2 into the other accumulator buffer; W, free from here on, is the scratch
+    enqueue_newton_schulz(ctx, r, bQ, bW, bQo, true);
+    for (int i = 0; i < r.nm; ++i) {   // ... and back with the columns in ascending order of their eigenvalue estimates (the padding keeps its identity)
+        if (r.bad[i]) continue;
+        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+        hipLaunchKernelGGL(blk_gather_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, (const float *)(r.Qalt + i * np2), ld,
+                           r.g.Qw + i * np2, ld, r.items[i].n, r.perm + (size_t)i * gp.npad);
+    }
+    enqueue_product(ctx, r, bF, bQ, bT, false);   // T = F Q1
+    enqueue_product(ctx, r, bQ, bT, bW, true);    // W = Q1^T T, made exactly symmetric
+    for (int i = 0; i < r.nm; ++i) {
+        if (r.bad[i]) continue;
+        KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
+        hipLaunchKernelGGL(blk_symmetrise_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, r.g.W + i * np2, ld, r.items[i].n);
     }
     r.refreshed = true;
     KFAC_HIP_CHECK(hipGetLastError());
@@ -1524,6 +1617,12 @@ int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
     const GroupPlan &gp = *r.plan;
     const size_t np2 = (size_t)gp.npad * gp.npad;
     hipStream_t st = r.st;
+    const int64_t ld = gp.npad;
+    const BatchOperand bW{r.g.W, (int64_t)np2, 0}, bQ{r.g.Qw, (int64_t)np2, 0}, bF{nullptr, 0, 1}, bOut{nullptr, 0, 2};
+    // one launch per product for the whole group: the orthogonalised accumulator goes to the caller's Q, F Q into the
+    // accumulator's place
+    enqueue_newton_schulz(ctx, r, bQ, bW, bOut, r.x3);
+    enqueue_product(ctx, r, bF, bOut, bQ, false);
     for (int i = 0; i < r.nm; ++i) {
         const int n = r.items[i].n;
         if (r.bad[i]) {   // non-finite input: non-finite output
@@ -1533,16 +1632,6 @@ int enqueue_post(kfac_ctx *ctx, GroupRun &r) {
             continue;
         }
         float *Wm = r.g.W + i * np2, *Qm = r.g.Qw + i * np2;
-        const int64_t ld = gp.npad;
-        const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
-        enqueue_newton_schulz(ctx, st, Qm, ld, n, Wm, r.items[i].Q, n, r.x3);
-        OpStrided<float, true> f_mk{r.items[i].F, n, 1, n, n, -1};
-        OpStrided<float, false> qo_kn{r.items[i].Q, 1, n, n, n, -1};
-        {
-            KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, st);
-            hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(qo_kn), EpiStore>), grid, block, 0, st,
-                               f_mk, qo_kn, EpiStore{Qm, ld}, n, n, n);
-        }
         double *l64 = r.lam64 + (size_t)i * gp.npad * (RAY_PARTS + 1), *lpart = l64 + gp.npad;
         int *pm = r.perm + (size_t)i * gp.npad;
         {
@@ -1755,28 +1844,13 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
         if (warm) {
             // W <- Q0^T F Q0 for the start basis Q0 now in the accumulator; the caller's Q buffer (to be overwritten
             // anyway) holds the intermediate F Q0
-            using namespace kfac;
+            const BatchOperand bW{g.W, (int64_t)np2, 0}, bQ{g.Qw, (int64_t)np2, 0}, bF{nullptr, 0, 1}, bOut{nullptr, 0, 2};
+            enqueue_product(ctx, r, bF, bQ, bOut, false);   // F Q0
+            enqueue_product(ctx, r, bQ, bOut, bW, true);    // Q0^T (F Q0)
             for (int i = 0; i < nm; ++i) {
-                const int n = r.items[i].n;
-                float *Wm = g.W + i * np2, *Qm = g.Qw + i * np2;
-                const int64_t ld = gp.npad;
-                const dim3 grid((n + BM - 1) / BM, (n + BM - 1) / BM), block(NTHREADS);
-                OpStrided<float, true> f_mk{r.items[i].F, n, 1, n, n, -1};
-                OpStrided<float, false> q_kn{Qm, 1, ld, n, n, -1};                  // elem(c,k) = Q0[k][c]
-                {
-                    KfacProfScope prof(ctx, KC_EIG_POST, 2.0 * n * n * n, 0.0, r.st);
-                    hipLaunchKernelGGL((gemm_generic_kernel<decltype(f_mk), decltype(q_kn), EpiStore>), grid, block, 0, r.st,
-                                       f_mk, q_kn, EpiStore{r.items[i].Q, n}, n, n, n);
-                }
-                OpStrided<float, false> qt_mk{Qm, 1, ld, n, n, -1};                 // elem(r,k) = Q0[k][r]
-                OpStrided<float, false> t_kn{r.items[i].Q, 1, n, n, n, -1};         // elem(c,k) = (F Q0)[k][c]
-                {
-                    KfacProfScope prof(ctx, KC_EIG_POST, sym_product_flops(n), 0.0, r.st);
-                    hipLaunchKernelGGL((gemm_generic_kernel<decltype(qt_mk), decltype(t_kn), EpiStore, true>), grid, block, 0, r.st,
-                                       qt_mk, t_kn, EpiStore{Wm, ld}, n, n, n);
-                }
                 KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
-                hipLaunchKernelGGL(blk_symmetrise_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, r.st, Wm, ld, n);
+                hipLaunchKernelGGL(blk_symmetrise_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, r.st, g.W + i * np2, (int64_t)gp.npad,
+                                   r.items[i].n);
             }
             KFAC_HIP_CHECK(hipGetLastError());
         }
