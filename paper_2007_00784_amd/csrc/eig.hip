@@ -825,29 +825,7 @@ struct EpiAddStore {
     int64_t ldc;
     __device__ void operator()(int r, int c, float v) const { C[(int64_t)r * ldc + c] = X[(int64_t)r * ldx + c] + v; }
 };
-template <class OpA, class OpB, class Epi, bool SYM = false>   // SYM: as for gemm_generic_kernel
-__global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void gemm_x3_kernel(OpA a, OpB b, Epi epi, int M, int N, int K,
-                                                                                                       float out_scale) {
-    using namespace kfac;
-    __shared__ X3Smem sm;
-    const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
-    if (SYM && j0 > i0) return;
-    floatx16 acc[2][2];
-    a.start(threadIdx.x, i0);
-    b.start(threadIdx.x, j0);
-    gemm_tile_x3(a, b, K, sm, acc);
-    for_each_acc(acc, [&](int r, int c, float v) {
-        const int gr = i0 + r, gc = j0 + c;
-        if (gr < M && gc < N) epi(gr, gc, v * out_scale);
-    });
-    if (SYM && j0 < i0)
-        for_each_acc_transposed(acc, reinterpret_cast<float *>(&sm), [&](int r, int c, float v) {
-            const int gr = j0 + r, gc = i0 + c;
-            if (gr < M && gc < N) epi(gr, gc, v * out_scale);
-        });
-}
-
-// ---- the same products for every factor of a group in one launch (blockIdx.z: factor) ----------------------------
+// ---- n x n products for every factor of a group in one launch (blockIdx.z: factor; y, x: row and column tile) ----
 // The post-processing and refresh products of the mid-size factors are a few hundred tiles each, half a machine at
 // best; launched one factor after another they left it half empty (and the flat groups' 25-tile products nearly
 // idle).  An operand is one of the group's buffers (factor z at base + z * stride, the group's pitch) or one of the
@@ -877,7 +855,9 @@ __device__ inline typename EpiOf<EPI>::type make_epi(float *c, int64_t ldc, cons
     else return typename EpiOf<EPI>::type{c, ldc};
 }
 // C = A B (elem(i,k) operands; AK / BK: the contraction index is the fast one in memory) on the fp32 engine, or with X3
-// on the split-fp16 engine (operands scaled by sc, result by out_scale); SYM as for gemm_generic_kernel.
+// on the split-fp16 engine (operands scaled by sc, result by out_scale).  SYM: the product is known to be symmetric;
+// tiles above the diagonal return at once and every tile below it also delivers its mirror image, epi(col, row,
+// value) -- half the matrix-core work, and the two halves agree to the last bit.
 template <bool AK, bool BK, int EPI, bool SYM, bool X3>
 __global__ __launch_bounds__(kfac::NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void gemm_batched_kernel(BatchOperand A, BatchOperand B, BatchOperand C,
                                                                                                             BatchOperand X, const BlkItem *items,

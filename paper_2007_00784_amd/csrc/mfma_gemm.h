@@ -441,32 +441,7 @@ __device__ inline void gemm_tile_ragged(OpA &a, OpB &b, int i0, int j0, int K, i
     }
 }
 
-// C = A * B over a rectangular grid of tiles (blockIdx.y: row tile, blockIdx.x: column tile); the
-// epilogue object is called as epi(row, col, value) for every in-range element.  SYM: the product is known to be
-// symmetric (M == N); tiles above the diagonal return at once and every tile below it also delivers its mirror
-// image, epi(col, row, value) -- half the matrix-core work, and the two halves agree to the last bit.
-template <class OpA, class OpB, class Epi, bool SYM = false>
-__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2))) void gemm_generic_kernel(OpA a, OpB b, Epi epi, int M, int N, int K) {
-    __shared__ TileSmem sm;
-    const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BM;
-    if (SYM && j0 > i0) return;
-    if (!SYM) {
-        gemm_tile_ragged(a, b, i0, j0, K, M, N, sm, epi);
-        return;
-    }
-    floatx16 acc[2][2];
-    gemm_tile(a, b, i0, j0, 0, K, sm, acc);
-    for_each_acc(acc, [&](int r, int c, float v) {
-        const int gr = i0 + r, gc = j0 + c;
-        if (gr < M && gc < N) epi(gr, gc, v);
-    });
-    if (SYM && j0 < i0)
-        for_each_acc_transposed(acc, reinterpret_cast<float *>(&sm), [&](int r, int c, float v) {
-            const int gr = j0 + r, gc = i0 + c;
-            if (gr < M && gc < N) epi(gr, gc, v);
-        });
-}
-
+// Epilogue objects are called as epi(row, col, value) for every in-range element of a tile.
 struct EpiStore {
     float *C;
     int64_t ld;
