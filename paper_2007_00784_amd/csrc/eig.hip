@@ -470,15 +470,19 @@ __global__ void blk_init_kernel(BlkGroup g, const BlkItem *items, int warm) {
     }
 }
 
-// W <- (W + W^T) / 2 on the leading n x n part (a warm start's Q^T F Q is symmetric only up to rounding).
-__global__ __launch_bounds__(NT) void blk_symmetrise_kernel(float *W, int64_t ld, int n) {
-    const int64_t n2 = (int64_t)n * n;
-    for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < n2; e += (int64_t)gridDim.x * NT) {
-        const int i = (int)(e / n), j = (int)(e - (int64_t)i * n);
+// W <- (W + W^T) / 2 inside the 128 x 128 tiles on the diagonal, for every factor of a group (blockIdx.y).  It follows
+// a symmetric product (gemm_batched_kernel with SYM), whose tiles below the diagonal and their mirror images agree
+// to the last bit already; only a diagonal tile computes both of its halves, each with its own rounding.
+__global__ __launch_bounds__(NT) void blk_symmetrise_tiles_kernel(float *W, int64_t stride, int64_t ld, const BlkItem *items) {
+    const int n = items[blockIdx.y].n;
+    float *Wm = W + blockIdx.y * stride;
+    const int64_t count = (int64_t)n * kfac::BM;
+    for (int64_t e = blockIdx.x * (int64_t)NT + threadIdx.x; e < count; e += (int64_t)gridDim.x * NT) {
+        const int i = (int)(e / kfac::BM), j = (i / kfac::BM) * kfac::BM + (int)(e % kfac::BM);
         if (j >= i) continue;
-        const float v = 0.5f * (W[(int64_t)i * ld + j] + W[(int64_t)j * ld + i]);
-        W[(int64_t)i * ld + j] = v;
-        W[(int64_t)j * ld + i] = v;
+        const float v = 0.5f * (Wm[(int64_t)i * ld + j] + Wm[(int64_t)j * ld + i]);
+        Wm[(int64_t)i * ld + j] = v;
+        Wm[(int64_t)j * ld + i] = v;
     }
 }
 
@@ -1579,10 +1583,10 @@ int enqueue_refresh(kfac_ctx *ctx, GroupRun &r) {
     }
     enqueue_product(ctx, r, bF, bQ, bT, false);   // T = F Q1
     enqueue_product(ctx, r, bQ, bT, bW, true);    // W = Q1^T T, made exactly symmetric
-    for (int i = 0; i < r.nm; ++i) {
-        if (r.bad[i]) continue;
+    {
         KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, st);
-        hipLaunchKernelGGL(blk_symmetrise_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, st, r.g.W + i * np2, ld, r.items[i].n);
+        hipLaunchKernelGGL(blk_symmetrise_tiles_kernel, dim3((r.nmax * BM + NT - 1) / NT, r.nm), dim3(NT), 0, st, r.g.W, (int64_t)np2, ld,
+                           (const BlkItem *)r.d_items);
     }
     r.refreshed = true;
     KFAC_HIP_CHECK(hipGetLastError());
@@ -1827,11 +1831,9 @@ static int eig_run(kfac_ctx *ctx, int batch, const float *const *F, const int *d
             const BatchOperand bW{g.W, (int64_t)np2, 0}, bQ{g.Qw, (int64_t)np2, 0}, bF{nullptr, 0, 1}, bOut{nullptr, 0, 2};
             enqueue_product(ctx, r, bF, bQ, bOut, false);   // F Q0
             enqueue_product(ctx, r, bQ, bOut, bW, true);    // Q0^T (F Q0)
-            for (int i = 0; i < nm; ++i) {
-                KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
-                hipLaunchKernelGGL(blk_symmetrise_kernel, dim3(std::min(r.fill_blocks, 2048)), dim3(NT), 0, r.st, g.W + i * np2, (int64_t)gp.npad,
-                                   r.items[i].n);
-            }
+            KfacProfScope prof(ctx, KC_EIG_MISC, 0.0, 0.0, r.st);
+            hipLaunchKernelGGL(blk_symmetrise_tiles_kernel, dim3((r.nmax * kfac::BM + NT - 1) / NT, nm), dim3(NT), 0, r.st, g.W, (int64_t)np2,
+                               (int64_t)gp.npad, (const BlkItem *)r.d_items);
             KFAC_HIP_CHECK(hipGetLastError());
         }
         int rc = enqueue_offnorm(ctx, r);
