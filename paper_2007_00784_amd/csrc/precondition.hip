@@ -349,23 +349,8 @@ int kfac_launch_precondition_batched(kfac_ctx *ctx, int n, const kfac_precond_it
         for (int t = 0; t < nt; ++t) byG.push_back(TileRef{i, t});
     }
     byA = byG;
-    // Longest tile first, by what a tile costs: its contraction length times the share of a full tile's MFMAs that its
-    // busiest wave issues (an edge tile of the fp32 engine runs under a wave map that skips empty accumulator blocks
-    // and shares narrow tiles between the waves; the split engine always computes whole tiles).
-    auto cost = [&](const TileRef &t, bool overA) {
-        const auto &it = items[t.layer];
-        double share = 1.0;
-        if (!it.split_f16) {
-            const int tn = (it.dA + BM - 1) / BM;
-            const int mext = std::min(BM, it.dG - (t.tile / tn) * BM), next = std::min(BM, it.dA - (t.tile % tn) * BM);
-            if (mext <= 32 || next <= 32) share = 0.25;
-            else if (mext <= 64 || next <= 64) share = 0.5;
-            else share = 0.25 * std::min(2, (mext + 31) / 32) * std::min(2, (next + 31) / 32);
-        }
-        return share * (overA ? it.dA : it.dG);
-    };
-    std::stable_sort(byG.begin(), byG.end(), [&](const TileRef &a, const TileRef &b) { return cost(a, false) > cost(b, false); });
-    std::stable_sort(byA.begin(), byA.end(), [&](const TileRef &a, const TileRef &b) { return cost(a, true) > cost(b, true); });
+    std::stable_sort(byG.begin(), byG.end(), [&](const TileRef &a, const TileRef &b) { return items[a.layer].dG > items[b.layer].dG; });
+    std::stable_sort(byA.begin(), byA.end(), [&](const TileRef &a, const TileRef &b) { return items[a.layer].dA > items[b.layer].dA; });
     LayerDev *d_layers = (LayerDev *)ctx->ws;
     TileRef *d_byG = (TileRef *)(ctx->ws + off_tiles), *d_byA = d_byG + ntiles;
     double *d_dots = scaled ? (double *)(ctx->ws + off_dots) : nullptr;
